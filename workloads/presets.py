@@ -1,0 +1,72 @@
+"""The five synthetic workloads (hyper-parameter records only).
+
+Notation follows the paper: N workers, minibatch size B, initial wait
+count K0, constant a of the staleness-threshold rule (Eq. 4), step size
+lr (eta).  `tau_cap` is the configured staleness threshold: the initial
+and largest value the adaptive threshold may take, so a = tau_cap - N/K0.
+"""
+from __future__ import annotations
+
+import copy
+
+# model ids / dtype ids / time-distribution ids are the integers the C-ABI uses
+MODEL_LINEAR, MODEL_SOFTMAX, MODEL_MLP = 0, 1, 2
+X_FP32, X_BF16 = 0, 1
+TIME_EXP, TIME_PARETO, TIME_CONST = 0, 1, 2
+K_ADAPTIVE, K_FIXED, K_REPLAY, K_ADAPTIVE_FREE = 0, 1, 2, 3
+TAU_ADAPTIVE, TAU_FIXED, TAU_INF = 0, 1, 2
+
+
+def _mk(idx, name, model, dims, x_dtype, M, n_classes, N, B, tau_cap, lr, T,
+        sa=0, time_dist=TIME_EXP, time_param=0.0, n_slow=0, slow_factor=1.0):
+    K0 = max(1, N // 4)
+    return dict(
+        index=idx, name=name, model=model, dims=list(dims), x_dtype=x_dtype,
+        M=M, n_classes=n_classes, N=N, B=B, K0=K0,
+        k_mode=K_ADAPTIVE, tau_mode=TAU_ADAPTIVE, tau_cap=tau_cap,
+        a=tau_cap - N // K0, lr=lr, sa_penalty=sa,
+        time_dist=time_dist, time_param=time_param,
+        n_slow=n_slow, slow_factor=slow_factor, T=T,
+        seed_data=1000 + idx, seed_init=2000 + idx, seed_sim=3000 + idx,
+    )
+
+
+PRESETS = [
+    _mk(1, "cfg1_linreg_d100", MODEL_LINEAR, [100, 1], X_FP32, 10_000, 0,
+        N=8, B=32, tau_cap=3, lr=0.01, T=200),
+    _mk(2, "cfg2_softmax_784x10", MODEL_SOFTMAX, [784, 10], X_FP32, 60_000, 10,
+        N=16, B=64, tau_cap=4, lr=1e-3, T=2000),
+    _mk(3, "cfg3_mlp_3072_512_10", MODEL_MLP, [3072, 512, 10], X_BF16, 50_000, 10,
+        N=32, B=128, tau_cap=4, lr=2e-4, T=2000, n_slow=6, slow_factor=5.0),
+    _mk(4, "cfg4_mlp_3072_1024_1024_10_sa", MODEL_MLP, [3072, 1024, 1024, 10], X_BF16,
+        50_000, 10, N=64, B=128, tau_cap=6, lr=2e-4, T=5000, sa=1),
+    _mk(5, "cfg5_mlp_3072_2048_2048_100", MODEL_MLP, [3072, 2048, 2048, 100], X_BF16,
+        100_000, 100, N=128, B=256, tau_cap=8, lr=2e-4, T=5000,
+        time_dist=TIME_PARETO, time_param=1.5),
+]
+
+
+def preset(i: int) -> dict:
+    """Config i in 1..5 (a fresh copy)."""
+    return copy.deepcopy(PRESETS[i - 1])
+
+
+def scaled_preset(i: int, **over) -> dict:
+    """Config i with some fields replaced (smaller M, dims, N, T ... for tests).
+
+    `a` is re-derived from tau_cap, N and K0 unless given explicitly.
+    """
+    p = preset(i)
+    p.update(over)
+    if "K0" not in over and "N" in over:
+        p["K0"] = max(1, p["N"] // 4)
+    if "a" not in over:
+        p["a"] = p["tau_cap"] - p["N"] // p["K0"]
+    return p
+
+
+def param_count(p: dict) -> int:
+    d = p["dims"]
+    if p["model"] == MODEL_LINEAR:
+        return d[0]
+    return sum(d[l] * d[l + 1] + d[l + 1] for l in range(len(d) - 1))
