@@ -1,0 +1,184 @@
+/*
+ * libabs: one simulated parameter-server round of ABS (Adaptive Bounded
+ * Staleness, Tan & Gao) on one AMD MI355X (gfx950).
+ *
+ * The paper's setting (Section II-A): N workers hold disjoint shards of a
+ * dataset; in round t the server waits for the K^t fastest uploads, each a
+ * minibatch stochastic gradient taken at the worker's own stale copy
+ * w^{t - tau} of the global model, and applies Eq. 3.  Section III adds the
+ * two adaptive rules: the wait count K^t (Eq. 5) and the staleness threshold
+ * tau_max^t (Eq. 4) that forces over-stale workers to restart (Eq. 6,
+ * Algorithm 1).  This library runs that loop with U = 1 local step: a host
+ * event-queue scheduler draws execution times, selects the K^t fastest
+ * workers and applies Eq. 4-6; HIP kernels compute the K^t gradients at mixed
+ * model versions out of a device-resident ring of past global models, reduce
+ * them, update the model and write the new snapshot.
+ *
+ * All entry points are plain C.  Pointers named d_* are DEVICE pointers owned
+ * by the caller, h_* are HOST pointers owned by the caller.  Every call
+ * returns ABS_OK or a negative error code; no exception crosses the boundary.
+ * A handle is not thread-safe.
+ */
+#ifndef ABS_H
+#define ABS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ABS_MAX_LAYERS   7      /* weight matrices of the MLP                          */
+#define ABS_MAX_WORKERS  128    /* N                                                    */
+#define ABS_TRACE_HEADER 12     /* int32 words before the per-worker lists              */
+
+enum {
+  ABS_OK = 0,
+  ABS_E_ARG = -1,        /* bad argument / unsupported configuration                    */
+  ABS_E_WORKSPACE = -2,  /* workspace smaller than abs_workspace_size()                 */
+  ABS_E_HIP = -3,        /* a HIP runtime call failed                                   */
+  ABS_E_VERSION = -4,    /* requested model version is no longer (or not yet) in the ring */
+  ABS_E_NONFINITE = -5,  /* a worker loss came back non-finite                          */
+  ABS_E_REPLAY = -6      /* k_mode 2: the replay array has no entry for this round      */
+};
+
+enum { ABS_MODEL_LINEAR = 0, ABS_MODEL_SOFTMAX = 1, ABS_MODEL_MLP = 2 };
+enum { ABS_X_FP32 = 0, ABS_X_BF16 = 1 };
+enum { ABS_K_ADAPTIVE = 0, ABS_K_FIXED = 1, ABS_K_REPLAY = 2, ABS_K_ADAPTIVE_FREE = 3 };
+enum { ABS_TAU_ADAPTIVE = 0, ABS_TAU_FIXED = 1, ABS_TAU_INF = 2 };
+enum { ABS_TIME_EXP = 0, ABS_TIME_PARETO = 1, ABS_TIME_CONST = 2 };
+
+typedef struct abs_ctx abs_ctx;   /* opaque: one simulation */
+
+/*
+ * One simulation's parameters.  Symbols follow the paper: N workers, minibatch
+ * size B, initial wait count K^0, constant a of Eq. 4, step size eta (lr).
+ *
+ *  model      0: linear least squares f = 1/2 (x.w - y)^2, dims = {d, 1}, no bias,
+ *                X fp32 [M, d], y fp32 [M].
+ *             1: softmax regression, dims = {d, C}, C <= 16, d % 4 == 0,
+ *                X fp32 [M, d], y int32 [M] in [0, C).
+ *             2: ReLU MLP with softmax cross-entropy, dims = {d_0, ..., d_L},
+ *                L = n_layers >= 2, d_0 % 8 == 0, d_L <= 256; X bf16 (uint16
+ *                payload) [M, d_0]; bf16 operands, fp32 accumulation and master
+ *                weights.
+ *  k_mode     0: Eq. 5, floor'ed, kept non-decreasing;  1: K^t = K0;
+ *             2: K^t = k_replay[t] (host array, copied at create);
+ *             3: Eq. 5 floor'ed and clamped to [1, N] only.
+ *  tau_mode   0: Eq. 4 with the threshold additionally capped at tau_cap;
+ *             1: fixed threshold tau_cap;  2: no threshold (no forced restarts).
+ *  tau_cap    bounds the ring of model versions (tau_cap + 3 slots); modes 0/1.
+ *             In mode 2 it only sizes the ring and the caller must make it large
+ *             enough (a selected worker staler than tau_cap + 1 is an error).
+ *  sa_penalty 1: a gradient of staleness tau is applied with eta / max(1, tau).
+ *  time_dist  execution time of a job, in units of 2^-20: 0: 1 + Exp(1);
+ *             1: Pareto(x_m = 1, alpha = time_param); 2: constant 1.  Workers
+ *             0 .. n_slow-1 are slowed by slow_factor.
+ *  seed       seeds execution times and minibatch draws (counter-based).
+ *  device_mode 1: run the device work.  0: schedule only (no HIP call is made, the
+ *             device pointers may be NULL, k_mode must be 1 or 2, losses are NaN);
+ *             used to plan or check the event trace on a machine without a GPU.
+ *  profile    1: bracket every kernel with events and accumulate per-kernel time
+ *             (read with abs_kernel_stats); costs a few microseconds per launch.
+ */
+typedef struct abs_config {
+  int32_t model;
+  int32_t n_layers;
+  int32_t dims[8];
+  int32_t x_dtype;
+  int32_t N;
+  int64_t M;
+  int32_t B;
+  int32_t K0;
+  int32_t k_mode;
+  int32_t tau_mode;
+  int32_t tau_cap;
+  int32_t a;
+  float   lr;
+  int32_t sa_penalty;
+  int32_t time_dist;
+  int32_t n_slow;
+  double  time_param;
+  double  slow_factor;
+  uint64_t seed;
+  const int32_t* k_replay;     /* host pointer, k_mode 2 only */
+  int64_t k_replay_len;
+  int32_t device_mode;
+  int32_t profile;
+} abs_config;
+
+/* sizeof(abs_config) as the library was built, so a binding can check its mirror. */
+int32_t abs_config_bytes(void);
+
+/* Bytes of device scratch abs_create needs for this configuration (ring of model
+ * versions, bf16 weight copies, activations, partial sums); 0 if the configuration
+ * is invalid. */
+size_t abs_workspace_size(const abs_config* cfg);
+
+/*
+ * Start a simulation (Algorithm 1, initialisation): w^0 goes to every worker,
+ * tau = 0, K = K^0, every worker's first execution time is drawn.
+ *  d_X, d_y   dataset, row-major, layouts above; read-only, must outlive the handle.
+ *  d_w0       initial parameters, fp32, boundary layout: per layer W_l [d_in, d_out]
+ *             row-major then b_l [d_out] (the linear model: w [d] only); copied.
+ *  d_workspace  >= abs_workspace_size(cfg) bytes, 256-byte aligned, owned by the
+ *             caller, used exclusively by this handle until abs_destroy.
+ *  hip_stream a hipStream_t (NULL = the null stream); all device work is issued on it.
+ * On failure *out is NULL and abs_last_error(NULL) describes the problem.
+ */
+int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const float* d_w0,
+               void* d_workspace, size_t workspace_bytes, void* hip_stream, abs_ctx** out);
+
+/* Advance n_rounds parameter-server rounds (Algorithm 1, server part, with the
+ * workers' gradients of Eq. 2 at U = 1 and the update of Eq. 3).  Returns when the
+ * host has every round's trace record, i.e. after the last round's losses arrived. */
+int abs_round(abs_ctx* ctx, int32_t n_rounds);
+
+/* Copy global model w^version (fp32, boundary layout, n_floats = parameter count)
+ * to host memory; version -1 = the latest.  Synchronises the stream. */
+int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats);
+
+/*
+ * Copy trace records of rounds [round_lo, round_hi) to h_out.  One record is
+ * ABS_TRACE_HEADER + 3 N int32 words:
+ *   0 t   1 K^t   2 floor(tau_max^t) (INT32_MAX: none)   3,4 completion tick lo,hi
+ *   5 number of forced restarts   6,7 cumulative uploads lo,hi (sum of K^t)
+ *   8,9 cumulative restart messages lo,hi   10 loss estimate of round t as fp32 bits
+ *   11 K^{t+1}   then ids[K^t] in arrival order, versions[K^t], staleness[K^t],
+ *   restarted ids ascending; unused tail = -1.
+ * The paper's communication-round count (Section V-B) is uploads + restarts.
+ */
+int abs_trace(abs_ctx* ctx, int64_t round_lo, int64_t round_hi, int32_t* h_out,
+              size_t cap_words, size_t* words_written);
+
+/* Rounds completed so far. */
+int64_t abs_rounds_done(const abs_ctx* ctx);
+
+/* Per-kernel accounting: launches always; total_ms only with profile = 1.  flops and
+ * bytes are the algorithmic work of the launches so far (not counter readings). */
+typedef struct abs_kernel_stat {
+  char    name[48];
+  int64_t launches;
+  double  total_ms;
+  double  flops;
+  double  bytes;
+} abs_kernel_stat;
+int abs_kernel_stats(abs_ctx* ctx, abs_kernel_stat* h_out, int32_t cap, int32_t* n_out);
+
+/* Text of the last error of this handle (ctx == NULL: of the last failed abs_create /
+ * abs_workspace_size on this thread).  Never NULL. */
+const char* abs_last_error(const abs_ctx* ctx);
+
+void abs_destroy(abs_ctx* ctx);
+
+/* Host-side helpers exposing the simulation's counter-based draws (for checking a
+ * binding or planning a run; no device work): execution time of job j of worker n in
+ * ticks, and the B dataset rows of that job's minibatch (h_rows_out: B entries). */
+uint64_t abs_draw_time_ticks(const abs_config* cfg, int32_t n, int64_t j);
+int abs_draw_batch_rows(const abs_config* cfg, int32_t n, int64_t j, int64_t* h_rows_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABS_H */

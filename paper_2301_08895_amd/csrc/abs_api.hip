@@ -1,0 +1,374 @@
+// C-ABI of libabs: handle, configuration checks, workspace carving, the per-round
+// host loop (select -> launch -> losses -> adapt), trace and model read-out.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "sched.h"
+
+using namespace abs_impl;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+size_t param_count(const abs_config& c) {
+  if (c.model == ABS_MODEL_LINEAR) return (size_t)c.dims[0];
+  size_t p = 0;
+  for (int l = 0; l < c.n_layers; ++l) p += (size_t)c.dims[l] * c.dims[l + 1] + c.dims[l + 1];
+  return p;
+}
+
+// Workspace of the two regression models.
+struct RegPlan {
+  size_t slot_stride;   // floats
+  size_t off_ring, off_dz, off_rowloss, off_rowidx, total;
+};
+
+bool validate(const abs_config& c, std::string& why) {
+  auto bad = [&](const char* m) { why = m; return false; };
+  if (c.N < 1 || c.N > ABS_MAX_WORKERS) return bad("N must be in [1, 128]");
+  if (c.B < 1 || c.B > 4096) return bad("B must be in [1, 4096]");
+  if (c.K0 < 1 || c.K0 > c.N) return bad("K0 must be in [1, N]");
+  if (c.M < c.N) return bad("M must be at least N (every worker needs a non-empty shard)");
+  if (c.M / c.N > 0xFFFFFFFFll || c.M > 0xFFFFFFFFll) return bad("M too large");
+  if (c.k_mode < 0 || c.k_mode > 3) return bad("k_mode must be 0..3");
+  if (c.tau_mode < 0 || c.tau_mode > 2) return bad("tau_mode must be 0..2");
+  if (c.tau_cap < 0 || c.tau_cap > 1024) return bad("tau_cap must be in [0, 1024]");
+  if (c.k_mode == ABS_K_REPLAY && (!c.k_replay || c.k_replay_len < 1)) return bad("k_mode 2 needs k_replay");
+  if (!(c.lr > 0.f) || !std::isfinite(c.lr)) return bad("lr must be positive and finite");
+  if (c.time_dist < 0 || c.time_dist > 2) return bad("time_dist must be 0..2");
+  if (c.time_dist == ABS_TIME_PARETO && !(c.time_param > 0.0)) return bad("Pareto needs time_param > 0");
+  if (c.n_slow < 0 || c.n_slow > c.N) return bad("n_slow must be in [0, N]");
+  if (c.n_slow > 0 && !(c.slow_factor > 0.0)) return bad("slow_factor must be positive");
+  if (c.device_mode == 0 && !(c.k_mode == ABS_K_FIXED || c.k_mode == ABS_K_REPLAY))
+    return bad("schedule-only mode needs k_mode 1 or 2 (there are no losses to adapt K with)");
+  switch (c.model) {
+    case ABS_MODEL_LINEAR:
+      if (c.n_layers != 1 || c.dims[1] != 1) return bad("linear model: n_layers 1, dims {d, 1}");
+      if (c.dims[0] < 1 || c.dims[0] > 512) return bad("linear model: d must be in [1, 512]");
+      if (c.x_dtype != ABS_X_FP32) return bad("linear model: X must be fp32");
+      break;
+    case ABS_MODEL_SOFTMAX:
+      if (c.n_layers != 1) return bad("softmax model: n_layers 1");
+      if (c.dims[0] < 4 || c.dims[0] > 1024 || c.dims[0] % 4) return bad("softmax model: d % 4 == 0, 4 <= d <= 1024");
+      if (c.dims[1] < 2 || c.dims[1] > 16) return bad("softmax model: 2 <= C <= 16");
+      if (c.x_dtype != ABS_X_FP32) return bad("softmax model: X must be fp32");
+      break;
+    case ABS_MODEL_MLP: {
+      if (c.n_layers < 2 || c.n_layers > ABS_MAX_LAYERS) return bad("MLP: 2 <= n_layers <= 7");
+      if (c.x_dtype != ABS_X_BF16) return bad("MLP: X must be bf16");
+      MlpPlan p;
+      const char* w = nullptr;
+      if (!mlp_plan(c, p, &w)) return bad(w ? w : "unsupported MLP configuration");
+      break;
+    }
+    default: return bad("model must be 0, 1 or 2");
+  }
+  return true;
+}
+
+void reg_plan(const abs_config& c, RegPlan& p) {
+  const size_t R = (size_t)c.tau_cap + 3, rows = (size_t)c.N * c.B;
+  p.slot_stride = round_up(param_count(c), 64);
+  size_t o = 0;
+  p.off_ring = o;    o = round_up(o + R * p.slot_stride * 4, 256);
+  p.off_dz = o;      o = round_up(o + rows * 16 * 4, 256);
+  p.off_rowloss = o; o = round_up(o + rows * 4, 256);
+  p.off_rowidx = o;  o = round_up(o + rows * 4, 256);
+  p.total = o;
+}
+
+struct Stat { int64_t launches = 0; double ms = 0, flops = 0, bytes = 0; };
+
+}  // namespace
+
+const char* abs_impl::kernel_kind_name(int kind) {
+  static const char* names[KK_COUNT] = {
+      "linreg_round", "softmax_rows", "softmax_update", "mlp_index", "mlp_gather_t", "mlp_fwd_l1",
+      "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_softmax_ce", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
+      "mlp_update", "mlp_bias_loss"};
+  return kind >= 0 && kind < KK_COUNT ? names[kind] : "?";
+}
+
+struct abs_ctx : public LaunchHook {
+  abs_config cfg;
+  std::unique_ptr<Scheduler> sched;
+  hipStream_t stream = nullptr;
+  char* ws = nullptr;
+  const void* dX = nullptr;
+  const void* dy = nullptr;
+  size_t P = 0, slot_stride = 0, off_ring = 0;
+  int R = 0;
+  RegPlan rplan{};
+  MlpArgs margs{};
+  float* h_loss = nullptr;     // pinned, device-visible
+  float* d_loss = nullptr;     // the device's address of h_loss
+  std::string err;
+  Stat stats[KK_COUNT];
+  // profile mode: one event pair per launch of the current round
+  std::vector<hipEvent_t> ev;
+  std::vector<int> ev_kind;
+  size_t ev_used = 0;
+
+  void begin(int kind, double flops, double bytes) override {
+    stats[kind].launches += 1;
+    stats[kind].flops += flops;
+    stats[kind].bytes += bytes;
+    if (cfg.profile) {
+      if (ev_used + 2 > ev.size()) {
+        for (int i = 0; i < 2; ++i) { hipEvent_t e; (void)hipEventCreate(&e); ev.push_back(e); }
+      }
+      (void)hipEventRecord(ev[ev_used], stream);
+    }
+  }
+  void end(int kind) override {
+    if (cfg.profile) {
+      (void)hipEventRecord(ev[ev_used + 1], stream);
+      ev_kind.push_back(kind);
+      ev_used += 2;
+    }
+  }
+  void harvest() {   // after the stream has been synchronised
+    for (size_t i = 0; i < ev_kind.size(); ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) == hipSuccess) stats[ev_kind[i]].ms += ms;
+    }
+    ev_kind.clear();
+    ev_used = 0;
+  }
+};
+
+#define ABS_HIP(ctx, call)                                                        \
+  do {                                                                            \
+    hipError_t e_ = (call);                                                       \
+    if (e_ != hipSuccess) {                                                       \
+      (ctx)->err = std::string(#call) + ": " + hipGetErrorString(e_);             \
+      return ABS_E_HIP;                                                           \
+    }                                                                             \
+  } while (0)
+
+extern "C" {
+
+int32_t abs_config_bytes(void) { return (int32_t)sizeof(abs_config); }
+
+size_t abs_workspace_size(const abs_config* cfg) {
+  if (!cfg) { g_create_error = "cfg is NULL"; return 0; }
+  std::string why;
+  if (!validate(*cfg, why)) { g_create_error = why; return 0; }
+  if (cfg->model == ABS_MODEL_MLP) {
+    MlpPlan p; const char* w = nullptr;
+    mlp_plan(*cfg, p, &w);
+    return p.total;
+  }
+  RegPlan p; reg_plan(*cfg, p);
+  return p.total;
+}
+
+int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const float* d_w0,
+               void* d_workspace, size_t workspace_bytes, void* hip_stream, abs_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) { g_create_error = "cfg / out is NULL"; return ABS_E_ARG; }
+  std::string why;
+  if (!validate(*cfg, why)) { g_create_error = why; return ABS_E_ARG; }
+  std::unique_ptr<abs_ctx> c(new abs_ctx());
+  c->cfg = *cfg;
+  c->sched.reset(new Scheduler(*cfg));
+  c->cfg.k_replay = nullptr;
+  c->P = param_count(*cfg);
+  c->R = cfg->tau_cap + 3;
+  c->stream = (hipStream_t)hip_stream;
+  if (!cfg->device_mode) { *out = c.release(); return ABS_OK; }
+
+  if (!d_X || !d_y || !d_w0 || !d_workspace) { g_create_error = "a device pointer is NULL"; return ABS_E_ARG; }
+  if (((uintptr_t)d_workspace & 255) || ((uintptr_t)d_X & 15)) {
+    g_create_error = "d_workspace must be 256-byte aligned and d_X 16-byte aligned"; return ABS_E_ARG;
+  }
+  const size_t need = abs_workspace_size(cfg);
+  if (workspace_bytes < need) { g_create_error = "workspace too small"; return ABS_E_WORKSPACE; }
+  c->ws = (char*)d_workspace;
+  c->dX = d_X; c->dy = d_y;
+  auto fail = [&](const char* what, hipError_t e) {
+    g_create_error = std::string(what) + ": " + hipGetErrorString(e);
+    if (c->h_loss) (void)hipHostFree(c->h_loss);
+    return ABS_E_HIP;
+  };
+  hipError_t e = hipHostMalloc((void**)&c->h_loss, ABS_MAX_WORKERS * sizeof(float), hipHostMallocMapped);
+  if (e != hipSuccess) { c->h_loss = nullptr; return fail("hipHostMalloc", e); }
+  e = hipHostGetDevicePointer((void**)&c->d_loss, c->h_loss, 0);
+  if (e != hipSuccess) return fail("hipHostGetDevicePointer", e);
+
+  const uint64_t shard = (uint64_t)(cfg->M / cfg->N);
+  const uint64_t bkey = stream_key(cfg->seed, kStreamBatch);
+  if (cfg->model == ABS_MODEL_MLP) {
+    const char* w = nullptr;
+    mlp_plan(*cfg, c->margs.plan, &w);
+    c->margs.ws = c->ws;
+    c->margs.X = (const uint16_t*)d_X;
+    c->margs.y = (const int32_t*)d_y;
+    c->margs.shard_rows = shard;
+    c->margs.batch_key = bkey;
+    c->margs.loss_out = c->d_loss;
+    c->slot_stride = c->margs.plan.slot_stride;
+    c->off_ring = c->margs.plan.off_ring;
+  } else {
+    reg_plan(*cfg, c->rplan);
+    c->slot_stride = c->rplan.slot_stride;
+    c->off_ring = c->rplan.off_ring;
+  }
+  // w^0 into ring slot 0 (Algorithm 1, initialisation)
+  e = hipMemcpyAsync(c->ws + c->off_ring, d_w0, c->P * sizeof(float), hipMemcpyDeviceToDevice, c->stream);
+  if (e != hipSuccess) return fail("hipMemcpyAsync(w0)", e);
+  if (cfg->model == ABS_MODEL_MLP) {
+    e = mlp_prepare(c->margs, c->stream);
+    if (e != hipSuccess) return fail("mlp_prepare", e);
+  }
+  e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail("hipStreamSynchronize", e);
+  *out = c.release();
+  return ABS_OK;
+}
+
+int abs_round(abs_ctx* ctx, int32_t n_rounds) {
+  if (!ctx || n_rounds < 0) return ABS_E_ARG;
+  const abs_config& cfg = ctx->cfg;
+  std::vector<Upload> sel;
+  RoundDesc rd;
+  std::memset(&rd, 0, sizeof(rd));
+  for (int32_t it = 0; it < n_rounds; ++it) {
+    int rc = ctx->sched->select(sel, ctx->err);
+    if (rc != ABS_OK) return rc;
+    const int64_t t = ctx->sched->round();
+    const int K = (int)sel.size();
+    if (!cfg.device_mode) {
+      rc = ctx->sched->complete(sel, nullptr, false, ctx->err);
+      if (rc != ABS_OK) return rc;
+      continue;
+    }
+    rd.K = K;
+    rd.slot_cur = (uint32_t)(t % ctx->R);
+    rd.slot_next = (uint32_t)((t + 1) % ctx->R);
+    for (int a = 0; a < K; ++a) {
+      const Upload& u = sel[(size_t)a];
+      // coefficient of this upload in Eq. 3: eta_k / (K^t B), eta_k = eta / max(1, tau_k) under
+      // the staleness-aware penalty
+      double eta = (double)cfg.lr;
+      if (cfg.sa_penalty && u.tau > 1) eta /= (double)u.tau;
+      rd.w[a].id = (uint32_t)u.id;
+      rd.w[a].job = u.job;
+      rd.w[a].slot = (uint32_t)(u.ver % ctx->R);
+      rd.w[a].c = (float)(eta / ((double)K * (double)cfg.B));
+    }
+    hipError_t e;
+    if (cfg.model == ABS_MODEL_MLP) {
+      e = launch_mlp_round(ctx->margs, rd, ctx->stream, ctx);
+    } else {
+      RegressionArgs ra;
+      ra.X = (const float*)ctx->dX;
+      ra.y = ctx->dy;
+      ra.ring = (float*)(ctx->ws + ctx->rplan.off_ring);
+      ra.slot_stride = ctx->slot_stride;
+      ra.d = cfg.dims[0];
+      ra.C = cfg.dims[1];
+      ra.B = cfg.B;
+      ra.shard_rows = (uint64_t)(cfg.M / cfg.N);
+      ra.batch_key = stream_key(cfg.seed, kStreamBatch);
+      ra.loss_out = ctx->d_loss;
+      ra.dz = (float*)(ctx->ws + ctx->rplan.off_dz);
+      ra.rowloss = (float*)(ctx->ws + ctx->rplan.off_rowloss);
+      ra.rowidx = (uint32_t*)(ctx->ws + ctx->rplan.off_rowidx);
+      e = cfg.model == ABS_MODEL_LINEAR ? launch_linreg_round(ra, rd, ctx->stream, ctx)
+                                        : launch_softmax_round(ra, rd, ctx->stream, ctx);
+    }
+    if (e != hipSuccess) { ctx->err = std::string("kernel launch: ") + hipGetErrorString(e); return ABS_E_HIP; }
+    // Eq. 5 needs this round's losses before the next round can be selected.
+    ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (cfg.profile) ctx->harvest();
+    rc = ctx->sched->complete(sel, ctx->h_loss, true, ctx->err);
+    if (rc != ABS_OK) return rc;
+  }
+  return ABS_OK;
+}
+
+int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats) {
+  if (!ctx || !h_out) return ABS_E_ARG;
+  if (!ctx->cfg.device_mode) { ctx->err = "no model in schedule-only mode"; return ABS_E_ARG; }
+  if (n_floats != ctx->P) { ctx->err = "n_floats must equal the parameter count"; return ABS_E_ARG; }
+  const int64_t t = ctx->sched->round();
+  if (version < 0) version = t;
+  if (version > t || version < t - (ctx->R - 1) + 0 || version < 0) {
+    ctx->err = "model version not in the ring"; return ABS_E_VERSION;
+  }
+  const char* src = ctx->ws + ctx->off_ring + (size_t)(version % ctx->R) * ctx->slot_stride * sizeof(float);
+  ABS_HIP(ctx, hipMemcpyAsync(h_out, src, n_floats * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+  ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return ABS_OK;
+}
+
+int abs_trace(abs_ctx* ctx, int64_t round_lo, int64_t round_hi, int32_t* h_out, size_t cap_words,
+              size_t* words_written) {
+  if (words_written) *words_written = 0;
+  if (!ctx || !h_out) return ABS_E_ARG;
+  const int64_t t = ctx->sched->round();
+  if (round_lo < 0 || round_hi < round_lo || round_hi > t) { ctx->err = "round range outside [0, rounds done]"; return ABS_E_ARG; }
+  const size_t stride = (size_t)ctx->sched->stride();
+  const size_t words = (size_t)(round_hi - round_lo) * stride;
+  if (words > cap_words) { ctx->err = "trace buffer too small"; return ABS_E_ARG; }
+  if (words) std::memcpy(h_out, ctx->sched->trace().data() + (size_t)round_lo * stride, words * sizeof(int32_t));
+  if (words_written) *words_written = words;
+  return ABS_OK;
+}
+
+int64_t abs_rounds_done(const abs_ctx* ctx) { return ctx ? ctx->sched->round() : -1; }
+
+int abs_kernel_stats(abs_ctx* ctx, abs_kernel_stat* h_out, int32_t cap, int32_t* n_out) {
+  if (!ctx || !h_out || !n_out) return ABS_E_ARG;
+  int n = 0;
+  for (int k = 0; k < KK_COUNT && n < cap; ++k) {
+    if (!ctx->stats[k].launches) continue;
+    std::memset(&h_out[n], 0, sizeof(abs_kernel_stat));
+    std::snprintf(h_out[n].name, sizeof(h_out[n].name), "%s", kernel_kind_name(k));
+    h_out[n].launches = ctx->stats[k].launches;
+    h_out[n].total_ms = ctx->stats[k].ms;
+    h_out[n].flops = ctx->stats[k].flops;
+    h_out[n].bytes = ctx->stats[k].bytes;
+    ++n;
+  }
+  *n_out = n;
+  return ABS_OK;
+}
+
+const char* abs_last_error(const abs_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+void abs_destroy(abs_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->cfg.device_mode) {
+    (void)hipStreamSynchronize(ctx->stream);
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    if (ctx->h_loss) (void)hipHostFree(ctx->h_loss);
+  }
+  delete ctx;
+}
+
+uint64_t abs_draw_time_ticks(const abs_config* cfg, int32_t n, int64_t j) {
+  return cfg ? Scheduler::time_ticks(*cfg, n, j) : 0;
+}
+
+int abs_draw_batch_rows(const abs_config* cfg, int32_t n, int64_t j, int64_t* h_rows_out) {
+  if (!cfg || !h_rows_out || cfg->N < 1 || cfg->M < cfg->N || n < 0 || n >= cfg->N) return ABS_E_ARG;
+  const uint64_t shard = (uint64_t)(cfg->M / cfg->N);
+  const uint64_t jk = job_key(stream_key(cfg->seed, kStreamBatch), (uint32_t)n, (uint32_t)j);
+  for (int b = 0; b < cfg->B; ++b)
+    h_rows_out[b] = (int64_t)((uint64_t)n * shard + draw(jk, (uint32_t)b) % shard);
+  return ABS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,95 @@
+// Launchers of the HIP kernels (defined in kernels_regression.hip / kernels_mlp.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include "abs_common.h"
+
+namespace abs_impl {
+
+// Called around every launch so that the API layer can count / time kernels.
+struct LaunchHook {
+  virtual void begin(int kind, double flops, double bytes) = 0;
+  virtual void end(int kind) = 0;
+  virtual ~LaunchHook() {}
+};
+
+enum KernelKind {
+  KK_LINREG_ROUND = 0,
+  KK_SOFTMAX_ROWS,
+  KK_SOFTMAX_UPDATE,
+  KK_MLP_INDEX,
+  KK_MLP_GATHER_T,
+  KK_MLP_FWD_L1,
+  KK_MLP_FWD_HIDDEN,
+  KK_MLP_FWD_LOGITS,
+  KK_MLP_SOFTMAX_CE,
+  KK_MLP_DGRAD,
+  KK_MLP_WGRAD_L1,
+  KK_MLP_WGRAD,
+  KK_MLP_UPDATE,
+  KK_MLP_BIAS_LOSS,
+  KK_COUNT
+};
+const char* kernel_kind_name(int kind);
+
+struct RegressionArgs {
+  const float* X;        // [M, d] fp32
+  const void*  y;        // fp32 [M] (linear) or int32 [M] (softmax)
+  float* ring;           // [R slots][slot_stride] fp32
+  size_t slot_stride;    // floats between slots
+  int d, C, B;
+  uint64_t shard_rows;   // rows per worker shard
+  uint64_t batch_key;    // stream_key(seed, kStreamBatch)
+  float* loss_out;       // [K] per-upload mean minibatch loss (device-visible host memory)
+  // softmax scratch
+  float* dz;             // [N*B][16]
+  float* rowloss;        // [N*B]
+  uint32_t* rowidx;      // [N*B]
+};
+
+hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
+                               LaunchHook* hook);
+hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
+                                LaunchHook* hook);
+
+}  // namespace abs_impl
+
+namespace abs_impl {
+
+// ---- MLP path --------------------------------------------------------------------------
+// Padded sizes and workspace offsets of the MLP path; filled by mlp_plan().
+struct MlpPlan {
+  int L;                 // weight matrices
+  int d[8], dp[8];       // layer widths and their padded values
+  int B, Bp;             // minibatch rows per upload, padded to the row tile
+  int N, Mp;             // workers; Mp = N * Bp stacked rows at most
+  int R;                 // ring slots
+  size_t P;              // parameters
+  size_t slot_stride;    // floats between fp32 ring slots
+  size_t w_off[8], b_off[8];      // W_l / b_l inside a slot (floats), l = 0 .. L-1
+  size_t shadow_stride;           // bf16 elements between shadow slots
+  size_t wt_off[8], wn_off[8];    // bf16 W_l^T [dp_out][dp_in] / W_l [dp_in][dp_out] inside a shadow slot
+  // byte offsets into the workspace
+  size_t off_ring, off_shadow, off_rowidx, off_label, off_xgt;
+  size_t off_h[8], off_ht[8];     // H_l [Mp][dp_l], H_l^T [dp_l][Mp], l = 1 .. L-1
+  size_t off_z;                   // logits fp32 [Mp][dp_L]
+  size_t off_dz[8], off_dzt[8];   // dZ_l [Mp][dp_l], dZ_l^T [dp_l][Mp], l = 1 .. L
+  size_t off_rowloss, off_partial;
+  size_t partial_floats;
+  size_t total;
+};
+// Returns false (with a message) if the configuration is not supported.
+bool mlp_plan(const abs_config& cfg, MlpPlan& plan, const char** why);
+
+struct MlpArgs {
+  MlpPlan plan;
+  char* ws;              // workspace base (device)
+  const uint16_t* X;     // bf16 payload [M, d0]
+  const int32_t* y;
+  uint64_t shard_rows, batch_key;
+  float* loss_out;
+};
+// One-time preparation on the stream: zero the padded buffers, build the bf16 copies of w^0.
+hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s);
+hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s, LaunchHook* hook);
+
+}  // namespace abs_impl

@@ -1,0 +1,673 @@
+// MLP rounds: bf16 operands on the matrix cores (MFMA 32x32x16), fp32 accumulation,
+// fp32 master weights.
+//
+// The K^t uploads of a round are stacked into one batch of K^t * Bp rows (Bp = B padded
+// to the 128-row tile, so a row tile never straddles two uploads).  Forward and
+// input-gradient products are grouped GEMMs: each 128-row tile multiplies with the bf16
+// copy of the model version its upload computed at (Eq. 2 at the stale model
+// w^{t - tau_k}).  The weight gradient and the K-of-N reduction of Eq. 3 are ONE
+// contraction over all stacked rows, G_l = H_{l-1}^T dZ_l: rows of dZ already carry their
+// upload's coefficient c_k = eta_k / (K^t B), so per-upload gradients are never
+// materialised.  The contraction is split along the rows into partial sums that are
+// combined in a fixed order by the update kernel, which also writes w^{t+1} = w^t - G
+// into the next ring slot together with its two bf16 copies.
+//
+// All three products have the form  C[m][n] = sum_k A[m][k] * Bt[n][k]  with both
+// operands contiguous along k, so one main loop serves them:
+//   forward    A = H_{l}      [rows][dp_l]      Bt = W_l^T  [dp_{l+1}][dp_l]   (per upload)
+//   dgrad      A = dZ_{l+1}   [rows][dp_{l+1}]  Bt = W_l    [dp_l][dp_{l+1}]   (per upload)
+//   wgrad      A = H_l^T      [dp_l][rows]      Bt = dZ_{l+1}^T [dp_{l+1}][rows]
+// which is why activations and output gradients are stored in both orientations and
+// the weights' bf16 copies in both orientations.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "kernels.h"
+
+namespace abs_impl {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 128;   // rows of C per workgroup
+constexpr int BK = 64;    // contraction elements per main-loop step
+constexpr int kMaxSplit = 16;
+
+size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  // round to nearest, ties to even (finite values)
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ------------------------------------------------------------------ minibatch rows
+// rowidx[m], label[m] for the stacked rows m = up * Bp + b.  Padding rows (b >= B) point
+// at a valid dataset row so that everything computed from them is finite; their label
+// is -1 and their output gradient is forced to zero.
+__global__ __launch_bounds__(256) void mlp_index_kernel(uint32_t* rowidx, int32_t* label, const int32_t* y,
+                                                       RoundDesc rd, int B, int Bp, uint64_t shard_rows,
+                                                       uint64_t batch_key) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  if (m >= rd.K * Bp) return;
+  const int up = m / Bp, b = m - up * Bp;
+  const WorkerDesc w = rd.w[up];
+  uint64_t row = (uint64_t)w.id * shard_rows;
+  if (b < B) row += draw(job_key(batch_key, w.id, w.job), (uint32_t)b) % shard_rows;
+  rowidx[m] = (uint32_t)row;
+  label[m] = b < B ? y[row] : -1;
+}
+
+// ------------------------------------------------------------------ gather + transpose of X
+// XgT[k][m] = X[rowidx[m]][k]  (zero for k >= d0): the A operand of the first layer's
+// weight-gradient contraction.  64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void mlp_gather_t_kernel(const uint16_t* X, int d0, const uint32_t* rowidx,
+                                                          uint16_t* XgT, size_t ldt) {
+  __shared__ uint16_t tile[64][72];
+  const int m0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = t + 256 * i;
+    const int r = q >> 3, c = q & 7;
+    const int k = k0 + c * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (k < d0) v = *(const uint4*)(X + (size_t)rowidx[m0 + r] * d0 + k);
+    *(uint4*)&tile[r][c * 8] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = t + 256 * i;
+    const int kk = q >> 3, c = q & 7;      // output row kk, 8 consecutive m
+    uint16_t v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = tile[c * 8 + j][kk];
+    uint4 o;
+    o.x = v[0] | ((uint32_t)v[1] << 16); o.y = v[2] | ((uint32_t)v[3] << 16);
+    o.z = v[4] | ((uint32_t)v[5] << 16); o.w = v[6] | ((uint32_t)v[7] << 16);
+    *(uint4*)(XgT + (size_t)(k0 + kk) * ldt + m0 + c * 8) = o;
+  }
+}
+
+// ------------------------------------------------------------------ the GEMM
+enum { EPI_RELU = 0, EPI_LOGITS = 1, EPI_DGRAD = 2, EPI_WGRAD = 3 };
+
+struct GemmArgs {
+  const uint16_t* A;  size_t lda;     // [Mdim][lda], k contiguous
+  const uint32_t* a_rowidx;           // GATHER: row m of A is A + a_rowidx[m] * lda
+  int a_kvalid;                       // GATHER: k >= a_kvalid reads as zero
+  const uint16_t* Bt; size_t ldb;     // [Ndim][ldb], k contiguous
+  size_t bt_slot_stride;              // PER_UPLOAD: Bt += slot(upload of the row tile) * stride
+  int rows_per_upload;                // Bp
+  int ksteps_total;                   // BK-steps of the whole contraction
+  int ksteps_per_split;               // BK-steps per blockIdx.z
+  const float* bias; size_t bias_slot_stride; int n_valid;   // EPI_RELU / EPI_LOGITS
+  uint16_t* out;  size_t ldo;         // bf16 [Mdim][ldo]   (may be null)
+  uint16_t* outT; size_t ldoT;        // bf16 [Ndim][ldoT]  (may be null)
+  float* outf;    size_t ldof;        // fp32 [Mdim][ldof]; EPI_WGRAD: + z * split_stride
+  size_t split_stride;
+  const uint16_t* mask; size_t ldmask;   // EPI_DGRAD: H_l, gradient passes where H_l > 0
+};
+
+// 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
+// 32x32x16 MFMA blocks.  A and B tiles of BK = 64 are staged in LDS, double buffered,
+// 16-byte chunks XOR-swizzled by row so that both the row-major stores and the
+// column-of-rows fragment loads spread over all banks.
+template <int TN, int EPI, bool GATHER, bool PER_UPLOAD>
+__global__ __launch_bounds__(256) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
+  constexpr int WN = TN / 2;          // columns per wavefront
+  constexpr int NI = WN / 32;         // MFMA blocks along n per wavefront
+  constexpr int BCH = TN * 8 / 256;   // 16-byte chunks of the B tile per thread
+  __shared__ __attribute__((aligned(16))) uint16_t sA[2][TM * BK];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[2][TN * BK];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  const int ks0 = blockIdx.z * g.ksteps_per_split;
+  const int ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
+
+  const uint16_t* Bt = g.Bt;
+  uint32_t slot = 0;
+  if (PER_UPLOAD) {
+    slot = rd.w[m0 / g.rows_per_upload].slot;
+    Bt += (size_t)slot * g.bt_slot_stride;
+  }
+
+  // per-thread source pointers of the chunks this thread stages
+  const uint16_t* pa[4];
+  int ca[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int q = t + 256 * i, r = q >> 3, c = q & 7;
+    const size_t row = GATHER ? (size_t)g.a_rowidx[m0 + r] : (size_t)(m0 + r);
+    pa[i] = g.A + row * g.lda + c * 8;
+    ca[i] = c * 8;
+  }
+  const uint16_t* pb[BCH];
+#pragma unroll
+  for (int i = 0; i < BCH; ++i) {
+    const int q = t + 256 * i, r = q >> 3, c = q & 7;
+    pb[i] = Bt + (size_t)(n0 + r) * g.ldb + c * 8;
+  }
+
+  f32x16_t acc[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  uint4 ra[4], rb[BCH];
+  auto fetch = [&](int ks) {
+    const int k0 = ks * BK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (GATHER && k0 + ca[i] >= g.a_kvalid) ra[i] = make_uint4(0, 0, 0, 0);
+      else ra[i] = *(const uint4*)(pa[i] + k0);
+    }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) rb[i] = *(const uint4*)(pb[i] + k0);
+  };
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int q = t + 256 * i, r = q >> 3, c = q & 7;
+      *(uint4*)&sA[buf][r * BK + ((c ^ (r & 7)) << 3)] = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) {
+      const int q = t + 256 * i, r = q >> 3, c = q & 7;
+      *(uint4*)&sB[buf][r * BK + ((c ^ (r & 7)) << 3)] = rb[i];
+    }
+  };
+
+  if (ks0 < ks1) {
+    fetch(ks0);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    const int lr = lane & 31, lk = lane >> 5;
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const bool more = ks + 1 < ks1;
+      if (more) fetch(ks + 1);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        bf16x8_t fa[2], fb[NI];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+          const int r = wm * 64 + mi * 32 + lr;
+          fa[mi] = *(const bf16x8_t*)&sA[buf][r * BK + (((s * 2 + lk) ^ (r & 7)) << 3)];
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          const int r = wn * WN + ni * 32 + lr;
+          fb[ni] = *(const bf16x8_t*)&sB[buf][r * BK + (((s * 2 + lk) ^ (r & 7)) << 3)];
+        }
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+      }
+      if (more) stage(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  // ---- epilogue.  Accumulator register r of lane l holds C[8 (r/4) + 4 (l/32) + r%4][l%32]
+  // of its 32 x 32 block.
+  const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
+  const float* bias = nullptr;
+  if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
+  float* outf = g.outf;
+  if (EPI == EPI_WGRAD) outf += (size_t)blockIdx.z * g.split_stride;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int n = n0 + wn * WN + ni * 32 + lcol;
+      float bv = 0.f;
+      if (EPI == EPI_RELU || EPI == EPI_LOGITS) bv = n < g.n_valid ? bias[n] : 0.f;
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int mbase = m0 + wm * 64 + mi * 32 + rg * 8 + lrow4;
+        uint16_t h[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int m = mbase + rr;
+          float v = acc[mi][ni][rg * 4 + rr];
+          if (EPI == EPI_RELU) {
+            v = fmaxf(v + bv, 0.f);
+          } else if (EPI == EPI_LOGITS) {
+            v += bv;
+            outf[(size_t)m * g.ldof + n] = v;
+          } else if (EPI == EPI_DGRAD) {
+            const uint16_t hm = g.mask[(size_t)m * g.ldmask + n];
+            v = (hm & 0x7FFFu) ? v : 0.f;
+          } else {
+            outf[(size_t)m * g.ldof + n] = v;
+          }
+          if (EPI == EPI_RELU || EPI == EPI_DGRAD) {
+            h[rr] = f32_to_bf16(v);
+            if (g.out) g.out[(size_t)m * g.ldo + n] = h[rr];
+          }
+        }
+        if ((EPI == EPI_RELU || EPI == EPI_DGRAD) && g.outT) {
+          uint2 o;
+          o.x = h[0] | ((uint32_t)h[1] << 16);
+          o.y = h[2] | ((uint32_t)h[3] << 16);
+          *(uint2*)(g.outT + (size_t)n * g.ldoT + mbase) = o;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+// One wavefront per stacked row: loss of the row, dZ_L = c_k (softmax - onehot) narrowed
+// to bf16 (zero for padding rows and padding columns), in both orientations.
+template <int NC>   // columns per lane: padded class count / 64
+__global__ __launch_bounds__(256) void mlp_softmax_ce_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
+                                                            RoundDesc rd, int Bp, uint16_t* dZ, size_t lddz,
+                                                            uint16_t* dZT, size_t lddzt, float* rowloss) {
+  __shared__ uint16_t sT[NC * 64][72];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m0 = blockIdx.x * 64;
+  const float coef = rd.w[m0 / Bp].c;
+  for (int i = 0; i < 16; ++i) {
+    const int ml = wave * 16 + i, m = m0 + ml;
+    const int lab = label[m];
+    float z[NC];
+    float zmax = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int c = lane + 64 * q;
+      z[q] = c < C ? Z[(size_t)m * ldz + c] : -INFINITY;
+      zmax = fmaxf(zmax, z[q]);
+    }
+    zmax = wave_max(zmax);
+    float ssum = 0.f, zy = 0.f;
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int c = lane + 64 * q;
+      if (c == lab) zy = z[q] - zmax;
+      z[q] = c < C ? expf(z[q] - zmax) : 0.f;
+      ssum += z[q];
+    }
+    ssum = wave_sum(ssum);
+    zy = wave_sum(zy);
+    if (lane == 0) rowloss[m] = lab >= 0 ? logf(ssum) - zy : 0.f;
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int c = lane + 64 * q;
+      float v = 0.f;
+      if (lab >= 0 && c < C) v = coef * (z[q] / ssum - (c == lab ? 1.f : 0.f));
+      const uint16_t h = f32_to_bf16(v);
+      dZ[(size_t)m * lddz + c] = h;
+      sT[c][ml] = h;
+    }
+  }
+  __syncthreads();
+  for (int q = threadIdx.x; q < NC * 64 * 8; q += 256) {
+    const int c = q >> 3, ch = q & 7;
+    *(uint4*)(dZT + (size_t)c * lddzt + m0 + ch * 8) = *(const uint4*)&sT[c][ch * 8];
+  }
+}
+
+// ------------------------------------------------------------------ update + snapshot
+// w^{t+1} = w^t - sum_z partial[z]  (fixed order), written as fp32 into the next ring slot
+// and as bf16 in both orientations into the next shadow slot.  64 x 64 tiles.
+struct UpdateArgs {
+  const float* partial; size_t split_stride; size_t ldp; int nsplit;
+  const float* w_cur; float* w_next;   // [d_in][d_out] fp32, pitch d_out
+  int d_in, d_out;
+  uint16_t* wn; size_t ldwn;           // bf16 [dp_in][dp_out] (may be null)
+  uint16_t* wt; size_t ldwt;           // bf16 [dp_out][dp_in]
+};
+__global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
+  __shared__ uint16_t tile[64][66];
+  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  const int tj = threadIdx.x & 63, ti = threadIdx.x >> 6;
+#pragma unroll 4
+  for (int r = 0; r < 16; ++r) {
+    const int il = ti + 4 * r, i = i0 + il, j = j0 + tj;
+    uint16_t h = 0;
+    if (i < u.d_in && j < u.d_out) {
+      float G = 0.f;
+      for (int z = 0; z < u.nsplit; ++z) G += u.partial[(size_t)z * u.split_stride + (size_t)i * u.ldp + j];
+      const float wnew = u.w_cur[(size_t)i * u.d_out + j] - G;
+      u.w_next[(size_t)i * u.d_out + j] = wnew;
+      h = f32_to_bf16(wnew);
+      if (u.wn) u.wn[(size_t)i * u.ldwn + j] = h;
+    }
+    tile[il][tj] = h;
+  }
+  __syncthreads();
+#pragma unroll 4
+  for (int r = 0; r < 16; ++r) {
+    const int jl = ti + 4 * r, j = j0 + jl, i = i0 + tj;
+    if (i < u.d_in && j < u.d_out) u.wt[(size_t)j * u.ldwt + i] = tile[tj][jl];
+  }
+}
+
+// ------------------------------------------------------------------ bias update + upload losses
+// One wavefront per bias entry: b^{t+1}_j = b^t_j - sum_m dZ_l[m][j], the column sum read
+// from the transposed copy (contiguous along m).  The trailing wavefronts reduce the
+// per-row losses to the mean minibatch loss each upload reports.
+struct BiasLossArgs {
+  int L;
+  int col_begin[ABS_MAX_LAYERS + 1];       // prefix of valid columns over the layers
+  const uint16_t* dzt[ABS_MAX_LAYERS]; size_t lddzt[ABS_MAX_LAYERS];
+  size_t b_off[ABS_MAX_LAYERS];
+  const float* w_cur; float* w_next;
+  int rows;                                // K * Bp
+  const float* rowloss; int B, Bp, K;
+  float* loss_out;
+};
+__global__ __launch_bounds__(256) void mlp_bias_loss_kernel(BiasLossArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int ncol = a.col_begin[a.L];
+  if (w < ncol) {
+    int l = 0;
+    while (w >= a.col_begin[l + 1]) ++l;
+    const int j = w - a.col_begin[l];
+    const uint16_t* src = a.dzt[l] + (size_t)j * a.lddzt[l];
+    float s = 0.f;
+    for (int m = lane * 8; m < a.rows; m += 512) {
+      const uint4 v = *(const uint4*)(src + m);
+      const uint32_t p[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s += __uint_as_float(p[e] << 16);
+        s += __uint_as_float(p[e] & 0xFFFF0000u);
+      }
+    }
+    s = wave_sum(s);
+    if (lane == 0) a.w_next[a.b_off[l] + j] = a.w_cur[a.b_off[l] + j] - s;
+  } else if (w - ncol < a.K) {
+    const int up = w - ncol;
+    float s = 0.f;
+    for (int b = lane; b < a.B; b += 64) s += a.rowloss[(size_t)up * a.Bp + b];
+    s = wave_sum(s);
+    if (lane == 0) a.loss_out[up] = s / (float)a.B;
+  }
+}
+
+__global__ void mlp_fill_zero_kernel(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t step = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += step) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+template <typename T>
+T* at(const MlpArgs& a, size_t off) { return (T*)(a.ws + off); }
+
+int pick_split(int tiles, int ksteps) {
+  int s = (768 + tiles - 1) / tiles;
+  s = std::max(1, std::min(s, std::min(ksteps, kMaxSplit)));
+  return s;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ planning
+bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
+  p = MlpPlan{};
+  const int L = c.n_layers;
+  if (c.dims[0] % 8) { *why = "MLP: d_0 must be a multiple of 8"; return false; }
+  if (c.dims[L] < 2 || c.dims[L] > 256) { *why = "MLP: 2 <= d_L <= 256"; return false; }
+  for (int l = 0; l <= L; ++l)
+    if (c.dims[l] < 1 || c.dims[l] > 16384) { *why = "MLP: layer widths must be in [1, 16384]"; return false; }
+  p.L = L;
+  for (int l = 0; l <= L; ++l) {
+    p.d[l] = c.dims[l];
+    p.dp[l] = (int)round_up((size_t)c.dims[l], 128);
+  }
+  if (c.dims[L] <= 64) p.dp[L] = 64;
+  p.B = c.B;
+  p.Bp = (int)round_up((size_t)c.B, TM);
+  p.N = c.N;
+  p.Mp = c.N * p.Bp;
+  p.R = c.tau_cap + 3;
+  size_t o = 0;
+  for (int l = 0; l < L; ++l) {
+    p.w_off[l] = o; o += (size_t)p.d[l] * p.d[l + 1];
+    p.b_off[l] = o; o += (size_t)p.d[l + 1];
+  }
+  p.P = o;
+  p.slot_stride = round_up(p.P, 64);
+  o = 0;
+  for (int l = 0; l < L; ++l) {
+    p.wt_off[l] = o; o += (size_t)p.dp[l + 1] * p.dp[l];
+    p.wn_off[l] = o; if (l >= 1) o += (size_t)p.dp[l] * p.dp[l + 1];
+  }
+  p.shadow_stride = round_up(o, 128);
+  size_t partial = 0;
+  for (int l = 0; l < L; ++l) partial = std::max(partial, (size_t)p.dp[l] * p.dp[l + 1]);
+  p.partial_floats = partial * kMaxSplit;
+
+  size_t b = 0;
+  auto take = [&](size_t bytes) { size_t at = b; b = round_up(b + bytes, 256); return at; };
+  const size_t Mp = (size_t)p.Mp;
+  p.off_ring = take((size_t)p.R * p.slot_stride * 4);
+  p.off_shadow = take((size_t)p.R * p.shadow_stride * 2);
+  p.off_rowidx = take(Mp * 4);
+  p.off_label = take(Mp * 4);
+  p.off_xgt = take((size_t)p.dp[0] * Mp * 2);
+  for (int l = 1; l < L; ++l) {
+    p.off_h[l] = take(Mp * p.dp[l] * 2);
+    p.off_ht[l] = take(Mp * p.dp[l] * 2);
+  }
+  p.off_z = take(Mp * p.dp[L] * 4);
+  for (int l = 1; l <= L; ++l) {
+    p.off_dz[l] = take(Mp * p.dp[l] * 2);
+    p.off_dzt[l] = take(Mp * p.dp[l] * 2);
+  }
+  p.off_rowloss = take(Mp * 4);
+  p.off_partial = take(p.partial_floats * 4);
+  p.total = b;
+  return true;
+}
+
+// ------------------------------------------------------------------ launches
+namespace {
+
+struct NullHook : LaunchHook {
+  void begin(int, double, double) override {}
+  void end(int) override {}
+};
+
+// w_next = w_cur - G for every layer's weights, plus the bf16 copies of w_next.
+void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_next, int nsplit,
+                   hipStream_t s, LaunchHook* hook) {
+  const MlpPlan& p = a.plan;
+  float* ring = at<float>(a, p.off_ring);
+  uint16_t* shadow = at<uint16_t>(a, p.off_shadow) + (size_t)slot_next * p.shadow_stride;
+  UpdateArgs u;
+  u.partial = at<float>(a, p.off_partial);
+  u.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
+  u.ldp = (size_t)p.dp[l + 1];
+  u.nsplit = nsplit;
+  u.w_cur = ring + (size_t)slot_cur * p.slot_stride + p.w_off[l];
+  u.w_next = ring + (size_t)slot_next * p.slot_stride + p.w_off[l];
+  u.d_in = p.d[l];
+  u.d_out = p.d[l + 1];
+  u.wn = l >= 1 ? shadow + p.wn_off[l] : nullptr;
+  u.ldwn = (size_t)p.dp[l + 1];
+  u.wt = shadow + p.wt_off[l];
+  u.ldwt = (size_t)p.dp[l];
+  const double n = (double)p.d[l] * p.d[l + 1];
+  hook->begin(KK_MLP_UPDATE, n * (nsplit + 1), n * (4.0 * (nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
+  mlp_update_kernel<<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64), dim3(256), 0, s>>>(u);
+  hook->end(KK_MLP_UPDATE);
+}
+
+template <int EPI, bool GATHER, bool PER_UPLOAD>
+void launch_gemm(const GemmArgs& g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
+  if (Ndim % 128 == 0)
+    mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 128, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+  else
+    mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 64, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+}
+
+}  // namespace
+
+hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s) {
+  const MlpPlan& p = a.plan;
+  // padding of every bf16 weight copy must read as zero
+  const size_t n16 = (size_t)p.R * p.shadow_stride * 2 / 16;
+  mlp_fill_zero_kernel<<<dim3(1024), dim3(256), 0, s>>>(at<uint4>(a, p.off_shadow), n16);
+  NullHook nh;
+  for (int l = 0; l < p.L; ++l) launch_update(a, l, 0, 0, 0, s, &nh);   // bf16 copies of w^0
+  return hipGetLastError();
+}
+
+hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s, LaunchHook* hook) {
+  const MlpPlan& p = a.plan;
+  const int L = p.L, K = rd.K;
+  const int rows = K * p.Bp;                 // stacked rows incl. padding (multiple of 128)
+  const double arows = (double)K * p.B;      // rows that carry samples
+  const size_t Mp = (size_t)p.Mp;
+  float* ring = at<float>(a, p.off_ring);
+  const uint16_t* shadow = at<uint16_t>(a, p.off_shadow);
+  uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
+  int32_t* label = at<int32_t>(a, p.off_label);
+
+  hook->begin(KK_MLP_INDEX, 0, arows * 12.0);
+  mlp_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, a.y, rd, p.B, p.Bp,
+                                                                  a.shard_rows, a.batch_key);
+  hook->end(KK_MLP_INDEX);
+
+  hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
+  mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
+                                                                          at<uint16_t>(a, p.off_xgt), Mp);
+  hook->end(KK_MLP_GATHER_T);
+
+  // ---- forward at the stale model versions
+  for (int l = 0; l < L; ++l) {
+    GemmArgs g{};
+    if (l == 0) { g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
+    else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.dp[l]; }
+    g.Bt = shadow + p.wt_off[l]; g.ldb = (size_t)p.dp[l];
+    g.bt_slot_stride = p.shadow_stride;
+    g.rows_per_upload = p.Bp;
+    g.ksteps_total = g.ksteps_per_split = p.dp[l] / BK;
+    g.bias = ring + p.b_off[l]; g.bias_slot_stride = p.slot_stride; g.n_valid = p.d[l + 1];
+    const double fl = 2.0 * arows * p.d[l] * p.d[l + 1];
+    if (l < L - 1) {
+      g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.dp[l + 1];
+      g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = Mp;
+      const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
+      hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+      if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      else        launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      hook->end(kind);
+    } else {
+      g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
+      hook->begin(KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+      launch_gemm<EPI_LOGITS, false, true>(g, rd, rows, p.dp[L], 1, s);
+      hook->end(KK_MLP_FWD_LOGITS);
+    }
+  }
+
+  // ---- loss and output gradient, already scaled by the uploads' coefficients
+  {
+    hook->begin(KK_MLP_SOFTMAX_CE, arows * p.d[L] * 8.0, arows * p.d[L] * 8.0);
+    const dim3 grid(rows / 64), block(256);
+    const float* Z = at<float>(a, p.off_z);
+    uint16_t* dz = at<uint16_t>(a, p.off_dz[L]);
+    uint16_t* dzt = at<uint16_t>(a, p.off_dzt[L]);
+    float* rl = at<float>(a, p.off_rowloss);
+    const size_t ld = (size_t)p.dp[L];
+    switch (p.dp[L] / 64) {
+      case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+      case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+      default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+    }
+    hook->end(KK_MLP_SOFTMAX_CE);
+  }
+
+  // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
+  for (int l = L - 1; l >= 1; --l) {
+    GemmArgs g{};
+    g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.dp[l + 1];
+    g.Bt = shadow + p.wn_off[l]; g.ldb = (size_t)p.dp[l + 1];
+    g.bt_slot_stride = p.shadow_stride;
+    g.rows_per_upload = p.Bp;
+    g.ksteps_total = g.ksteps_per_split = p.dp[l + 1] / BK;
+    g.mask = at<uint16_t>(a, p.off_h[l]); g.ldmask = (size_t)p.dp[l];
+    g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.dp[l];
+    g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = Mp;
+    hook->begin(KK_MLP_DGRAD, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
+    launch_gemm<EPI_DGRAD, false, true>(g, rd, rows, p.dp[l], 1, s);
+    hook->end(KK_MLP_DGRAD);
+  }
+
+  // ---- weight gradients = K-of-N reduction (one contraction over all stacked rows),
+  //      then update + snapshot per layer
+  for (int l = L - 1; l >= 0; --l) {
+    GemmArgs g{};
+    g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = Mp;
+    g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = Mp;
+    const int ksteps = rows / BK;
+    const int tn = p.dp[l + 1] % 128 == 0 ? 128 : 64;
+    const int tiles = (p.dp[l] / TM) * (p.dp[l + 1] / tn);
+    const int nsplit = pick_split(tiles, ksteps);
+    g.ksteps_total = ksteps;
+    g.ksteps_per_split = (ksteps + nsplit - 1) / nsplit;
+    g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1];
+    g.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
+    const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
+    hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
+                arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
+    launch_gemm<EPI_WGRAD, false, false>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+    hook->end(kind);
+    launch_update(a, l, rd.slot_cur, rd.slot_next, nsplit, s, hook);
+  }
+
+  // ---- biases and the uploads' mean minibatch losses
+  {
+    BiasLossArgs b{};
+    b.L = L;
+    int c = 0;
+    for (int l = 0; l < L; ++l) {
+      b.col_begin[l] = c; c += p.d[l + 1];
+      b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = Mp;
+      b.b_off[l] = p.b_off[l];
+    }
+    b.col_begin[L] = c;
+    b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
+    b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
+    b.rows = rows;
+    b.rowloss = at<float>(a, p.off_rowloss);
+    b.B = p.B; b.Bp = p.Bp; b.K = K;
+    b.loss_out = a.loss_out;
+    hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
+    mlp_bias_loss_kernel<<<dim3((c + K + 3) / 4), dim3(256), 0, s>>>(b);
+    hook->end(KK_MLP_BIAS_LOSS);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace abs_impl

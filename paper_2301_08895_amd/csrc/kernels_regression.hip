@@ -1,0 +1,279 @@
+// Bandwidth-bound rounds: linear least squares and softmax regression (fp32).
+//
+// One round = Eq. 2 (U = 1) for each of the K^t uploads at its own stale model,
+// the K-of-N reduction and update of Eq. 3, and the snapshot write into the ring.
+// Per-upload gradients are never materialised: every row's contribution is scaled
+// by its upload's coefficient c = eta_k / (K^t B) and summed straight into the
+// aggregate.  All reductions have a fixed order (no floating-point atomics), so a
+// round is bitwise reproducible.
+#include <hip/hip_runtime.h>
+#include "kernels.h"
+
+namespace abs_impl {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ uint64_t batch_row(const WorkerDesc& w, uint64_t batch_key,
+                                              uint64_t shard_rows, uint32_t b) {
+  // minibatch draw b of job w.job of worker w.id: uniform over the worker's own shard
+  const uint64_t jk = job_key(batch_key, w.id, w.job);
+  return (uint64_t)w.id * shard_rows + draw(jk, b) % shard_rows;
+}
+
+// ------------------------------------------------------------------ linear least squares
+// One workgroup of 16 wavefronts.  A wavefront owns a contiguous run of the K*B stacked
+// rows; a lane owns features lane, lane+64, ... of x, w and the gradient.  Per row: the
+// residual by a wavefront reduction, then g += c * r * x in registers.  The 16 partial
+// gradients are combined through LDS in wavefront order, followed by w^{t+1} = w^t - G.
+constexpr int kLinWaves = 16;
+
+template <int Q>
+__global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(RegressionArgs a, RoundDesc rd) {
+  __shared__ float s_g[kLinWaves][Q * 64];
+  __shared__ float s_loss[kLinWaves][ABS_MAX_WORKERS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int K = rd.K, d = a.d, B = a.B;
+  const int R = K * B;
+  const float* y = (const float*)a.y;
+  for (int i = threadIdx.x; i < kLinWaves * ABS_MAX_WORKERS; i += blockDim.x) (&s_loss[0][0])[i] = 0.f;
+  __syncthreads();
+
+  float g[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) g[q] = 0.f;
+  const int per = (R + kLinWaves - 1) / kLinWaves;
+  const int r0 = wave * per, r1 = min(R, r0 + per);
+  for (int r = r0; r < r1; ++r) {
+    const int up = r / B;
+    const WorkerDesc w = rd.w[up];
+    const uint64_t row = batch_row(w, a.batch_key, a.shard_rows, (uint32_t)(r - up * B));
+    const float* xr = a.X + row * (uint64_t)d;
+    const float* wv = a.ring + (size_t)w.slot * a.slot_stride;
+    float x[Q];
+    float dot = 0.f;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      const int i = lane + 64 * q;
+      x[q] = i < d ? xr[i] : 0.f;
+      const float wi = i < d ? wv[i] : 0.f;
+      dot = fmaf(x[q], wi, dot);
+    }
+    dot = wave_sum(dot);
+    const float res = dot - y[row];
+    const float coef = w.c * res;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) g[q] = fmaf(coef, x[q], g[q]);
+    if (lane == 0) s_loss[wave][up] += 0.5f * res * res;
+  }
+#pragma unroll
+  for (int q = 0; q < Q; ++q) s_g[wave][lane + 64 * q] = g[q];
+  __syncthreads();
+  const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
+  float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    float G = 0.f;
+#pragma unroll
+    for (int w = 0; w < kLinWaves; ++w) G += s_g[w][i];
+    nxt[i] = cur[i] - G;
+  }
+  for (int up = threadIdx.x; up < K; up += blockDim.x) {
+    float l = 0.f;
+#pragma unroll
+    for (int w = 0; w < kLinWaves; ++w) l += s_loss[w][up];
+    a.loss_out[up] = l / (float)B;
+  }
+}
+
+hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
+                               LaunchHook* hook) {
+  const double rows = (double)rd.K * a.B;
+  hook->begin(KK_LINREG_ROUND, rows * a.d * 4.0, rows * (a.d + 1) * 4.0 + 2.0 * a.d * 4.0);
+  const dim3 grid(1), block(kLinWaves * 64);
+  if (a.d <= 128)       linreg_round_kernel<2><<<grid, block, 0, s>>>(a, rd);
+  else if (a.d <= 256)  linreg_round_kernel<4><<<grid, block, 0, s>>>(a, rd);
+  else                  linreg_round_kernel<8><<<grid, block, 0, s>>>(a, rd);   // d <= 512
+  hook->end(KK_LINREG_ROUND);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ softmax regression
+// Kernel 1 (one wavefront per stacked row): logits of the row at its upload's stale
+// model, softmax cross-entropy, and the row of dZ = c (softmax - onehot).
+// A lane owns float4 chunks lane, lane+64, ... of x; the matching 4 x C block of W is
+// 4C contiguous floats, read as C float4.  Logits are completed by wavefront reductions.
+constexpr int kSoftQF = 4;          // float4 chunks per lane  ->  d <= 1024
+constexpr int kDzPitch = 16;        // floats per dZ row (C <= 16)
+
+template <int C>
+__global__ __launch_bounds__(256) void softmax_rows_kernel(RegressionArgs a, RoundDesc rd) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int B = a.B, d = a.d;
+  if (r >= rd.K * B) return;
+  const int up = r / B;
+  const WorkerDesc w = rd.w[up];
+  const uint64_t row = batch_row(w, a.batch_key, a.shard_rows, (uint32_t)(r - up * B));
+  const float4* xr = (const float4*)(a.X + row * (uint64_t)d);
+  const float* Wv = a.ring + (size_t)w.slot * a.slot_stride;
+  const int nchunk = d >> 2;
+  float acc[C];
+#pragma unroll
+  for (int c = 0; c < C; ++c) acc[c] = 0.f;
+#pragma unroll
+  for (int q = 0; q < kSoftQF; ++q) {
+    const int ch = lane + 64 * q;
+    if (ch < nchunk) {
+      const float4 xv = xr[ch];
+      const float4* wp = (const float4*)(Wv + (size_t)ch * 4 * C);
+      float wf[4 * C];
+#pragma unroll
+      for (int i = 0; i < C; ++i) {
+        const float4 t = wp[i];
+        wf[4 * i + 0] = t.x; wf[4 * i + 1] = t.y; wf[4 * i + 2] = t.z; wf[4 * i + 3] = t.w;
+      }
+#pragma unroll
+      for (int c = 0; c < C; ++c) {
+        acc[c] = fmaf(xv.x, wf[0 * C + c], acc[c]);
+        acc[c] = fmaf(xv.y, wf[1 * C + c], acc[c]);
+        acc[c] = fmaf(xv.z, wf[2 * C + c], acc[c]);
+        acc[c] = fmaf(xv.w, wf[3 * C + c], acc[c]);
+      }
+    }
+  }
+  const float* bias = Wv + (size_t)d * C;
+  float zmax = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    acc[c] = wave_sum(acc[c]) + bias[c];
+    zmax = fmaxf(zmax, acc[c]);
+  }
+  const int label = ((const int32_t*)a.y)[row];
+  float ssum = 0.f, zy = 0.f, mine = 0.f;
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    if (c == label) zy = acc[c] - zmax;
+    acc[c] = expf(acc[c] - zmax);
+    ssum += acc[c];
+  }
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    const float p = acc[c] / ssum;
+    if (c == lane) mine = w.c * (p - (c == label ? 1.f : 0.f));
+  }
+  if (lane < kDzPitch) a.dz[(size_t)r * kDzPitch + lane] = lane < C ? mine : 0.f;
+  if (lane == 0) {
+    // -log softmax_y = log(sum exp(z - zmax)) - (z_y - zmax)
+    a.rowloss[r] = logf(ssum) - zy;
+    a.rowidx[r] = (uint32_t)row;
+  }
+}
+
+// Kernel 2: G = X^T dZ over all K*B stacked rows, sliced by feature, then the update
+// w^{t+1} = w^t - G written into the next ring slot.  A workgroup owns 8 features; its
+// 256 threads are 8 features x 32 row groups; the 32 partial sums are combined through
+// LDS in group order.  The last workgroup reduces the bias gradient and the per-upload
+// losses.
+constexpr int kUpdF = 8, kUpdG = 32;
+
+template <int C>
+__global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
+  __shared__ float s_red[kUpdG][kUpdF * C + 1];
+  const int B = a.B, d = a.d, R = rd.K * B;
+  const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
+  float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
+  const int nslice = (d + kUpdF - 1) / kUpdF;
+  if ((int)blockIdx.x < nslice) {
+    const int f = threadIdx.x % kUpdF, g = threadIdx.x / kUpdF;
+    const int i = blockIdx.x * kUpdF + f;
+    float acc[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) acc[c] = 0.f;
+    if (i < d) {
+      for (int r = g; r < R; r += kUpdG) {
+        const float x = a.X[(uint64_t)a.rowidx[r] * (uint64_t)d + i];
+        const float4* dzp = (const float4*)(a.dz + (size_t)r * kDzPitch);
+        float dzr[16];
+#pragma unroll
+        for (int v = 0; v < (C + 3) / 4; ++v) {
+          const float4 t = dzp[v];
+          dzr[4 * v] = t.x; dzr[4 * v + 1] = t.y; dzr[4 * v + 2] = t.z; dzr[4 * v + 3] = t.w;
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c) acc[c] = fmaf(x, dzr[c], acc[c]);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c) s_red[g][f * C + c] = acc[c];
+    __syncthreads();
+    if ((int)threadIdx.x < kUpdF * C) {
+      const int ff = threadIdx.x / C, c = threadIdx.x % C;
+      const int ii = blockIdx.x * kUpdF + ff;
+      if (ii < d) {
+        float G = 0.f;
+#pragma unroll 8
+        for (int gg = 0; gg < kUpdG; ++gg) G += s_red[gg][threadIdx.x];
+        nxt[(size_t)ii * C + c] = cur[(size_t)ii * C + c] - G;
+      }
+    }
+    return;
+  }
+  // bias gradient: column sums of dZ (16 columns x 16 row groups), then b^{t+1}
+  {
+    const int c = threadIdx.x % 16, g = threadIdx.x / 16;
+    float s = 0.f;
+    for (int r = g; r < R; r += 16) s += a.dz[(size_t)r * kDzPitch + c];
+    float* red = &s_red[0][0];
+    red[g * 16 + c] = s;
+    __syncthreads();
+    if ((int)threadIdx.x < C) {
+      float G = 0.f;
+#pragma unroll
+      for (int gg = 0; gg < 16; ++gg) G += red[gg * 16 + threadIdx.x];
+      nxt[(size_t)d * C + threadIdx.x] = cur[(size_t)d * C + threadIdx.x] - G;
+    }
+  }
+  // per-upload mean minibatch loss (the "average local loss" each worker uploads)
+  {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int up = wave; up < rd.K; up += 4) {
+      float s = 0.f;
+      for (int b = lane; b < B; b += 64) s += a.rowloss[up * B + b];
+      s = wave_sum(s);
+      if (lane == 0) a.loss_out[up] = s / (float)B;
+    }
+  }
+}
+
+template <int C>
+static hipError_t softmax_round_c(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
+                                  LaunchHook* hook) {
+  const int R = rd.K * a.B;
+  const double rows = (double)R;
+  hook->begin(KK_SOFTMAX_ROWS, rows * a.d * C * 2.0, rows * (a.d + 1) * 4.0);
+  softmax_rows_kernel<C><<<dim3((R + 3) / 4), dim3(256), 0, s>>>(a, rd);
+  hook->end(KK_SOFTMAX_ROWS);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int nslice = (a.d + kUpdF - 1) / kUpdF;
+  hook->begin(KK_SOFTMAX_UPDATE, rows * a.d * C * 2.0, 2.0 * (a.d + 1) * C * 4.0);
+  softmax_update_kernel<C><<<dim3(nslice + 1), dim3(256), 0, s>>>(a, rd);
+  hook->end(KK_SOFTMAX_UPDATE);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
+                                LaunchHook* hook) {
+  switch (a.C) {
+#define ABS_CASE(c) case c: return softmax_round_c<c>(a, rd, s, hook);
+    ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
+    ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
+#undef ABS_CASE
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace abs_impl

@@ -1,0 +1,82 @@
+"""GPU parity of the two regression workloads against the CPU oracle (through the C-ABI)."""
+import numpy as np
+import pytest
+
+import workloads
+from parity_util import run_pair, assert_trace_equal, rel_err
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = 1e-5     # relative, stated for the fp32 workloads
+
+
+@pytest.mark.parametrize("over,T", [
+    (dict(), 200),                                              # the workload as specified
+    (dict(dims=[100, 1], N=8, B=32, seed_sim=4001), 200),       # second simulation seed
+    (dict(dims=[37, 1], M=999, N=5, B=7, K0=2, tau_cap=2), 150),   # ragged: odd d, B, shard remainder
+    (dict(dims=[300, 1], M=5000, N=16, B=40, tau_cap=1, tau_mode=1), 100),
+    (dict(dims=[512, 1], M=4000, N=3, B=1, K0=1, sa_penalty=1, lr=1e-3), 60),      # B = 1, SA step
+    (dict(N=128, B=8, M=12800, tau_cap=8, time_dist=1, time_param=1.5), 120),      # N at its maximum
+    (dict(N=1, K0=1, M=500, B=16), 50),                          # a single worker
+])
+def test_linear_least_squares(over, T):
+    p = workloads.scaled_preset(1, **over)
+    res = run_pair(p, T, checkpoints=(1, 10))
+    assert_trace_equal(res, 1e-4)
+    for cp, (g, w) in res["models"].items():
+        assert rel_err(g, w) <= FP32_TOL, (cp, rel_err(g, w))
+    assert np.all(np.isfinite(res["models"][T][0]))
+
+
+@pytest.mark.parametrize("over,T", [
+    (dict(M=6000), 300),                                          # real shape, shorter dataset
+    (dict(M=4000, dims=[52, 3], n_classes=3, N=6, B=10, K0=2, tau_cap=2, lr=5e-3), 200),
+    (dict(M=4000, dims=[1024, 16], n_classes=16, N=4, B=33, lr=2e-4), 60),
+    (dict(M=2000, dims=[8, 2], n_classes=2, N=16, B=5, sa_penalty=1, lr=2e-2), 150),
+])
+def test_softmax_regression(over, T):
+    p = workloads.scaled_preset(2, **over)
+    res = run_pair(p, T, checkpoints=(1, 10))
+    assert_trace_equal(res, 1e-4)
+    for cp, (g, w) in res["models"].items():
+        assert rel_err(g, w) <= FP32_TOL, (cp, rel_err(g, w))
+
+
+def test_softmax_full_workload():
+    p = workloads.preset(2)
+    res = run_pair(p, p["T"])
+    assert_trace_equal(res, 1e-4)
+    g, w = res["models"][p["T"]]
+    assert rel_err(g, w) <= FP32_TOL
+    assert res["got"][-1, 1] == p["N"]          # K has grown to N
+
+
+def test_run_to_run_bitwise_determinism():
+    import paper_2301_08895_amd as lib
+    p = workloads.scaled_preset(2, M=6000)
+    d = workloads.make_inputs(p)
+    outs = []
+    for _ in range(2):
+        sim = lib.Simulation(p, d)
+        sim.round(150)
+        outs.append((sim.model().copy(), sim.trace().copy()))
+        sim.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_get_model_versions_and_errors():
+    import paper_2301_08895_amd as lib
+    p = workloads.preset(1)
+    d = workloads.make_inputs(p)
+    sim = lib.Simulation(p, d)
+    assert np.array_equal(sim.model(0), d["w0"])
+    sim.round(10)
+    R = p["tau_cap"] + 3
+    assert np.array_equal(sim.model(-1), sim.model(10))
+    sim.model(10 - R + 1)
+    with pytest.raises(lib.AbsError) as e:
+        sim.model(10 - R)
+    assert e.value.code == -4
+    with pytest.raises(lib.AbsError):
+        sim.model(11)
+    sim.close()
