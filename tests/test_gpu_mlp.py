@@ -1,0 +1,60 @@
+"""GPU parity of the MLP workloads (bf16 operands, fp32 accumulation) against the CPU
+oracle with its bf16 rounding points switched on, through the C-ABI."""
+import numpy as np
+import pytest
+
+import workloads
+from parity_util import run_pair, assert_trace_equal, rel_err
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 2e-2     # relative, stated for the bf16-input workloads
+
+
+def _check(res, tol=BF16_TOL):
+    assert_trace_equal(res, 2e-3)
+    for cp, (g, w) in res["models"].items():
+        e = rel_err(g, w)
+        print(f"round {cp}: rel err {e:.3e}")
+        assert np.all(np.isfinite(g))
+        assert e <= tol, (cp, e)
+    # the update itself (w^T - w^0) must agree too, not only the weights it is small against
+    T = max(res["models"])
+    g, w = res["models"][T]
+    w0 = res["sim_inputs"]["w0"].astype(np.float64)
+    assert rel_err(g - w0, w - w0) <= tol, rel_err(g - w0, w - w0)
+
+
+@pytest.mark.parametrize("over,T", [
+    # two layers, several row tiles per upload boundary, ragged B, d_0 not a tile multiple
+    (dict(M=4096, dims=[200, 96, 10], N=8, B=40, n_slow=2, lr=1e-3), 40),
+    # three layers, B = one tile, hidden = one and two tiles, 100 classes (128-wide logits)
+    (dict(M=8192, dims=[256, 128, 256, 100], n_classes=100, N=8, B=128, n_slow=0, lr=5e-4), 30),
+    # staleness-aware step, fixed threshold, many restarts
+    (dict(M=4096, dims=[128, 64, 3], n_classes=3, N=16, B=16, n_slow=4, sa_penalty=1,
+          tau_mode=1, tau_cap=1, lr=2e-3), 60),
+    # B > one tile (two row tiles per upload), Pareto times
+    (dict(M=8192, dims=[384, 128, 10], N=4, B=200, n_slow=0, time_dist=1, time_param=1.5, lr=1e-3), 25),
+])
+def test_mlp_small(over, T):
+    p = workloads.scaled_preset(3, **over)
+    _check(run_pair(p, T, checkpoints=(1, 5)))
+
+
+def test_cfg3_shape_prefix():
+    """The 3072-512-10 workload at its real layer and batch shapes (shorter dataset), first rounds."""
+    p = workloads.scaled_preset(3, M=6400)
+    _check(run_pair(p, 12, checkpoints=(1,)))
+
+
+def test_run_to_run_bitwise_determinism():
+    import paper_2301_08895_amd as lib
+    p = workloads.scaled_preset(3, M=4096, dims=[256, 128, 10], N=8, B=64, n_slow=2, lr=1e-3)
+    d = workloads.make_inputs(p)
+    outs = []
+    for _ in range(2):
+        sim = lib.Simulation(p, d)
+        sim.round(30)
+        outs.append((sim.model().copy(), sim.trace().copy()))
+        sim.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
