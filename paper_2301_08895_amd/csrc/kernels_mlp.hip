@@ -123,20 +123,34 @@ struct GemmArgs {
   uint16_t* outT; size_t ldoT;        // bf16 [Ndim][ldoT]  (may be null)
   float* outf;    size_t ldof;        // fp32 [Mdim][ldof]; EPI_WGRAD: + z * split_stride
   size_t split_stride;
-  const uint16_t* mask; size_t ldmask;   // EPI_DGRAD: H_l, gradient passes where H_l > 0
+  const uint16_t* maskT; size_t ldmaskT; // EPI_DGRAD: H_l^T [Ndim][ldmaskT]; the gradient passes where H_l > 0
 };
 
 // 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
-// 32x32x16 MFMA blocks.  A and B tiles of BK = 64 are staged in LDS, double buffered,
-// 16-byte chunks XOR-swizzled by row so that both the row-major stores and the
-// column-of-rows fragment loads spread over all banks.
+// 32x32x16 MFMA blocks (TN = 256: 2 x 4 blocks, 128 accumulator registers).  A and B
+// tiles of BK = 64 are staged in LDS (one stage; the next tile's global loads are in
+// flight in registers while the current one is multiplied, and two workgroups per CU
+// cover each other's barriers).  16-byte chunks are XOR-swizzled by row so that both the
+// row-major stores and the column-of-rows fragment loads spread over all banks.
+template <int TN>
+struct GemmCfg {
+  static constexpr int WN = TN / 2;            // columns per wavefront
+  static constexpr int NI = WN / 32;           // MFMA blocks along n per wavefront
+  static constexpr int BCH = TN / 32;          // 16-byte chunks of the B tile per thread
+  static constexpr int kMainElems = (TM + TN) * BK;
+  static constexpr int kEpiPitch = 64 + 8;     // transposed staging: [WN][64 + 8] per wavefront
+  static constexpr int kEpiElems = 4 * WN * kEpiPitch;
+};
+
 template <int TN, int EPI, bool GATHER, bool PER_UPLOAD>
-__global__ __launch_bounds__(256) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
-  constexpr int WN = TN / 2;          // columns per wavefront
-  constexpr int NI = WN / 32;         // MFMA blocks along n per wavefront
-  constexpr int BCH = TN * 8 / 256;   // 16-byte chunks of the B tile per thread
-  __shared__ __attribute__((aligned(16))) uint16_t sA[2][TM * BK];
-  __shared__ __attribute__((aligned(16))) uint16_t sB[2][TN * BK];
+__global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
+  using Cfg = GemmCfg<TN>;
+  constexpr int WN = Cfg::WN, NI = Cfg::NI, BCH = Cfg::BCH;
+  constexpr bool kStageT = (EPI == EPI_RELU || EPI == EPI_DGRAD);
+  constexpr int kSmem = kStageT && Cfg::kEpiElems > Cfg::kMainElems ? Cfg::kEpiElems : Cfg::kMainElems;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem];
+  uint16_t* const sA = smem;
+  uint16_t* const sB = smem + TM * BK;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -151,22 +165,22 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd)
     Bt += (size_t)slot * g.bt_slot_stride;
   }
 
-  // per-thread source pointers of the chunks this thread stages
-  const uint16_t* pa[4];
-  int ca[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int q = t + 256 * i, r = q >> 3, c = q & 7;
-    const size_t row = GATHER ? (size_t)g.a_rowidx[m0 + r] : (size_t)(m0 + r);
-    pa[i] = g.A + row * g.lda + c * 8;
-    ca[i] = c * 8;
+  // staging: thread t moves chunk (row r0 + 32 i, 16-byte column c) of each tile
+  const int r0 = t >> 3, c8 = (t & 7) * 8;
+  const int st_off = r0 * BK + (((t & 7) ^ (r0 & 7)) << 3);     // swizzled LDS offset of chunk i = 0
+  const uint16_t* pa0; const uint16_t* pa1; const uint16_t* pa2; const uint16_t* pa3;
+  if (GATHER) {
+    pa0 = g.A + (size_t)g.a_rowidx[m0 + r0] * g.lda + c8;
+    pa1 = g.A + (size_t)g.a_rowidx[m0 + r0 + 32] * g.lda + c8;
+    pa2 = g.A + (size_t)g.a_rowidx[m0 + r0 + 64] * g.lda + c8;
+    pa3 = g.A + (size_t)g.a_rowidx[m0 + r0 + 96] * g.lda + c8;
+  } else {
+    pa0 = g.A + (size_t)(m0 + r0) * g.lda + c8;
+    pa1 = pa0 + 32 * g.lda; pa2 = pa0 + 64 * g.lda; pa3 = pa0 + 96 * g.lda;
   }
-  const uint16_t* pb[BCH];
-#pragma unroll
-  for (int i = 0; i < BCH; ++i) {
-    const int q = t + 256 * i, r = q >> 3, c = q & 7;
-    pb[i] = Bt + (size_t)(n0 + r) * g.ldb + c * 8;
-  }
+  const uint16_t* pb0 = Bt + (size_t)(n0 + r0) * g.ldb + c8;
+  const size_t b_step = 32 * g.ldb;
+  const bool a_ok = !GATHER || c8 < g.a_kvalid;       // refined per k-step below
 
   f32x16_t acc[2][NI];
 #pragma unroll
@@ -176,63 +190,63 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-  uint4 ra[4], rb[BCH];
-  auto fetch = [&](int ks) {
-    const int k0 = ks * BK;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (GATHER && k0 + ca[i] >= g.a_kvalid) ra[i] = make_uint4(0, 0, 0, 0);
-      else ra[i] = *(const uint4*)(pa[i] + k0);
-    }
-#pragma unroll
-    for (int i = 0; i < BCH; ++i) rb[i] = *(const uint4*)(pb[i] + k0);
-  };
-  auto stage = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int q = t + 256 * i, r = q >> 3, c = q & 7;
-      *(uint4*)&sA[buf][r * BK + ((c ^ (r & 7)) << 3)] = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < BCH; ++i) {
-      const int q = t + 256 * i, r = q >> 3, c = q & 7;
-      *(uint4*)&sB[buf][r * BK + ((c ^ (r & 7)) << 3)] = rb[i];
-    }
-  };
+  uint4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3, rb4, rb5, rb6, rb7;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  rb2 = rb3 = rb4 = rb5 = rb6 = rb7 = zero4;
+#define ABS_FETCH(ks)                                                                     \
+  {                                                                                       \
+    const int k0_ = (ks) * BK;                                                            \
+    if (GATHER && (!a_ok || k0_ + c8 >= g.a_kvalid)) {                                    \
+      ra0 = zero4; ra1 = zero4; ra2 = zero4; ra3 = zero4;                                 \
+    } else {                                                                              \
+      ra0 = *(const uint4*)(pa0 + k0_); ra1 = *(const uint4*)(pa1 + k0_);                 \
+      ra2 = *(const uint4*)(pa2 + k0_); ra3 = *(const uint4*)(pa3 + k0_);                 \
+    }                                                                                     \
+    const uint16_t* pb_ = pb0 + k0_;                                                      \
+    rb0 = *(const uint4*)(pb_); rb1 = *(const uint4*)(pb_ + b_step);                      \
+    if (BCH > 2) { rb2 = *(const uint4*)(pb_ + 2 * b_step); rb3 = *(const uint4*)(pb_ + 3 * b_step); } \
+    if (BCH > 4) { rb4 = *(const uint4*)(pb_ + 4 * b_step); rb5 = *(const uint4*)(pb_ + 5 * b_step);   \
+                   rb6 = *(const uint4*)(pb_ + 6 * b_step); rb7 = *(const uint4*)(pb_ + 7 * b_step); } \
+  }
+#define ABS_STAGE()                                                                       \
+  {                                                                                       \
+    *(uint4*)&sA[st_off] = ra0;            *(uint4*)&sA[st_off + 32 * BK] = ra1;          \
+    *(uint4*)&sA[st_off + 64 * BK] = ra2;  *(uint4*)&sA[st_off + 96 * BK] = ra3;          \
+    *(uint4*)&sB[st_off] = rb0;            *(uint4*)&sB[st_off + 32 * BK] = rb1;          \
+    if (BCH > 2) { *(uint4*)&sB[st_off + 64 * BK] = rb2; *(uint4*)&sB[st_off + 96 * BK] = rb3; }   \
+    if (BCH > 4) { *(uint4*)&sB[st_off + 128 * BK] = rb4; *(uint4*)&sB[st_off + 160 * BK] = rb5;   \
+                   *(uint4*)&sB[st_off + 192 * BK] = rb6; *(uint4*)&sB[st_off + 224 * BK] = rb7; } \
+  }
 
+  const int lr = lane & 31, lk = lane >> 5;
+  const int fa_row = (wm * 64 + lr) * BK, fb_row = (wn * WN + lr) * BK;
+  const int sw = lr & 7;
   if (ks0 < ks1) {
-    fetch(ks0);
-    stage(0);
-    __syncthreads();
-    int buf = 0;
-    const int lr = lane & 31, lk = lane >> 5;
+    ABS_FETCH(ks0);
     for (int ks = ks0; ks < ks1; ++ks) {
-      const bool more = ks + 1 < ks1;
-      if (more) fetch(ks + 1);
+      ABS_STAGE();
+      __syncthreads();
+      if (ks + 1 < ks1) ABS_FETCH(ks + 1);
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
+        const int ch = (((s << 1) | lk) ^ sw) << 3;
         bf16x8_t fa[2], fb[NI];
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-          const int r = wm * 64 + mi * 32 + lr;
-          fa[mi] = *(const bf16x8_t*)&sA[buf][r * BK + (((s * 2 + lk) ^ (r & 7)) << 3)];
-        }
+        for (int mi = 0; mi < 2; ++mi) fa[mi] = *(const bf16x8_t*)&sA[fa_row + mi * 32 * BK + ch];
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-          const int r = wn * WN + ni * 32 + lr;
-          fb[ni] = *(const bf16x8_t*)&sB[buf][r * BK + (((s * 2 + lk) ^ (r & 7)) << 3)];
-        }
+        for (int ni = 0; ni < NI; ++ni) fb[ni] = *(const bf16x8_t*)&sB[fb_row + ni * 32 * BK + ch];
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
           for (int ni = 0; ni < NI; ++ni)
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
       }
-      if (more) stage(buf ^ 1);
       __syncthreads();
-      buf ^= 1;
     }
   }
+
+#undef ABS_FETCH
+#undef ABS_STAGE
 
   // ---- epilogue.  Accumulator register r of lane l holds C[8 (r/4) + 4 (l/32) + r%4][l%32]
   // of its 32 x 32 block.
@@ -241,17 +255,22 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd)
   if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
   float* outf = g.outf;
   if (EPI == EPI_WGRAD) outf += (size_t)blockIdx.z * g.split_stride;
+  uint16_t* const sE = smem + wave * (WN * Cfg::kEpiPitch);     // this wavefront's [WN][72] staging
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-      const int n = n0 + wn * WN + ni * 32 + lcol;
+      const int nl = ni * 32 + lcol;
+      const int n = n0 + wn * WN + nl;
       float bv = 0.f;
       if (EPI == EPI_RELU || EPI == EPI_LOGITS) bv = n < g.n_valid ? bias[n] : 0.f;
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
-        const int mbase = m0 + wm * 64 + mi * 32 + rg * 8 + lrow4;
+        const int ml = mi * 32 + rg * 8 + lrow4;
+        const int mbase = m0 + wm * 64 + ml;
         uint16_t h[4];
+        uint2 hm = make_uint2(0, 0);     // H_l of the 4 consecutive rows this lane holds
+        if (EPI == EPI_DGRAD) hm = *(const uint2*)(g.maskT + (size_t)n * g.ldmaskT + mbase);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           const int m = mbase + rr;
@@ -262,23 +281,34 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd)
             v += bv;
             outf[(size_t)m * g.ldof + n] = v;
           } else if (EPI == EPI_DGRAD) {
-            const uint16_t hm = g.mask[(size_t)m * g.ldmask + n];
-            v = (hm & 0x7FFFu) ? v : 0.f;
+            const uint32_t pair = rr < 2 ? hm.x : hm.y;
+            v = ((pair >> ((rr & 1) * 16)) & 0x7FFFu) ? v : 0.f;
           } else {
             outf[(size_t)m * g.ldof + n] = v;
           }
-          if (EPI == EPI_RELU || EPI == EPI_DGRAD) {
+          if (kStageT) {
             h[rr] = f32_to_bf16(v);
             if (g.out) g.out[(size_t)m * g.ldo + n] = h[rr];
           }
         }
-        if ((EPI == EPI_RELU || EPI == EPI_DGRAD) && g.outT) {
+        if (kStageT) {
           uint2 o;
           o.x = h[0] | ((uint32_t)h[1] << 16);
           o.y = h[2] | ((uint32_t)h[3] << 16);
-          *(uint2*)(g.outT + (size_t)n * g.ldoT + mbase) = o;
+          *(uint2*)&sE[nl * Cfg::kEpiPitch + ml] = o;
         }
       }
+    }
+  }
+  if (kStageT) {
+    // transposed copy: each staged row is 64 consecutive m of one n -> 16-byte stores
+    __syncthreads();
+    const int mrow = m0 + wm * 64;
+#pragma unroll
+    for (int i = 0; i < WN / 8; ++i) {
+      const int q = lane + 64 * i, nl = q >> 3, ch = (q & 7) * 8;
+      const uint4 v = *(const uint4*)&sE[nl * Cfg::kEpiPitch + ch];
+      *(uint4*)(g.outT + (size_t)(n0 + wn * WN + nl) * g.ldoT + mrow + ch) = v;
     }
   }
 }
@@ -525,7 +555,9 @@ void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_nex
 
 template <int EPI, bool GATHER, bool PER_UPLOAD>
 void launch_gemm(const GemmArgs& g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
-  if (Ndim % 128 == 0)
+  if (Ndim % 256 == 0)
+    mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 256, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+  else if (Ndim % 128 == 0)
     mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 128, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
   else
     mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 64, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
@@ -616,7 +648,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     g.bt_slot_stride = p.shadow_stride;
     g.rows_per_upload = p.Bp;
     g.ksteps_total = g.ksteps_per_split = p.dp[l + 1] / BK;
-    g.mask = at<uint16_t>(a, p.off_h[l]); g.ldmask = (size_t)p.dp[l];
+    g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = Mp;
     g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.dp[l];
     g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = Mp;
     hook->begin(KK_MLP_DGRAD, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
@@ -631,7 +663,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = Mp;
     g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = Mp;
     const int ksteps = rows / BK;
-    const int tn = p.dp[l + 1] % 128 == 0 ? 128 : 64;
+    const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
     const int tiles = (p.dp[l] / TM) * (p.dp[l + 1] / tn);
     const int nsplit = pick_split(tiles, ksteps);
     g.ksteps_total = ksteps;
