@@ -29,7 +29,7 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 MFMA_KINDS = {"mlp_fwd_l1", "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad"}
 
 # default (warmup, steps) per workload: short enough for a default run of about a minute
-DEFAULT_STEPS = {1: (20, 180), 2: (200, 1800), 3: (200, 1800), 4: (200, 1500), 5: (100, 600)}
+DEFAULT_STEPS = {1: (20, 180), 2: (200, 1800), 3: (200, 1800), 4: (200, 4800), 5: (100, 4900)}
 
 
 def cpu_baseline(p, inputs, budget_s: float):
@@ -119,7 +119,11 @@ def main():
             roofline = dict(bound="hbm", kernel=dom["name"], achieved=ach, peak=PEAK_HBM_GBS,
                             unit="GB/s", frac=ach / PEAK_HBM_GBS, traffic=None,
                             avg_launch_us=avg_s * 1e6, launches=dom["launches"])
-    kernel_ms = {k["name"]: round(k["ms"], 3) for k in sorted(kern, key=lambda k: -k["ms"])}
+    kernels = [dict(name=k["name"], launches=k["launches"], total_ms=round(k["ms"], 3),
+                    avg_us=round(k["ms"] / k["launches"] * 1e3, 2),
+                    tflops=round(k["flops"] / k["ms"] / 1e9, 1) if k["ms"] > 0 else None,
+                    gbs=round(k["bytes"] / k["ms"] / 1e6, 1) if k["ms"] > 0 else None)
+               for k in sorted(kern, key=lambda k: -k["ms"])]
 
     cpu = cpu_baseline(p, inputs, args.cpu_budget) if args.cpu_budget > 0 else None
 
@@ -141,7 +145,7 @@ def main():
                    "K_first": int(tr[0, 1]), "K_last": int(tr[-1, 1])},
         "samples_per_sec": value * p["B"],
         "rounds_per_sec": steps / elapsed,
-        "kernel_ms": kernel_ms,
+        "kernels": kernels,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

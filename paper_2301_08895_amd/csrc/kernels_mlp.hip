@@ -142,7 +142,8 @@ struct GemmCfg {
   static constexpr int kEpiElems = 4 * WN * kEpiPitch;
 };
 
-template <int TN, int EPI, bool GATHER, bool PER_UPLOAD>
+// TAG only separates kernel symbols (first layer / other layers) for profilers.
+template <int TN, int EPI, bool GATHER, bool PER_UPLOAD, int TAG>
 __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
   using Cfg = GemmCfg<TN>;
   constexpr int WN = Cfg::WN, NI = Cfg::NI, BCH = Cfg::BCH;
@@ -553,14 +554,14 @@ void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_nex
   hook->end(KK_MLP_UPDATE);
 }
 
-template <int EPI, bool GATHER, bool PER_UPLOAD>
+template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
 void launch_gemm(const GemmArgs& g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   if (Ndim % 256 == 0)
-    mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 256, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+    mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<dim3(Ndim / 256, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
   else if (Ndim % 128 == 0)
-    mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 128, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+    mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<dim3(Ndim / 128, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
   else
-    mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD><<<dim3(Ndim / 64, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+    mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<dim3(Ndim / 64, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
 }
 
 }  // namespace
@@ -673,7 +674,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
     hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
                 arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
-    launch_gemm<EPI_WGRAD, false, false>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+    if (l == 0) launch_gemm<EPI_WGRAD, false, false, 1>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+    else        launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
     hook->end(kind);
     launch_update(a, l, rd.slot_cur, rd.slot_next, nsplit, s, hook);
   }
