@@ -130,8 +130,9 @@ struct GemmArgs {
 // 32x32x16 MFMA blocks (TN = 256: 2 x 4 blocks, 128 accumulator registers).  A and B
 // tiles of BK = 64 are staged in LDS (one stage; the next tile's global loads are in
 // flight in registers while the current one is multiplied, and two workgroups per CU
-// cover each other's barriers).  16-byte chunks are XOR-swizzled by row so that both the
-// row-major stores and the column-of-rows fragment loads spread over all banks.
+// cover each other's barriers).  A tile row is 128 bytes; its 16-byte chunk c is stored at
+// position c ^ ((row >> 1) & 7): the 16 lanes that one cycle of a 128-bit LDS read serves
+// (16 consecutive rows of a fragment) then cover all 64 banks.
 template <int TN>
 struct GemmCfg {
   static constexpr int WN = TN / 2;            // columns per wavefront
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 
   // staging: thread t moves chunk (row r0 + 32 i, 16-byte column c) of each tile
   const int r0 = t >> 3, c8 = (t & 7) * 8;
-  const int st_off = r0 * BK + (((t & 7) ^ (r0 & 7)) << 3);     // swizzled LDS offset of chunk i = 0
+  const int st_off = r0 * BK + (((t & 7) ^ ((r0 >> 1) & 7)) << 3);   // swizzled LDS offset of chunk i = 0
   const uint16_t* pa0; const uint16_t* pa1; const uint16_t* pa2; const uint16_t* pa3;
   if (GATHER) {
     pa0 = g.A + (size_t)g.a_rowidx[m0 + r0] * g.lda + c8;
@@ -221,27 +222,46 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 
   const int lr = lane & 31, lk = lane >> 5;
   const int fa_row = (wm * 64 + lr) * BK, fb_row = (wn * WN + lr) * BK;
-  const int sw = lr & 7;
+  const int sw = (lr >> 1) & 7;
   if (ks0 < ks1) {
     ABS_FETCH(ks0);
     for (int ks = ks0; ks < ks1; ++ks) {
       ABS_STAGE();
       __syncthreads();
       if (ks + 1 < ks1) ABS_FETCH(ks + 1);
+      // fragments of sub-step s+1 are read while the MFMAs of sub-step s run
+      bf16x8_t fa[2][2], fb[2][NI];
+#define ABS_FRAGS(set, s_)                                                                        \
+  {                                                                                               \
+    const int ch_ = ((((s_) << 1) | lk) ^ sw) << 3;                                               \
+    _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                                              \
+      fa[set][mi] = *(const bf16x8_t*)&sA[fa_row + mi * 32 * BK + ch_];                           \
+    _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                             \
+      fb[set][ni] = *(const bf16x8_t*)&sB[fb_row + ni * 32 * BK + ch_];                           \
+  }
+      ABS_FRAGS(0, 0);
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const int ch = (((s << 1) | lk) ^ sw) << 3;
-        bf16x8_t fa[2], fb[NI];
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) fa[mi] = *(const bf16x8_t*)&sA[fa_row + mi * 32 * BK + ch];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) fb[ni] = *(const bf16x8_t*)&sB[fb_row + ni * 32 * BK + ch];
+        if (s < 3) ABS_FRAGS((s + 1) & 1, s + 1);
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
           for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][mi], fb[s & 1][ni], acc[mi][ni], 0, 0, 0);
       }
+#undef ABS_FRAGS
+      // pin the interleaving: first fragment set, then one LDS read behind each MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 + NI, 0);
+#pragma unroll
+      for (int s = 0; s < 3; ++s) {
+#pragma unroll
+        for (int i = 0; i < 2 + NI; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        if (2 * NI > 2 + NI) __builtin_amdgcn_sched_group_barrier(0x008, 2 * NI - (2 + NI), 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NI, 0);
       __syncthreads();
     }
   }
