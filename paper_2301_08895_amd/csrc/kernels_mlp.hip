@@ -123,6 +123,7 @@ struct GemmArgs {
   uint16_t* outT; size_t ldoT;        // bf16 [Ndim][ldoT]  (may be null)
   float* outf;    size_t ldof;        // fp32 [Mdim][ldof]; EPI_WGRAD: + z * split_stride
   size_t split_stride;
+  int mt, nt, nsplit, rows_per_xcd;   // tile grid (see the block -> tile mapping in the kernel)
   const uint16_t* maskT; size_t ldmaskT; // EPI_DGRAD: H_l^T [Ndim][ldmaskT]; the gradient passes where H_l > 0
 };
 
@@ -156,8 +157,17 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
-  const int ks0 = blockIdx.z * g.ksteps_per_split;
+  // Block -> tile mapping.  Workgroups are handed to the 8 XCDs round-robin and every XCD has
+  // its own L2, so block b works for XCD b % 8.  The (split, row-tile) pairs are cut into 8
+  // contiguous ranges, one per XCD, and inside a range consecutive blocks sweep the column
+  // tiles of one row tile: the blocks resident on an XCD then share their A rows (and, for
+  // neighbouring row tiles of the same upload, their B rows) through that XCD's L2.
+  const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
+  const int trow = xcd * g.rows_per_xcd + jx / g.nt;
+  if (trow >= g.mt * g.nsplit) return;
+  const int zsplit = trow / g.mt;
+  const int m0 = (trow - zsplit * g.mt) * TM, n0 = (jx % g.nt) * TN;
+  const int ks0 = zsplit * g.ksteps_per_split;
   const int ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
 
   const uint16_t* Bt = g.Bt;
@@ -275,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
   const float* bias = nullptr;
   if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
   float* outf = g.outf;
-  if (EPI == EPI_WGRAD) outf += (size_t)blockIdx.z * g.split_stride;
+  if (EPI == EPI_WGRAD) outf += (size_t)zsplit * g.split_stride;
   uint16_t* const sE = smem + wave * (WN * Cfg::kEpiPitch);     // this wavefront's [WN][72] staging
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi) {
@@ -330,6 +340,204 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
       const int q = lane + 64 * i, nl = q >> 3, ch = (q & 7) * 8;
       const uint4 v = *(const uint4*)&sE[nl * Cfg::kEpiPitch + ch];
       *(uint4*)(g.outT + (size_t)(n0 + wn * WN + nl) * g.ldoT + mrow + ch) = v;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ the large-tile GEMM
+// 256 x 256 tile, 512 threads = 2 x 4 wavefronts of 128 x 64 (4 x 2 MFMA blocks, 128
+// accumulator registers), BK = 64.  On gfx950 the LDS accepts about 64 B/clk of writes
+// against 256 B/clk of reads and the L1 delivers 64 B/clk, so what bounds a bf16 GEMM
+// tile is the bytes staged per flop: a 256 x 256 tile stages 64 KB per 8.4 MFLOP, two
+// thirds of what the 128 x 256 tile needs.  Tiles go from global memory straight into
+// LDS (global_load_lds_dwordx4: lane l of a wavefront fills bytes [16 l, 16 l + 16) of a
+// 1 KB LDS block, i.e. 8 rows of 128 B), two stages, so the loads of step k+1 are in
+// flight during all of step k and there is one barrier per step.  The XOR swizzle is
+// applied on the global side: the lane that fills chunk position p of row r fetches
+// logical chunk p ^ ((r >> 1) & 7).
+// Needs: row count and column count multiples of 256, GATHER with d_0 % 64 == 0.
+constexpr int TM3 = 256, TN3 = 256;
+constexpr int kStage3 = (TM3 + TN3) * BK;            // elements per LDS stage (64 KB)
+constexpr int kEpiPitch3 = 128 + 8;                  // transposed staging [64 n][128 m + 8] per wavefront
+constexpr int kSmem3 = 8 * 64 * kEpiPitch3;          // 139264 B >= 2 stages (131072 B)
+
+__device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_block) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
+}
+
+template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG>
+__global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDesc rd) {
+  constexpr bool kStageT = (EPI == EPI_RELU || EPI == EPI_DGRAD);
+  __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem3];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
+  const int trow = xcd * g.rows_per_xcd + jx / g.nt;
+  if (trow >= g.mt * g.nsplit) return;
+  const int zsplit = trow / g.mt;
+  const int m0 = (trow - zsplit * g.mt) * TM3, n0 = (jx % g.nt) * TN3;
+  const int ks0 = zsplit * g.ksteps_per_split;
+  const int ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
+
+  const uint16_t* Bt = g.Bt;
+  uint32_t slot = 0;
+  if (PER_UPLOAD) {
+    slot = rd.w[m0 / g.rows_per_upload].slot;
+    Bt += (size_t)slot * g.bt_slot_stride;
+  }
+
+  // DMA assignment: wavefront w, instruction i fills rows (4 w + i) 8 .. + 8 of a tile;
+  // lane l handles row + (l >> 3), chunk position l & 7.
+  const int dr = wave * 32 + (lane >> 3);                  // row for i = 0; + 8 i
+  const int pc = lane & 7;
+  const int c_even = (pc ^ (((lane >> 4)) & 7)) * 8;        // (r >> 1) & 7 for i even
+  const int c_odd = (pc ^ ((4 + (lane >> 4)) & 7)) * 8;     //               for i odd
+  const uint16_t *pa0, *pa1, *pa2, *pa3;
+  if (GATHER) {
+    pa0 = g.A + (size_t)g.a_rowidx[m0 + dr] * g.lda + c_even;
+    pa1 = g.A + (size_t)g.a_rowidx[m0 + dr + 8] * g.lda + c_odd;
+    pa2 = g.A + (size_t)g.a_rowidx[m0 + dr + 16] * g.lda + c_even;
+    pa3 = g.A + (size_t)g.a_rowidx[m0 + dr + 24] * g.lda + c_odd;
+  } else {
+    const uint16_t* base = g.A + (size_t)(m0 + dr) * g.lda;
+    pa0 = base + c_even; pa1 = base + 8 * g.lda + c_odd;
+    pa2 = base + 16 * g.lda + c_even; pa3 = base + 24 * g.lda + c_odd;
+  }
+  const uint16_t* bbase = Bt + (size_t)(n0 + dr) * g.ldb;
+  const uint16_t* pb0 = bbase + c_even;
+  const uint16_t* pb1 = bbase + 8 * g.ldb + c_odd;
+  const uint16_t* pb2 = bbase + 16 * g.ldb + c_even;
+  const uint16_t* pb3 = bbase + 24 * g.ldb + c_odd;
+  uint16_t* const dmaA = smem + wave * 4 * 512;              // 512 elements = 1 KB per instruction
+  uint16_t* const dmaB = smem + TM3 * BK + wave * 4 * 512;
+
+#define ABS_DMA(ks, stage)                                                        \
+  {                                                                               \
+    const int k0_ = (ks) * BK;                                                    \
+    uint16_t* a_ = dmaA + (stage) * kStage3;                                      \
+    uint16_t* b_ = dmaB + (stage) * kStage3;                                      \
+    lds_dma16(pa0 + k0_, a_);        lds_dma16(pa1 + k0_, a_ + 512);              \
+    lds_dma16(pa2 + k0_, a_ + 1024); lds_dma16(pa3 + k0_, a_ + 1536);             \
+    lds_dma16(pb0 + k0_, b_);        lds_dma16(pb1 + k0_, b_ + 512);              \
+    lds_dma16(pb2 + k0_, b_ + 1024); lds_dma16(pb3 + k0_, b_ + 1536);             \
+  }
+
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  const int lr = lane & 31, lk = lane >> 5;
+  const int fa_row = (wm * 128 + lr) * BK, fb_row = TM3 * BK + (wn * 64 + lr) * BK;
+  const int sw = (lr >> 1) & 7;
+  if (ks0 < ks1) {
+    ABS_DMA(ks0, 0);
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const int stage = (ks - ks0) & 1;
+      __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's part of tile ks is in LDS
+      __syncthreads();                         // ... and everybody's; everybody is done with tile ks-1
+      if (ks + 1 < ks1) ABS_DMA(ks + 1, stage ^ 1);
+      const uint16_t* sS = smem + stage * kStage3;
+      bf16x8_t fa[2][4], fb[2][2];
+#define ABS_FRAGS(set, s_)                                                                        \
+  {                                                                                               \
+    const int ch_ = ((((s_) << 1) | lk) ^ sw) << 3;                                               \
+    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                              \
+      fa[set][mi] = *(const bf16x8_t*)&sS[fa_row + mi * 32 * BK + ch_];                           \
+    _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                              \
+      fb[set][ni] = *(const bf16x8_t*)&sS[fb_row + ni * 32 * BK + ch_];                           \
+  }
+      ABS_FRAGS(0, 0);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (s < 3) ABS_FRAGS((s + 1) & 1, s + 1);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][mi], fb[s & 1][ni], acc[mi][ni], 0, 0, 0);
+      }
+#undef ABS_FRAGS
+      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+      for (int s = 0; s < 3; ++s) {
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
+  }
+#undef ABS_DMA
+  __syncthreads();      // all fragment reads done before the staging area is reused
+
+  // ---- epilogue (accumulator layout as in the 128-row kernel)
+  const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
+  const float* bias = nullptr;
+  if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
+  float* outf = g.outf;
+  if (EPI == EPI_WGRAD) outf += (size_t)zsplit * g.split_stride;
+  uint16_t* const sE = smem + wave * (64 * kEpiPitch3);
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+      const int nl = ni * 32 + lcol;
+      const int n = n0 + wn * 64 + nl;
+      float bv = 0.f;
+      if (EPI == EPI_RELU || EPI == EPI_LOGITS) bv = n < g.n_valid ? bias[n] : 0.f;
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int ml = mi * 32 + rg * 8 + lrow4;
+        const int mbase = m0 + wm * 128 + ml;
+        uint16_t h[4];
+        uint2 hm = make_uint2(0, 0);
+        if (EPI == EPI_DGRAD) hm = *(const uint2*)(g.maskT + (size_t)n * g.ldmaskT + mbase);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int m = mbase + rr;
+          float v = acc[mi][ni][rg * 4 + rr];
+          if (EPI == EPI_RELU) {
+            v = fmaxf(v + bv, 0.f);
+          } else if (EPI == EPI_LOGITS) {
+            v += bv;
+            outf[(size_t)m * g.ldof + n] = v;
+          } else if (EPI == EPI_DGRAD) {
+            const uint32_t pair = rr < 2 ? hm.x : hm.y;
+            v = ((pair >> ((rr & 1) * 16)) & 0x7FFFu) ? v : 0.f;
+          } else {
+            outf[(size_t)m * g.ldof + n] = v;
+          }
+          if (kStageT) {
+            h[rr] = f32_to_bf16(v);
+            if (g.out) g.out[(size_t)m * g.ldo + n] = h[rr];
+          }
+        }
+        if (kStageT) {
+          uint2 o;
+          o.x = h[0] | ((uint32_t)h[1] << 16);
+          o.y = h[2] | ((uint32_t)h[3] << 16);
+          *(uint2*)&sE[nl * kEpiPitch3 + ml] = o;
+        }
+      }
+    }
+  }
+  if (kStageT) {
+    __syncthreads();
+    const int mrow = m0 + wm * 128;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int q = lane + 64 * i, nl = q >> 4, ch = (q & 15) * 8;
+      const uint4 v = *(const uint4*)&sE[nl * kEpiPitch3 + ch];
+      *(uint4*)(g.outT + (size_t)(n0 + wn * 64 + nl) * g.ldoT + mrow + ch) = v;
     }
   }
 }
@@ -575,13 +783,26 @@ void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_nex
 }
 
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
-void launch_gemm(const GemmArgs& g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
-  if (Ndim % 256 == 0)
-    mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<dim3(Ndim / 256, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
-  else if (Ndim % 128 == 0)
-    mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<dim3(Ndim / 128, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
-  else
-    mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<dim3(Ndim / 64, Mdim / TM, nsplit), dim3(256), 0, s>>>(g, rd);
+void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
+  g.nsplit = nsplit;
+  const bool big = Mdim % TM3 == 0 && Ndim % TN3 == 0 && (!PER_UPLOAD || g.rows_per_upload % TM3 == 0) &&
+                   (!GATHER || g.a_kvalid % BK == 0);
+  if (big) {
+    g.mt = Mdim / TM3;
+    g.nt = Ndim / TN3;
+    g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
+    mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd);
+    return;
+  }
+  const int tn = Ndim % 256 == 0 ? 256 : Ndim % 128 == 0 ? 128 : 64;
+  g.mt = Mdim / TM;
+  g.nt = Ndim / tn;
+  g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
+  const dim3 block(256);
+  const dim3 grid1(8 * g.rows_per_xcd * g.nt, 1, 1);
+  if (tn == 256)      mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
+  else if (tn == 128) mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
+  else                mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
 }
 
 }  // namespace
@@ -685,7 +906,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = Mp;
     const int ksteps = rows / BK;
     const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
-    const int tiles = (p.dp[l] / TM) * (p.dp[l + 1] / tn);
+    const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
+    const int tiles = big ? (p.dp[l] / TM3) * (p.dp[l + 1] / TN3) : (p.dp[l] / TM) * (p.dp[l + 1] / tn);
     const int nsplit = pick_split(tiles, ksteps);
     g.ksteps_total = ksteps;
     g.ksteps_per_split = (ksteps + nsplit - 1) / nsplit;

@@ -33,6 +33,10 @@ def _check(res, tol=BF16_TOL):
     # staleness-aware step, fixed threshold, many restarts
     (dict(M=4096, dims=[128, 64, 3], n_classes=3, N=16, B=16, n_slow=4, sa_penalty=1,
           tau_mode=1, tau_cap=1, lr=2e-3), 60),
+    # everything a multiple of 256: all products take the 256 x 256 tile kernel
+    (dict(M=8192, dims=[256, 256, 512, 10], N=6, B=256, K0=2, n_slow=1, lr=5e-4), 20),
+    # mixed: 256-row uploads but a 128-wide hidden layer (both GEMM kernels in one round)
+    (dict(M=8192, dims=[320, 128, 256, 10], N=4, B=256, n_slow=0, lr=5e-4), 15),
     # B > one tile (two row tiles per upload), Pareto times
     (dict(M=8192, dims=[384, 128, 10], N=4, B=200, n_slow=0, time_dist=1, time_param=1.5, lr=1e-3), 25),
 ])
