@@ -603,29 +603,67 @@ struct UpdateArgs {
   uint16_t* wn; size_t ldwn;           // bf16 [dp_in][dp_out] (may be null)
   uint16_t* wt; size_t ldwt;           // bf16 [dp_out][dp_in]
 };
+// VEC: rows of w and of the partials are 16-byte aligned and d_out % 4 == 0, so a thread
+// moves 4 consecutive columns at a time.
+template <bool VEC>
 __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
-  __shared__ uint16_t tile[64][66];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];
   const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const int tj = threadIdx.x & 63, ti = threadIdx.x >> 6;
-#pragma unroll 4
-  for (int r = 0; r < 16; ++r) {
-    const int il = ti + 4 * r, i = i0 + il, j = j0 + tj;
-    uint16_t h = 0;
-    if (i < u.d_in && j < u.d_out) {
-      float G = 0.f;
-      for (int z = 0; z < u.nsplit; ++z) G += u.partial[(size_t)z * u.split_stride + (size_t)i * u.ldp + j];
-      const float wnew = u.w_cur[(size_t)i * u.d_out + j] - G;
-      u.w_next[(size_t)i * u.d_out + j] = wnew;
-      h = f32_to_bf16(wnew);
-      if (u.wn) u.wn[(size_t)i * u.ldwn + j] = h;
+  if (VEC) {
+    const int jq = (threadIdx.x & 15) * 4, ir = threadIdx.x >> 4;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int il = ir + 16 * r, i = i0 + il, j = j0 + jq;
+      uint2 hh = make_uint2(0, 0);
+      if (i < u.d_in && j < u.d_out) {
+        const float* pp = u.partial + (size_t)i * u.ldp + j;
+        float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int z = 0; z < u.nsplit; ++z) {
+          const float4 v = *(const float4*)(pp + (size_t)z * u.split_stride);
+          G.x += v.x; G.y += v.y; G.z += v.z; G.w += v.w;
+        }
+        float4 w = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
+        w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
+        *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
+        hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
+        hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+        if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
+      }
+      *(uint2*)&tile[il][jq] = hh;
     }
-    tile[il][tj] = h;
+  } else {
+    const int tj = threadIdx.x & 63, ti = threadIdx.x >> 6;
+#pragma unroll 4
+    for (int r = 0; r < 16; ++r) {
+      const int il = ti + 4 * r, i = i0 + il, j = j0 + tj;
+      uint16_t h = 0;
+      if (i < u.d_in && j < u.d_out) {
+        float G = 0.f;
+        for (int z = 0; z < u.nsplit; ++z) G += u.partial[(size_t)z * u.split_stride + (size_t)i * u.ldp + j];
+        const float wnew = u.w_cur[(size_t)i * u.d_out + j] - G;
+        u.w_next[(size_t)i * u.d_out + j] = wnew;
+        h = f32_to_bf16(wnew);
+        if (u.wn) u.wn[(size_t)i * u.ldwn + j] = h;
+      }
+      tile[il][tj] = h;
+    }
   }
   __syncthreads();
-#pragma unroll 4
-  for (int r = 0; r < 16; ++r) {
-    const int jl = ti + 4 * r, j = j0 + jl, i = i0 + tj;
-    if (i < u.d_in && j < u.d_out) u.wt[(size_t)j * u.ldwt + i] = tile[tj][jl];
+  // transposed bf16 copy: thread -> column j, 8 consecutive rows i (the padded pitch of wt makes
+  // the 16-byte store safe; rows beyond d_in hold zeros, which is what the padding must be)
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int q = threadIdx.x + 256 * r, jl = q >> 3, ib = (q & 7) * 8;
+    const int j = j0 + jl;
+    if (j < u.d_out) {
+      uint16_t v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = tile[ib + e][jl];
+      uint4 o;
+      o.x = v[0] | ((uint32_t)v[1] << 16); o.y = v[2] | ((uint32_t)v[3] << 16);
+      o.z = v[4] | ((uint32_t)v[5] << 16); o.w = v[6] | ((uint32_t)v[7] << 16);
+      *(uint4*)(u.wt + (size_t)j * u.ldwt + i0 + ib) = o;
+    }
   }
 }
 
@@ -682,10 +720,21 @@ __global__ void mlp_fill_zero_kernel(uint4* p, size_t n16) {
 template <typename T>
 T* at(const MlpArgs& a, size_t off) { return (T*)(a.ws + off); }
 
-int pick_split(int tiles, int ksteps) {
-  int s = (768 + tiles - 1) / tiles;
-  s = std::max(1, std::min(s, std::min(ksteps, kMaxSplit)));
-  return s;
+// Number of row-range splits of a weight-gradient contraction.  `slots` workgroups run at
+// once; a split costs one k-step time per step of its range and every extra split adds a
+// partial tile to write and read back.  Picks the cheapest under that model.
+int pick_split(int tiles, int ksteps, int slots, double tile_bytes) {
+  const double step_us = 2.0, bytes_per_us = 3.0e6;
+  int best = 1;
+  double best_cost = 1e300;
+  for (int z = 1; z <= std::min(ksteps, kMaxSplit); ++z) {
+    const int rounds = (tiles * z + slots - 1) / slots;
+    const int steps = (ksteps + z - 1) / z;
+    const double cost = rounds * steps * step_us * (tile_bytes / (256.0 * 256 * 4)) +
+                        (double)z * tiles * tile_bytes * 2.0 / bytes_per_us;
+    if (cost < best_cost) { best_cost = cost; best = z; }
+  }
+  return best;
 }
 
 }  // namespace
@@ -778,7 +827,10 @@ void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_nex
   u.ldwt = (size_t)p.dp[l];
   const double n = (double)p.d[l] * p.d[l + 1];
   hook->begin(KK_MLP_UPDATE, n * (nsplit + 1), n * (4.0 * (nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
-  mlp_update_kernel<<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64), dim3(256), 0, s>>>(u);
+  const dim3 grid((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64), block(256);
+  const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
+  if (vec) mlp_update_kernel<true><<<grid, block, 0, s>>>(u);
+  else     mlp_update_kernel<false><<<grid, block, 0, s>>>(u);
   hook->end(KK_MLP_UPDATE);
 }
 
@@ -908,7 +960,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
     const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
     const int tiles = big ? (p.dp[l] / TM3) * (p.dp[l + 1] / TN3) : (p.dp[l] / TM) * (p.dp[l + 1] / tn);
-    const int nsplit = pick_split(tiles, ksteps);
+    const int nsplit = big ? pick_split(tiles, ksteps, 256, 256.0 * 256 * 4)
+                           : pick_split(tiles, ksteps, 512, 128.0 * tn * 4);
     g.ksteps_total = ksteps;
     g.ksteps_per_split = (ksteps + nsplit - 1) / nsplit;
     g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1];
