@@ -358,8 +358,10 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 // Needs: row count and column count multiples of 256, GATHER with d_0 % 64 == 0.
 constexpr int TM3 = 256, TN3 = 256;
 constexpr int kStage3 = (TM3 + TN3) * BK;            // elements per LDS stage (64 KB)
-constexpr int kEpiPitch3 = 128 + 8;                  // transposed staging [64 n][128 m + 8] per wavefront
-constexpr int kSmem3 = 8 * 64 * kEpiPitch3;          // 139264 B >= 2 stages (131072 B)
+constexpr int kEpiPitch3 = 64 + 8;                   // per wavefront: staging [64 n][72] and [64 m][72]
+constexpr int kEpiElems3 = 8 * 2 * 64 * kEpiPitch3;   // 147456 B
+constexpr int kSmem3 = 2 * kStage3 > kEpiElems3 ? 2 * kStage3 : kEpiElems3;
+static_assert(kSmem3 * 2 <= 160 * 1024, "LDS budget");
 
 __device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_block) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
@@ -479,65 +481,78 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 #undef ABS_DMA
   __syncthreads();      // all fragment reads done before the staging area is reused
 
-  // ---- epilogue (accumulator layout as in the 128-row kernel)
+  // ---- epilogue (accumulator layout as in the 128-row kernel).  bf16 outputs leave through
+  // this wavefront's private LDS staging, once per orientation, so that every global store
+  // is 16 bytes per lane and 128 contiguous bytes per row: half of the wavefront's tile
+  // (64 x 64) at a time, staged as [n][m] for the transposed copy and as [m][n] for the
+  // row-major one.  LDS operations of one wavefront execute in order, so no barrier is
+  // needed between a wavefront's own staging writes and reads.
   const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
   const float* bias = nullptr;
   if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
   float* outf = g.outf;
   if (EPI == EPI_WGRAD) outf += (size_t)zsplit * g.split_stride;
-  uint16_t* const sE = smem + wave * (64 * kEpiPitch3);
+  uint16_t* const sT = smem + wave * (2 * 64 * kEpiPitch3);     // [64 n][72]
+  uint16_t* const sN = sT + 64 * kEpiPitch3;                    // [64 m][72]
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) {
+  for (int half = 0; half < 2; ++half) {
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      const int nl = ni * 32 + lcol;
-      const int n = n0 + wn * 64 + nl;
-      float bv = 0.f;
-      if (EPI == EPI_RELU || EPI == EPI_LOGITS) bv = n < g.n_valid ? bias[n] : 0.f;
+    for (int mh = 0; mh < 2; ++mh) {
+      const int mi = half * 2 + mh;
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const int ml = mi * 32 + rg * 8 + lrow4;
-        const int mbase = m0 + wm * 128 + ml;
-        uint16_t h[4];
-        uint2 hm = make_uint2(0, 0);
-        if (EPI == EPI_DGRAD) hm = *(const uint2*)(g.maskT + (size_t)n * g.ldmaskT + mbase);
+      for (int ni = 0; ni < 2; ++ni) {
+        const int nl = ni * 32 + lcol;
+        const int n = n0 + wn * 64 + nl;
+        float bv = 0.f;
+        if (EPI == EPI_RELU || EPI == EPI_LOGITS) bv = n < g.n_valid ? bias[n] : 0.f;
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          const int m = mbase + rr;
-          float v = acc[mi][ni][rg * 4 + rr];
-          if (EPI == EPI_RELU) {
-            v = fmaxf(v + bv, 0.f);
-          } else if (EPI == EPI_LOGITS) {
-            v += bv;
-            outf[(size_t)m * g.ldof + n] = v;
-          } else if (EPI == EPI_DGRAD) {
-            const uint32_t pair = rr < 2 ? hm.x : hm.y;
-            v = ((pair >> ((rr & 1) * 16)) & 0x7FFFu) ? v : 0.f;
-          } else {
-            outf[(size_t)m * g.ldof + n] = v;
+        for (int rg = 0; rg < 4; ++rg) {
+          const int ml = mh * 32 + rg * 8 + lrow4;                // row inside this half
+          const int mbase = m0 + wm * 128 + half * 64 + ml;
+          uint16_t h[4];
+          uint2 hm = make_uint2(0, 0);
+          if (EPI == EPI_DGRAD) hm = *(const uint2*)(g.maskT + (size_t)n * g.ldmaskT + mbase);
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int m = mbase + rr;
+            float v = acc[mi][ni][rg * 4 + rr];
+            if (EPI == EPI_RELU) {
+              v = fmaxf(v + bv, 0.f);
+            } else if (EPI == EPI_LOGITS) {
+              v += bv;
+              outf[(size_t)m * g.ldof + n] = v;
+            } else if (EPI == EPI_DGRAD) {
+              const uint32_t pair = rr < 2 ? hm.x : hm.y;
+              v = ((pair >> ((rr & 1) * 16)) & 0x7FFFu) ? v : 0.f;
+            } else {
+              outf[(size_t)m * g.ldof + n] = v;
+            }
+            if (kStageT) {
+              h[rr] = f32_to_bf16(v);
+              if (g.out) sN[(ml + rr) * kEpiPitch3 + nl] = h[rr];
+            }
           }
           if (kStageT) {
-            h[rr] = f32_to_bf16(v);
-            if (g.out) g.out[(size_t)m * g.ldo + n] = h[rr];
+            uint2 o;
+            o.x = h[0] | ((uint32_t)h[1] << 16);
+            o.y = h[2] | ((uint32_t)h[3] << 16);
+            *(uint2*)&sT[nl * kEpiPitch3 + ml] = o;
           }
-        }
-        if (kStageT) {
-          uint2 o;
-          o.x = h[0] | ((uint32_t)h[1] << 16);
-          o.y = h[2] | ((uint32_t)h[3] << 16);
-          *(uint2*)&sE[nl * kEpiPitch3 + ml] = o;
         }
       }
     }
-  }
-  if (kStageT) {
-    __syncthreads();
-    const int mrow = m0 + wm * 128;
+    if (kStageT) {
+      const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int q = lane + 64 * i, nl = q >> 4, ch = (q & 15) * 8;
-      const uint4 v = *(const uint4*)&sE[nl * kEpiPitch3 + ch];
-      *(uint4*)(g.outT + (size_t)(n0 + wn * 64 + nl) * g.ldoT + mrow + ch) = v;
+      for (int i = 0; i < 8; ++i) {
+        const int q = lane + 64 * i, r = q >> 3, ch = (q & 7) * 8;
+        const uint4 vt = *(const uint4*)&sT[r * kEpiPitch3 + ch];
+        *(uint4*)(g.outT + (size_t)(ncol + r) * g.ldoT + mrow + ch) = vt;
+        if (g.out) {
+          const uint4 vn = *(const uint4*)&sN[r * kEpiPitch3 + ch];
+          *(uint4*)(g.out + (size_t)(mrow + r) * g.ldo + ncol + ch) = vn;
+        }
+      }
     }
   }
 }
