@@ -132,7 +132,9 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
 
 /* Advance n_rounds parameter-server rounds (Algorithm 1, server part, with the
  * workers' gradients of Eq. 2 at U = 1 and the update of Eq. 3).  Returns when the
- * host has every round's trace record, i.e. after the last round's losses arrived. */
+ * host has every round's trace record, i.e. after the last round's losses arrived;
+ * the tail of that round's device work (backward pass, update, snapshot) may still be
+ * running on the stream.  abs_get_model and abs_destroy synchronise the stream. */
 int abs_round(abs_ctx* ctx, int32_t n_rounds);
 
 /* Copy global model w^version (fp32, boundary layout, n_floats = parameter count)

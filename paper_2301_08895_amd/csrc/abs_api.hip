@@ -2,6 +2,7 @@
 // host loop (select -> launch -> losses -> adapt), trace and model read-out.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -94,7 +95,7 @@ struct Stat { int64_t launches = 0; double ms = 0, flops = 0, bytes = 0; };
 const char* abs_impl::kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {
       "linreg_round", "softmax_rows", "softmax_update", "mlp_index", "mlp_gather_t", "mlp_fwd_l1",
-      "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_softmax_ce", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
+      "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_softmax_ce", "mlp_loss", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
       "mlp_update", "mlp_bias_loss"};
   return kind >= 0 && kind < KK_COUNT ? names[kind] : "?";
 }
@@ -110,8 +111,8 @@ struct abs_ctx : public LaunchHook {
   int R = 0;
   RegPlan rplan{};
   MlpArgs margs{};
-  float* h_loss = nullptr;     // pinned, device-visible
-  float* d_loss = nullptr;     // the device's address of h_loss
+  LossMailbox* h_box = nullptr;   // pinned, device-visible
+  LossMailbox* d_box = nullptr;   // the device's address of h_box
   std::string err;
   Stat stats[KK_COUNT];
   // profile mode: one event pair per launch of the current round
@@ -135,6 +136,25 @@ struct abs_ctx : public LaunchHook {
       (void)hipEventRecord(ev[ev_used + 1], stream);
       ev_kind.push_back(kind);
       ev_used += 2;
+    }
+  }
+  // Spin until the device has stamped the mailbox; every so often ask the runtime whether the
+  // stream has failed or drained without the stamp, so a broken launch cannot hang the host.
+  int wait_mailbox(uint32_t stamp) {
+    for (uint64_t spin = 1;; ++spin) {
+      if (h_box->stamp == stamp) { std::atomic_thread_fence(std::memory_order_acquire); return ABS_OK; }
+      if ((spin & 0x3FFF) == 0) {
+        const hipError_t q = hipStreamQuery(stream);
+        if (q == hipSuccess) {
+          if (h_box->stamp == stamp) return ABS_OK;
+          err = "stream drained but the loss mailbox was not written";
+          return ABS_E_HIP;
+        }
+        if (q != hipErrorNotReady) { err = std::string("hipStreamQuery: ") + hipGetErrorString(q); return ABS_E_HIP; }
+      }
+#if defined(__x86_64__)
+      __builtin_ia32_pause();
+#endif
     }
   }
   void harvest() {   // after the stream has been synchronised
@@ -198,12 +218,13 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
   c->dX = d_X; c->dy = d_y;
   auto fail = [&](const char* what, hipError_t e) {
     g_create_error = std::string(what) + ": " + hipGetErrorString(e);
-    if (c->h_loss) (void)hipHostFree(c->h_loss);
+    if (c->h_box) (void)hipHostFree(c->h_box);
     return ABS_E_HIP;
   };
-  hipError_t e = hipHostMalloc((void**)&c->h_loss, ABS_MAX_WORKERS * sizeof(float), hipHostMallocMapped);
-  if (e != hipSuccess) { c->h_loss = nullptr; return fail("hipHostMalloc", e); }
-  e = hipHostGetDevicePointer((void**)&c->d_loss, c->h_loss, 0);
+  hipError_t e = hipHostMalloc((void**)&c->h_box, sizeof(LossMailbox), hipHostMallocMapped);
+  if (e != hipSuccess) { c->h_box = nullptr; return fail("hipHostMalloc", e); }
+  std::memset(c->h_box, 0, sizeof(LossMailbox));
+  e = hipHostGetDevicePointer((void**)&c->d_box, c->h_box, 0);
   if (e != hipSuccess) return fail("hipHostGetDevicePointer", e);
 
   const uint64_t shard = (uint64_t)(cfg->M / cfg->N);
@@ -216,7 +237,7 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
     c->margs.y = (const int32_t*)d_y;
     c->margs.shard_rows = shard;
     c->margs.batch_key = bkey;
-    c->margs.loss_out = c->d_loss;
+    c->margs.mailbox = c->d_box;
     c->slot_stride = c->margs.plan.slot_stride;
     c->off_ring = c->margs.plan.off_ring;
   } else {
@@ -256,6 +277,7 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
     rd.K = K;
     rd.slot_cur = (uint32_t)(t % ctx->R);
     rd.slot_next = (uint32_t)((t + 1) % ctx->R);
+    rd.stamp = (uint32_t)(t + 1);
     for (int a = 0; a < K; ++a) {
       const Upload& u = sel[(size_t)a];
       // coefficient of this upload in Eq. 3: eta_k / (K^t B), eta_k = eta / max(1, tau_k) under
@@ -281,7 +303,7 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       ra.B = cfg.B;
       ra.shard_rows = (uint64_t)(cfg.M / cfg.N);
       ra.batch_key = stream_key(cfg.seed, kStreamBatch);
-      ra.loss_out = ctx->d_loss;
+      ra.mailbox = ctx->d_box;
       ra.dz = (float*)(ctx->ws + ctx->rplan.off_dz);
       ra.rowloss = (float*)(ctx->ws + ctx->rplan.off_rowloss);
       ra.rowidx = (uint32_t*)(ctx->ws + ctx->rplan.off_rowidx);
@@ -289,10 +311,20 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
                                         : launch_softmax_round(ra, rd, ctx->stream, ctx);
     }
     if (e != hipSuccess) { ctx->err = std::string("kernel launch: ") + hipGetErrorString(e); return ABS_E_HIP; }
-    // Eq. 5 needs this round's losses before the next round can be selected.
-    ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (cfg.profile) ctx->harvest();
-    rc = ctx->sched->complete(sel, ctx->h_loss, true, ctx->err);
+    // Eq. 5 needs this round's losses before the next round can be selected.  They arrive in
+    // the mailbox as soon as the forward pass is through (the stamp is written last), so the
+    // host prepares and enqueues round t+1 while the device still works on round t; stream
+    // order keeps the rounds apart on the device.
+    rc = ctx->wait_mailbox(rd.stamp);
+    if (rc != ABS_OK) return rc;
+    // profile mode: the rounds' events are read back in batches, after draining the stream
+    if (cfg.profile && (ctx->ev_kind.size() >= 512 || it + 1 == n_rounds)) {
+      ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+      ctx->harvest();
+    }
+    float losses[ABS_MAX_WORKERS];
+    for (int a = 0; a < K; ++a) losses[a] = ctx->h_box->loss[a];
+    rc = ctx->sched->complete(sel, losses, true, ctx->err);
     if (rc != ABS_OK) return rc;
   }
   return ABS_OK;
@@ -353,7 +385,7 @@ void abs_destroy(abs_ctx* ctx) {
   if (ctx->cfg.device_mode) {
     (void)hipStreamSynchronize(ctx->stream);
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
-    if (ctx->h_loss) (void)hipHostFree(ctx->h_loss);
+    if (ctx->h_box) (void)hipHostFree(ctx->h_box);
   }
   delete ctx;
 }

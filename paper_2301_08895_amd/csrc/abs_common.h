@@ -45,11 +45,18 @@ struct WorkerDesc {
   uint32_t slot;
   float    c;
 };
+// The losses travel through a small mailbox in device-visible host memory: loss[a] for
+// upload a, then `stamp`, written last, so the host can pick them up by polling.
+struct LossMailbox {
+  float loss[ABS_MAX_WORKERS];
+  volatile uint32_t stamp;
+};
+
 struct RoundDesc {
   int32_t  K;          // uploads aggregated this round
   uint32_t slot_cur;   // ring slot of w^t
   uint32_t slot_next;  // ring slot that receives w^{t+1}
-  int32_t  pad;
+  uint32_t stamp;      // written to the loss mailbox after this round's losses (round + 1)
   WorkerDesc w[ABS_MAX_WORKERS];
 };
 

@@ -22,6 +22,7 @@ enum KernelKind {
   KK_MLP_FWD_HIDDEN,
   KK_MLP_FWD_LOGITS,
   KK_MLP_SOFTMAX_CE,
+  KK_MLP_LOSS,
   KK_MLP_DGRAD,
   KK_MLP_WGRAD_L1,
   KK_MLP_WGRAD,
@@ -39,7 +40,7 @@ struct RegressionArgs {
   int d, C, B;
   uint64_t shard_rows;   // rows per worker shard
   uint64_t batch_key;    // stream_key(seed, kStreamBatch)
-  float* loss_out;       // [K] per-upload mean minibatch loss (device-visible host memory)
+  LossMailbox* mailbox;  // per-upload mean minibatch losses + completion stamp (device-visible host memory)
   // softmax scratch
   float* dz;             // [N*B][16]
   float* rowloss;        // [N*B]
@@ -86,7 +87,7 @@ struct MlpArgs {
   const uint16_t* X;     // bf16 payload [M, d0]
   const int32_t* y;
   uint64_t shard_rows, batch_key;
-  float* loss_out;
+  LossMailbox* mailbox;
 };
 // One-time preparation on the stream: zero the padded buffers, build the bf16 copies of w^0.
 hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s);

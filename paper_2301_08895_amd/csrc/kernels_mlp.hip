@@ -682,10 +682,9 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
   }
 }
 
-// ------------------------------------------------------------------ bias update + upload losses
+// ------------------------------------------------------------------ bias update, upload losses
 // One wavefront per bias entry: b^{t+1}_j = b^t_j - sum_m dZ_l[m][j], the column sum read
-// from the transposed copy (contiguous along m).  The trailing wavefronts reduce the
-// per-row losses to the mean minibatch loss each upload reports.
+// from the transposed copy (contiguous along m).
 struct BiasLossArgs {
   int L;
   int col_begin[ABS_MAX_LAYERS + 1];       // prefix of valid columns over the layers
@@ -693,8 +692,6 @@ struct BiasLossArgs {
   size_t b_off[ABS_MAX_LAYERS];
   const float* w_cur; float* w_next;
   int rows;                                // K * Bp
-  const float* rowloss; int B, Bp, K;
-  float* loss_out;
 };
 __global__ __launch_bounds__(256) void mlp_bias_loss_kernel(BiasLossArgs a) {
   const int lane = threadIdx.x & 63;
@@ -717,13 +714,23 @@ __global__ __launch_bounds__(256) void mlp_bias_loss_kernel(BiasLossArgs a) {
     }
     s = wave_sum(s);
     if (lane == 0) a.w_next[a.b_off[l] + j] = a.w_cur[a.b_off[l] + j] - s;
-  } else if (w - ncol < a.K) {
-    const int up = w - ncol;
-    float s = 0.f;
-    for (int b = lane; b < a.B; b += 64) s += a.rowloss[(size_t)up * a.Bp + b];
-    s = wave_sum(s);
-    if (lane == 0) a.loss_out[up] = s / (float)a.B;
   }
+}
+
+// The uploads' mean minibatch losses (what each worker reports next to its gradient), one
+// wavefront per upload in a single workgroup, then the mailbox stamp.  Runs right after the
+// loss kernel so that the host can prepare the next round under this round's backward pass.
+__global__ __launch_bounds__(1024) void mlp_loss_kernel(const float* rowloss, int B, int Bp, int K, uint32_t stamp,
+                                                       LossMailbox* mailbox) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int up = wave; up < K; up += 16) {
+    float s = 0.f;
+    for (int b = lane; b < B; b += 64) s += rowloss[(size_t)up * Bp + b];
+    s = wave_sum(s);
+    if (lane == 0) { mailbox->loss[up] = s / (float)B; __threadfence_system(); }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) { __threadfence_system(); mailbox->stamp = stamp; }
 }
 
 __global__ void mlp_fill_zero_kernel(uint4* p, size_t n16) {
@@ -853,7 +860,7 @@ template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
 void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   g.nsplit = nsplit;
   const bool big = Mdim % TM3 == 0 && Ndim % TN3 == 0 && (!PER_UPLOAD || g.rows_per_upload % TM3 == 0) &&
-                   (!GATHER || g.a_kvalid % BK == 0);
+                   (!GATHER || g.a_kvalid % BK == 0) && (Mdim / TM3) * (Ndim / TN3) * nsplit >= 128;
   if (big) {
     g.mt = Mdim / TM3;
     g.nt = Ndim / TN3;
@@ -861,7 +868,12 @@ void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd);
     return;
   }
-  const int tn = Ndim % 256 == 0 ? 256 : Ndim % 128 == 0 ? 128 : 64;
+  // widest column tile that still gives every CU a workgroup (narrower tiles otherwise)
+  int tn = 64;
+  for (int cand : {256, 128}) {
+    if (Ndim % cand) continue;
+    if ((Mdim / TM) * (Ndim / cand) * nsplit >= 256 || Ndim % (cand / 2)) { tn = cand; break; }
+  }
   g.mt = Mdim / TM;
   g.nt = Ndim / tn;
   g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
@@ -947,6 +959,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
     }
     hook->end(KK_MLP_SOFTMAX_CE);
+    hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
+    mlp_loss_kernel<<<dim3(1), dim3(1024), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox);
+    hook->end(KK_MLP_LOSS);
   }
 
   // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
@@ -1004,11 +1019,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
     b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
     b.rows = rows;
-    b.rowloss = at<float>(a, p.off_rowloss);
-    b.B = p.B; b.Bp = p.Bp; b.K = K;
-    b.loss_out = a.loss_out;
     hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
-    mlp_bias_loss_kernel<<<dim3((c + K + 3) / 4), dim3(256), 0, s>>>(b);
+    mlp_bias_loss_kernel<<<dim3((c + 3) / 4), dim3(256), 0, s>>>(b);
     hook->end(KK_MLP_BIAS_LOSS);
   }
   return hipGetLastError();

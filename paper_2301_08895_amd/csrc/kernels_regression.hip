@@ -84,8 +84,11 @@ __global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(Regression
     float l = 0.f;
 #pragma unroll
     for (int w = 0; w < kLinWaves; ++w) l += s_loss[w][up];
-    a.loss_out[up] = l / (float)B;
+    a.mailbox->loss[up] = l / (float)B;
+    __threadfence_system();
   }
+  __syncthreads();
+  if (threadIdx.x == 0) { __threadfence_system(); a.mailbox->stamp = rd.stamp; }
 }
 
 hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
@@ -243,8 +246,10 @@ __global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, R
       float s = 0.f;
       for (int b = lane; b < B; b += 64) s += a.rowloss[up * B + b];
       s = wave_sum(s);
-      if (lane == 0) a.loss_out[up] = s / (float)B;
+      if (lane == 0) { a.mailbox->loss[up] = s / (float)B; __threadfence_system(); }
     }
+    __syncthreads();
+    if (threadIdx.x == 0) { __threadfence_system(); a.mailbox->stamp = rd.stamp; }
   }
 }
 
