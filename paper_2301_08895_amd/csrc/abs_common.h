@@ -52,6 +52,20 @@ struct LossMailbox {
   volatile uint32_t stamp;
 };
 
+#if defined(__HIPCC__)
+// Publish K losses that sit in LDS: one wavefront writes them all, fences once at system
+// scope and only then writes the stamp, so a host that sees the stamp sees the losses.
+// (One fence per loss would cost a trip over the host link each.)  Call with the whole
+// workgroup after a __syncthreads() that follows the LDS writes.
+__device__ __forceinline__ void publish_losses(LossMailbox* box, const float* s_loss, int K, uint32_t stamp) {
+  if (threadIdx.x < 64) {
+    for (int a = threadIdx.x; a < K; a += 64) box->loss[a] = s_loss[a];
+    __threadfence_system();
+    if (threadIdx.x == 0) box->stamp = stamp;
+  }
+}
+#endif
+
 struct RoundDesc {
   int32_t  K;          // uploads aggregated this round
   uint32_t slot_cur;   // ring slot of w^t

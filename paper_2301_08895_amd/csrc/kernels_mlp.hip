@@ -722,15 +722,16 @@ __global__ __launch_bounds__(256) void mlp_bias_loss_kernel(BiasLossArgs a) {
 // loss kernel so that the host can prepare the next round under this round's backward pass.
 __global__ __launch_bounds__(1024) void mlp_loss_kernel(const float* rowloss, int B, int Bp, int K, uint32_t stamp,
                                                        LossMailbox* mailbox) {
+  __shared__ float s_loss[ABS_MAX_WORKERS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int up = wave; up < K; up += 16) {
     float s = 0.f;
     for (int b = lane; b < B; b += 64) s += rowloss[(size_t)up * Bp + b];
     s = wave_sum(s);
-    if (lane == 0) { mailbox->loss[up] = s / (float)B; __threadfence_system(); }
+    if (lane == 0) s_loss[up] = s / (float)B;
   }
   __syncthreads();
-  if (threadIdx.x == 0) { __threadfence_system(); mailbox->stamp = stamp; }
+  publish_losses(mailbox, s_loss, K, stamp);
 }
 
 __global__ void mlp_fill_zero_kernel(uint4* p, size_t n16) {

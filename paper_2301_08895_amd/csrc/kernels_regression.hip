@@ -80,15 +80,14 @@ __global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(Regression
     for (int w = 0; w < kLinWaves; ++w) G += s_g[w][i];
     nxt[i] = cur[i] - G;
   }
-  for (int up = threadIdx.x; up < K; up += blockDim.x) {
+  for (int up = threadIdx.x; up < K; up += blockDim.x) {   // thread `up` owns column `up` of s_loss
     float l = 0.f;
 #pragma unroll
     for (int w = 0; w < kLinWaves; ++w) l += s_loss[w][up];
-    a.mailbox->loss[up] = l / (float)B;
-    __threadfence_system();
+    s_loss[0][up] = l / (float)B;
   }
   __syncthreads();
-  if (threadIdx.x == 0) { __threadfence_system(); a.mailbox->stamp = rd.stamp; }
+  publish_losses(a.mailbox, &s_loss[0][0], K, rd.stamp);
 }
 
 hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
@@ -185,6 +184,7 @@ constexpr int kUpdF = 8, kUpdG = 32;
 template <int C>
 __global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
   __shared__ float s_red[kUpdG][kUpdF * C + 1];
+  __shared__ float s_loss[ABS_MAX_WORKERS];
   const int B = a.B, d = a.d, R = rd.K * B;
   const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
   float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
@@ -246,10 +246,10 @@ __global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, R
       float s = 0.f;
       for (int b = lane; b < B; b += 64) s += a.rowloss[up * B + b];
       s = wave_sum(s);
-      if (lane == 0) { a.mailbox->loss[up] = s / (float)B; __threadfence_system(); }
+      if (lane == 0) s_loss[up] = s / (float)B;
     }
     __syncthreads();
-    if (threadIdx.x == 0) { __threadfence_system(); a.mailbox->stamp = rd.stamp; }
+    publish_losses(a.mailbox, s_loss, rd.K, rd.stamp);
   }
 }
 
