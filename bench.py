@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 
-MFMA_KINDS = {"mlp_fwd_l1", "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad"}
+MFMA_KINDS = {"mlp_fwd_l1", "mlp_fwd_hidden", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad"}
 
 # default (warmup, steps) per workload: short enough for a default run of about a minute
 DEFAULT_STEPS = {1: (20, 180), 2: (200, 1800), 3: (200, 1800), 4: (200, 4800), 5: (100, 4900)}

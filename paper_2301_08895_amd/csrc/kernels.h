@@ -23,6 +23,7 @@ enum KernelKind {
   KK_MLP_FWD_LOGITS,
   KK_MLP_SOFTMAX_CE,
   KK_MLP_LOSS,
+  KK_MLP_DGRAD_OUT,
   KK_MLP_DGRAD,
   KK_MLP_WGRAD_L1,
   KK_MLP_WGRAD,

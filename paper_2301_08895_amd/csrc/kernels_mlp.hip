@@ -558,18 +558,20 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 }
 
 // ------------------------------------------------------------------ softmax cross-entropy
-// One wavefront per stacked row: loss of the row, dZ_L = c_k (softmax - onehot) narrowed
+// A wavefront per stacked row (16 wavefronts, 4 rows each, 64 rows per workgroup): loss of the
+// row, dZ_L = c_k (softmax - onehot) narrowed
 // to bf16 (zero for padding rows and padding columns), in both orientations.
 template <int NC>   // columns per lane: padded class count / 64
-__global__ __launch_bounds__(256) void mlp_softmax_ce_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
+__global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
                                                             RoundDesc rd, int Bp, uint16_t* dZ, size_t lddz,
                                                             uint16_t* dZT, size_t lddzt, float* rowloss) {
   __shared__ uint16_t sT[NC * 64][72];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m0 = blockIdx.x * 64;
   const float coef = rd.w[m0 / Bp].c;
-  for (int i = 0; i < 16; ++i) {
-    const int ml = wave * 16 + i, m = m0 + ml;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ml = wave * 4 + i, m = m0 + ml;
     const int lab = label[m];
     float z[NC];
     float zmax = -INFINITY;
@@ -602,7 +604,7 @@ __global__ __launch_bounds__(256) void mlp_softmax_ce_kernel(const float* Z, siz
     }
   }
   __syncthreads();
-  for (int q = threadIdx.x; q < NC * 64 * 8; q += 256) {
+  for (int q = threadIdx.x; q < NC * 64 * 8; q += 1024) {
     const int c = q >> 3, ch = q & 7;
     *(uint4*)(dZT + (size_t)c * lddzt + m0 + ch * 8) = *(const uint4*)&sT[c][ch * 8];
   }
@@ -618,50 +620,39 @@ struct UpdateArgs {
   uint16_t* wn; size_t ldwn;           // bf16 [dp_in][dp_out] (may be null)
   uint16_t* wt; size_t ldwt;           // bf16 [dp_out][dp_in]
 };
-// VEC: rows of w and of the partials are 16-byte aligned and d_out % 4 == 0, so a thread
-// moves 4 consecutive columns at a time.
-template <bool VEC>
+// Tiled version for 16-byte aligned rows (d_out % 4 == 0): a thread moves 4 consecutive
+// columns at a time.
 __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
   __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];
   const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  if (VEC) {
-    const int jq = (threadIdx.x & 15) * 4, ir = threadIdx.x >> 4;
+  const int jq = (threadIdx.x & 15) * 4, ir = threadIdx.x >> 4;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int il = ir + 16 * r, i = i0 + il, j = j0 + jq;
-      uint2 hh = make_uint2(0, 0);
-      if (i < u.d_in && j < u.d_out) {
-        const float* pp = u.partial + (size_t)i * u.ldp + j;
-        float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int z = 0; z < u.nsplit; ++z) {
-          const float4 v = *(const float4*)(pp + (size_t)z * u.split_stride);
-          G.x += v.x; G.y += v.y; G.z += v.z; G.w += v.w;
-        }
-        float4 w = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
-        w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
-        *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
-        hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
-        hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
-        if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
+  for (int r = 0; r < 4; ++r) {
+    const int il = ir + 16 * r, i = i0 + il, j = j0 + jq;
+    uint2 hh = make_uint2(0, 0);
+    if (i < u.d_in && j < u.d_out) {
+      const float* pp = u.partial + (size_t)i * u.ldp + j;
+      float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
+      int z = 0;
+      for (; z + 4 <= u.nsplit; z += 4) {      // four loads in flight, summed in split order
+        float4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = *(const float4*)(pp + (size_t)(z + q) * u.split_stride);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { G.x += v[q].x; G.y += v[q].y; G.z += v[q].z; G.w += v[q].w; }
       }
-      *(uint2*)&tile[il][jq] = hh;
-    }
-  } else {
-    const int tj = threadIdx.x & 63, ti = threadIdx.x >> 6;
-#pragma unroll 4
-    for (int r = 0; r < 16; ++r) {
-      const int il = ti + 4 * r, i = i0 + il, j = j0 + tj;
-      uint16_t h = 0;
-      if (i < u.d_in && j < u.d_out) {
-        float G = 0.f;
-        for (int z = 0; z < u.nsplit; ++z) G += u.partial[(size_t)z * u.split_stride + (size_t)i * u.ldp + j];
-        const float wnew = u.w_cur[(size_t)i * u.d_out + j] - G;
-        u.w_next[(size_t)i * u.d_out + j] = wnew;
-        h = f32_to_bf16(wnew);
-        if (u.wn) u.wn[(size_t)i * u.ldwn + j] = h;
+      for (; z < u.nsplit; ++z) {
+        const float4 v = *(const float4*)(pp + (size_t)z * u.split_stride);
+        G.x += v.x; G.y += v.y; G.z += v.z; G.w += v.w;
       }
-      tile[il][tj] = h;
+      float4 w = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
+      w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
+      *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
+      hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
+      hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+      if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
     }
+    *(uint2*)&tile[il][jq] = hh;
   }
   __syncthreads();
   // transposed bf16 copy: thread -> column j, 8 consecutive rows i (the padded pitch of wt makes
@@ -680,6 +671,30 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
       *(uint4*)(u.wt + (size_t)j * u.ldwt + i0 + ib) = o;
     }
   }
+}
+
+// Element-wise version for narrow or odd output widths (e.g. the 10-class output layer):
+// one thread per weight, four partial loads in flight.
+__global__ __launch_bounds__(256) void mlp_update_small_kernel(UpdateArgs u) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= u.d_in * u.d_out) return;
+  const int i = e / u.d_out, j = e - i * u.d_out;
+  const float* pp = u.partial + (size_t)i * u.ldp + j;
+  float G = 0.f;
+  int z = 0;
+  for (; z + 4 <= u.nsplit; z += 4) {
+    float v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = pp[(size_t)(z + q) * u.split_stride];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) G += v[q];
+  }
+  for (; z < u.nsplit; ++z) G += pp[(size_t)z * u.split_stride];
+  const float wnew = u.w_cur[e] - G;
+  u.w_next[e] = wnew;
+  const uint16_t h = f32_to_bf16(wnew);
+  if (u.wn) u.wn[(size_t)i * u.ldwn + j] = h;
+  u.wt[(size_t)j * u.ldwt + i] = h;
 }
 
 // ------------------------------------------------------------------ bias update, upload losses
@@ -852,8 +867,8 @@ void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_nex
   hook->begin(KK_MLP_UPDATE, n * (nsplit + 1), n * (4.0 * (nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
   const dim3 grid((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64), block(256);
   const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
-  if (vec) mlp_update_kernel<true><<<grid, block, 0, s>>>(u);
-  else     mlp_update_kernel<false><<<grid, block, 0, s>>>(u);
+  if (vec) mlp_update_kernel<<<grid, block, 0, s>>>(u);
+  else     mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256), block, 0, s>>>(u);
   hook->end(KK_MLP_UPDATE);
 }
 
@@ -948,7 +963,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
   // ---- loss and output gradient, already scaled by the uploads' coefficients
   {
     hook->begin(KK_MLP_SOFTMAX_CE, arows * p.d[L] * 8.0, arows * p.d[L] * 8.0);
-    const dim3 grid(rows / 64), block(256);
+    const dim3 grid(rows / 64), block(1024);
     const float* Z = at<float>(a, p.off_z);
     uint16_t* dz = at<uint16_t>(a, p.off_dz[L]);
     uint16_t* dzt = at<uint16_t>(a, p.off_dzt[L]);
@@ -976,9 +991,12 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = Mp;
     g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.dp[l];
     g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = Mp;
-    hook->begin(KK_MLP_DGRAD, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
-    launch_gemm<EPI_DGRAD, false, true>(g, rd, rows, p.dp[l], 1, s);
-    hook->end(KK_MLP_DGRAD);
+    // the product through the output layer contracts over the classes only: bandwidth-bound
+    const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
+    hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
+    if (l == L - 1) launch_gemm<EPI_DGRAD, false, true, 1>(g, rd, rows, p.dp[l], 1, s);
+    else            launch_gemm<EPI_DGRAD, false, true, 0>(g, rd, rows, p.dp[l], 1, s);
+    hook->end(kind);
   }
 
   // ---- weight gradients = K-of-N reduction (one contraction over all stacked rows),
