@@ -28,6 +28,78 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
 
 MFMA_KINDS = {"mlp_fwd_l1", "mlp_fwd_hidden", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad"}
 
+# rocprofv3 symbol (substring) of each kernel kind in the cfg 5 run, for the HBM-traffic import
+KIND_SYMBOL = {
+    "mlp_fwd_l1": "mlp_gemm256_kernel<0, true, true, 0>",
+    "mlp_fwd_hidden": "mlp_gemm256_kernel<0, false, true, 0>",
+    "mlp_dgrad": "mlp_gemm256_kernel<2, false, true, 0>",
+    "mlp_wgrad_l1": "mlp_gemm256_kernel<3, false, false, 1>",
+}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_hbm_traffic.txt")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2301_08895_amd", "csrc", "kernels_mlp.hip")
+COPY_BYTES = 1 << 30          # --calibrate-copy moves this many bytes with a plain copy kernel
+
+
+def source_hash():
+    import hashlib
+    return hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:16]
+
+
+def import_traffic(fetch_csv, write_csv):
+    """Turn two rocprofv3 --pmc runs of `bench.py --config 5 --calibrate-copy` (FETCH_SIZE, then
+    WRITE_SIZE; counters in KiB per dispatch) into profiles/cfg5_hbm_traffic.txt: HBM bytes
+    per launch of each GEMM kind, each counter scaled by what it reads for the 1 GiB copy."""
+    import csv
+    def per_kernel(path, counter):
+        acc = {}
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            a = acc.setdefault(r["Kernel_Name"], [0.0, 0, 0.0])
+            v = float(r["Counter_Value"]) * 1024.0
+            a[0] += v
+            a[1] += 1
+            a[2] = max(a[2], v)
+        return acc
+    fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
+    def copy_factor(acc):
+        # the calibration copy is the largest single dispatch of a copy kernel
+        big = max([a[2] for name, a in acc.items() if "copy" in name.lower()] or [0.0])
+        if big <= 0.0:
+            raise SystemExit("no copy kernel in the counter file: run bench.py with --calibrate-copy")
+        return COPY_BYTES / big
+    ff, fw = copy_factor(fetch), copy_factor(write)
+    lines = [f"# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),",
+             f"# scaled by the same counters' reading for a {COPY_BYTES >> 20} MiB copy kernel",
+             f"source_hash {source_hash()}", f"fetch_factor {ff:.4f}", f"write_factor {fw:.4f}"]
+    for kind, sym in KIND_SYMBOL.items():
+        f = [v for k, v in fetch.items() if sym in k]
+        w = [v for k, v in write.items() if sym in k]
+        if not f or not w:
+            continue
+        fb, wb = f[0][0] / f[0][1] * ff, w[0][0] / w[0][1] * fw
+        lines.append(f"{kind} launches {f[0][1]} fetch_bytes {fb:.0f} write_bytes {wb:.0f}")
+    open(TRAFFIC_FILE, "w").write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
+def stored_traffic(kind, flops_per_launch, flops_per_launch_ref=None):
+    """HBM bytes per launch of `kind` from the stored counters, or None when there are none or
+    the kernel source has changed since they were taken."""
+    if not os.path.exists(TRAFFIC_FILE):
+        return None
+    rows = {}
+    for line in open(TRAFFIC_FILE):
+        t = line.split()
+        if t and not t[0].startswith("#"):
+            rows[t[0]] = t[1:]
+    if rows.get("source_hash", [""])[0] != source_hash() or kind not in rows:
+        return None
+    r = rows[kind]
+    d = dict(zip(r[0::2], r[1::2]))
+    return float(d["fetch_bytes"]) + float(d["write_bytes"])
+
+
 # default (warmup, steps) per workload: short enough for a default run of about a minute
 DEFAULT_STEPS = {1: (20, 180), 2: (200, 1800), 3: (200, 1800), 4: (200, 4800), 5: (100, 4900)}
 
@@ -55,6 +127,18 @@ def cpu_baseline(p, inputs, budget_s: float):
                        f"NumPy fp64, {os.cpu_count()} host cpus visible")
 
 
+def _flops_at_full_k(p, kind):
+    """Algorithmic flops of one launch of `kind` when all N workers upload."""
+    d, rows = p["dims"], p["N"] * p["B"]
+    if kind in ("mlp_fwd_l1", "mlp_wgrad_l1"):
+        return 2.0 * rows * d[0] * d[1]
+    if kind == "mlp_fwd_hidden":
+        return sum(2.0 * rows * d[l] * d[l + 1] for l in range(1, len(d) - 2)) / max(1, len(d) - 3)
+    if kind == "mlp_dgrad":
+        return sum(2.0 * rows * d[l] * d[l + 1] for l in range(1, len(d) - 2)) / max(1, len(d) - 3)
+    return sum(2.0 * rows * d[l] * d[l + 1] for l in range(1, len(d) - 1)) / max(1, len(d) - 2)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,7 +147,16 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time (0: skip)")
+    ap.add_argument("--fixed-k", action="store_true",
+                    help="counter runs only: wait for all N workers every round (the steady state)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="counter runs only: end with a plain 1 GiB device copy to calibrate FETCH/WRITE_SIZE")
+    ap.add_argument("--traffic-import", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="write profiles/cfg5_hbm_traffic.txt from two rocprofv3 --pmc counter files and exit")
     args = ap.parse_args()
+    if args.traffic_import:
+        import_traffic(*args.traffic_import)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one simulated parameter server per device); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
@@ -75,6 +168,8 @@ def main():
     import paper_2301_08895_amd as lib
 
     p = workloads.preset(args.config)
+    if args.fixed_k:
+        p["k_mode"], p["K0"] = 1, p["N"]
     dw, ds = DEFAULT_STEPS[args.config]
     warmup = dw if args.warmup is None else args.warmup
     steps = ds if args.steps is None else args.steps
@@ -92,6 +187,11 @@ def main():
     tr = sim.trace(warmup, warmup + steps)
     final = sim.model()
     sim.close()
+    if args.calibrate_copy:
+        src = torch.ones(COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     assert np.all(np.isfinite(final)), "non-finite parameters after the timed run"
     grads = int(tr[:, 1].sum())
     value = grads / elapsed
@@ -111,8 +211,12 @@ def main():
         avg_s = dom["ms"] / dom["launches"] * 1e-3
         if dom["name"] in MFMA_KINDS:
             ach = dom["flops"] / dom["launches"] / avg_s / 1e12
+            # stored counters were taken at K = N; a launch's traffic scales with its rows
+            traffic = stored_traffic(dom["name"], None) if args.config == 5 else None
+            if traffic is not None:
+                traffic *= (dom["flops"] / dom["launches"]) / _flops_at_full_k(p, dom["name"])
             roofline = dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS,
-                            unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS, traffic=None,
+                            unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS, traffic=traffic,
                             avg_launch_us=avg_s * 1e6, launches=dom["launches"])
         else:
             ach = dom["bytes"] / dom["launches"] / avg_s / 1e9
