@@ -47,27 +47,51 @@ __global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(Regression
   for (int q = 0; q < Q; ++q) g[q] = 0.f;
   const int per = (R + kLinWaves - 1) / kLinWaves;
   const int r0 = wave * per, r1 = min(R, r0 + per);
-  for (int r = r0; r < r1; ++r) {
-    const int up = r / B;
-    const WorkerDesc w = rd.w[up];
-    const uint64_t row = batch_row(w, a.batch_key, a.shard_rows, (uint32_t)(r - up * B));
-    const float* xr = a.X + row * (uint64_t)d;
-    const float* wv = a.ring + (size_t)w.slot * a.slot_stride;
-    float x[Q];
-    float dot = 0.f;
-#pragma unroll
-    for (int q = 0; q < Q; ++q) {
-      const int i = lane + 64 * q;
-      x[q] = i < d ? xr[i] : 0.f;
-      const float wi = i < d ? wv[i] : 0.f;
-      dot = fmaf(x[q], wi, dot);
+  // 64 rows at a time: lane i prepares row i of the chunk (minibatch draw, target, upload),
+  // then the rows are processed eight at a time so that their loads overlap.
+  for (int c0 = r0; c0 < r1; c0 += 64) {
+    const int mine = c0 + lane;
+    uint64_t my_row = 0;
+    float my_y = 0.f, my_c = 0.f;
+    int my_up = 0, my_slot = 0;
+    if (mine < r1) {
+      my_up = mine / B;
+      const WorkerDesc w = rd.w[my_up];
+      my_row = batch_row(w, a.batch_key, a.shard_rows, (uint32_t)(mine - my_up * B));
+      my_y = y[my_row];
+      my_c = w.c;
+      my_slot = (int)w.slot;
     }
-    dot = wave_sum(dot);
-    const float res = dot - y[row];
-    const float coef = w.c * res;
+    const int n = min(64, r1 - c0);
+    for (int j0 = 0; j0 < n; j0 += 8) {
+      float x[8][Q], dot[8];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) g[q] = fmaf(coef, x[q], g[q]);
-    if (lane == 0) s_loss[wave][up] += 0.5f * res * res;
+      for (int j = 0; j < 8; ++j) {
+        const int src = min(j0 + j, n - 1);           // the tail repeats the last row, masked below
+        const uint64_t row = __shfl(my_row, src, 64);
+        const int slot = __shfl(my_slot, src, 64);
+        const float* xr = a.X + row * (uint64_t)d;
+        const float* wv = a.ring + (size_t)slot * a.slot_stride;
+        dot[j] = 0.f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+          const int i = lane + 64 * q;
+          x[j][q] = i < d ? xr[i] : 0.f;
+          const float wi = i < d ? wv[i] : 0.f;
+          dot[j] = fmaf(x[j][q], wi, dot[j]);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int src = min(j0 + j, n - 1);
+        const float res = wave_sum(dot[j]) - __shfl(my_y, src, 64);
+        const float coef = j0 + j < n ? __shfl(my_c, src, 64) * res : 0.f;
+        const int up = __shfl(my_up, src, 64);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) g[q] = fmaf(coef, x[j][q], g[q]);
+        if (lane == 0 && j0 + j < n) s_loss[wave][up] += 0.5f * res * res;
+      }
+    }
   }
 #pragma unroll
   for (int q = 0; q < Q; ++q) s_g[wave][lane + 64 * q] = g[q];
@@ -176,13 +200,13 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(RegressionArgs a, Rou
 
 // Kernel 2: G = X^T dZ over all K*B stacked rows, sliced by feature, then the update
 // w^{t+1} = w^t - G written into the next ring slot.  A workgroup owns 8 features; its
-// 256 threads are 8 features x 32 row groups; the 32 partial sums are combined through
+// 1024 threads are 8 features x 128 row groups; the 128 partial sums are combined through
 // LDS in group order.  The last workgroup reduces the bias gradient and the per-upload
 // losses.
-constexpr int kUpdF = 8, kUpdG = 32;
+constexpr int kUpdF = 8, kUpdG = 128;
 
 template <int C>
-__global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
+__global__ __launch_bounds__(1024) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
   __shared__ float s_red[kUpdG][kUpdF * C + 1];
   __shared__ float s_loss[ABS_MAX_WORKERS];
   const int B = a.B, d = a.d, R = rd.K * B;
@@ -196,17 +220,27 @@ __global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, R
 #pragma unroll
     for (int c = 0; c < C; ++c) acc[c] = 0.f;
     if (i < d) {
-      for (int r = g; r < R; r += kUpdG) {
-        const float x = a.X[(uint64_t)a.rowidx[r] * (uint64_t)d + i];
-        const float4* dzp = (const float4*)(a.dz + (size_t)r * kDzPitch);
-        float dzr[16];
+      // four rows per trip so that the dependent loads (row index -> x) of different rows overlap
+      for (int r = g; r < R; r += 4 * kUpdG) {
+        float x[4];
+        float dzr[4][16];
 #pragma unroll
-        for (int v = 0; v < (C + 3) / 4; ++v) {
-          const float4 t = dzp[v];
-          dzr[4 * v] = t.x; dzr[4 * v + 1] = t.y; dzr[4 * v + 2] = t.z; dzr[4 * v + 3] = t.w;
+        for (int u = 0; u < 4; ++u) {
+          const int rr = r + u * kUpdG;
+          const bool ok = rr < R;
+          const int rs = ok ? rr : r;
+          x[u] = ok ? a.X[(uint64_t)a.rowidx[rs] * (uint64_t)d + i] : 0.f;
+          const float4* dzp = (const float4*)(a.dz + (size_t)rs * kDzPitch);
+#pragma unroll
+          for (int v = 0; v < (C + 3) / 4; ++v) {
+            const float4 t = dzp[v];
+            dzr[u][4 * v] = t.x; dzr[u][4 * v + 1] = t.y; dzr[u][4 * v + 2] = t.z; dzr[u][4 * v + 3] = t.w;
+          }
         }
 #pragma unroll
-        for (int c = 0; c < C; ++c) acc[c] = fmaf(x, dzr[c], acc[c]);
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int c = 0; c < C; ++c) acc[c] = fmaf(x[u], dzr[u][c], acc[c]);
       }
     }
 #pragma unroll
@@ -224,25 +258,25 @@ __global__ __launch_bounds__(256) void softmax_update_kernel(RegressionArgs a, R
     }
     return;
   }
-  // bias gradient: column sums of dZ (16 columns x 16 row groups), then b^{t+1}
+  // bias gradient: column sums of dZ (16 columns x 64 row groups), then b^{t+1}
   {
     const int c = threadIdx.x % 16, g = threadIdx.x / 16;
     float s = 0.f;
-    for (int r = g; r < R; r += 16) s += a.dz[(size_t)r * kDzPitch + c];
+    for (int r = g; r < R; r += 64) s += a.dz[(size_t)r * kDzPitch + c];
     float* red = &s_red[0][0];
     red[g * 16 + c] = s;
     __syncthreads();
     if ((int)threadIdx.x < C) {
       float G = 0.f;
 #pragma unroll
-      for (int gg = 0; gg < 16; ++gg) G += red[gg * 16 + threadIdx.x];
+      for (int gg = 0; gg < 64; ++gg) G += red[gg * 16 + threadIdx.x];
       nxt[(size_t)d * C + threadIdx.x] = cur[(size_t)d * C + threadIdx.x] - G;
     }
   }
   // per-upload mean minibatch loss (the "average local loss" each worker uploads)
   {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int up = wave; up < rd.K; up += 4) {
+    for (int up = wave; up < rd.K; up += 16) {
       float s = 0.f;
       for (int b = lane; b < B; b += 64) s += a.rowloss[up * B + b];
       s = wave_sum(s);
@@ -265,7 +299,7 @@ static hipError_t softmax_round_c(const RegressionArgs& a, const RoundDesc& rd, 
   if (e != hipSuccess) return e;
   const int nslice = (a.d + kUpdF - 1) / kUpdF;
   hook->begin(KK_SOFTMAX_UPDATE, rows * a.d * C * 2.0, 2.0 * (a.d + 1) * C * 4.0);
-  softmax_update_kernel<C><<<dim3(nslice + 1), dim3(256), 0, s>>>(a, rd);
+  softmax_update_kernel<C><<<dim3(nslice + 1), dim3(1024), 0, s>>>(a, rd);
   hook->end(KK_SOFTMAX_UPDATE);
   return hipGetLastError();
 }
