@@ -1,4 +1,4 @@
-"""Oracle simulator of ABS (Algorithm 1 of the paper) with U = 1 local step.
+"""Oracle simulator of ABS (Algorithm 1 of the paper), U >= 1 local steps.
 
 State kept by the parameter server (Section III): round t, wait count K,
 the staleness vector tau (initialised to zero), plus what a simulation needs:
@@ -11,6 +11,13 @@ One round, in the paper's order (server part of Algorithm 1):
   the over-stale workers receive w^{t+1} and start a new job.
 A job that is cut short by a forced restart is never uploaded, so its gradient
 is never formed.
+
+With U > 1 (cfg key "U") a worker takes U local SGD steps of Eq. 2 on a private copy of the
+model it received, each on a fresh minibatch, and uploads the accumulated change
+w^{t,0} - w^{t,U} together with its average local loss (worker part of Algorithm 1); the
+server averages the K^t uploads (Eq. 3).  At U = 1 this is the same update: the single
+step's eta_k g_k.  (Algorithm 1 lists its local loop as u = 0..U, one more than Eq. 2's
+u = 0..U-1; Eq. 2 is followed: exactly U steps.)
 
 Readings taken where the paper is silent (each is repeated in the repository's
 design notes): K^t is floor'ed and clamped to [1, N]; k_mode 0 keeps it
@@ -82,9 +89,13 @@ class AbsOracle:
     """cfg keys: model, dims, x_dtype, M, N, B, K0, k_mode, tau_mode, tau_cap, a, lr,
     sa_penalty, time_dist, time_param, n_slow, slow_factor, seed_sim, k_replay (opt)."""
 
-    def __init__(self, cfg: dict, X, y, w0, emulate_bf16=None, keep_models=True):
+    def __init__(self, cfg: dict, X, y, w0, emulate_bf16=None, keep_models=True, local_path=None):
         self.cfg = dict(cfg)
         self.N, self.B = cfg["N"], cfg["B"]
+        self.U = int(cfg.get("U", 1))
+        # U = 1 folds 1/K into the back-propagation seed (one rounding point fewer under bf16
+        # emulation); local_path=True takes the general U-step route even for U = 1
+        self.local_path = (self.U > 1) if local_path is None else local_path
         self.lr = float(np.float32(cfg["lr"]))   # the step size is handed over as fp32
         if cfg["x_dtype"] == 1:
             self.Xbits, self.X = np.asarray(X), None
@@ -131,11 +142,24 @@ class AbsOracle:
             assert tau_k == self.tau[k]
             idx = crng.batch_indices(cfg, k, self.job[k])
             eta_k = self.lr / max(1, tau_k) if cfg["sa_penalty"] else self.lr
-            if v not in self._narrowed:
-                self._narrowed[v] = narrowed_weights(cfg, self.models[v], self.emulate)
-            u_k, loss_k = worker_update(cfg, self.models[v], self._rows(idx), self.y[idx],
-                                        eta_k / K, self.emulate, self._narrowed[v])
-            w_next -= u_k
+            if not self.local_path:
+                if v not in self._narrowed:
+                    self._narrowed[v] = narrowed_weights(cfg, self.models[v], self.emulate)
+                u_k, loss_k = worker_update(cfg, self.models[v], self._rows(idx), self.y[idx],
+                                            eta_k / K, self.emulate, self._narrowed[v])
+                w_next -= u_k
+            else:
+                # Eq. 2, U local steps on a private copy; the upload is w^{t,0} - w^{t,U}
+                w_loc = self.models[v].copy()
+                step_losses = []
+                for u in range(self.U):
+                    idx_u = crng.batch_indices(cfg, k, self.job[k], u)
+                    step, loss_u = worker_update(cfg, w_loc, self._rows(idx_u), self.y[idx_u],
+                                                 eta_k, self.emulate)
+                    w_loc -= step
+                    step_losses.append(loss_u)
+                w_next -= (self.models[v] - w_loc) / K
+                loss_k = sum(step_losses) / self.U
             losses.append(loss_k); vers.append(v); taus.append(tau_k)
         self.models[t + 1] = w_next
         # loss of the global model := mean of the uploaded minibatch losses (Section III)

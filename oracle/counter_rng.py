@@ -79,10 +79,12 @@ def shard_rows(cfg: dict) -> int:
     return cfg["M"] // cfg["N"]
 
 
-def batch_indices(cfg: dict, n: int, j: int):
-    """Dataset rows of the minibatch of job j of worker n: B draws, iid uniform
-    (with replacement) from the worker's own shard."""
+def batch_indices(cfg: dict, n: int, j: int, u: int = 0):
+    """Dataset rows of the minibatch of local step u of job j of worker n: B draws, iid
+    uniform (with replacement) from the worker's own shard; draw b of step u has counter
+    index u * B + b, so minibatches are independent across workers, local steps and rounds."""
     S = shard_rows(cfg)
     base = n * S
-    return [base + counter_hash(cfg["seed_sim"], STREAM_BATCH, n, j, b) % S
-            for b in range(cfg["B"])]
+    B = cfg["B"]
+    return [base + counter_hash(cfg["seed_sim"], STREAM_BATCH, n, j, u * B + b) % S
+            for b in range(B)]

@@ -89,6 +89,44 @@ def test_reduces_to_asgd_and_k_async(K):
     assert max(max(r["taus"]) for r in o.trace) > 2     # staleness is unbounded here
 
 
+@pytest.mark.parametrize("model", [0, 1, 2])
+def test_local_steps_reduce_to_model_averaging(model):
+    """U > 1 with K^t = N and tau = 0 is classical (synchronous) local SGD (Section II-B):
+    every worker takes U SGD steps of Eq. 2 from w^t on fresh minibatches and the server
+    keeps the average of the N local models; the reported loss is the mean local loss."""
+    U = 3
+    p, d = _small(model, k_mode=1, K0=4, time_dist=2, tau_mode=1, sa_penalty=0, n_slow=0, U=U)
+    o = AbsOracle(p, d["X"], d["y"], d["w0"], emulate_bf16=False).run(6)
+    lr = float(np.float32(p["lr"]))
+    w = d["w0"].astype(np.float64)
+    for t in range(6):
+        finals, losses = [], []
+        for n in range(4):
+            wn = w.copy()
+            for u in range(U):
+                idx = crng.batch_indices(p, n, t, u)
+                g, l = worker_update(p, wn, _rows(p, d, idx), d["y"][idx], 1.0, False)
+                wn = wn - lr * g
+                losses.append(l)
+            finals.append(wn)
+        w_avg = np.mean(finals, axis=0)
+        assert np.allclose(o.model(t + 1), w_avg, rtol=1e-12, atol=1e-15)
+        assert np.isclose(o.trace[t]["loss"], np.mean(losses), rtol=1e-12)
+        w = o.model(t + 1).copy()
+    # the minibatches of different local steps differ, and differ from the next job's
+    assert crng.batch_indices(p, 1, 0, 0) != crng.batch_indices(p, 1, 0, 1)
+    assert crng.batch_indices(p, 1, 0, 1) != crng.batch_indices(p, 1, 1, 0)
+
+
+def test_one_local_step_is_the_plain_update():
+    """The U-step route at U = 1 (upload w^{t,0} - w^{t,1} = eta_k g_k) is Eq. 3's update."""
+    p, d = _small(1, T=40, lr=0.05, sa_penalty=1)
+    a = AbsOracle(p, d["X"], d["y"], d["w0"]).run(40)
+    b = AbsOracle(p, d["X"], d["y"], d["w0"], local_path=True).run(40)
+    assert [r["ids"] for r in a.trace] == [r["ids"] for r in b.trace]
+    assert np.allclose(a.model(), b.model(), rtol=1e-11, atol=1e-14)
+
+
 def test_staleness_aware_penalty_scales_the_stale_gradient():
     """SA: the step of a gradient with delay tau is eta / tau (Section I); one ASGD
     round with a stale upload must move the model by (eta/tau_k) g_k exactly."""
