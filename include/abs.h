@@ -81,6 +81,10 @@ typedef struct abs_ctx abs_ctx;   /* opaque: one simulation */
  *             used to plan or check the event trace on a machine without a GPU.
  *  profile    1: bracket every kernel with events and accumulate per-kernel time
  *             (read with abs_kernel_stats); costs a few microseconds per launch.
+ *  U          local SGD steps per job (Eq. 2), 1 <= U <= 64.  With U > 1 every upload is
+ *             the change w^{t,0} - w^{t,U} of a private copy of the model after U steps
+ *             on fresh minibatches (worker part of Algorithm 1) and the reported loss is
+ *             the job's mean local loss; 0 is read as 1.
  */
 typedef struct abs_config {
   int32_t model;
@@ -106,6 +110,8 @@ typedef struct abs_config {
   int64_t k_replay_len;
   int32_t device_mode;
   int32_t profile;
+  int32_t U;
+  int32_t reserved;            /* must be 0 */
 } abs_config;
 
 /* sizeof(abs_config) as the library was built, so a binding can check its mirror. */

@@ -33,7 +33,7 @@ class AbsConfig(C.Structure):
         ("time_dist", C.c_int32), ("n_slow", C.c_int32), ("time_param", C.c_double),
         ("slow_factor", C.c_double), ("seed", C.c_uint64),
         ("k_replay", C.POINTER(C.c_int32)), ("k_replay_len", C.c_int64),
-        ("device_mode", C.c_int32), ("profile", C.c_int32),
+        ("device_mode", C.c_int32), ("profile", C.c_int32), ("U", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -114,6 +114,7 @@ def make_config(p: dict, device_mode: int = 1, profile: int = 0, k_replay=None) 
         c.k_replay = arr.ctypes.data_as(C.POINTER(C.c_int32))
         c.k_replay_len = arr.size
     c.device_mode, c.profile = device_mode, profile
+    c.U = int(p.get("U", 1))
     return c
 
 

@@ -31,7 +31,7 @@ size_t param_count(const abs_config& c) {
 // Workspace of the two regression models.
 struct RegPlan {
   size_t slot_stride;   // floats
-  size_t off_ring, off_dz, off_rowloss, off_rowidx, total;
+  size_t off_ring, off_dz, off_rowloss, off_rowidx, off_delta, off_lossbuf, total;
 };
 
 bool validate(const abs_config& c, std::string& why) {
@@ -50,6 +50,8 @@ bool validate(const abs_config& c, std::string& why) {
   if (c.time_dist == ABS_TIME_PARETO && !(c.time_param > 0.0)) return bad("Pareto needs time_param > 0");
   if (c.n_slow < 0 || c.n_slow > c.N) return bad("n_slow must be in [0, N]");
   if (c.n_slow > 0 && !(c.slow_factor > 0.0)) return bad("slow_factor must be positive");
+  if (c.U < 0 || c.U > 64) return bad("U must be in [1, 64]");
+  if (c.reserved != 0) return bad("reserved must be 0");
   if (c.device_mode == 0 && !(c.k_mode == ABS_K_FIXED || c.k_mode == ABS_K_REPLAY))
     return bad("schedule-only mode needs k_mode 1 or 2 (there are no losses to adapt K with)");
   switch (c.model) {
@@ -85,6 +87,8 @@ void reg_plan(const abs_config& c, RegPlan& p) {
   p.off_dz = o;      o = round_up(o + rows * 16 * 4, 256);
   p.off_rowloss = o; o = round_up(o + rows * 4, 256);
   p.off_rowidx = o;  o = round_up(o + rows * 4, 256);
+  p.off_delta = o;   if (c.U > 1) o = round_up(o + (size_t)c.N * p.slot_stride * 4, 256);
+  p.off_lossbuf = o; if (c.U > 1) o = round_up(o + (size_t)c.N * 4, 256);
   p.total = o;
 }
 
@@ -96,7 +100,7 @@ const char* abs_impl::kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {
       "linreg_round", "softmax_rows", "softmax_update", "mlp_index", "mlp_gather_t", "mlp_fwd_l1",
       "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_softmax_ce", "mlp_loss", "mlp_dgrad_out", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
-      "mlp_update", "mlp_bias_loss"};
+      "mlp_update", "mlp_bias_loss", "local_steps", "delta_update"};
   return kind >= 0 && kind < KK_COUNT ? names[kind] : "?";
 }
 
@@ -201,6 +205,7 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
   if (!validate(*cfg, why)) { g_create_error = why; return ABS_E_ARG; }
   std::unique_ptr<abs_ctx> c(new abs_ctx());
   c->cfg = *cfg;
+  if (c->cfg.U == 0) c->cfg.U = 1;
   c->sched.reset(new Scheduler(*cfg));
   c->cfg.k_replay = nullptr;
   c->P = param_count(*cfg);
@@ -287,7 +292,8 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       rd.w[a].id = (uint32_t)u.id;
       rd.w[a].job = u.job;
       rd.w[a].slot = (uint32_t)(u.ver % ctx->R);
-      rd.w[a].c = (float)(eta / ((double)K * (double)cfg.B));
+      // (with U > 1 the 1/K^t of Eq. 3 is applied when the uploads' changes are averaged)
+      rd.w[a].c = cfg.U > 1 ? (float)(eta / (double)cfg.B) : (float)(eta / ((double)K * (double)cfg.B));
     }
     hipError_t e;
     if (cfg.model == ABS_MODEL_MLP) {
@@ -307,8 +313,14 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       ra.dz = (float*)(ctx->ws + ctx->rplan.off_dz);
       ra.rowloss = (float*)(ctx->ws + ctx->rplan.off_rowloss);
       ra.rowidx = (uint32_t*)(ctx->ws + ctx->rplan.off_rowidx);
-      e = cfg.model == ABS_MODEL_LINEAR ? launch_linreg_round(ra, rd, ctx->stream, ctx)
-                                        : launch_softmax_round(ra, rd, ctx->stream, ctx);
+      ra.U = cfg.U;
+      ra.delta = (float*)(ctx->ws + ctx->rplan.off_delta);
+      ra.lossbuf = (float*)(ctx->ws + ctx->rplan.off_lossbuf);
+      if (cfg.U > 1)
+        e = launch_regression_local_round(ra, rd, cfg.model == ABS_MODEL_SOFTMAX, ctx->stream, ctx);
+      else
+        e = cfg.model == ABS_MODEL_LINEAR ? launch_linreg_round(ra, rd, ctx->stream, ctx)
+                                          : launch_softmax_round(ra, rd, ctx->stream, ctx);
     }
     if (e != hipSuccess) { ctx->err = std::string("kernel launch: ") + hipGetErrorString(e); return ABS_E_HIP; }
     // Eq. 5 needs this round's losses before the next round can be selected.  They arrive in

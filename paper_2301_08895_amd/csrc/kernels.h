@@ -29,6 +29,8 @@ enum KernelKind {
   KK_MLP_WGRAD,
   KK_MLP_UPDATE,
   KK_MLP_BIAS_LOSS,
+  KK_LOCAL_STEPS,
+  KK_DELTA_UPDATE,
   KK_COUNT
 };
 const char* kernel_kind_name(int kind);
@@ -46,12 +48,19 @@ struct RegressionArgs {
   float* dz;             // [N*B][16]
   float* rowloss;        // [N*B]
   uint32_t* rowidx;      // [N*B]
+  // local SGD (U > 1): per-upload accumulated change and mean local loss
+  int U;
+  float* delta;          // [N][slot_stride]
+  float* lossbuf;        // [N]
 };
 
 hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
                                LaunchHook* hook);
 hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
                                 LaunchHook* hook);
+// U > 1: every upload runs its U local steps in one workgroup, then the uploads' changes are averaged
+hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDesc& rd, bool softmax,
+                                         hipStream_t s, LaunchHook* hook);
 
 }  // namespace abs_impl
 

@@ -1,0 +1,44 @@
+"""GPU parity of local SGD (U > 1 steps of Eq. 2 per job, uploads w^{t,0} - w^{t,U}) against
+the CPU oracle, through the C-ABI."""
+import numpy as np
+import pytest
+
+import workloads
+from parity_util import run_pair, assert_trace_equal, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(res, tol, loss_rtol):
+    assert_trace_equal(res, loss_rtol)
+    T = max(res["models"])
+    for cp, (g, w) in res["models"].items():
+        e = rel_err(g, w)
+        print(f"round {cp}: rel err {e:.3e}", flush=True)
+        assert np.all(np.isfinite(g)) and e <= tol, (cp, e)
+    g, w = res["models"][T]
+    w0 = res["sim_inputs"]["w0"].astype(np.float64)
+    if np.linalg.norm(w - w0) > 0:
+        assert rel_err(g - w0, w - w0) <= max(tol, 1e-4)
+
+
+@pytest.mark.parametrize("over,T", [
+    (dict(U=10), 120),                                                      # cfg 1 with the paper's U = 10
+    (dict(U=3, dims=[37, 1], M=999, N=5, B=7, K0=2, tau_cap=2), 100),       # ragged sizes
+    (dict(U=2, dims=[512, 1], M=4000, N=3, B=1, K0=1, sa_penalty=1, lr=1e-3), 40),
+    (dict(U=4, N=128, B=8, M=12800, tau_cap=8, time_dist=1, time_param=1.5), 60),
+])
+def test_linear_local_steps(over, T):
+    p = workloads.scaled_preset(1, **over)
+    _check(run_pair(p, T, checkpoints=(1, 5)), 1e-5, 1e-4)
+
+
+@pytest.mark.parametrize("over,T", [
+    (dict(U=10, M=6000), 100),                                               # cfg 2 shape, U = 10
+    (dict(U=3, M=4000, dims=[52, 3], n_classes=3, N=6, B=10, K0=2, tau_cap=2, lr=5e-3), 100),
+    (dict(U=2, M=4000, dims=[1024, 16], n_classes=16, N=4, B=300, lr=2e-4), 20),    # two row batches
+    (dict(U=5, M=2000, dims=[8, 2], n_classes=2, N=16, B=5, sa_penalty=1, lr=2e-2), 80),
+])
+def test_softmax_local_steps(over, T):
+    p = workloads.scaled_preset(2, **over)
+    _check(run_pair(p, T, checkpoints=(1, 5)), 1e-5, 1e-4)

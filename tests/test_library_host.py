@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
     dll = ctypes.CDLL(lib.library_path())
     for n in sorted(names):
         assert hasattr(dll, n), n
-    assert lib.abs_config_bytes() == ctypes.sizeof(lib.AbsConfig) == 144
+    assert lib.abs_config_bytes() == ctypes.sizeof(lib.AbsConfig) == 152
 
 
 def _dry_vs_oracle(p, T):

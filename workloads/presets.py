@@ -26,7 +26,7 @@ def _mk(idx, name, model, dims, x_dtype, M, n_classes, N, B, tau_cap, lr, T,
         k_mode=K_ADAPTIVE, tau_mode=TAU_ADAPTIVE, tau_cap=tau_cap,
         a=tau_cap - N // K0, lr=lr, sa_penalty=sa,
         time_dist=time_dist, time_param=time_param,
-        n_slow=n_slow, slow_factor=slow_factor, T=T,
+        n_slow=n_slow, slow_factor=slow_factor, T=T, U=1,
         seed_data=1000 + idx, seed_init=2000 + idx, seed_sim=3000 + idx,
     )
 
