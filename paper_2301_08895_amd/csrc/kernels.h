@@ -86,6 +86,10 @@ struct MlpPlan {
   size_t off_dz[8], off_dzt[8];   // dZ_l [Mp][dp_l], dZ_l^T [dp_l][Mp], l = 1 .. L
   size_t off_rowloss, off_partial;
   size_t partial_floats;
+  // local SGD (U > 1): the uploads' private models (same slot layouts as the two rings),
+  // their running mean losses, and the averaged change of Eq. 3
+  int U;
+  size_t off_priv, off_priv_shadow, off_lossacc, off_delta;
   size_t total;
 };
 // Returns false (with a message) if the configuration is not supported.

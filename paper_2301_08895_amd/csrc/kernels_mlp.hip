@@ -63,13 +63,13 @@ __device__ __forceinline__ float wave_max(float v) {
 // is -1 and their output gradient is forced to zero.
 __global__ __launch_bounds__(256) void mlp_index_kernel(uint32_t* rowidx, int32_t* label, const int32_t* y,
                                                        RoundDesc rd, int B, int Bp, uint64_t shard_rows,
-                                                       uint64_t batch_key) {
+                                                       uint64_t batch_key, uint32_t draw0) {
   const int m = blockIdx.x * 256 + threadIdx.x;
   if (m >= rd.K * Bp) return;
   const int up = m / Bp, b = m - up * Bp;
   const WorkerDesc w = rd.w[up];
   uint64_t row = (uint64_t)w.id * shard_rows;
-  if (b < B) row += draw(job_key(batch_key, w.id, w.job), (uint32_t)b) % shard_rows;
+  if (b < B) row += draw(job_key(batch_key, w.id, w.job), draw0 + (uint32_t)b) % shard_rows;   // draw0 = u * B
   rowidx[m] = (uint32_t)row;
   label[m] = b < B ? y[row] : -1;
 }
@@ -116,6 +116,7 @@ struct GemmArgs {
   const uint16_t* Bt; size_t ldb;     // [Ndim][ldb], k contiguous
   size_t bt_slot_stride;              // PER_UPLOAD: Bt += slot(upload of the row tile) * stride
   int rows_per_upload;                // Bp
+  int by_upload;                      // PER_UPLOAD: the slot is the upload's position (private models) instead of its ring slot
   int ksteps_total;                   // BK-steps of the whole contraction
   int ksteps_per_split;               // BK-steps per blockIdx.z
   const float* bias; size_t bias_slot_stride; int n_valid;   // EPI_RELU / EPI_LOGITS
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
   const uint16_t* Bt = g.Bt;
   uint32_t slot = 0;
   if (PER_UPLOAD) {
-    slot = rd.w[m0 / g.rows_per_upload].slot;
+    slot = g.by_upload ? (uint32_t)(m0 / g.rows_per_upload) : rd.w[m0 / g.rows_per_upload].slot;
     Bt += (size_t)slot * g.bt_slot_stride;
   }
 
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const uint16_t* Bt = g.Bt;
   uint32_t slot = 0;
   if (PER_UPLOAD) {
-    slot = rd.w[m0 / g.rows_per_upload].slot;
+    slot = g.by_upload ? (uint32_t)(m0 / g.rows_per_upload) : rd.w[m0 / g.rows_per_upload].slot;
     Bt += (size_t)slot * g.bt_slot_stride;
   }
 
@@ -619,11 +620,26 @@ struct UpdateArgs {
   int d_in, d_out;
   uint16_t* wn; size_t ldwn;           // bf16 [dp_in][dp_out] (may be null)
   uint16_t* wt; size_t ldwt;           // bf16 [dp_out][dp_in]
+  // batched form (local SGD): blockIdx.z = upload a; partial a, nsplit = 1, the model read from
+  // slot cur_index[a] of w_cur's ring and written to slot a of w_next's ring / shadow ring
+  int batched;
+  size_t cur_stride, next_stride, shadow_stride;
+  uint16_t cur_index[ABS_MAX_WORKERS];
 };
+__device__ __forceinline__ void update_select_upload(UpdateArgs& u) {
+  if (!u.batched) return;
+  const int a = blockIdx.z;
+  u.partial += (size_t)a * u.split_stride;
+  u.w_cur += (size_t)u.cur_index[a] * u.cur_stride;
+  u.w_next += (size_t)a * u.next_stride;
+  if (u.wn) u.wn += (size_t)a * u.shadow_stride;
+  u.wt += (size_t)a * u.shadow_stride;
+}
 // Tiled version for 16-byte aligned rows (d_out % 4 == 0): a thread moves 4 consecutive
 // columns at a time.
 __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
   __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];
+  update_select_upload(u);
   const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
   const int jq = (threadIdx.x & 15) * 4, ir = threadIdx.x >> 4;
 #pragma unroll
@@ -676,6 +692,7 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
 // Element-wise version for narrow or odd output widths (e.g. the 10-class output layer):
 // one thread per weight, four partial loads in flight.
 __global__ __launch_bounds__(256) void mlp_update_small_kernel(UpdateArgs u) {
+  update_select_upload(u);
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= u.d_in * u.d_out) return;
   const int i = e / u.d_out, j = e - i * u.d_out;
@@ -735,18 +752,90 @@ __global__ __launch_bounds__(256) void mlp_bias_loss_kernel(BiasLossArgs a) {
 // The uploads' mean minibatch losses (what each worker reports next to its gradient), one
 // wavefront per upload in a single workgroup, then the mailbox stamp.  Runs right after the
 // loss kernel so that the host can prepare the next round under this round's backward pass.
+// Local SGD: lossacc carries the sum over the job's steps; only the last step publishes.
 __global__ __launch_bounds__(1024) void mlp_loss_kernel(const float* rowloss, int B, int Bp, int K, uint32_t stamp,
-                                                       LossMailbox* mailbox) {
+                                                       LossMailbox* mailbox, float* lossacc, int first, int last,
+                                                       int U) {
   __shared__ float s_loss[ABS_MAX_WORKERS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int up = wave; up < K; up += 16) {
     float s = 0.f;
     for (int b = lane; b < B; b += 64) s += rowloss[(size_t)up * Bp + b];
-    s = wave_sum(s);
-    if (lane == 0) s_loss[up] = s / (float)B;
+    s = wave_sum(s) / (float)B;
+    if (lane == 0) {
+      if (lossacc) {
+        s += first ? 0.f : lossacc[up];
+        lossacc[up] = s;
+        s /= (float)U;
+      }
+      s_loss[up] = s;
+    }
   }
   __syncthreads();
-  publish_losses(mailbox, s_loss, K, stamp);
+  if (last) publish_losses(mailbox, s_loss, K, stamp);
+}
+
+// ------------------------------------------------------------------ local SGD helpers
+// Bias step of one upload: b_a <- b_a - sum over the upload's own rows of dZ_l (Eq. 2); one
+// wavefront per (upload, bias entry).
+struct BiasLocalArgs {
+  int L, K, Bp;
+  int col_begin[ABS_MAX_LAYERS + 1];
+  const uint16_t* dzt[ABS_MAX_LAYERS]; size_t lddzt[ABS_MAX_LAYERS];
+  size_t b_off[ABS_MAX_LAYERS];
+  const float* cur; size_t cur_stride;      // model read from slot cur_index[a]
+  float* priv; size_t priv_stride;          // written to slot a
+  uint16_t cur_index[ABS_MAX_WORKERS];
+};
+__global__ __launch_bounds__(256) void mlp_bias_local_kernel(BiasLocalArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int up = blockIdx.y;
+  const int ncol = a.col_begin[a.L];
+  if (w >= ncol) return;
+  int l = 0;
+  while (w >= a.col_begin[l + 1]) ++l;
+  const int j = w - a.col_begin[l];
+  const uint16_t* src = a.dzt[l] + (size_t)j * a.lddzt[l] + (size_t)up * a.Bp;
+  float s = 0.f;
+  for (int m = lane * 8; m < a.Bp; m += 512) {
+    const uint4 v = *(const uint4*)(src + m);
+    const uint32_t p[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s += __uint_as_float(p[e] << 16);
+      s += __uint_as_float(p[e] & 0xFFFF0000u);
+    }
+  }
+  s = wave_sum(s);
+  if (lane == 0) {
+    const float b_old = a.cur[(size_t)a.cur_index[up] * a.cur_stride + a.b_off[l] + j];
+    a.priv[(size_t)up * a.priv_stride + a.b_off[l] + j] = b_old - s;
+  }
+}
+
+// Eq. 3 over the uploads: D = (1/K) sum_a (w^{t - tau_a} - w_a^{U}) in arrival order, for every
+// parameter; bias entries are applied right away, weight matrices go through the update kernels
+// (which also refresh the bf16 copies).
+struct DeltaArgs {
+  const float* ring; size_t slot_stride;
+  const float* priv;
+  float* D;
+  size_t P;
+  int L;
+  size_t b_off[ABS_MAX_LAYERS]; int b_len[ABS_MAX_LAYERS];
+  const float* w_cur; float* w_next;
+};
+__global__ __launch_bounds__(256) void mlp_delta_kernel(DeltaArgs a, RoundDesc rd) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.P) return;
+  float s = 0.f;
+  for (int up = 0; up < rd.K; ++up)
+    s += a.ring[(size_t)rd.w[up].slot * a.slot_stride + i] - a.priv[(size_t)up * a.slot_stride + i];
+  const float d = s / (float)rd.K;
+  a.D[i] = d;
+  for (int l = 0; l < a.L; ++l)
+    if (i >= a.b_off[l] && i < a.b_off[l] + (size_t)a.b_len[l]) a.w_next[i] = a.w_cur[i] - d;
 }
 
 __global__ void mlp_fill_zero_kernel(uint4* p, size_t n16) {
@@ -791,6 +880,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
     p.dp[l] = (int)round_up((size_t)c.dims[l], 128);
   }
   if (c.dims[L] <= 64) p.dp[L] = 64;
+  p.U = c.U > 1 ? c.U : 1;
   p.B = c.B;
   p.Bp = (int)round_up((size_t)c.B, TM);
   p.N = c.N;
@@ -811,7 +901,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   p.shadow_stride = round_up(o, 128);
   size_t partial = 0;
   for (int l = 0; l < L; ++l) partial = std::max(partial, (size_t)p.dp[l] * p.dp[l + 1]);
-  p.partial_floats = partial * kMaxSplit;
+  p.partial_floats = partial * (p.U > 1 ? std::max<size_t>(kMaxSplit, (size_t)c.N) : (size_t)kMaxSplit);
 
   size_t b = 0;
   auto take = [&](size_t bytes) { size_t at = b; b = round_up(b + bytes, 256); return at; };
@@ -832,6 +922,12 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   }
   p.off_rowloss = take(Mp * 4);
   p.off_partial = take(p.partial_floats * 4);
+  if (p.U > 1) {
+    p.off_priv = take((size_t)c.N * p.slot_stride * 4);
+    p.off_priv_shadow = take((size_t)c.N * p.shadow_stride * 2);
+    p.off_lossacc = take((size_t)c.N * 4);
+    p.off_delta = take(p.slot_stride * 4);
+  }
   p.total = b;
   return true;
 }
@@ -844,31 +940,63 @@ struct NullHook : LaunchHook {
   void end(int) override {}
 };
 
-// w_next = w_cur - G for every layer's weights, plus the bf16 copies of w_next.
-void launch_update(const MlpArgs& a, int l, uint32_t slot_cur, uint32_t slot_next, int nsplit,
+// The three uses of the update kernels:
+//   UPD_GLOBAL  w^{t+1} = w^t - sum of the split partials                    (U = 1, Eq. 3)
+//   UPD_LOCAL   private model of upload a <- its model - its own partial     (Eq. 2, step u)
+//   UPD_DELTA   w^{t+1} = w^t - D, D = the averaged change of the uploads    (U > 1, Eq. 3)
+// each also writes the bf16 copies of what it produced.
+enum { UPD_GLOBAL = 0, UPD_LOCAL = 1, UPD_DELTA = 2 };
+void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int step, int nsplit,
                    hipStream_t s, LaunchHook* hook) {
   const MlpPlan& p = a.plan;
   float* ring = at<float>(a, p.off_ring);
-  uint16_t* shadow = at<uint16_t>(a, p.off_shadow) + (size_t)slot_next * p.shadow_stride;
-  UpdateArgs u;
-  u.partial = at<float>(a, p.off_partial);
-  u.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
-  u.ldp = (size_t)p.dp[l + 1];
-  u.nsplit = nsplit;
-  u.w_cur = ring + (size_t)slot_cur * p.slot_stride + p.w_off[l];
-  u.w_next = ring + (size_t)slot_next * p.slot_stride + p.w_off[l];
+  UpdateArgs u{};
   u.d_in = p.d[l];
   u.d_out = p.d[l + 1];
-  u.wn = l >= 1 ? shadow + p.wn_off[l] : nullptr;
   u.ldwn = (size_t)p.dp[l + 1];
-  u.wt = shadow + p.wt_off[l];
   u.ldwt = (size_t)p.dp[l];
-  const double n = (double)p.d[l] * p.d[l + 1];
-  hook->begin(KK_MLP_UPDATE, n * (nsplit + 1), n * (4.0 * (nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
-  const dim3 grid((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64), block(256);
+  int batch = 1;
+  if (mode == UPD_LOCAL) {
+    float* priv = at<float>(a, p.off_priv);
+    uint16_t* pshadow = at<uint16_t>(a, p.off_priv_shadow);
+    u.batched = 1;
+    batch = rd.K;
+    u.partial = at<float>(a, p.off_partial);
+    u.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
+    u.ldp = (size_t)p.dp[l + 1];
+    u.nsplit = 1;
+    u.w_cur = (step == 0 ? ring : priv) + p.w_off[l];
+    u.cur_stride = p.slot_stride;
+    for (int k = 0; k < rd.K; ++k) u.cur_index[k] = (uint16_t)(step == 0 ? rd.w[k].slot : (uint32_t)k);
+    u.w_next = priv + p.w_off[l];
+    u.next_stride = p.slot_stride;
+    u.wn = l >= 1 ? pshadow + p.wn_off[l] : nullptr;
+    u.wt = pshadow + p.wt_off[l];
+    u.shadow_stride = p.shadow_stride;
+  } else {
+    uint16_t* shadow = at<uint16_t>(a, p.off_shadow) + (size_t)rd.slot_next * p.shadow_stride;
+    if (mode == UPD_GLOBAL) {
+      u.partial = at<float>(a, p.off_partial);
+      u.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
+      u.ldp = (size_t)p.dp[l + 1];
+      u.nsplit = nsplit;
+    } else {
+      u.partial = at<float>(a, p.off_delta) + p.w_off[l];
+      u.split_stride = 0;
+      u.ldp = (size_t)p.d[l + 1];
+      u.nsplit = 1;
+    }
+    u.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride + p.w_off[l];
+    u.w_next = ring + (size_t)rd.slot_next * p.slot_stride + p.w_off[l];
+    u.wn = l >= 1 ? shadow + p.wn_off[l] : nullptr;
+    u.wt = shadow + p.wt_off[l];
+  }
+  const double n = (double)p.d[l] * p.d[l + 1] * batch;
+  hook->begin(KK_MLP_UPDATE, n * (u.nsplit + 1), n * (4.0 * (u.nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
+  const dim3 block(256);
   const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
-  if (vec) mlp_update_kernel<<<grid, block, 0, s>>>(u);
-  else     mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256), block, 0, s>>>(u);
+  if (vec) mlp_update_kernel<<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
+  else     mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, 0, s>>>(u);
   hook->end(KK_MLP_UPDATE);
 }
 
@@ -907,140 +1035,197 @@ hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s) {
   // padding of every bf16 weight copy must read as zero
   const size_t n16 = (size_t)p.R * p.shadow_stride * 2 / 16;
   mlp_fill_zero_kernel<<<dim3(1024), dim3(256), 0, s>>>(at<uint4>(a, p.off_shadow), n16);
+  if (p.U > 1)
+    mlp_fill_zero_kernel<<<dim3(1024), dim3(256), 0, s>>>(at<uint4>(a, p.off_priv_shadow),
+                                                          (size_t)p.N * p.shadow_stride * 2 / 16);
   NullHook nh;
-  for (int l = 0; l < p.L; ++l) launch_update(a, l, 0, 0, 0, s, &nh);   // bf16 copies of w^0
+  RoundDesc rd0{};                       // slot_cur = slot_next = 0, no partials: w^0 onto itself
+  for (int l = 0; l < p.L; ++l) launch_update(a, l, rd0, UPD_GLOBAL, 0, 0, s, &nh);   // bf16 copies of w^0
   return hipGetLastError();
 }
 
+// One pass of minibatch gradients for the K uploads of the round: U = 1 runs it once and folds
+// the K-of-N reduction into the weight-gradient contraction (Eq. 3); U > 1 runs it U times on
+// the uploads' private models (Eq. 2), each upload's weight gradient being its own range of
+// the stacked rows, and then averages the uploads' changes into w^{t+1}.
 hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s, LaunchHook* hook) {
   const MlpPlan& p = a.plan;
-  const int L = p.L, K = rd.K;
+  const int L = p.L, K = rd.K, U = p.U;
+  const bool local = U > 1;
   const int rows = K * p.Bp;                 // stacked rows incl. padding (multiple of 128)
   const double arows = (double)K * p.B;      // rows that carry samples
   const size_t Mp = (size_t)p.Mp;
   float* ring = at<float>(a, p.off_ring);
   const uint16_t* shadow = at<uint16_t>(a, p.off_shadow);
+  float* priv = local ? at<float>(a, p.off_priv) : nullptr;
+  const uint16_t* pshadow = local ? at<uint16_t>(a, p.off_priv_shadow) : nullptr;
   uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
   int32_t* label = at<int32_t>(a, p.off_label);
 
-  hook->begin(KK_MLP_INDEX, 0, arows * 12.0);
-  mlp_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, a.y, rd, p.B, p.Bp,
-                                                                  a.shard_rows, a.batch_key);
-  hook->end(KK_MLP_INDEX);
+  for (int step = 0; step < U; ++step) {
+    // where the uploads' models live during this step: the ring (by slot) or the private copies
+    const bool own = local && step > 0;
+    const float* wbase = own ? priv : ring;
+    const uint16_t* sbase = own ? pshadow : shadow;
 
-  hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
-  mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
-                                                                          at<uint16_t>(a, p.off_xgt), Mp);
-  hook->end(KK_MLP_GATHER_T);
+    hook->begin(KK_MLP_INDEX, 0, arows * 12.0);
+    mlp_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, a.y, rd, p.B, p.Bp,
+                                                                    a.shard_rows, a.batch_key,
+                                                                    (uint32_t)step * (uint32_t)p.B);
+    hook->end(KK_MLP_INDEX);
 
-  // ---- forward at the stale model versions
-  for (int l = 0; l < L; ++l) {
-    GemmArgs g{};
-    if (l == 0) { g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
-    else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.dp[l]; }
-    g.Bt = shadow + p.wt_off[l]; g.ldb = (size_t)p.dp[l];
-    g.bt_slot_stride = p.shadow_stride;
-    g.rows_per_upload = p.Bp;
-    g.ksteps_total = g.ksteps_per_split = p.dp[l] / BK;
-    g.bias = ring + p.b_off[l]; g.bias_slot_stride = p.slot_stride; g.n_valid = p.d[l + 1];
-    const double fl = 2.0 * arows * p.d[l] * p.d[l + 1];
-    if (l < L - 1) {
-      g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.dp[l + 1];
-      g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = Mp;
-      const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
-      hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
-      if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
-      else        launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
-      hook->end(kind);
-    } else {
-      g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
-      hook->begin(KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
-      launch_gemm<EPI_LOGITS, false, true>(g, rd, rows, p.dp[L], 1, s);
-      hook->end(KK_MLP_FWD_LOGITS);
-    }
-  }
+    hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
+    mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
+                                                                            at<uint16_t>(a, p.off_xgt), Mp);
+    hook->end(KK_MLP_GATHER_T);
 
-  // ---- loss and output gradient, already scaled by the uploads' coefficients
-  {
-    hook->begin(KK_MLP_SOFTMAX_CE, arows * p.d[L] * 8.0, arows * p.d[L] * 8.0);
-    const dim3 grid(rows / 64), block(1024);
-    const float* Z = at<float>(a, p.off_z);
-    uint16_t* dz = at<uint16_t>(a, p.off_dz[L]);
-    uint16_t* dzt = at<uint16_t>(a, p.off_dzt[L]);
-    float* rl = at<float>(a, p.off_rowloss);
-    const size_t ld = (size_t)p.dp[L];
-    switch (p.dp[L] / 64) {
-      case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
-      case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
-      default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
-    }
-    hook->end(KK_MLP_SOFTMAX_CE);
-    hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
-    mlp_loss_kernel<<<dim3(1), dim3(1024), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox);
-    hook->end(KK_MLP_LOSS);
-  }
-
-  // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
-  for (int l = L - 1; l >= 1; --l) {
-    GemmArgs g{};
-    g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.dp[l + 1];
-    g.Bt = shadow + p.wn_off[l]; g.ldb = (size_t)p.dp[l + 1];
-    g.bt_slot_stride = p.shadow_stride;
-    g.rows_per_upload = p.Bp;
-    g.ksteps_total = g.ksteps_per_split = p.dp[l + 1] / BK;
-    g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = Mp;
-    g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.dp[l];
-    g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = Mp;
-    // the product through the output layer contracts over the classes only: bandwidth-bound
-    const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
-    hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
-    if (l == L - 1) launch_gemm<EPI_DGRAD, false, true, 1>(g, rd, rows, p.dp[l], 1, s);
-    else            launch_gemm<EPI_DGRAD, false, true, 0>(g, rd, rows, p.dp[l], 1, s);
-    hook->end(kind);
-  }
-
-  // ---- weight gradients = K-of-N reduction (one contraction over all stacked rows),
-  //      then update + snapshot per layer
-  for (int l = L - 1; l >= 0; --l) {
-    GemmArgs g{};
-    g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = Mp;
-    g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = Mp;
-    const int ksteps = rows / BK;
-    const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
-    const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
-    const int tiles = big ? (p.dp[l] / TM3) * (p.dp[l + 1] / TN3) : (p.dp[l] / TM) * (p.dp[l + 1] / tn);
-    const int nsplit = big ? pick_split(tiles, ksteps, 256, 256.0 * 256 * 4)
-                           : pick_split(tiles, ksteps, 512, 128.0 * tn * 4);
-    g.ksteps_total = ksteps;
-    g.ksteps_per_split = (ksteps + nsplit - 1) / nsplit;
-    g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1];
-    g.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
-    const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
-    hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
-                arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
-    if (l == 0) launch_gemm<EPI_WGRAD, false, false, 1>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
-    else        launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
-    hook->end(kind);
-    launch_update(a, l, rd.slot_cur, rd.slot_next, nsplit, s, hook);
-  }
-
-  // ---- biases and the uploads' mean minibatch losses
-  {
-    BiasLossArgs b{};
-    b.L = L;
-    int c = 0;
+    // ---- forward at the uploads' model versions
     for (int l = 0; l < L; ++l) {
-      b.col_begin[l] = c; c += p.d[l + 1];
-      b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = Mp;
-      b.b_off[l] = p.b_off[l];
+      GemmArgs g{};
+      if (l == 0) { g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
+      else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.dp[l]; }
+      g.Bt = sbase + p.wt_off[l]; g.ldb = (size_t)p.dp[l];
+      g.bt_slot_stride = p.shadow_stride;
+      g.by_upload = own;
+      g.rows_per_upload = p.Bp;
+      g.ksteps_total = g.ksteps_per_split = p.dp[l] / BK;
+      g.bias = wbase + p.b_off[l]; g.bias_slot_stride = p.slot_stride; g.n_valid = p.d[l + 1];
+      const double fl = 2.0 * arows * p.d[l] * p.d[l + 1];
+      if (l < L - 1) {
+        g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.dp[l + 1];
+        g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = Mp;
+        const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
+        hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+        if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
+        else        launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+        hook->end(kind);
+      } else {
+        g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
+        hook->begin(KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+        launch_gemm<EPI_LOGITS, false, true>(g, rd, rows, p.dp[L], 1, s);
+        hook->end(KK_MLP_FWD_LOGITS);
+      }
     }
-    b.col_begin[L] = c;
-    b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
-    b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
-    b.rows = rows;
-    hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
-    mlp_bias_loss_kernel<<<dim3((c + 3) / 4), dim3(256), 0, s>>>(b);
-    hook->end(KK_MLP_BIAS_LOSS);
+
+    // ---- loss and output gradient, already scaled by the uploads' coefficients
+    {
+      hook->begin(KK_MLP_SOFTMAX_CE, arows * p.d[L] * 8.0, arows * p.d[L] * 8.0);
+      const dim3 grid(rows / 64), block(1024);
+      const float* Z = at<float>(a, p.off_z);
+      uint16_t* dz = at<uint16_t>(a, p.off_dz[L]);
+      uint16_t* dzt = at<uint16_t>(a, p.off_dzt[L]);
+      float* rl = at<float>(a, p.off_rowloss);
+      const size_t ld = (size_t)p.dp[L];
+      switch (p.dp[L] / 64) {
+        case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+        case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+        default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+      }
+      hook->end(KK_MLP_SOFTMAX_CE);
+      hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
+      mlp_loss_kernel<<<dim3(1), dim3(1024), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox,
+                                                     local ? at<float>(a, p.off_lossacc) : nullptr,
+                                                     step == 0, step == U - 1, U);
+      hook->end(KK_MLP_LOSS);
+    }
+
+    // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
+    for (int l = L - 1; l >= 1; --l) {
+      GemmArgs g{};
+      g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.dp[l + 1];
+      g.Bt = sbase + p.wn_off[l]; g.ldb = (size_t)p.dp[l + 1];
+      g.bt_slot_stride = p.shadow_stride;
+      g.by_upload = own;
+      g.rows_per_upload = p.Bp;
+      g.ksteps_total = g.ksteps_per_split = p.dp[l + 1] / BK;
+      g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = Mp;
+      g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.dp[l];
+      g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = Mp;
+      // the product through the output layer contracts over the classes only: bandwidth-bound
+      const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
+      hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
+      if (l == L - 1) launch_gemm<EPI_DGRAD, false, true, 1>(g, rd, rows, p.dp[l], 1, s);
+      else            launch_gemm<EPI_DGRAD, false, true, 0>(g, rd, rows, p.dp[l], 1, s);
+      hook->end(kind);
+    }
+
+    // ---- weight gradients.  U = 1: one contraction over all stacked rows = the K-of-N
+    //      reduction, split over row ranges for occupancy, then update + snapshot per layer.
+    //      U > 1: split a = the rows of upload a, applied to that upload's private model.
+    for (int l = L - 1; l >= 0; --l) {
+      GemmArgs g{};
+      g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = Mp;
+      g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = Mp;
+      const int ksteps = rows / BK;
+      const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
+      const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
+      const int tiles = big ? (p.dp[l] / TM3) * (p.dp[l + 1] / TN3) : (p.dp[l] / TM) * (p.dp[l + 1] / tn);
+      const int nsplit = local ? K
+                         : big ? pick_split(tiles, ksteps, 256, 256.0 * 256 * 4)
+                               : pick_split(tiles, ksteps, 512, 128.0 * tn * 4);
+      g.ksteps_total = ksteps;
+      g.ksteps_per_split = local ? p.Bp / BK : (ksteps + nsplit - 1) / nsplit;
+      g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1];
+      g.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
+      const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
+      hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
+                  arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
+      if (l == 0) launch_gemm<EPI_WGRAD, false, false, 1>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+      else        launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+      hook->end(kind);
+      launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, nsplit, s, hook);
+    }
+
+    // ---- biases
+    int c = 0;
+    if (!local) {
+      BiasLossArgs b{};
+      b.L = L;
+      for (int l = 0; l < L; ++l) {
+        b.col_begin[l] = c; c += p.d[l + 1];
+        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = Mp;
+        b.b_off[l] = p.b_off[l];
+      }
+      b.col_begin[L] = c;
+      b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
+      b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
+      b.rows = rows;
+      hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
+      mlp_bias_loss_kernel<<<dim3((c + 3) / 4), dim3(256), 0, s>>>(b);
+      hook->end(KK_MLP_BIAS_LOSS);
+    } else {
+      BiasLocalArgs b{};
+      b.L = L; b.K = K; b.Bp = p.Bp;
+      for (int l = 0; l < L; ++l) {
+        b.col_begin[l] = c; c += p.d[l + 1];
+        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = Mp;
+        b.b_off[l] = p.b_off[l];
+      }
+      b.col_begin[L] = c;
+      b.cur = wbase; b.cur_stride = p.slot_stride;
+      b.priv = priv; b.priv_stride = p.slot_stride;
+      for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
+      hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
+      mlp_bias_local_kernel<<<dim3((c + 3) / 4, K), dim3(256), 0, s>>>(b);
+      hook->end(KK_MLP_BIAS_LOSS);
+    }
+  }
+
+  if (local) {
+    // ---- Eq. 3 over the uploads' changes, then update + snapshot per layer
+    DeltaArgs d{};
+    d.ring = ring; d.slot_stride = p.slot_stride;
+    d.priv = priv;
+    d.D = at<float>(a, p.off_delta);
+    d.P = p.P;
+    d.L = L;
+    for (int l = 0; l < L; ++l) { d.b_off[l] = p.b_off[l]; d.b_len[l] = p.d[l + 1]; }
+    d.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
+    d.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
+    hook->begin(KK_DELTA_UPDATE, 2.0 * K * p.P, (2.0 * K + 1.0) * p.P * 4.0);
+    mlp_delta_kernel<<<dim3((unsigned)((p.P + 255) / 256)), dim3(256), 0, s>>>(d, rd);
+    hook->end(KK_DELTA_UPDATE);
+    for (int l = L - 1; l >= 0; --l) launch_update(a, l, rd, UPD_DELTA, 0, 1, s, hook);
   }
   return hipGetLastError();
 }

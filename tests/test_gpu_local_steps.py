@@ -42,3 +42,25 @@ def test_linear_local_steps(over, T):
 def test_softmax_local_steps(over, T):
     p = workloads.scaled_preset(2, **over)
     _check(run_pair(p, T, checkpoints=(1, 5)), 1e-5, 1e-4)
+
+
+@pytest.mark.parametrize("over,T", [
+    # two layers, ragged B and d_0, every upload's private copy in use from step 1 on
+    (dict(U=3, M=4096, dims=[200, 96, 10], N=8, B=40, n_slow=2, lr=1e-3), 30),
+    # three layers on the 256 x 256 tile kernel, uploads of two row tiles
+    (dict(U=2, M=8192, dims=[256, 256, 512, 10], N=6, B=256, K0=2, n_slow=1, lr=5e-4), 12),
+    # staleness-aware step, restarts, narrow layers, 3 classes
+    (dict(U=4, M=4096, dims=[128, 64, 3], n_classes=3, N=16, B=16, n_slow=4, sa_penalty=1,
+          tau_mode=1, tau_cap=1, lr=2e-3), 40),
+    # 100 classes (128-wide logits), B = one tile
+    (dict(U=2, M=8192, dims=[256, 128, 256, 100], n_classes=100, N=8, B=128, n_slow=0, lr=5e-4), 12),
+])
+def test_mlp_local_steps(over, T):
+    p = workloads.scaled_preset(3, **over)
+    _check(run_pair(p, T, checkpoints=(1, 5)), 2e-2, 2e-3)       # the bf16 workloads' tolerance
+
+
+def test_cfg3_shape_local_steps():
+    """The 3072-512-10 workload at its real layer and batch shapes (shorter dataset) with U = 2."""
+    p = workloads.scaled_preset(3, M=6400, U=2)
+    _check(run_pair(p, 8, checkpoints=(1,)), 2e-2, 2e-3)
