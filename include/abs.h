@@ -8,7 +8,7 @@
  * w^{t - tau} of the global model, and applies Eq. 3.  Section III adds the
  * two adaptive rules: the wait count K^t (Eq. 5) and the staleness threshold
  * tau_max^t (Eq. 4) that forces over-stale workers to restart (Eq. 6,
- * Algorithm 1).  This library runs that loop with U = 1 local step: a host
+ * Algorithm 1).  This library runs that loop with U >= 1 local steps: a host
  * event-queue scheduler draws execution times, selects the K^t fastest
  * workers and applies Eq. 4-6; HIP kernels compute the K^t gradients at mixed
  * model versions out of a device-resident ring of past global models, reduce
@@ -137,7 +137,7 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
                void* d_workspace, size_t workspace_bytes, void* hip_stream, abs_ctx** out);
 
 /* Advance n_rounds parameter-server rounds (Algorithm 1, server part, with the
- * workers' gradients of Eq. 2 at U = 1 and the update of Eq. 3).  Returns when the
+ * workers' U local steps of Eq. 2 and the update of Eq. 3).  Returns when the
  * host has every round's trace record, i.e. after the last round's losses arrived;
  * the tail of that round's device work (backward pass, update, snapshot) may still be
  * running on the stream.  abs_get_model and abs_destroy synchronise the stream. */
