@@ -71,6 +71,8 @@ namespace abs_impl {
 struct MlpPlan {
   int L;                 // weight matrices
   int d[8], dp[8];       // layer widths and their padded values
+  int ld[8];             // row pitch (elements) of the bf16 arrays with dp[l] columns
+  size_t ldm;            // row pitch of the transposed arrays [dp_l][Mp]
   int B, Bp;             // minibatch rows per upload, padded to the row tile
   int N, Mp;             // workers; Mp = N * Bp stacked rows at most
   int R;                 // ring slots
@@ -78,12 +80,12 @@ struct MlpPlan {
   size_t slot_stride;    // floats between fp32 ring slots
   size_t w_off[8], b_off[8];      // W_l / b_l inside a slot (floats), l = 0 .. L-1
   size_t shadow_stride;           // bf16 elements between shadow slots
-  size_t wt_off[8], wn_off[8];    // bf16 W_l^T [dp_out][dp_in] / W_l [dp_in][dp_out] inside a shadow slot
+  size_t wt_off[8], wn_off[8];    // bf16 W_l^T [dp_out][ld_in] / W_l [dp_in][ld_out] inside a shadow slot
   // byte offsets into the workspace
   size_t off_ring, off_shadow, off_rowidx, off_label, off_xgt;
-  size_t off_h[8], off_ht[8];     // H_l [Mp][dp_l], H_l^T [dp_l][Mp], l = 1 .. L-1
+  size_t off_h[8], off_ht[8];     // H_l [Mp][ld_l], H_l^T [dp_l][ldm], l = 1 .. L-1
   size_t off_z;                   // logits fp32 [Mp][dp_L]
-  size_t off_dz[8], off_dzt[8];   // dZ_l [Mp][dp_l], dZ_l^T [dp_l][Mp], l = 1 .. L
+  size_t off_dz[8], off_dzt[8];   // dZ_l [Mp][ld_l], dZ_l^T [dp_l][ldm], l = 1 .. L
   size_t off_rowloss, off_partial;
   size_t partial_floats;
   // local SGD (U > 1): the uploads' private models (same slot layouts as the two rings),

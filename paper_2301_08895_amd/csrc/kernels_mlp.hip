@@ -35,6 +35,13 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int TM = 128;   // rows of C per workgroup
 constexpr int BK = 64;    // contraction elements per main-loop step
 constexpr int kMaxSplit = 16;
+// Row pitches of the bf16 operand arrays are the padded width plus this many elements (128 B):
+// with a pitch that is a multiple of 4 KB the same 128-byte column of every row of a tile maps
+// to one L2 channel, and all workgroups walk the k dimension in step.
+#ifndef ABS_PITCH_PAD
+#define ABS_PITCH_PAD 64
+#endif
+constexpr int kPitchPad = ABS_PITCH_PAD;
 
 size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
@@ -880,11 +887,13 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
     p.dp[l] = (int)round_up((size_t)c.dims[l], 128);
   }
   if (c.dims[L] <= 64) p.dp[L] = 64;
+  for (int l = 0; l <= L; ++l) p.ld[l] = p.dp[l] + kPitchPad;
   p.U = c.U > 1 ? c.U : 1;
   p.B = c.B;
   p.Bp = (int)round_up((size_t)c.B, TM);
   p.N = c.N;
   p.Mp = c.N * p.Bp;
+  p.ldm = (size_t)p.Mp + kPitchPad;
   p.R = c.tau_cap + 3;
   size_t o = 0;
   for (int l = 0; l < L; ++l) {
@@ -895,8 +904,8 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   p.slot_stride = round_up(p.P, 64);
   o = 0;
   for (int l = 0; l < L; ++l) {
-    p.wt_off[l] = o; o += (size_t)p.dp[l + 1] * p.dp[l];
-    p.wn_off[l] = o; if (l >= 1) o += (size_t)p.dp[l] * p.dp[l + 1];
+    p.wt_off[l] = o; o += (size_t)p.dp[l + 1] * p.ld[l];
+    p.wn_off[l] = o; if (l >= 1) o += (size_t)p.dp[l] * p.ld[l + 1];
   }
   p.shadow_stride = round_up(o, 128);
   size_t partial = 0;
@@ -910,15 +919,15 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   p.off_shadow = take((size_t)p.R * p.shadow_stride * 2);
   p.off_rowidx = take(Mp * 4);
   p.off_label = take(Mp * 4);
-  p.off_xgt = take((size_t)p.dp[0] * Mp * 2);
+  p.off_xgt = take((size_t)p.dp[0] * p.ldm * 2);
   for (int l = 1; l < L; ++l) {
-    p.off_h[l] = take(Mp * p.dp[l] * 2);
-    p.off_ht[l] = take(Mp * p.dp[l] * 2);
+    p.off_h[l] = take(Mp * p.ld[l] * 2);
+    p.off_ht[l] = take(p.ldm * p.dp[l] * 2);
   }
   p.off_z = take(Mp * p.dp[L] * 4);
   for (int l = 1; l <= L; ++l) {
-    p.off_dz[l] = take(Mp * p.dp[l] * 2);
-    p.off_dzt[l] = take(Mp * p.dp[l] * 2);
+    p.off_dz[l] = take(Mp * p.ld[l] * 2);
+    p.off_dzt[l] = take(p.ldm * p.dp[l] * 2);
   }
   p.off_rowloss = take(Mp * 4);
   p.off_partial = take(p.partial_floats * 4);
@@ -953,8 +962,8 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
   UpdateArgs u{};
   u.d_in = p.d[l];
   u.d_out = p.d[l + 1];
-  u.ldwn = (size_t)p.dp[l + 1];
-  u.ldwt = (size_t)p.dp[l];
+  u.ldwn = (size_t)p.ld[l + 1];
+  u.ldwt = (size_t)p.ld[l];
   int batch = 1;
   if (mode == UPD_LOCAL) {
     float* priv = at<float>(a, p.off_priv);
@@ -1054,7 +1063,6 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
   const bool local = U > 1;
   const int rows = K * p.Bp;                 // stacked rows incl. padding (multiple of 128)
   const double arows = (double)K * p.B;      // rows that carry samples
-  const size_t Mp = (size_t)p.Mp;
   float* ring = at<float>(a, p.off_ring);
   const uint16_t* shadow = at<uint16_t>(a, p.off_shadow);
   float* priv = local ? at<float>(a, p.off_priv) : nullptr;
@@ -1076,15 +1084,15 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
 
     hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
     mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
-                                                                            at<uint16_t>(a, p.off_xgt), Mp);
+                                                                            at<uint16_t>(a, p.off_xgt), p.ldm);
     hook->end(KK_MLP_GATHER_T);
 
     // ---- forward at the uploads' model versions
     for (int l = 0; l < L; ++l) {
       GemmArgs g{};
       if (l == 0) { g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
-      else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.dp[l]; }
-      g.Bt = sbase + p.wt_off[l]; g.ldb = (size_t)p.dp[l];
+      else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.ld[l]; }
+      g.Bt = sbase + p.wt_off[l]; g.ldb = (size_t)p.ld[l];
       g.bt_slot_stride = p.shadow_stride;
       g.by_upload = own;
       g.rows_per_upload = p.Bp;
@@ -1092,8 +1100,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       g.bias = wbase + p.b_off[l]; g.bias_slot_stride = p.slot_stride; g.n_valid = p.d[l + 1];
       const double fl = 2.0 * arows * p.d[l] * p.d[l + 1];
       if (l < L - 1) {
-        g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.dp[l + 1];
-        g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = Mp;
+        g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.ld[l + 1];
+        g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = p.ldm;
         const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
         hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
         if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
@@ -1115,11 +1123,11 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       uint16_t* dz = at<uint16_t>(a, p.off_dz[L]);
       uint16_t* dzt = at<uint16_t>(a, p.off_dzt[L]);
       float* rl = at<float>(a, p.off_rowloss);
-      const size_t ld = (size_t)p.dp[L];
+      const size_t ld = (size_t)p.dp[L], lddz = (size_t)p.ld[L];
       switch (p.dp[L] / 64) {
-        case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
-        case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
-        default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, ld, dzt, Mp, rl); break;
+        case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl); break;
+        case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl); break;
+        default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl); break;
       }
       hook->end(KK_MLP_SOFTMAX_CE);
       hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
@@ -1132,15 +1140,15 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
     for (int l = L - 1; l >= 1; --l) {
       GemmArgs g{};
-      g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.dp[l + 1];
-      g.Bt = sbase + p.wn_off[l]; g.ldb = (size_t)p.dp[l + 1];
+      g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.ld[l + 1];
+      g.Bt = sbase + p.wn_off[l]; g.ldb = (size_t)p.ld[l + 1];
       g.bt_slot_stride = p.shadow_stride;
       g.by_upload = own;
       g.rows_per_upload = p.Bp;
       g.ksteps_total = g.ksteps_per_split = p.dp[l + 1] / BK;
-      g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = Mp;
-      g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.dp[l];
-      g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = Mp;
+      g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = p.ldm;
+      g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.ld[l];
+      g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = p.ldm;
       // the product through the output layer contracts over the classes only: bandwidth-bound
       const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
       hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
@@ -1154,8 +1162,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     //      U > 1: split a = the rows of upload a, applied to that upload's private model.
     for (int l = L - 1; l >= 0; --l) {
       GemmArgs g{};
-      g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = Mp;
-      g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = Mp;
+      g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = p.ldm;
+      g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = p.ldm;
       const int ksteps = rows / BK;
       const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
       const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
@@ -1183,7 +1191,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       b.L = L;
       for (int l = 0; l < L; ++l) {
         b.col_begin[l] = c; c += p.d[l + 1];
-        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = Mp;
+        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = p.ldm;
         b.b_off[l] = p.b_off[l];
       }
       b.col_begin[L] = c;
@@ -1198,7 +1206,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       b.L = L; b.K = K; b.Bp = p.Bp;
       for (int l = 0; l < L; ++l) {
         b.col_begin[l] = c; c += p.d[l + 1];
-        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = Mp;
+        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = p.ldm;
         b.b_off[l] = p.b_off[l];
       }
       b.col_begin[L] = c;
