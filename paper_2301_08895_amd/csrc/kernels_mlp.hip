@@ -363,7 +363,8 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 // flight during all of step k and there is one barrier per step.  The XOR swizzle is
 // applied on the global side: the lane that fills chunk position p of row r fetches
 // logical chunk p ^ ((r >> 1) & 7).
-// Needs: row count and column count multiples of 256, GATHER with d_0 % 64 == 0.
+// Needs: row count and column count multiples of 256, GATHER with d_0 equal to the padded
+// k extent (d_0 % 128 == 0: a gathered row is read over the whole k range).
 constexpr int TM3 = 256, TN3 = 256;
 constexpr int kStage3 = (TM3 + TN3) * BK;            // elements per LDS stage (64 KB)
 constexpr int kEpiPitch3 = 64 + 8;                   // per wavefront: staging [64 n][72] and [64 m][72]
@@ -1013,7 +1014,7 @@ template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
 void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   g.nsplit = nsplit;
   const bool big = Mdim % TM3 == 0 && Ndim % TN3 == 0 && (!PER_UPLOAD || g.rows_per_upload % TM3 == 0) &&
-                   (!GATHER || g.a_kvalid % BK == 0) && (Mdim / TM3) * (Ndim / TN3) * nsplit >= 128;
+                   (!GATHER || g.a_kvalid == g.ksteps_total * BK) && (Mdim / TM3) * (Ndim / TN3) * nsplit >= 128;
   if (big) {
     g.mt = Mdim / TM3;
     g.nt = Ndim / TN3;
