@@ -148,6 +148,21 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds);
 int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats);
 
 /*
+ * Held-out evaluation of global model w^version (-1 = the latest): the read-outs the paper
+ * plots against wall-clock time and communication rounds (Section V-B).  *h_loss is the mean
+ * per-sample loss f(w; xi) of Eq. 1 over the n_rows evaluation rows, *h_accuracy the fraction of
+ * rows whose largest logit is the label (ties: the lowest class; NaN for the linear model).
+ *  d_X, d_y   DEVICE, caller-owned, [n_rows, d_0] and [n_rows] in the dtypes of the training
+ *             payload; read only.  1 <= n_rows < 2^32.
+ * The forward pass is the training one (MLP: bf16 weights of that version, bf16 hidden
+ * activations, fp32 logits); row losses are added in a fixed order in fp64.  Runs on the
+ * handle's stream after the rounds enqueued so far and synchronises it.  The version must still
+ * be in the ring (ABS_E_VERSION otherwise).  Does not change the simulation.
+ */
+int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
+                 double* h_loss, double* h_accuracy);
+
+/*
  * Copy trace records of rounds [round_lo, round_hi) to h_out.  One record is
  * ABS_TRACE_HEADER + 3 N int32 words:
  *   0 t   1 K^t   2 floor(tau_max^t) (INT32_MAX: none)   3,4 completion tick lo,hi

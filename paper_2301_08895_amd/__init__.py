@@ -5,11 +5,11 @@ only loads it and marshals arguments.  There is no CPU fallback: importing
 `binding` without a built library raises.
 """
 from .binding import (AbsConfig, AbsError, abs_config_bytes, abs_workspace_size, abs_create,
-                      abs_round, abs_get_model, abs_trace, abs_rounds_done, abs_kernel_stats,
+                      abs_round, abs_get_model, abs_evaluate, abs_trace, abs_rounds_done, abs_kernel_stats,
                       abs_last_error, abs_destroy, abs_draw_time_ticks, abs_draw_batch_rows,
                       make_config, trace_stride, Simulation, library_path)
 
 __all__ = ["AbsConfig", "AbsError", "abs_config_bytes", "abs_workspace_size", "abs_create",
-           "abs_round", "abs_get_model", "abs_trace", "abs_rounds_done", "abs_kernel_stats",
+           "abs_round", "abs_get_model", "abs_evaluate", "abs_trace", "abs_rounds_done", "abs_kernel_stats",
            "abs_last_error", "abs_destroy", "abs_draw_time_ticks", "abs_draw_batch_rows",
            "make_config", "trace_stride", "Simulation", "library_path"]

@@ -62,6 +62,8 @@ def _load():
     lib.abs_create.argtypes = [cfgp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
     lib.abs_round.restype = C.c_int
     lib.abs_round.argtypes = [vp, i32]
+    lib.abs_evaluate.restype = C.c_int
+    lib.abs_evaluate.argtypes = [vp, i64, vp, vp, i64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.abs_get_model.restype = C.c_int
     lib.abs_get_model.argtypes = [vp, i64, C.POINTER(C.c_float), sz]
     lib.abs_trace.restype = C.c_int
@@ -153,6 +155,13 @@ def abs_get_model(handle: int, version: int, n_floats: int) -> np.ndarray:
     return out
 
 
+def abs_evaluate(handle: int, version: int, d_X: int, d_y: int, n_rows: int):
+    """(mean loss, accuracy) of model `version` on an evaluation set given by device pointers."""
+    loss, acc = C.c_double(), C.c_double()
+    _check(_lib.abs_evaluate(handle, version, d_X, d_y, n_rows, C.byref(loss), C.byref(acc)), handle)
+    return loss.value, acc.value
+
+
 def abs_trace(handle: int, round_lo: int, round_hi: int, N: int) -> np.ndarray:
     stride = trace_stride(N)
     out = np.empty((max(0, round_hi - round_lo), stride), dtype=np.int32)
@@ -234,6 +243,13 @@ class Simulation:
 
     def model(self, version: int = -1) -> np.ndarray:
         return abs_get_model(self.handle, version, self.P)
+
+    def evaluate(self, X: np.ndarray, y: np.ndarray, version: int = -1):
+        """Held-out loss and accuracy of a model version; X, y are host arrays in the payload's dtypes."""
+        dev = self.d_X.device
+        xt = self.torch.from_numpy(X.view(np.int16) if X.dtype == np.uint16 else X).to(dev)
+        yt = self.torch.from_numpy(y).to(dev)
+        return abs_evaluate(self.handle, version, xt.data_ptr(), yt.data_ptr(), int(X.shape[0]))
 
     def trace(self, lo: int = 0, hi: int | None = None) -> np.ndarray:
         hi = abs_rounds_done(self.handle) if hi is None else hi

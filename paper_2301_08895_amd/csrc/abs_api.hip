@@ -31,7 +31,7 @@ size_t param_count(const abs_config& c) {
 // Workspace of the two regression models.
 struct RegPlan {
   size_t slot_stride;   // floats
-  size_t off_ring, off_dz, off_rowloss, off_rowidx, off_delta, off_lossbuf, total;
+  size_t off_ring, off_dz, off_rowloss, off_rowidx, off_delta, off_lossbuf, off_eval, total;
 };
 
 bool validate(const abs_config& c, std::string& why) {
@@ -89,6 +89,7 @@ void reg_plan(const abs_config& c, RegPlan& p) {
   p.off_rowidx = o;  o = round_up(o + rows * 4, 256);
   p.off_delta = o;   if (c.U > 1) o = round_up(o + (size_t)c.N * p.slot_stride * 4, 256);
   p.off_lossbuf = o; if (c.U > 1) o = round_up(o + (size_t)c.N * 4, 256);
+  p.off_eval = o;    o = round_up(o + eval_scratch_bytes(kEvalChunk), 256);
   p.total = o;
 }
 
@@ -100,7 +101,7 @@ const char* abs_impl::kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {
       "linreg_round", "softmax_rows", "softmax_update", "mlp_index", "mlp_gather_t", "mlp_fwd_l1",
       "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_softmax_ce", "mlp_loss", "mlp_dgrad_out", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
-      "mlp_update", "mlp_bias_loss", "local_steps", "delta_update"};
+      "mlp_update", "mlp_bias_loss", "local_steps", "delta_update", "evaluate"};
   return kind >= 0 && kind < KK_COUNT ? names[kind] : "?";
 }
 
@@ -354,6 +355,44 @@ int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats) 
   const char* src = ctx->ws + ctx->off_ring + (size_t)(version % ctx->R) * ctx->slot_stride * sizeof(float);
   ABS_HIP(ctx, hipMemcpyAsync(h_out, src, n_floats * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
   ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return ABS_OK;
+}
+
+int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
+                 double* h_loss, double* h_accuracy) {
+  if (!ctx || !h_loss || !h_accuracy) return ABS_E_ARG;
+  if (!ctx->cfg.device_mode) { ctx->err = "no model in schedule-only mode"; return ABS_E_ARG; }
+  if (!d_X || !d_y) { ctx->err = "evaluation set pointers are NULL"; return ABS_E_ARG; }
+  if (n_rows < 1 || n_rows > 0xFFFFFFFFll) { ctx->err = "n_rows must be in [1, 2^32)"; return ABS_E_ARG; }
+  const int64_t t = ctx->sched->round();
+  if (version < 0) version = t;
+  if (version > t || version < t - (ctx->R - 1) || version < 0) {
+    ctx->err = "model version not in the ring"; return ABS_E_VERSION;
+  }
+  const abs_config& cfg = ctx->cfg;
+  const uint32_t slot = (uint32_t)(version % ctx->R);
+  const bool mlp = cfg.model == ABS_MODEL_MLP;
+  char* scratch = ctx->ws + (mlp ? ctx->margs.plan.off_eval : ctx->rplan.off_eval);
+  EvalArgs e;
+  e.X = d_X; e.y = d_y; e.n_rows = n_rows;
+  e.cap = mlp ? ctx->margs.plan.Mp : kEvalChunk;
+  e.acc = (double*)scratch;
+  e.rowloss = (float*)(scratch + 256);
+  e.correct = (float*)(scratch + 256 + ((size_t)e.cap * 4 + 255) / 256 * 256);
+  hipError_t err;
+  if (mlp) {
+    err = launch_mlp_eval(ctx->margs, slot, e, ctx->stream, ctx);
+  } else {
+    const float* w = (const float*)(ctx->ws + ctx->off_ring) + (size_t)slot * ctx->slot_stride;
+    err = launch_regression_eval(w, cfg.dims[0], cfg.dims[1], cfg.model == ABS_MODEL_SOFTMAX, e, ctx->stream, ctx);
+  }
+  if (err != hipSuccess) { ctx->err = std::string("kernel launch: ") + hipGetErrorString(err); return ABS_E_HIP; }
+  double acc[2];
+  ABS_HIP(ctx, hipMemcpyAsync(acc, e.acc, sizeof(acc), hipMemcpyDeviceToHost, ctx->stream));
+  ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (cfg.profile) ctx->harvest();
+  *h_loss = acc[0] / (double)n_rows;
+  *h_accuracy = cfg.model == ABS_MODEL_LINEAR ? std::nan("") : acc[1] / (double)n_rows;
   return ABS_OK;
 }
 

@@ -31,6 +31,7 @@ enum KernelKind {
   KK_MLP_BIAS_LOSS,
   KK_LOCAL_STEPS,
   KK_DELTA_UPDATE,
+  KK_EVAL,
   KK_COUNT
 };
 const char* kernel_kind_name(int kind);
@@ -62,6 +63,26 @@ hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hi
 hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDesc& rd, bool softmax,
                                          hipStream_t s, LaunchHook* hook);
 
+// ---- held-out evaluation (the read-outs of Section V-B: loss of the global model, accuracy) ----
+// Per-row losses and "argmax is the label" flags go to a scratch of `cap` rows; a single
+// workgroup adds them, in a fixed order and in fp64, to acc[0] (loss sum) and acc[1] (hits).
+constexpr int kEvalChunk = 16384;          // rows per pass of the regression models
+struct EvalArgs {
+  const void* X;         // evaluation rows, dtype and layout of the training payload
+  const void* y;         // their targets
+  int64_t n_rows;
+  double* acc;           // [2], cleared by the launch
+  float* rowloss;        // [cap]
+  float* correct;        // [cap]
+  int cap;
+};
+inline size_t eval_scratch_bytes(size_t cap) { return 256 + 2 * ((cap * 4 + 255) / 256 * 256); }
+hipError_t launch_eval_clear(const EvalArgs& e, hipStream_t s);
+hipError_t launch_eval_reduce(const EvalArgs& e, int n, hipStream_t s, LaunchHook* hook);
+// w: the model version to evaluate (fp32, boundary layout); softmax = false: linear least squares
+hipError_t launch_regression_eval(const float* w, int d, int C, bool softmax, const EvalArgs& e,
+                                  hipStream_t s, LaunchHook* hook);
+
 }  // namespace abs_impl
 
 namespace abs_impl {
@@ -92,6 +113,7 @@ struct MlpPlan {
   // their running mean losses, and the averaged change of Eq. 3
   int U;
   size_t off_priv, off_priv_shadow, off_lossacc, off_delta;
+  size_t off_eval;       // evaluation scratch for Mp rows
   size_t total;
 };
 // Returns false (with a message) if the configuration is not supported.
@@ -108,5 +130,7 @@ struct MlpArgs {
 // One-time preparation on the stream: zero the padded buffers, build the bf16 copies of w^0.
 hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s);
 hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s, LaunchHook* hook);
+// forward pass of ring slot `slot` over e.n_rows evaluation rows, Mp rows at a time (e.cap >= Mp)
+hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, hipStream_t s, LaunchHook* hook);
 
 }  // namespace abs_impl

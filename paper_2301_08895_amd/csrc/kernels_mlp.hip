@@ -852,6 +852,52 @@ __global__ void mlp_fill_zero_kernel(uint4* p, size_t n16) {
   for (; i < n16; i += step) p[i] = make_uint4(0, 0, 0, 0);
 }
 
+// ------------------------------------------------------------------ held-out evaluation
+// Sequential evaluation rows row0 .. row0 + n in the index arrays of the forward pass; the
+// padding rows read a valid row and carry label -1.
+__global__ void mlp_eval_index_kernel(uint32_t* rowidx, int32_t* label, const int32_t* y, int64_t row0, int n,
+                                      int rows) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= rows) return;
+  rowidx[m] = (uint32_t)(row0 + (m < n ? m : 0));
+  label[m] = m < n ? y[row0 + m] : -1;
+}
+
+// One wavefront per row of the logits: -log softmax(z)_y and whether the first largest logit
+// is the label.  NC = logits width / 64.
+template <int NC>
+__global__ __launch_bounds__(256) void mlp_eval_rows_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
+                                                            int n, float* rowloss, float* correct) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= n) return;
+  const int lab = label[m];
+  float z[NC], zmax = -INFINITY;
+  int best = 0;
+#pragma unroll
+  for (int q = 0; q < NC; ++q) {
+    const int c = lane + 64 * q;
+    z[q] = c < C ? Z[(size_t)m * ldz + c] : -INFINITY;
+    if (z[q] > zmax) { zmax = z[q]; best = c; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {            // largest value, lowest class among equals
+    const float ov = __shfl_xor(zmax, o, 64);
+    const int ob = __shfl_xor(best, o, 64);
+    if (ov > zmax || (ov == zmax && ob < best)) { zmax = ov; best = ob; }
+  }
+  float ssum = 0.f, zy = 0.f;
+#pragma unroll
+  for (int q = 0; q < NC; ++q) {
+    const int c = lane + 64 * q;
+    if (c == lab) zy = z[q] - zmax;
+    ssum += c < C ? expf(z[q] - zmax) : 0.f;
+  }
+  ssum = wave_sum(ssum);
+  zy = wave_sum(zy);
+  if (lane == 0) { rowloss[m] = logf(ssum) - zy; correct[m] = best == lab ? 1.f : 0.f; }
+}
+
 template <typename T>
 T* at(const MlpArgs& a, size_t off) { return (T*)(a.ws + off); }
 
@@ -938,6 +984,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
     p.off_lossacc = take((size_t)c.N * 4);
     p.off_delta = take(p.slot_stride * 4);
   }
+  p.off_eval = take(eval_scratch_bytes((size_t)p.Mp));
   p.total = b;
   return true;
 }
@@ -1038,6 +1085,42 @@ void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   else                mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
 }
 
+// Forward pass over `rows` stacked rows (rowidx gives the rows of Xsrc): H_l and H_l^T for the
+// hidden layers, fp32 logits; the model of the rows of upload a is slot rd.w[a].slot of the
+// ring given by wbase / sbase (own: slot a of the private models).
+void mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd, int rows, double arows,
+                 const float* wbase, const uint16_t* sbase, bool own, hipStream_t s, LaunchHook* hook) {
+  const MlpPlan& p = a.plan;
+  const int L = p.L;
+  const uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
+  for (int l = 0; l < L; ++l) {
+    GemmArgs g{};
+    if (l == 0) { g.A = Xsrc; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
+    else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.ld[l]; }
+    g.Bt = sbase + p.wt_off[l]; g.ldb = (size_t)p.ld[l];
+    g.bt_slot_stride = p.shadow_stride;
+    g.by_upload = own;
+    g.rows_per_upload = p.Bp;
+    g.ksteps_total = g.ksteps_per_split = p.dp[l] / BK;
+    g.bias = wbase + p.b_off[l]; g.bias_slot_stride = p.slot_stride; g.n_valid = p.d[l + 1];
+    const double fl = 2.0 * arows * p.d[l] * p.d[l + 1];
+    if (l < L - 1) {
+      g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.ld[l + 1];
+      g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = p.ldm;
+      const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
+      hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+      if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      else        launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      hook->end(kind);
+    } else {
+      g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
+      hook->begin(KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+      launch_gemm<EPI_LOGITS, false, true>(g, rd, rows, p.dp[L], 1, s);
+      hook->end(KK_MLP_FWD_LOGITS);
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s) {
@@ -1089,32 +1172,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     hook->end(KK_MLP_GATHER_T);
 
     // ---- forward at the uploads' model versions
-    for (int l = 0; l < L; ++l) {
-      GemmArgs g{};
-      if (l == 0) { g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
-      else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.ld[l]; }
-      g.Bt = sbase + p.wt_off[l]; g.ldb = (size_t)p.ld[l];
-      g.bt_slot_stride = p.shadow_stride;
-      g.by_upload = own;
-      g.rows_per_upload = p.Bp;
-      g.ksteps_total = g.ksteps_per_split = p.dp[l] / BK;
-      g.bias = wbase + p.b_off[l]; g.bias_slot_stride = p.slot_stride; g.n_valid = p.d[l + 1];
-      const double fl = 2.0 * arows * p.d[l] * p.d[l + 1];
-      if (l < L - 1) {
-        g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.ld[l + 1];
-        g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = p.ldm;
-        const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
-        hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
-        if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
-        else        launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
-        hook->end(kind);
-      } else {
-        g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
-        hook->begin(KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
-        launch_gemm<EPI_LOGITS, false, true>(g, rd, rows, p.dp[L], 1, s);
-        hook->end(KK_MLP_FWD_LOGITS);
-      }
-    }
+    mlp_forward(a, a.X, rd, rows, arows, wbase, sbase, own, s, hook);
 
     // ---- loss and output gradient, already scaled by the uploads' coefficients
     {
@@ -1237,6 +1295,39 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     for (int l = L - 1; l >= 0; --l) launch_update(a, l, rd, UPD_DELTA, 0, 1, s, hook);
   }
   return hipGetLastError();
+}
+
+hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, hipStream_t s, LaunchHook* hook) {
+  const MlpPlan& p = a.plan;
+  if (e.cap < p.Mp) return hipErrorInvalidValue;
+  uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
+  int32_t* label = at<int32_t>(a, p.off_label);
+  hipError_t err = launch_eval_clear(e, s);
+  for (int64_t row0 = 0; row0 < e.n_rows && err == hipSuccess; row0 += p.Mp) {
+    const int n = (int)(e.n_rows - row0 < p.Mp ? e.n_rows - row0 : p.Mp);
+    RoundDesc rd{};                               // every block of Bp rows uses the same version
+    rd.K = (n + p.Bp - 1) / p.Bp;
+    for (int k = 0; k < rd.K; ++k) rd.w[k].slot = slot;
+    const int rows = rd.K * p.Bp;
+    hook->begin(KK_EVAL, 0, 12.0 * n);
+    mlp_eval_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, (const int32_t*)e.y, row0, n, rows);
+    hook->end(KK_EVAL);
+    mlp_forward(a, (const uint16_t*)e.X, rd, rows, (double)n, at<float>(a, p.off_ring), at<uint16_t>(a, p.off_shadow),
+                false, s, hook);
+    hook->begin(KK_EVAL, 8.0 * n * p.d[p.L], 4.0 * n * p.d[p.L]);
+    const dim3 grid((n + 3) / 4), block(256);
+    const float* Z = at<float>(a, p.off_z);
+    const size_t ld = (size_t)p.dp[p.L];
+    switch (p.dp[p.L] / 64) {
+      case 1: mlp_eval_rows_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[p.L], label, n, e.rowloss, e.correct); break;
+      case 2: mlp_eval_rows_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[p.L], label, n, e.rowloss, e.correct); break;
+      default: mlp_eval_rows_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[p.L], label, n, e.rowloss, e.correct); break;
+    }
+    hook->end(KK_EVAL);
+    err = hipGetLastError();
+    if (err == hipSuccess) err = launch_eval_reduce(e, n, s, hook);
+  }
+  return err;
 }
 
 }  // namespace abs_impl

@@ -65,3 +65,13 @@ def make_inputs(p: dict):
         w0 = np.concatenate(parts).astype(np.float32)
     out["w0"] = w0
     return out
+
+
+def make_split(p: dict, eval_rows: int):
+    """(training inputs for p, X_eval, y_eval): one draw of p["M"] + eval_rows rows from the
+    preset's generator (same w* / class means), the last eval_rows of them held out."""
+    M = p["M"]
+    d = make_inputs(dict(p, M=M + eval_rows))
+    train = dict(X=np.ascontiguousarray(d["X"][:M]), y=np.ascontiguousarray(d["y"][:M]),
+                 w0=d["w0"], w_star=d["w_star"])
+    return train, np.ascontiguousarray(d["X"][M:]), np.ascontiguousarray(d["y"][M:])
