@@ -1,0 +1,33 @@
+"""GPU parity of the comparison systems (settings of the same round) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workloads
+from parity_util import run_pair, assert_trace_equal, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SOFTMAX = workloads.scaled_preset(2, M=3000, dims=[16, 4], n_classes=4, N=12, B=8, K0=3, lr=5e-2, n_slow=3,
+                                  slow_factor=5.0)
+LINEAR = workloads.scaled_preset(1, M=4000, N=8, B=16)
+MLP = workloads.scaled_preset(3, M=4096, dims=[128, 64, 10], N=8, B=32, n_slow=2, lr=1e-3)
+
+
+@pytest.mark.parametrize("name", workloads.METHODS)
+@pytest.mark.parametrize("base,tol,loss_rtol", [(LINEAR, 1e-5, 1e-4), (SOFTMAX, 1e-5, 1e-4), (MLP, 2e-2, 2e-3)],
+                         ids=["linear", "softmax", "mlp"])
+def test_method(base, tol, loss_rtol, name):
+    over = dict(U=3) if name == "local_sgd" else {}
+    p = workloads.method_preset(base, name, **over)
+    T = 25 if name in ("sync_sgd", "local_sgd") else 80
+    res = run_pair(p, T, checkpoints=(1,))
+    assert_trace_equal(res, loss_rtol)
+    for cp, (g, w) in res["models"].items():
+        assert np.all(np.isfinite(g)) and rel_err(g, w) <= tol, (name, cp, rel_err(g, w))
+    tr = res["got"]
+    if name in ("adasync", "sa_adasync", "k_async", "asgd", "sync_sgd", "local_sgd"):
+        assert np.all(tr[:, 5] == 0)                       # no forced restarts without a threshold
+    if name == "asgd":
+        assert np.all(tr[:, 1] == 1)
+    if name in ("sync_sgd", "local_sgd"):
+        assert np.all(tr[:, 1] == p["N"])
