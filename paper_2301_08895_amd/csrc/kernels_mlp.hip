@@ -133,6 +133,7 @@ struct GemmArgs {
   size_t split_stride;
   int mt, nt, nsplit, rows_per_xcd;   // tile grid (see the block -> tile mapping in the kernel)
   const uint16_t* maskT; size_t ldmaskT; // EPI_DGRAD: H_l^T [Ndim][ldmaskT]; the gradient passes where H_l > 0
+  float* colsum; size_t ldcs;         // EPI_DGRAD: column sums of the bf16 results per block of 64 rows, [Mdim / 64][ldcs]
 };
 
 // 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
@@ -295,6 +296,20 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
   float* outf = g.outf;
   if (EPI == EPI_WGRAD) outf += (size_t)zsplit * g.split_stride;
   uint16_t* const sE = smem + wave * (WN * Cfg::kEpiPitch);     // this wavefront's [WN][72] staging
+  float cs[NI];                           // EPI_DGRAD: column sums over this wavefront's 64 rows
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) cs[ni] = 0.f;
+  if (EPI == EPI_DGRAD) {
+    // the ReLU mask of this wavefront's tile, H_l^T [n][m], fetched as whole 128-byte rows into
+    // the staging area; every lane later replaces the 4 entries it read by its 4 results
+    const int mrow = m0 + wm * 64;
+#pragma unroll
+    for (int i = 0; i < WN / 8; ++i) {
+      const int q = lane + 64 * i, nl = q >> 3, ch = (q & 7) * 8;
+      *(uint4*)&sE[nl * Cfg::kEpiPitch + ch] =
+          *(const uint4*)(g.maskT + (size_t)(n0 + wn * WN + nl) * g.ldmaskT + mrow + ch);
+    }
+  }
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
@@ -309,7 +324,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
         const int mbase = m0 + wm * 64 + ml;
         uint16_t h[4];
         uint2 hm = make_uint2(0, 0);     // H_l of the 4 consecutive rows this lane holds
-        if (EPI == EPI_DGRAD) hm = *(const uint2*)(g.maskT + (size_t)n * g.ldmaskT + mbase);
+        if (EPI == EPI_DGRAD) hm = *(const uint2*)&sE[nl * Cfg::kEpiPitch + ml];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           const int m = mbase + rr;
@@ -327,6 +342,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
           }
           if (kStageT) {
             h[rr] = f32_to_bf16(v);
+            if (EPI == EPI_DGRAD) cs[ni] += __uint_as_float((uint32_t)h[rr] << 16);
             if (g.out) g.out[(size_t)m * g.ldo + n] = h[rr];
           }
         }
@@ -337,6 +353,14 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
           *(uint2*)&sE[nl * Cfg::kEpiPitch + ml] = o;
         }
       }
+    }
+  }
+  if (EPI == EPI_DGRAD) {
+    // the bias gradient's share of these 64 rows (the two half-wavefronts hold alternate rows)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const float c = cs[ni] + __shfl_xor(cs[ni], 32, 64);
+      if (lane < 32) g.colsum[(size_t)((m0 + wm * 64) >> 6) * g.ldcs + n0 + wn * WN + ni * 32 + lcol] = c;
     }
   }
   if (kStageT) {
@@ -505,6 +529,17 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   uint16_t* const sN = sT + 64 * kEpiPitch3;                    // [64 m][72]
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
+    float cs[2] = {0.f, 0.f};             // EPI_DGRAD: column sums over this half's 64 rows
+    if (EPI == EPI_DGRAD) {
+      // the ReLU mask of this half, H_l^T [64 n][64 m], fetched as whole 128-byte rows into sT;
+      // every lane later replaces the 4 entries it read by its 4 results
+      const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int q = lane + 64 * i, r = q >> 3, ch = (q & 7) * 8;
+        *(uint4*)&sT[r * kEpiPitch3 + ch] = *(const uint4*)(g.maskT + (size_t)(ncol + r) * g.ldmaskT + mrow + ch);
+      }
+    }
 #pragma unroll
     for (int mh = 0; mh < 2; ++mh) {
       const int mi = half * 2 + mh;
@@ -520,7 +555,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
           const int mbase = m0 + wm * 128 + half * 64 + ml;
           uint16_t h[4];
           uint2 hm = make_uint2(0, 0);
-          if (EPI == EPI_DGRAD) hm = *(const uint2*)(g.maskT + (size_t)n * g.ldmaskT + mbase);
+          if (EPI == EPI_DGRAD) hm = *(const uint2*)&sT[nl * kEpiPitch3 + ml];
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
             const int m = mbase + rr;
@@ -538,6 +573,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
             }
             if (kStageT) {
               h[rr] = f32_to_bf16(v);
+              if (EPI == EPI_DGRAD) cs[ni] += __uint_as_float((uint32_t)h[rr] << 16);
               if (g.out) sN[(ml + rr) * kEpiPitch3 + nl] = h[rr];
             }
           }
@@ -548,6 +584,15 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
             *(uint2*)&sT[nl * kEpiPitch3 + ml] = o;
           }
         }
+      }
+    }
+    if (EPI == EPI_DGRAD) {
+      // the bias gradient's share of these 64 rows (the two half-wavefronts hold alternate rows)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const float c = cs[ni] + __shfl_xor(cs[ni], 32, 64);
+        if (lane < 32)
+          g.colsum[(size_t)((m0 + wm * 128 + half * 64) >> 6) * g.ldcs + n0 + wn * 64 + ni * 32 + lcol] = c;
       }
     }
     if (kStageT) {
@@ -573,7 +618,8 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 template <int NC>   // columns per lane: padded class count / 64
 __global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
                                                             RoundDesc rd, int Bp, uint16_t* dZ, size_t lddz,
-                                                            uint16_t* dZT, size_t lddzt, float* rowloss) {
+                                                            uint16_t* dZT, size_t lddzt, float* rowloss,
+                                                            float* colsum, size_t ldcs) {
   __shared__ uint16_t sT[NC * 64][72];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m0 = blockIdx.x * 64;
@@ -616,6 +662,12 @@ __global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, si
   for (int q = threadIdx.x; q < NC * 64 * 8; q += 1024) {
     const int c = q >> 3, ch = q & 7;
     *(uint4*)(dZT + (size_t)c * lddzt + m0 + ch * 8) = *(const uint4*)&sT[c][ch * 8];
+  }
+  if (threadIdx.x < NC * 64) {            // the bias gradient's share of these 64 rows
+    float c = 0.f;
+#pragma unroll 8
+    for (int ml = 0; ml < 64; ++ml) c += __uint_as_float((uint32_t)sT[threadIdx.x][ml] << 16);
+    colsum[(size_t)blockIdx.x * ldcs + threadIdx.x] = c;
   }
 }
 
@@ -722,38 +774,52 @@ __global__ __launch_bounds__(256) void mlp_update_small_kernel(UpdateArgs u) {
   u.wt[(size_t)j * u.ldwt + i] = h;
 }
 
-// ------------------------------------------------------------------ bias update, upload losses
-// One wavefront per bias entry: b^{t+1}_j = b^t_j - sum_m dZ_l[m][j], the column sum read
-// from the transposed copy (contiguous along m).
-struct BiasLossArgs {
+// ------------------------------------------------------------------ bias update
+// b_j <- b_j - sum over the rows of dZ_l[.][j] (Eq. 2 / Eq. 3 for the biases).  The producers of
+// dZ_l leave the column sums of every block of 64 rows; 16 threads per entry add them (partial
+// row g, g + 16, ... each, then the 16 shares in order).  Global form: all `prow` blocks, model
+// w_cur -> w_next.  Per-upload form (local SGD, blockIdx.y = upload a): the blocks of a's own
+// rows, model slot cur_index[a] of w_cur -> slot a of w_next.
+struct BiasArgs {
   int L;
   int col_begin[ABS_MAX_LAYERS + 1];       // prefix of valid columns over the layers
-  const uint16_t* dzt[ABS_MAX_LAYERS]; size_t lddzt[ABS_MAX_LAYERS];
+  const float* colsum[ABS_MAX_LAYERS]; size_t ldcs[ABS_MAX_LAYERS];
   size_t b_off[ABS_MAX_LAYERS];
   const float* w_cur; float* w_next;
-  int rows;                                // K * Bp
+  int prow;                                // blocks of 64 rows (per upload in the per-upload form)
+  int batched;
+  size_t cur_stride, next_stride;
+  uint16_t cur_index[ABS_MAX_WORKERS];
 };
-__global__ __launch_bounds__(256) void mlp_bias_loss_kernel(BiasLossArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+__global__ __launch_bounds__(256) void mlp_bias_kernel(BiasArgs a) {
+  __shared__ float s_part[16][17];
+  const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int w = blockIdx.x * 16 + cl;
   const int ncol = a.col_begin[a.L];
+  const int up = blockIdx.y;
+  float s = 0.f;
+  int l = 0, j = 0;
   if (w < ncol) {
-    int l = 0;
     while (w >= a.col_begin[l + 1]) ++l;
-    const int j = w - a.col_begin[l];
-    const uint16_t* src = a.dzt[l] + (size_t)j * a.lddzt[l];
-    float s = 0.f;
-    for (int m = lane * 8; m < a.rows; m += 512) {
-      const uint4 v = *(const uint4*)(src + m);
-      const uint32_t p[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s += __uint_as_float(p[e] << 16);
-        s += __uint_as_float(p[e] & 0xFFFF0000u);
-      }
+    j = w - a.col_begin[l];
+    const float* src = a.colsum[l] + (size_t)(a.batched ? up * a.prow : 0) * a.ldcs[l] + j;
+    int r = grp;
+    for (; r + 48 < a.prow; r += 64) {       // four loads in flight
+      const float v0 = src[(size_t)r * a.ldcs[l]], v1 = src[(size_t)(r + 16) * a.ldcs[l]];
+      const float v2 = src[(size_t)(r + 32) * a.ldcs[l]], v3 = src[(size_t)(r + 48) * a.ldcs[l]];
+      s += v0; s += v1; s += v2; s += v3;
     }
-    s = wave_sum(s);
-    if (lane == 0) a.w_next[a.b_off[l] + j] = a.w_cur[a.b_off[l] + j] - s;
+    for (; r < a.prow; r += 16) s += src[(size_t)r * a.ldcs[l]];
+  }
+  s_part[grp][cl] = s;
+  __syncthreads();
+  if (grp == 0 && w < ncol) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t += s_part[g][cl];
+    const float* cur = a.w_cur + (a.batched ? (size_t)a.cur_index[up] * a.cur_stride : 0);
+    float* nxt = a.w_next + (a.batched ? (size_t)up * a.next_stride : 0);
+    nxt[a.b_off[l] + j] = cur[a.b_off[l] + j] - t;
   }
 }
 
@@ -784,44 +850,6 @@ __global__ __launch_bounds__(1024) void mlp_loss_kernel(const float* rowloss, in
 }
 
 // ------------------------------------------------------------------ local SGD helpers
-// Bias step of one upload: b_a <- b_a - sum over the upload's own rows of dZ_l (Eq. 2); one
-// wavefront per (upload, bias entry).
-struct BiasLocalArgs {
-  int L, K, Bp;
-  int col_begin[ABS_MAX_LAYERS + 1];
-  const uint16_t* dzt[ABS_MAX_LAYERS]; size_t lddzt[ABS_MAX_LAYERS];
-  size_t b_off[ABS_MAX_LAYERS];
-  const float* cur; size_t cur_stride;      // model read from slot cur_index[a]
-  float* priv; size_t priv_stride;          // written to slot a
-  uint16_t cur_index[ABS_MAX_WORKERS];
-};
-__global__ __launch_bounds__(256) void mlp_bias_local_kernel(BiasLocalArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int up = blockIdx.y;
-  const int ncol = a.col_begin[a.L];
-  if (w >= ncol) return;
-  int l = 0;
-  while (w >= a.col_begin[l + 1]) ++l;
-  const int j = w - a.col_begin[l];
-  const uint16_t* src = a.dzt[l] + (size_t)j * a.lddzt[l] + (size_t)up * a.Bp;
-  float s = 0.f;
-  for (int m = lane * 8; m < a.Bp; m += 512) {
-    const uint4 v = *(const uint4*)(src + m);
-    const uint32_t p[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      s += __uint_as_float(p[e] << 16);
-      s += __uint_as_float(p[e] & 0xFFFF0000u);
-    }
-  }
-  s = wave_sum(s);
-  if (lane == 0) {
-    const float b_old = a.cur[(size_t)a.cur_index[up] * a.cur_stride + a.b_off[l] + j];
-    a.priv[(size_t)up * a.priv_stride + a.b_off[l] + j] = b_old - s;
-  }
-}
-
 // Eq. 3 over the uploads: D = (1/K) sum_a (w^{t - tau_a} - w_a^{U}) in arrival order, for every
 // parameter; bias entries are applied right away, weight matrices go through the update kernels
 // (which also refresh the bf16 copies).
@@ -977,6 +1005,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
     p.off_dzt[l] = take(p.ldm * p.dp[l] * 2);
   }
   p.off_rowloss = take(Mp * 4);
+  for (int l = 1; l <= L; ++l) p.off_colsum[l] = take(Mp / 64 * p.dp[l] * 4);
   p.off_partial = take(p.partial_floats * 4);
   if (p.U > 1) {
     p.off_priv = take((size_t)c.N * p.slot_stride * 4);
@@ -1184,9 +1213,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       float* rl = at<float>(a, p.off_rowloss);
       const size_t ld = (size_t)p.dp[L], lddz = (size_t)p.ld[L];
       switch (p.dp[L] / 64) {
-        case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl); break;
-        case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl); break;
-        default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl); break;
+        case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld); break;
+        case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld); break;
+        default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld); break;
       }
       hook->end(KK_MLP_SOFTMAX_CE);
       hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
@@ -1208,6 +1237,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = p.ldm;
       g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.ld[l];
       g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = p.ldm;
+      g.colsum = at<float>(a, p.off_colsum[l]); g.ldcs = (size_t)p.dp[l];
       // the product through the output layer contracts over the classes only: bandwidth-bound
       const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
       hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
@@ -1243,37 +1273,30 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, nsplit, s, hook);
     }
 
-    // ---- biases
-    int c = 0;
-    if (!local) {
-      BiasLossArgs b{};
+    // ---- biases, from the column sums the producers of dZ_l left per block of 64 rows
+    {
+      BiasArgs b{};
       b.L = L;
+      int c = 0;
       for (int l = 0; l < L; ++l) {
         b.col_begin[l] = c; c += p.d[l + 1];
-        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = p.ldm;
+        b.colsum[l] = at<float>(a, p.off_colsum[l + 1]); b.ldcs[l] = (size_t)p.dp[l + 1];
         b.b_off[l] = p.b_off[l];
       }
       b.col_begin[L] = c;
-      b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
-      b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
-      b.rows = rows;
-      hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
-      mlp_bias_loss_kernel<<<dim3((c + 3) / 4), dim3(256), 0, s>>>(b);
-      hook->end(KK_MLP_BIAS_LOSS);
-    } else {
-      BiasLocalArgs b{};
-      b.L = L; b.K = K; b.Bp = p.Bp;
-      for (int l = 0; l < L; ++l) {
-        b.col_begin[l] = c; c += p.d[l + 1];
-        b.dzt[l] = at<uint16_t>(a, p.off_dzt[l + 1]); b.lddzt[l] = p.ldm;
-        b.b_off[l] = p.b_off[l];
+      if (!local) {
+        b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
+        b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
+        b.prow = rows / 64;
+      } else {
+        b.batched = 1;
+        b.w_cur = wbase; b.cur_stride = p.slot_stride;
+        b.w_next = priv; b.next_stride = p.slot_stride;
+        b.prow = p.Bp / 64;
+        for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
       }
-      b.col_begin[L] = c;
-      b.cur = wbase; b.cur_stride = p.slot_stride;
-      b.priv = priv; b.priv_stride = p.slot_stride;
-      for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
-      hook->begin(KK_MLP_BIAS_LOSS, (double)c * arows, (double)c * arows * 2.0);
-      mlp_bias_local_kernel<<<dim3((c + 3) / 4, K), dim3(256), 0, s>>>(b);
+      hook->begin(KK_MLP_BIAS_LOSS, (double)c * rows / 64, (double)c * rows / 64 * 4.0);
+      mlp_bias_kernel<<<dim3((c + 15) / 16, local ? K : 1), dim3(256), 0, s>>>(b);
       hook->end(KK_MLP_BIAS_LOSS);
     }
   }
