@@ -195,6 +195,29 @@ const char* abs_last_error(const abs_ctx* ctx);
 
 void abs_destroy(abs_ctx* ctx);
 
+/*
+ * Batched simulations.  The paper's results are sweeps over seeds and hyper-parameters (a, K^0,
+ * the step size; Section V), and a single round of the small workloads is too little work for
+ * one launch: a batch advances n simulations of one shape together, every round of all of them
+ * in one set of launches (one workgroup column per simulation).
+ *  abs_batch_create   ctxs: n handles (1 <= n <= 4096) created with the same model (linear or
+ *                     softmax), dims, N, B and stream, U = 1, profile = 0; seeds, K0, a, tau
+ *                     settings, step sizes, time models and datasets may differ.  The batch
+ *                     borrows the handles: they must outlive it, and stay usable on their own
+ *                     (abs_get_model, abs_trace, abs_evaluate, abs_round) between batch calls.
+ *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
+ *                     count); results are exactly those of abs_round on each handle alone.
+ *                     On an error of one simulation the call stops: the simulations before it
+ *                     in the batch have completed that round, the others have not.
+ *  abs_batch_last_error  text of the last error (b == NULL: of the last failed abs_batch_create
+ *                     on this thread).
+ */
+typedef struct abs_batch abs_batch;
+int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out);
+int abs_batch_round(abs_batch* b, int32_t n_rounds);
+const char* abs_batch_last_error(const abs_batch* b);
+void abs_batch_destroy(abs_batch* b);
+
 /* Host-side helpers exposing the simulation's counter-based draws (for checking a
  * binding or planning a run; no device work): execution time of job j of worker n in
  * ticks, and the B dataset rows of that job's minibatch (h_rows_out: B entries). */

@@ -64,6 +64,14 @@ def _load():
     lib.abs_round.argtypes = [vp, i32]
     lib.abs_evaluate.restype = C.c_int
     lib.abs_evaluate.argtypes = [vp, i64, vp, vp, i64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.abs_batch_create.restype = C.c_int
+    lib.abs_batch_create.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
+    lib.abs_batch_round.restype = C.c_int
+    lib.abs_batch_round.argtypes = [vp, i32]
+    lib.abs_batch_last_error.restype = C.c_char_p
+    lib.abs_batch_last_error.argtypes = [vp]
+    lib.abs_batch_destroy.restype = None
+    lib.abs_batch_destroy.argtypes = [vp]
     lib.abs_get_model.restype = C.c_int
     lib.abs_get_model.argtypes = [vp, i64, C.POINTER(C.c_float), sz]
     lib.abs_trace.restype = C.c_int
@@ -153,6 +161,25 @@ def abs_get_model(handle: int, version: int, n_floats: int) -> np.ndarray:
     out = np.empty(n_floats, dtype=np.float32)
     _check(_lib.abs_get_model(handle, version, out.ctypes.data_as(C.POINTER(C.c_float)), n_floats), handle)
     return out
+
+
+def abs_batch_create(handles) -> int:
+    arr = (C.c_void_p * len(handles))(*handles)
+    out = C.c_void_p()
+    rc = _lib.abs_batch_create(arr, len(handles), C.byref(out))
+    if rc != 0:
+        raise AbsError(rc, _lib.abs_batch_last_error(None).decode())
+    return out.value
+
+
+def abs_batch_round(batch: int, n_rounds: int) -> None:
+    rc = _lib.abs_batch_round(batch, n_rounds)
+    if rc != 0:
+        raise AbsError(rc, _lib.abs_batch_last_error(batch).decode())
+
+
+def abs_batch_destroy(batch: int) -> None:
+    _lib.abs_batch_destroy(batch)
 
 
 def abs_evaluate(handle: int, version: int, d_X: int, d_y: int, n_rows: int):
@@ -261,6 +288,29 @@ class Simulation:
     def close(self):
         if self.handle is not None:
             abs_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Batch:
+    """S simulations of one shape advanced together (abs_batch_*); sims: Simulation objects."""
+
+    def __init__(self, sims):
+        self.sims = list(sims)
+        self.handle = abs_batch_create([s.handle for s in self.sims])
+
+    def round(self, n: int = 1):
+        abs_batch_round(self.handle, n)
+        return self
+
+    def close(self):
+        if self.handle is not None:
+            abs_batch_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -2,6 +2,7 @@
 // host loop (select -> launch -> losses -> adapt), trace and model read-out.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdio>
@@ -264,6 +265,49 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
   return ABS_OK;
 }
 
+// The device's view of round t of one simulation: the K^t uploads in arrival order with the ring
+// slot of their model version and their coefficient in Eq. 3.
+static void fill_round_desc(const abs_ctx* ctx, const std::vector<Upload>& sel, int64_t t, RoundDesc& rd) {
+  const abs_config& cfg = ctx->cfg;
+  const int K = (int)sel.size();
+  rd.K = K;
+  rd.slot_cur = (uint32_t)(t % ctx->R);
+  rd.slot_next = (uint32_t)((t + 1) % ctx->R);
+  rd.stamp = (uint32_t)(t + 1);
+  for (int a = 0; a < K; ++a) {
+    const Upload& u = sel[(size_t)a];
+    // coefficient of this upload in Eq. 3: eta_k / (K^t B), eta_k = eta / max(1, tau_k) under
+    // the staleness-aware penalty
+    double eta = (double)cfg.lr;
+    if (cfg.sa_penalty && u.tau > 1) eta /= (double)u.tau;
+    rd.w[a].id = (uint32_t)u.id;
+    rd.w[a].job = u.job;
+    rd.w[a].slot = (uint32_t)(u.ver % ctx->R);
+    // (with U > 1 the 1/K^t of Eq. 3 is applied when the uploads' changes are averaged)
+    rd.w[a].c = cfg.U > 1 ? (float)(eta / (double)cfg.B) : (float)(eta / ((double)K * (double)cfg.B));
+  }
+}
+
+static void fill_regression_args(const abs_ctx* ctx, RegressionArgs& ra) {
+  const abs_config& cfg = ctx->cfg;
+  ra.X = (const float*)ctx->dX;
+  ra.y = ctx->dy;
+  ra.ring = (float*)(ctx->ws + ctx->rplan.off_ring);
+  ra.slot_stride = ctx->slot_stride;
+  ra.d = cfg.dims[0];
+  ra.C = cfg.dims[1];
+  ra.B = cfg.B;
+  ra.shard_rows = (uint64_t)(cfg.M / cfg.N);
+  ra.batch_key = stream_key(cfg.seed, kStreamBatch);
+  ra.mailbox = ctx->d_box;
+  ra.dz = (float*)(ctx->ws + ctx->rplan.off_dz);
+  ra.rowloss = (float*)(ctx->ws + ctx->rplan.off_rowloss);
+  ra.rowidx = (uint32_t*)(ctx->ws + ctx->rplan.off_rowidx);
+  ra.U = cfg.U;
+  ra.delta = (float*)(ctx->ws + ctx->rplan.off_delta);
+  ra.lossbuf = (float*)(ctx->ws + ctx->rplan.off_lossbuf);
+}
+
 int abs_round(abs_ctx* ctx, int32_t n_rounds) {
   if (!ctx || n_rounds < 0) return ABS_E_ARG;
   const abs_config& cfg = ctx->cfg;
@@ -280,43 +324,13 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       if (rc != ABS_OK) return rc;
       continue;
     }
-    rd.K = K;
-    rd.slot_cur = (uint32_t)(t % ctx->R);
-    rd.slot_next = (uint32_t)((t + 1) % ctx->R);
-    rd.stamp = (uint32_t)(t + 1);
-    for (int a = 0; a < K; ++a) {
-      const Upload& u = sel[(size_t)a];
-      // coefficient of this upload in Eq. 3: eta_k / (K^t B), eta_k = eta / max(1, tau_k) under
-      // the staleness-aware penalty
-      double eta = (double)cfg.lr;
-      if (cfg.sa_penalty && u.tau > 1) eta /= (double)u.tau;
-      rd.w[a].id = (uint32_t)u.id;
-      rd.w[a].job = u.job;
-      rd.w[a].slot = (uint32_t)(u.ver % ctx->R);
-      // (with U > 1 the 1/K^t of Eq. 3 is applied when the uploads' changes are averaged)
-      rd.w[a].c = cfg.U > 1 ? (float)(eta / (double)cfg.B) : (float)(eta / ((double)K * (double)cfg.B));
-    }
+    fill_round_desc(ctx, sel, t, rd);
     hipError_t e;
     if (cfg.model == ABS_MODEL_MLP) {
       e = launch_mlp_round(ctx->margs, rd, ctx->stream, ctx);
     } else {
       RegressionArgs ra;
-      ra.X = (const float*)ctx->dX;
-      ra.y = ctx->dy;
-      ra.ring = (float*)(ctx->ws + ctx->rplan.off_ring);
-      ra.slot_stride = ctx->slot_stride;
-      ra.d = cfg.dims[0];
-      ra.C = cfg.dims[1];
-      ra.B = cfg.B;
-      ra.shard_rows = (uint64_t)(cfg.M / cfg.N);
-      ra.batch_key = stream_key(cfg.seed, kStreamBatch);
-      ra.mailbox = ctx->d_box;
-      ra.dz = (float*)(ctx->ws + ctx->rplan.off_dz);
-      ra.rowloss = (float*)(ctx->ws + ctx->rplan.off_rowloss);
-      ra.rowidx = (uint32_t*)(ctx->ws + ctx->rplan.off_rowidx);
-      ra.U = cfg.U;
-      ra.delta = (float*)(ctx->ws + ctx->rplan.off_delta);
-      ra.lossbuf = (float*)(ctx->ws + ctx->rplan.off_lossbuf);
+      fill_regression_args(ctx, ra);
       if (cfg.U > 1)
         e = launch_regression_local_round(ra, rd, cfg.model == ABS_MODEL_SOFTMAX, ctx->stream, ctx);
       else
@@ -342,6 +356,138 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
   }
   return ABS_OK;
 }
+
+// ---- batched simulations: S handles of one shape advance together, one set of launches per round
+struct abs_batch {
+  std::vector<abs_ctx*> ctx;
+  hipStream_t stream = nullptr;
+  RegressionArgs* d_args = nullptr;        // device [S]
+  char* h_rds[2] = {nullptr, nullptr};     // pinned host, S descriptors, alternating by round
+  char* d_rds[2] = {nullptr, nullptr};     // device copies
+  size_t rd_stride = 0;
+  LossMailbox* h_box = nullptr;            // pinned, device-visible [S]
+  LossMailbox* d_box = nullptr;
+  uint64_t rounds = 0;
+  std::string err;
+};
+namespace { thread_local std::string g_batch_error; }
+
+void abs_batch_destroy(abs_batch* b) {
+  if (!b) return;
+  if (b->stream || !b->ctx.empty()) (void)hipStreamSynchronize(b->stream);
+  if (b->d_args) (void)hipFree(b->d_args);
+  for (int i = 0; i < 2; ++i) {
+    if (b->h_rds[i]) (void)hipHostFree(b->h_rds[i]);
+    if (b->d_rds[i]) (void)hipFree(b->d_rds[i]);
+  }
+  if (b->h_box) (void)hipHostFree(b->h_box);
+  delete b;
+}
+
+int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
+  if (out) *out = nullptr;
+  auto bad = [&](const char* m) { g_batch_error = m; return ABS_E_ARG; };
+  if (!ctxs || !out) return bad("NULL argument");
+  if (n < 1 || n > 4096) return bad("a batch holds 1..4096 simulations");
+  const abs_ctx* c0 = ctxs[0];
+  for (int32_t i = 0; i < n; ++i) {
+    const abs_ctx* c = ctxs[i];
+    if (!c) return bad("NULL handle in the batch");
+    for (int32_t j = 0; j < i; ++j) if (ctxs[j] == c) return bad("a handle appears twice in the batch");
+    if (!c->cfg.device_mode) return bad("schedule-only handles cannot be batched");
+    if (c->cfg.model == ABS_MODEL_MLP) return bad("MLP rounds fill the GPU on their own: batches are for the regression models");
+    if (c->cfg.U != 1) return bad("batched rounds take U = 1");
+    if (c->cfg.profile) return bad("batched rounds are not profiled per kernel (profile must be 0)");
+    if (c->cfg.model != c0->cfg.model || c->cfg.dims[0] != c0->cfg.dims[0] || c->cfg.dims[1] != c0->cfg.dims[1] ||
+        c->cfg.B != c0->cfg.B || c->cfg.N != c0->cfg.N || c->stream != c0->stream)
+      return bad("all simulations of a batch need the same model, dims, N, B and stream");
+  }
+  std::unique_ptr<abs_batch, void (*)(abs_batch*)> b(new abs_batch, abs_batch_destroy);
+  b->ctx.assign(ctxs, ctxs + n);
+  b->stream = c0->stream;
+  b->rd_stride = 16 + (size_t)c0->cfg.N * sizeof(WorkerDesc);
+  auto hip = [&](hipError_t e, const char* what) {
+    if (e == hipSuccess) return true;
+    g_batch_error = std::string(what) + ": " + hipGetErrorString(e);
+    return false;
+  };
+  if (!hip(hipMalloc((void**)&b->d_args, (size_t)n * sizeof(RegressionArgs)), "hipMalloc")) return ABS_E_HIP;
+  for (int i = 0; i < 2; ++i) {
+    if (!hip(hipHostMalloc((void**)&b->h_rds[i], (size_t)n * b->rd_stride, hipHostMallocDefault), "hipHostMalloc")) return ABS_E_HIP;
+    if (!hip(hipMalloc((void**)&b->d_rds[i], (size_t)n * b->rd_stride), "hipMalloc")) return ABS_E_HIP;
+  }
+  if (!hip(hipHostMalloc((void**)&b->h_box, (size_t)n * sizeof(LossMailbox), hipHostMallocMapped), "hipHostMalloc")) return ABS_E_HIP;
+  std::memset(b->h_box, 0, (size_t)n * sizeof(LossMailbox));
+  if (!hip(hipHostGetDevicePointer((void**)&b->d_box, b->h_box, 0), "hipHostGetDevicePointer")) return ABS_E_HIP;
+  std::vector<RegressionArgs> args((size_t)n);
+  for (int32_t i = 0; i < n; ++i) {
+    fill_regression_args(ctxs[i], args[(size_t)i]);
+    args[(size_t)i].mailbox = b->d_box + i;          // the batch's own mailboxes
+  }
+  if (!hip(hipMemcpyAsync(b->d_args, args.data(), (size_t)n * sizeof(RegressionArgs), hipMemcpyHostToDevice, b->stream), "hipMemcpyAsync")) return ABS_E_HIP;
+  if (!hip(hipStreamSynchronize(b->stream), "hipStreamSynchronize")) return ABS_E_HIP;
+  *out = b.release();
+  return ABS_OK;
+}
+
+int abs_batch_round(abs_batch* b, int32_t n_rounds) {
+  if (!b || n_rounds < 0) return ABS_E_ARG;
+  const int S = (int)b->ctx.size();
+  const abs_config& c0 = b->ctx[0]->cfg;
+  std::vector<std::vector<Upload>> sel((size_t)S);
+  std::vector<uint32_t> stamp((size_t)S);
+  RoundDesc rd;
+  std::memset(&rd, 0, sizeof(rd));
+  for (int32_t it = 0; it < n_rounds; ++it) {
+    const int buf = (int)(b->rounds & 1);
+    int Kmax = 0;
+    for (int i = 0; i < S; ++i) {
+      abs_ctx* ctx = b->ctx[(size_t)i];
+      int rc = ctx->sched->select(sel[(size_t)i], ctx->err);
+      if (rc != ABS_OK) { b->err = "simulation " + std::to_string(i) + ": " + ctx->err; return rc; }
+      fill_round_desc(ctx, sel[(size_t)i], ctx->sched->round(), rd);
+      std::memcpy(b->h_rds[buf] + (size_t)i * b->rd_stride, &rd, 16 + (size_t)rd.K * sizeof(WorkerDesc));
+      stamp[(size_t)i] = rd.stamp;
+      Kmax = std::max(Kmax, (int)rd.K);
+    }
+    hipError_t e = hipMemcpyAsync(b->d_rds[buf], b->h_rds[buf], (size_t)S * b->rd_stride, hipMemcpyHostToDevice, b->stream);
+    if (e == hipSuccess)
+      e = launch_regression_round_batch(b->d_args, b->d_rds[buf], b->rd_stride, S, c0.model == ABS_MODEL_SOFTMAX,
+                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->stream);
+    if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); return ABS_E_HIP; }
+    b->rounds += 1;
+    // all S mailboxes; now and then ask the runtime whether the stream failed or drained
+    for (int i = 0; i < S; ++i) {
+      const volatile LossMailbox* box = b->h_box + i;
+      for (uint64_t spin = 1; box->stamp != stamp[(size_t)i]; ++spin) {
+        if ((spin & 0x3FFF) == 0) {
+          const hipError_t q = hipStreamQuery(b->stream);
+          if (q == hipSuccess) {
+            if (box->stamp == stamp[(size_t)i]) break;
+            b->err = "stream drained but a loss mailbox was not written";
+            return ABS_E_HIP;
+          }
+          if (q != hipErrorNotReady) { b->err = std::string("hipStreamQuery: ") + hipGetErrorString(q); return ABS_E_HIP; }
+        }
+#if defined(__x86_64__)
+        __builtin_ia32_pause();
+#endif
+      }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    for (int i = 0; i < S; ++i) {
+      abs_ctx* ctx = b->ctx[(size_t)i];
+      float losses[ABS_MAX_WORKERS];
+      const int K = (int)sel[(size_t)i].size();
+      for (int a = 0; a < K; ++a) losses[a] = b->h_box[i].loss[a];
+      int rc = ctx->sched->complete(sel[(size_t)i], losses, true, ctx->err);
+      if (rc != ABS_OK) { b->err = "simulation " + std::to_string(i) + ": " + ctx->err; return rc; }
+    }
+  }
+  return ABS_OK;
+}
+
+const char* abs_batch_last_error(const abs_batch* b) { return b ? b->err.c_str() : g_batch_error.c_str(); }
 
 int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats) {
   if (!ctx || !h_out) return ABS_E_ARG;

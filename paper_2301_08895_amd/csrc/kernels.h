@@ -63,6 +63,12 @@ hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hi
 hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDesc& rd, bool softmax,
                                          hipStream_t s, LaunchHook* hook);
 
+// One round of S simulations of one shape in a single set of launches (blockIdx.y = simulation):
+// d_args [S] and the S round descriptors (header + uploads, `stride` bytes apart) live in device
+// memory; Kmax = the largest K^t among them.
+hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
+                                         bool softmax, int d, int C, int B, int Kmax, hipStream_t s);
+
 // ---- held-out evaluation (the read-outs of Section V-B: loss of the global model, accuracy) ----
 // Per-row losses and "argmax is the label" flags go to a scratch of `cap` rows; a single
 // workgroup adds them, in a fixed order and in fp64, to acc[0] (loss sum) and acc[1] (hits).

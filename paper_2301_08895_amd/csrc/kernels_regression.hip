@@ -32,7 +32,7 @@ __device__ __forceinline__ uint64_t batch_row(const WorkerDesc& w, uint64_t batc
 constexpr int kLinWaves = 16;
 
 template <int Q>
-__global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(RegressionArgs a, RoundDesc rd) {
+__device__ __forceinline__ void linreg_round_body(const RegressionArgs& a, const RoundDesc& rd) {
   __shared__ float s_g[kLinWaves][Q * 64];
   __shared__ float s_loss[kLinWaves][ABS_MAX_WORKERS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -113,6 +113,18 @@ __global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(Regression
   __syncthreads();
   publish_losses(a.mailbox, &s_loss[0][0], K, rd.stamp);
 }
+template <int Q>
+__global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(RegressionArgs a, RoundDesc rd) {
+  linreg_round_body<Q>(a, rd);
+}
+// Batched form: blockIdx.y = simulation; its arguments and this round's descriptor (a header and
+// the K^t uploads, `stride` bytes apart) come from device memory.
+template <int Q>
+__global__ __launch_bounds__(kLinWaves * 64) void linreg_round_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                            size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  linreg_round_body<Q>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
+}
 
 hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
                                LaunchHook* hook) {
@@ -135,7 +147,7 @@ constexpr int kSoftQF = 4;          // float4 chunks per lane  ->  d <= 1024
 constexpr int kDzPitch = 16;        // floats per dZ row (C <= 16)
 
 template <int C>
-__global__ __launch_bounds__(256) void softmax_rows_kernel(RegressionArgs a, RoundDesc rd) {
+__device__ __forceinline__ void softmax_rows_body(const RegressionArgs& a, const RoundDesc& rd) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int B = a.B, d = a.d;
@@ -206,7 +218,7 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(RegressionArgs a, Rou
 constexpr int kUpdF = 8, kUpdG = 128;
 
 template <int C>
-__global__ __launch_bounds__(1024) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
+__device__ __forceinline__ void softmax_update_body(const RegressionArgs& a, const RoundDesc& rd) {
   __shared__ float s_red[kUpdG][kUpdF * C + 1];
   __shared__ float s_loss[ABS_MAX_WORKERS];
   const int B = a.B, d = a.d, R = rd.K * B;
@@ -288,6 +300,28 @@ __global__ __launch_bounds__(1024) void softmax_update_kernel(RegressionArgs a, 
 }
 
 template <int C>
+__global__ __launch_bounds__(256) void softmax_rows_kernel(RegressionArgs a, RoundDesc rd) {
+  softmax_rows_body<C>(a, rd);
+}
+template <int C>
+__global__ __launch_bounds__(1024) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
+  softmax_update_body<C>(a, rd);
+}
+// Batched forms: blockIdx.y = simulation (see linreg_round_batch_kernel).
+template <int C>
+__global__ __launch_bounds__(256) void softmax_rows_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                 size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  softmax_rows_body<C>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
+}
+template <int C>
+__global__ __launch_bounds__(1024) void softmax_update_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                    size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  softmax_update_body<C>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
+}
+
+template <int C>
 static hipError_t softmax_round_c(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
                                   LaunchHook* hook) {
   const int R = rd.K * a.B;
@@ -313,6 +347,31 @@ hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hi
 #undef ABS_CASE
     default: return hipErrorInvalidValue;
   }
+}
+
+// One round of S simulations of the same shape (model, d, C, B) in one set of launches.
+hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
+                                         bool softmax, int d, int C, int B, int Kmax, hipStream_t s) {
+  if (!softmax) {
+    const dim3 grid(1, S), block(kLinWaves * 64);
+    if (d <= 128)       linreg_round_batch_kernel<2><<<grid, block, 0, s>>>(d_args, d_rds, stride);
+    else if (d <= 256)  linreg_round_batch_kernel<4><<<grid, block, 0, s>>>(d_args, d_rds, stride);
+    else                linreg_round_batch_kernel<8><<<grid, block, 0, s>>>(d_args, d_rds, stride);
+    return hipGetLastError();
+  }
+  const int R = Kmax * B, nslice = (d + kUpdF - 1) / kUpdF;
+  switch (C) {
+#define ABS_CASE(c)                                                                                          \
+  case c:                                                                                                    \
+    softmax_rows_batch_kernel<c><<<dim3((R + 3) / 4, S), dim3(256), 0, s>>>(d_args, d_rds, stride);          \
+    softmax_update_batch_kernel<c><<<dim3(nslice + 1, S), dim3(1024), 0, s>>>(d_args, d_rds, stride);        \
+    break;
+    ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
+    ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
+#undef ABS_CASE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace abs_impl
