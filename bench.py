@@ -139,6 +139,52 @@ def _flops_at_full_k(p, kind):
     return sum(2.0 * rows * d[l] * d[l + 1] for l in range(1, len(d) - 1)) / max(1, len(d) - 2)
 
 
+def bench_batch(args, p, inputs, warmup, steps):
+    """S independent simulations (different simulation seeds) of a regression workload, advanced
+    together by abs_batch_round: the sweep shape of the paper's experiments."""
+    import numpy as np
+    import torch
+    import paper_2301_08895_amd as lib
+
+    if p["model"] == 2:
+        print("bench.py: --batch is for the regression workloads (configs 1 and 2)", file=sys.stderr)
+        sys.exit(2)
+    S = args.batch
+    sims = [lib.Simulation(dict(p, seed_sim=p["seed_sim"] + 7919 * i), inputs) for i in range(S)]
+    batch = lib.Batch(sims)
+    batch.round(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    batch.round(steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    grads = 0
+    for sim in sims:
+        tr = sim.trace(warmup, warmup + steps)
+        grads += int(tr[:, 1].sum())
+        assert np.all(np.isfinite(sim.model())), "non-finite parameters after the timed run"
+    batch.close()
+    for sim in sims:
+        sim.close()
+    value = grads / elapsed
+    d = p["dims"][0]
+    # algorithmic bytes: every aggregated gradient reads B rows of d features and B targets once
+    ach = grads * p["B"] * (d + 1) * 4.0 / elapsed / 1e9
+    cpu = cpu_baseline(p, inputs, args.cpu_budget) if args.cpu_budget > 0 else None
+    print(json.dumps({
+        "metric": "worker_gradients_per_sec", "value": value, "unit": "worker-gradients/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{p['name']}_x{S}_simulations", "N": p["N"], "B": p["B"], "dims": p["dims"],
+                   "K0": p["K0"], "tau_cap": p["tau_cap"], "a": p["a"], "lr": p["lr"], "simulations": S},
+        "samples_per_sec": value * p["B"], "rounds_per_sec": steps * S / elapsed,
+        "roofline": {"bound": "hbm", "kernel": "whole round (all launches and the host, wall clock)",
+                     "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                     "traffic": None},
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +197,8 @@ def main():
                     help="counter runs only: wait for all N workers every round (the steady state)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="counter runs only: end with a plain 1 GiB device copy to calibrate FETCH/WRITE_SIZE")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="configs 1-2: advance this many independent simulations (seeds) per launch")
     ap.add_argument("--traffic-import", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="write profiles/cfg5_hbm_traffic.txt from two rocprofv3 --pmc counter files and exit")
     args = ap.parse_args()
@@ -174,6 +222,9 @@ def main():
     warmup = dw if args.warmup is None else args.warmup
     steps = ds if args.steps is None else args.steps
     inputs = workloads.make_inputs(p)
+
+    if args.batch:
+        return bench_batch(args, p, inputs, warmup, steps)
 
     sim = lib.Simulation(p, inputs, profile=0 if args.no_profile else 1)
     sim.round(warmup)
