@@ -401,9 +401,28 @@ __device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_bl
                                    (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
 }
 
+// The same request written out by hand.  The compiler makes every LDS read that it cannot tell
+// apart from a pending global->LDS request wait for all of them, and it cannot for the
+// transposing read: a k-step would then start by waiting for the tile it has just requested.
+// Requests issued this way are invisible to that bookkeeping; the loop's own vmcnt(0) and
+// barrier order them against the reads.
+__device__ __forceinline__ void lds_dma16_raw(const uint16_t* gsrc, uint16_t* lds_block) {
+  const uint32_t lds = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_block);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gsrc), "s"(lds)
+               : "memory");      // (m0: nothing else in these kernels keeps a value in it)
+}
+
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG>
 __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDesc rd) {
   constexpr bool kStageT = (EPI == EPI_RELU || EPI == EPI_DGRAD);
+  // TAG 2 (first-layer weight gradient): the A operand is the dataset itself, rows gathered by
+  // a_rowidx and the contraction running over those rows, i.e. A arrives as [k][m] instead of
+  // [m][k]; its fragments are read with the transposing LDS read, so no transposed copy of
+  // the minibatch is ever written.
+  constexpr bool kATR = (EPI == EPI_WGRAD && TAG == 2);
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem3];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -429,8 +448,18 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const int pc = lane & 7;
   const int c_even = (pc ^ (((lane >> 4)) & 7)) * 8;        // (r >> 1) & 7 for i even
   const int c_odd = (pc ^ ((4 + (lane >> 4)) & 7)) * 8;     //               for i odd
-  const uint16_t *pa0, *pa1, *pa2, *pa3;
-  if (GATHER) {
+  const uint16_t *pa0 = nullptr, *pa1 = nullptr, *pa2 = nullptr, *pa3 = nullptr;
+  // kATR: a k-step's A tile is 64 gathered rows x 256 columns (512 B per row); a DMA instruction
+  // fills two rows, wavefront w takes rows 8 w .. 8 w + 7.  Lane l of instruction q handles row
+  // 8 w + 2 q + (l >> 5) and chunk position l & 31; the 64-byte blocks of a row are stored at block
+  // position b ^ (row & 3), so that the four rows one transposing read touches cover all banks.
+  const int atr_row = wave * 8 + (lane >> 5);                 // + 2 q
+  const int atr_c = lane & 31;
+  const int atr_col_even = m0 + (((((atr_c >> 2) ^ (lane >> 5)) << 2) | (atr_c & 3)) << 3);          // q even
+  const int atr_col_odd = m0 + (((((atr_c >> 2) ^ (2 + (lane >> 5))) << 2) | (atr_c & 3)) << 3);     // q odd
+  uint32_t aidx0 = 0, aidx1 = 0, aidx2 = 0, aidx3 = 0;       // dataset rows of the next tile to request
+  if (kATR) {
+  } else if (GATHER) {
     pa0 = g.A + (size_t)g.a_rowidx[m0 + dr] * g.lda + c_even;
     pa1 = g.A + (size_t)g.a_rowidx[m0 + dr + 8] * g.lda + c_odd;
     pa2 = g.A + (size_t)g.a_rowidx[m0 + dr + 16] * g.lda + c_even;
@@ -448,15 +477,30 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   uint16_t* const dmaA = smem + wave * 4 * 512;              // 512 elements = 1 KB per instruction
   uint16_t* const dmaB = smem + TM3 * BK + wave * 4 * 512;
 
+  // (kATR) the four dataset rows this lane requests for k-step ks
+#define ABS_AIDX(ks)                                                              \
+  {                                                                               \
+    const uint32_t* ri_ = g.a_rowidx + (size_t)(ks) * BK + atr_row;               \
+    aidx0 = ri_[0]; aidx1 = ri_[2]; aidx2 = ri_[4]; aidx3 = ri_[6];               \
+  }
 #define ABS_DMA(ks, stage)                                                        \
   {                                                                               \
     const int k0_ = (ks) * BK;                                                    \
     uint16_t* a_ = dmaA + (stage) * kStage3;                                      \
     uint16_t* b_ = dmaB + (stage) * kStage3;                                      \
-    lds_dma16(pa0 + k0_, a_);        lds_dma16(pa1 + k0_, a_ + 512);              \
-    lds_dma16(pa2 + k0_, a_ + 1024); lds_dma16(pa3 + k0_, a_ + 1536);             \
-    lds_dma16(pb0 + k0_, b_);        lds_dma16(pb1 + k0_, b_ + 512);              \
-    lds_dma16(pb2 + k0_, b_ + 1024); lds_dma16(pb3 + k0_, b_ + 1536);             \
+    if (kATR) {                                                                   \
+      lds_dma16_raw(g.A + (size_t)aidx0 * g.lda + atr_col_even, a_);              \
+      lds_dma16_raw(g.A + (size_t)aidx1 * g.lda + atr_col_odd, a_ + 512);         \
+      lds_dma16_raw(g.A + (size_t)aidx2 * g.lda + atr_col_even, a_ + 1024);       \
+      lds_dma16_raw(g.A + (size_t)aidx3 * g.lda + atr_col_odd, a_ + 1536);        \
+      lds_dma16_raw(pb0 + k0_, b_);        lds_dma16_raw(pb1 + k0_, b_ + 512);    \
+      lds_dma16_raw(pb2 + k0_, b_ + 1024); lds_dma16_raw(pb3 + k0_, b_ + 1536);   \
+    } else {                                                                      \
+      lds_dma16(pa0 + k0_, a_);        lds_dma16(pa1 + k0_, a_ + 512);            \
+      lds_dma16(pa2 + k0_, a_ + 1024); lds_dma16(pa3 + k0_, a_ + 1536);           \
+      lds_dma16(pb0 + k0_, b_);        lds_dma16(pb1 + k0_, b_ + 512);            \
+      lds_dma16(pb2 + k0_, b_ + 1024); lds_dma16(pb3 + k0_, b_ + 1536);           \
+    }                                                                             \
   }
 
   f32x16_t acc[4][2];
@@ -470,20 +514,43 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const int lr = lane & 31, lk = lane >> 5;
   const int fa_row = (wm * 128 + lr) * BK, fb_row = TM3 * BK + (wn * 64 + lr) * BK;
   const int sw = (lr >> 1) & 7;
+  // kATR fragment addresses.  A transposing read works on groups of 16 lanes: lane s of a group
+  // points at 4 consecutive columns of row s / 4 of a 4 x 16 block and receives column s of its
+  // 4 rows.  Group g of the wavefront takes columns 16 (g & 1) .. + 16 of the 32-column MFMA block
+  // and rows 8 (g >> 1) .. of the 16-row sub-step; two reads (rows + 0 and + 4) give the 8 k values
+  // of a lane.  The block position is XORed with the row's low bits (= s / 4) as stored.
+  const int tg = lane >> 4, ts = lane & 15, tr = ts >> 2;
+  int fa_tr[4];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+    fa_tr[mi] = (tr + 8 * (tg >> 1)) * TM3 + (wm * 4 + (mi ^ tr)) * 32 + 16 * (tg & 1) + 4 * (ts & 3);
   if (ks0 < ks1) {
+    if (kATR) ABS_AIDX(ks0);
     ABS_DMA(ks0, 0);
+    if (kATR) ABS_AIDX(min(ks0 + 1, ks1 - 1));
     for (int ks = ks0; ks < ks1; ++ks) {
       const int stage = (ks - ks0) & 1;
       __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's part of tile ks is in LDS
       __syncthreads();                         // ... and everybody's; everybody is done with tile ks-1
       if (ks + 1 < ks1) ABS_DMA(ks + 1, stage ^ 1);
+      if (kATR) ABS_AIDX(min(ks + 2, ks1 - 1));
       const uint16_t* sS = smem + stage * kStage3;
       bf16x8_t fa[2][4], fb[2][2];
 #define ABS_FRAGS(set, s_)                                                                        \
   {                                                                                               \
     const int ch_ = ((((s_) << 1) | lk) ^ sw) << 3;                                               \
-    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                              \
-      fa[set][mi] = *(const bf16x8_t*)&sS[fa_row + mi * 32 * BK + ch_];                           \
+    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) {                                            \
+      if (kATR) {                                                                                 \
+        typedef short s16x4_ __attribute__((ext_vector_type(4)));                                 \
+        const uint16_t* q_ = sS + fa_tr[mi] + (s_) * 16 * TM3;                                    \
+        union { s16x4_ h[2]; bf16x8_t v; } u_;                                                    \
+        u_.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_*)(q_));            \
+        u_.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_*)(q_ + 4 * TM3));  \
+        fa[set][mi] = u_.v;                                                                       \
+      } else {                                                                                    \
+        fa[set][mi] = *(const bf16x8_t*)&sS[fa_row + mi * 32 * BK + ch_];                         \
+      }                                                                                           \
+    }                                                                                             \
     _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                              \
       fb[set][ni] = *(const bf16x8_t*)&sS[fb_row + ni * 32 * BK + ch_];                           \
   }
@@ -498,15 +565,34 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][mi], fb[s & 1][ni], acc[mi][ni], 0, 0, 0);
       }
 #undef ABS_FRAGS
-      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+      // issue order: the first fragment set, then one LDS read behind each MFMA (a transposed
+      // A operand takes two reads per fragment: 10 instead of 6 reads per sub-step)
+      if (kATR) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
 #pragma unroll
-      for (int s = 0; s < 3; ++s) {
+        for (int s = 0; s < 3; ++s) {
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          for (int i = 0; i < 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          }
+#pragma unroll
+          for (int i = 0; i < 6; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+#pragma unroll
+          for (int i = 0; i < 6; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
@@ -946,6 +1032,17 @@ int pick_split(int tiles, int ksteps, int slots, double tile_bytes) {
   return best;
 }
 
+// Row-range splits of layer l's weight-gradient contraction over `rows` stacked rows
+// (per_upload > 0: local SGD, one split per upload).
+int wgrad_split(const MlpPlan& p, int l, int rows, int per_upload) {
+  if (per_upload > 0) return per_upload;
+  const int ksteps = rows / BK;
+  const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
+  const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
+  const int tiles = big ? (p.dp[l] / TM3) * (p.dp[l + 1] / TN3) : (p.dp[l] / TM) * (p.dp[l + 1] / tn);
+  return big ? pick_split(tiles, ksteps, 256, 256.0 * 256 * 4) : pick_split(tiles, ksteps, 512, 128.0 * tn * 4);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ planning
@@ -1086,11 +1183,16 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
   hook->end(KK_MLP_UPDATE);
 }
 
+// Whether a product goes to the 256 x 256 tile kernel.
+inline bool gemm_is_big(bool gather, bool per_upload, const GemmArgs& g, int Mdim, int Ndim, int nsplit) {
+  return Mdim % TM3 == 0 && Ndim % TN3 == 0 && (!per_upload || g.rows_per_upload % TM3 == 0) &&
+         (!gather || g.a_kvalid == g.ksteps_total * BK) && (Mdim / TM3) * (Ndim / TN3) * nsplit >= 128;
+}
+
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
 void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   g.nsplit = nsplit;
-  const bool big = Mdim % TM3 == 0 && Ndim % TN3 == 0 && (!PER_UPLOAD || g.rows_per_upload % TM3 == 0) &&
-                   (!GATHER || g.a_kvalid == g.ksteps_total * BK) && (Mdim / TM3) * (Ndim / TN3) * nsplit >= 128;
+  const bool big = gemm_is_big(GATHER, PER_UPLOAD, g, Mdim, Ndim, nsplit);
   if (big) {
     g.mt = Mdim / TM3;
     g.nt = Ndim / TN3;
@@ -1195,10 +1297,17 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
                                                                     (uint32_t)step * (uint32_t)p.B);
     hook->end(KK_MLP_INDEX);
 
-    hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
-    mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
-                                                                            at<uint16_t>(a, p.off_xgt), p.ldm);
-    hook->end(KK_MLP_GATHER_T);
+    // The first layer's weight gradient reads the minibatch rows straight from the dataset when
+    // it runs on the 256 x 256 tile kernel and the rows are whole tiles wide; otherwise it needs
+    // the transposed bf16 copy of the gathered rows.
+    const bool wg0_direct = p.d[0] % TM3 == 0 && gemm_is_big(false, false, GemmArgs{}, p.dp[0], p.dp[1],
+                                                               wgrad_split(p, 0, rows, local ? K : 0));
+    if (!wg0_direct) {
+      hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
+      mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
+                                                                              at<uint16_t>(a, p.off_xgt), p.ldm);
+      hook->end(KK_MLP_GATHER_T);
+    }
 
     // ---- forward at the uploads' model versions
     mlp_forward(a, a.X, rd, rows, arows, wbase, sbase, own, s, hook);
@@ -1254,12 +1363,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = p.ldm;
       g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = p.ldm;
       const int ksteps = rows / BK;
-      const int tn = p.dp[l + 1] % 256 == 0 ? 256 : p.dp[l + 1] % 128 == 0 ? 128 : 64;
-      const bool big = p.dp[l] % TM3 == 0 && p.dp[l + 1] % TN3 == 0;
-      const int tiles = big ? (p.dp[l] / TM3) * (p.dp[l + 1] / TN3) : (p.dp[l] / TM) * (p.dp[l + 1] / tn);
-      const int nsplit = local ? K
-                         : big ? pick_split(tiles, ksteps, 256, 256.0 * 256 * 4)
-                               : pick_split(tiles, ksteps, 512, 128.0 * tn * 4);
+      const int nsplit = wgrad_split(p, l, rows, local ? K : 0);
       g.ksteps_total = ksteps;
       g.ksteps_per_split = local ? p.Bp / BK : (ksteps + nsplit - 1) / nsplit;
       g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1];
@@ -1267,8 +1371,14 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
       hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
                   arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
-      if (l == 0) launch_gemm<EPI_WGRAD, false, false, 1>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
-      else        launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+      if (l == 0 && wg0_direct) {
+        g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx;
+        launch_gemm<EPI_WGRAD, false, false, 2>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+      } else if (l == 0) {
+        launch_gemm<EPI_WGRAD, false, false, 1>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+      } else {
+        launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
+      }
       hook->end(kind);
       launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, nsplit, s, hook);
     }
