@@ -33,7 +33,7 @@ KIND_SYMBOL = {
     "mlp_fwd_l1": "mlp_gemm256_kernel<0, true, true, 0>",
     "mlp_fwd_hidden": "mlp_gemm256_kernel<0, false, true, 0>",
     "mlp_dgrad": "mlp_gemm256_kernel<2, false, true, 0>",
-    "mlp_wgrad_l1": "mlp_gemm256_kernel<3, false, false, 1>",
+    "mlp_wgrad_l1": "mlp_gemm256_kernel<3, false, false, 2>",
 }
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_hbm_traffic.txt")
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2301_08895_amd", "csrc", "kernels_mlp.hip")

@@ -42,6 +42,7 @@ constexpr int kMaxSplit = 16;
 #define ABS_PITCH_PAD 64
 #endif
 constexpr int kPitchPad = ABS_PITCH_PAD;
+constexpr int kPartialPad = 32;         // the same for the fp32 weight-gradient partials (floats)
 
 size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
@@ -781,46 +782,65 @@ __device__ __forceinline__ void update_select_upload(UpdateArgs& u) {
   if (u.wn) u.wn += (size_t)a * u.shadow_stride;
   u.wt += (size_t)a * u.shadow_stride;
 }
-// Tiled version for 16-byte aligned rows (d_out % 4 == 0): a thread moves 4 consecutive
-// columns at a time.
+// Tiled version for 16-byte aligned rows (d_out % 4 == 0): a 64 x TJ tile; a thread moves 4
+// consecutive columns at a time, TJ / 4 threads cover a row (TJ = 256: 1 KB of a model row per
+// row of the tile, so that the rows of a tile - a whole number of 4 KB apart for the usual widths -
+// do not all fall on one memory channel).
+template <int TJ>
 __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
-  __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];
+  constexpr int TPR = TJ / 4;            // threads per row
+  constexpr int RPP = 256 / TPR;         // rows per pass
+  constexpr int NP = 64 / RPP;           // passes
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64][TJ + 8];
   update_select_upload(u);
-  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const int jq = (threadIdx.x & 15) * 4, ir = threadIdx.x >> 4;
+  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * TJ;
+  const int jq = (threadIdx.x % TPR) * 4, ir = threadIdx.x / TPR;
+  // two of the thread's rows at a time, with the model row and up to 8 partials of both in
+  // flight together (a partial beyond the 8th, rare, is fetched afterwards); summed in split order
+#pragma unroll 1
+  for (int r2 = 0; r2 < NP / 2; ++r2) {
+    float4 wc[2], v[2][8];
+    bool ok[2];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int il = ir + 16 * r, i = i0 + il, j = j0 + jq;
-    uint2 hh = make_uint2(0, 0);
-    if (i < u.d_in && j < u.d_out) {
-      const float* pp = u.partial + (size_t)i * u.ldp + j;
-      float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
-      int z = 0;
-      for (; z + 4 <= u.nsplit; z += 4) {      // four loads in flight, summed in split order
-        float4 v[4];
+    for (int h = 0; h < 2; ++h) {
+      const int i = i0 + ir + RPP * (2 * r2 + h), j = j0 + jq;
+      ok[h] = i < u.d_in && j < u.d_out;
+      if (ok[h]) {
+        const float* pp = u.partial + (size_t)i * u.ldp + j;
+        wc[h] = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = *(const float4*)(pp + (size_t)(z + q) * u.split_stride);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { G.x += v[q].x; G.y += v[q].y; G.z += v[q].z; G.w += v[q].w; }
+        for (int z = 0; z < 8; ++z)
+          if (z < u.nsplit) v[h][z] = *(const float4*)(pp + (size_t)z * u.split_stride);
       }
-      for (; z < u.nsplit; ++z) {
-        const float4 v = *(const float4*)(pp + (size_t)z * u.split_stride);
-        G.x += v.x; G.y += v.y; G.z += v.z; G.w += v.w;
-      }
-      float4 w = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
-      w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
-      *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
-      hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
-      hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
-      if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
     }
-    *(uint2*)&tile[il][jq] = hh;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int il = ir + RPP * (2 * r2 + h), i = i0 + il, j = j0 + jq;
+      uint2 hh = make_uint2(0, 0);
+      if (ok[h]) {
+        float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int z = 0; z < 8; ++z)
+          if (z < u.nsplit) { G.x += v[h][z].x; G.y += v[h][z].y; G.z += v[h][z].z; G.w += v[h][z].w; }
+        for (int z = 8; z < u.nsplit; ++z) {
+          const float4 t = *(const float4*)(u.partial + (size_t)i * u.ldp + j + (size_t)z * u.split_stride);
+          G.x += t.x; G.y += t.y; G.z += t.z; G.w += t.w;
+        }
+        float4 w = wc[h];
+        w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
+        *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
+        hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
+        hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+        if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
+      }
+      *(uint2*)&tile[il][jq] = hh;
+    }
   }
   __syncthreads();
   // transposed bf16 copy: thread -> column j, 8 consecutive rows i (the padded pitch of wt makes
   // the 16-byte store safe; rows beyond d_in hold zeros, which is what the padding must be)
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
+  for (int r = 0; r < TJ / 32; ++r) {
     const int q = threadIdx.x + 256 * r, jl = q >> 3, ib = (q & 7) * 8;
     const int j = j0 + jl;
     if (j < u.d_out) {
@@ -1081,7 +1101,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   }
   p.shadow_stride = round_up(o, 128);
   size_t partial = 0;
-  for (int l = 0; l < L; ++l) partial = std::max(partial, (size_t)p.dp[l] * p.dp[l + 1]);
+  for (int l = 0; l < L; ++l) partial = std::max(partial, (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad));
   p.partial_floats = partial * (p.U > 1 ? std::max<size_t>(kMaxSplit, (size_t)c.N) : (size_t)kMaxSplit);
 
   size_t b = 0;
@@ -1145,8 +1165,8 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
     u.batched = 1;
     batch = rd.K;
     u.partial = at<float>(a, p.off_partial);
-    u.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
-    u.ldp = (size_t)p.dp[l + 1];
+    u.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
+    u.ldp = (size_t)p.dp[l + 1] + kPartialPad;
     u.nsplit = 1;
     u.w_cur = (step == 0 ? ring : priv) + p.w_off[l];
     u.cur_stride = p.slot_stride;
@@ -1160,8 +1180,8 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
     uint16_t* shadow = at<uint16_t>(a, p.off_shadow) + (size_t)rd.slot_next * p.shadow_stride;
     if (mode == UPD_GLOBAL) {
       u.partial = at<float>(a, p.off_partial);
-      u.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
-      u.ldp = (size_t)p.dp[l + 1];
+      u.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
+      u.ldp = (size_t)p.dp[l + 1] + kPartialPad;
       u.nsplit = nsplit;
     } else {
       u.partial = at<float>(a, p.off_delta) + p.w_off[l];
@@ -1178,7 +1198,8 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
   hook->begin(KK_MLP_UPDATE, n * (u.nsplit + 1), n * (4.0 * (u.nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
   const dim3 block(256);
   const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
-  if (vec) mlp_update_kernel<<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
+  if (vec && p.d[l + 1] >= 256) mlp_update_kernel<256><<<dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
+  else if (vec) mlp_update_kernel<64><<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
   else     mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, 0, s>>>(u);
   hook->end(KK_MLP_UPDATE);
 }
@@ -1366,8 +1387,8 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       const int nsplit = wgrad_split(p, l, rows, local ? K : 0);
       g.ksteps_total = ksteps;
       g.ksteps_per_split = local ? p.Bp / BK : (ksteps + nsplit - 1) / nsplit;
-      g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1];
-      g.split_stride = (size_t)p.dp[l] * p.dp[l + 1];
+      g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1] + kPartialPad;
+      g.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
       const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
       hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
                   arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
