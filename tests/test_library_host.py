@@ -99,3 +99,19 @@ def test_argument_errors():
         sim.round(200)
     assert e.value.code == -4
     sim.close()
+
+
+def test_batch_and_evaluate_argument_errors_without_a_gpu():
+    """Schedule-only handles have no model: they can be neither evaluated nor batched."""
+    p = dict(workloads.preset(1), k_mode=1)
+    a = lib.Simulation(p, None, device_mode=0)
+    b = lib.Simulation(dict(p, seed_sim=7), None, device_mode=0)
+    with pytest.raises(lib.AbsError) as e:
+        lib.abs_evaluate(a.handle, -1, None, None, 10)
+    assert e.value.code == -1
+    with pytest.raises(lib.AbsError) as e:
+        lib.abs_batch_create([a.handle, b.handle])
+    assert e.value.code == -1 and "schedule-only" in str(e.value)
+    with pytest.raises(lib.AbsError):
+        lib.abs_batch_create([])
+    a.close(); b.close()
