@@ -207,8 +207,10 @@ void abs_destroy(abs_ctx* ctx);
  *                     (abs_get_model, abs_trace, abs_evaluate, abs_round) between batch calls.
  *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
  *                     count); results are exactly those of abs_round on each handle alone.
- *                     On an error of one simulation the call stops: the simulations before it
- *                     in the batch have completed that round, the others have not.
+ *                     On an error of one simulation the call stops and names it: simulations
+ *                     before it in the batch may have completed that round, the failing one and
+ *                     those after it have not (a handle that did not complete a round repeats
+ *                     it, with the same result, the next time it is advanced).
  *  abs_batch_last_error  text of the last error (b == NULL: of the last failed abs_batch_create
  *                     on this thread).
  */
