@@ -9,6 +9,7 @@
 #include <cstring>
 #include <memory>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "kernels.h"
@@ -430,61 +431,133 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
   return ABS_OK;
 }
 
-int abs_batch_round(abs_batch* b, int32_t n_rounds) {
-  if (!b || n_rounds < 0) return ABS_E_ARG;
-  const int S = (int)b->ctx.size();
-  const abs_config& c0 = b->ctx[0]->cfg;
-  std::vector<std::vector<Upload>> sel((size_t)S);
-  std::vector<uint32_t> stamp((size_t)S);
-  RoundDesc rd;
-  std::memset(&rd, 0, sizeof(rd));
-  for (int32_t it = 0; it < n_rounds; ++it) {
-    const int buf = (int)(b->rounds & 1);
-    int Kmax = 0;
-    for (int i = 0; i < S; ++i) {
+// The host part of a batched round (select, descriptor, mailbox, Eq. 4-6 per simulation) is
+// independent per simulation, so large batches spread it over a few threads that live for the
+// duration of the call: thread k owns simulations k, k + T, ...  A round has two parallel phases
+// around the launch; workers spin on a phase counter (a round lasts tens of microseconds).
+namespace {
+struct BatchRoundState {
+  abs_batch* b;
+  int S, T;
+  std::vector<std::vector<Upload>> sel;
+  std::vector<uint32_t> stamp;
+  std::vector<int> kmax, rc, bad_sim;          // per thread
+  std::atomic<int> phase{0};                   // 2 r + 1: prepare round r, 2 r + 2: finish round r, -1: exit
+  std::atomic<int> done{0};
+  std::atomic<bool> abort{false};
+  int buf = 0;
+
+  // Thread 0, now and then while mailboxes are awaited: has the stream failed?  (A stream that has
+  // drained has written every mailbox, so only a runtime error ends the wait.)
+  bool stream_failed() {
+    const hipError_t q = hipStreamQuery(b->stream);
+    if (q == hipSuccess || q == hipErrorNotReady) return false;
+    b->err = std::string("hipStreamQuery: ") + hipGetErrorString(q);
+    rc[0] = ABS_E_HIP; bad_sim[0] = -1;
+    abort.store(true);
+    return true;
+  }
+  void prepare(int k) {                        // select the uploads, write the descriptors
+    int km = 0;
+    for (int i = k; i < S; i += T) {
       abs_ctx* ctx = b->ctx[(size_t)i];
-      int rc = ctx->sched->select(sel[(size_t)i], ctx->err);
-      if (rc != ABS_OK) { b->err = "simulation " + std::to_string(i) + ": " + ctx->err; return rc; }
+      const int r = ctx->sched->select(sel[(size_t)i], ctx->err);
+      if (r != ABS_OK) { if (rc[(size_t)k] == ABS_OK) { rc[(size_t)k] = r; bad_sim[(size_t)k] = i; } continue; }
+      RoundDesc rd;
       fill_round_desc(ctx, sel[(size_t)i], ctx->sched->round(), rd);
       std::memcpy(b->h_rds[buf] + (size_t)i * b->rd_stride, &rd, 16 + (size_t)rd.K * sizeof(WorkerDesc));
       stamp[(size_t)i] = rd.stamp;
-      Kmax = std::max(Kmax, (int)rd.K);
+      km = std::max(km, (int)rd.K);
     }
-    hipError_t e = hipMemcpyAsync(b->d_rds[buf], b->h_rds[buf], (size_t)S * b->rd_stride, hipMemcpyHostToDevice, b->stream);
-    if (e == hipSuccess)
-      e = launch_regression_round_batch(b->d_args, b->d_rds[buf], b->rd_stride, S, c0.model == ABS_MODEL_SOFTMAX,
-                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->stream);
-    if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); return ABS_E_HIP; }
-    b->rounds += 1;
-    // all S mailboxes; now and then ask the runtime whether the stream failed or drained
-    for (int i = 0; i < S; ++i) {
+    kmax[(size_t)k] = km;
+  }
+  void finish(int k) {                         // wait for the losses, apply Eq. 4-6
+    for (int i = k; i < S; i += T) {
       const volatile LossMailbox* box = b->h_box + i;
       for (uint64_t spin = 1; box->stamp != stamp[(size_t)i]; ++spin) {
-        if ((spin & 0x3FFF) == 0) {
-          const hipError_t q = hipStreamQuery(b->stream);
-          if (q == hipSuccess) {
-            if (box->stamp == stamp[(size_t)i]) break;
-            b->err = "stream drained but a loss mailbox was not written";
-            return ABS_E_HIP;
-          }
-          if (q != hipErrorNotReady) { b->err = std::string("hipStreamQuery: ") + hipGetErrorString(q); return ABS_E_HIP; }
-        }
+        if (abort.load(std::memory_order_relaxed)) return;
+        if (k == 0 && (spin & 0x3FFF) == 0 && stream_failed()) return;
 #if defined(__x86_64__)
         __builtin_ia32_pause();
 #endif
       }
-    }
-    std::atomic_thread_fence(std::memory_order_acquire);
-    for (int i = 0; i < S; ++i) {
+      std::atomic_thread_fence(std::memory_order_acquire);
       abs_ctx* ctx = b->ctx[(size_t)i];
       float losses[ABS_MAX_WORKERS];
       const int K = (int)sel[(size_t)i].size();
       for (int a = 0; a < K; ++a) losses[a] = b->h_box[i].loss[a];
-      int rc = ctx->sched->complete(sel[(size_t)i], losses, true, ctx->err);
-      if (rc != ABS_OK) { b->err = "simulation " + std::to_string(i) + ": " + ctx->err; return rc; }
+      const int r = ctx->sched->complete(sel[(size_t)i], losses, true, ctx->err);
+      if (r != ABS_OK && rc[(size_t)k] == ABS_OK) { rc[(size_t)k] = r; bad_sim[(size_t)k] = i; }
     }
   }
-  return ABS_OK;
+  void worker(int k) {
+    int seen = 0;
+    for (;;) {
+      int p;
+      while ((p = phase.load(std::memory_order_acquire)) == seen) {
+#if defined(__x86_64__)
+        __builtin_ia32_pause();
+#endif
+      }
+      if (p < 0) return;
+      seen = p;
+      if (p & 1) prepare(k); else finish(k);
+      done.fetch_add(1, std::memory_order_release);
+    }
+  }
+  // run one phase on all threads (this one is thread 0); returns the first failing simulation's code
+  int run(int p) {
+    done.store(0, std::memory_order_relaxed);
+    phase.store(p, std::memory_order_release);
+    if (p & 1) prepare(0); else finish(0);
+    for (uint64_t spin = 1; done.load(std::memory_order_acquire) != T - 1; ++spin) {
+      if (!(p & 1) && (spin & 0x3FFF) == 0 && !abort.load()) stream_failed();   // the others may still wait for mailboxes
+#if defined(__x86_64__)
+      __builtin_ia32_pause();
+#endif
+    }
+    int first = -2, code = ABS_OK;
+    for (int k = 0; k < T; ++k)
+      if (rc[(size_t)k] != ABS_OK && (first == -2 || bad_sim[(size_t)k] < first)) { first = bad_sim[(size_t)k]; code = rc[(size_t)k]; }
+    if (code != ABS_OK && first >= 0) b->err = "simulation " + std::to_string(first) + ": " + b->ctx[(size_t)first]->err;
+    return code;
+  }
+};
+}  // namespace
+
+int abs_batch_round(abs_batch* b, int32_t n_rounds) {
+  if (!b || n_rounds < 0) return ABS_E_ARG;
+  const int S = (int)b->ctx.size();
+  const abs_config& c0 = b->ctx[0]->cfg;
+  BatchRoundState st;
+  st.b = b;
+  st.S = S;
+  st.T = std::max(1, std::min({8, S / 32, (int)std::thread::hardware_concurrency() / 2}));
+  st.sel.resize((size_t)S);
+  st.stamp.resize((size_t)S);
+  st.kmax.assign((size_t)st.T, 0);
+  st.rc.assign((size_t)st.T, ABS_OK);
+  st.bad_sim.assign((size_t)st.T, -1);
+  std::vector<std::thread> pool;
+  for (int k = 1; k < st.T; ++k) pool.emplace_back([&st, k] { st.worker(k); });
+  int rc = ABS_OK;
+  for (int32_t it = 0; it < n_rounds && rc == ABS_OK; ++it) {
+    st.buf = (int)(b->rounds & 1);
+    rc = st.run(2 * it + 1);
+    if (rc != ABS_OK) break;
+    int Kmax = 0;
+    for (int k = 0; k < st.T; ++k) Kmax = std::max(Kmax, st.kmax[(size_t)k]);
+    hipError_t e = hipMemcpyAsync(b->d_rds[st.buf], b->h_rds[st.buf], (size_t)S * b->rd_stride, hipMemcpyHostToDevice, b->stream);
+    if (e == hipSuccess)
+      e = launch_regression_round_batch(b->d_args, b->d_rds[st.buf], b->rd_stride, S, c0.model == ABS_MODEL_SOFTMAX,
+                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->stream);
+    if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); rc = ABS_E_HIP; break; }
+    b->rounds += 1;
+    rc = st.run(2 * it + 2);
+  }
+  st.phase.store(-1, std::memory_order_release);
+  for (std::thread& t : pool) t.join();
+  return rc;
 }
 
 const char* abs_batch_last_error(const abs_batch* b) { return b ? b->err.c_str() : g_batch_error.c_str(); }
