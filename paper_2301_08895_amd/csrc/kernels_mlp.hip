@@ -699,8 +699,8 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 }
 
 // ------------------------------------------------------------------ softmax cross-entropy
-// A wavefront per stacked row (16 wavefronts, 4 rows each, 64 rows per workgroup): loss of the
-// row, dZ_L = c_k (softmax - onehot) narrowed
+// A wavefront per stacked row (16 wavefronts, 4 rows each, 64 rows per workgroup): the 64 rows'
+// loss sum (rowloss[workgroup]), dZ_L = c_k (softmax - onehot) narrowed
 // to bf16 (zero for padding rows and padding columns), in both orientations.
 template <int NC>   // columns per lane: padded class count / 64
 __global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
@@ -708,19 +708,32 @@ __global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, si
                                                             uint16_t* dZT, size_t lddzt, float* rowloss,
                                                             float* colsum, size_t ldcs) {
   __shared__ uint16_t sT[NC * 64][72];
+  __shared__ float s_l[16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m0 = blockIdx.x * 64;
   const float coef = rd.w[m0 / Bp].c;
+  float zin[4][NC];                      // the wavefront's four rows: all loads first
+  int labs[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wave * 4 + i;
+    labs[i] = label[m];
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int c = lane + 64 * q;
+      zin[i][q] = c < C ? Z[(size_t)m * ldz + c] : -INFINITY;
+    }
+  }
+  float lsum = 0.f;                      // lane 0: loss of the wavefront's rows
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int ml = wave * 4 + i, m = m0 + ml;
-    const int lab = label[m];
+    const int lab = labs[i];
     float z[NC];
     float zmax = -INFINITY;
 #pragma unroll
     for (int q = 0; q < NC; ++q) {
-      const int c = lane + 64 * q;
-      z[q] = c < C ? Z[(size_t)m * ldz + c] : -INFINITY;
+      z[q] = zin[i][q];
       zmax = fmaxf(zmax, z[q]);
     }
     zmax = wave_max(zmax);
@@ -734,7 +747,7 @@ __global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, si
     }
     ssum = wave_sum(ssum);
     zy = wave_sum(zy);
-    if (lane == 0) rowloss[m] = lab >= 0 ? logf(ssum) - zy : 0.f;
+    if (lane == 0) lsum += lab >= 0 ? logf(ssum) - zy : 0.f;
 #pragma unroll
     for (int q = 0; q < NC; ++q) {
       const int c = lane + 64 * q;
@@ -745,7 +758,14 @@ __global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, si
       sT[c][ml] = h;
     }
   }
+  if (lane == 0) s_l[wave] = lsum;
   __syncthreads();
+  if (threadIdx.x == 0) {                // the 64 rows' losses, in wavefront order
+    float l = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) l += s_l[v];
+    rowloss[blockIdx.x] = l;
+  }
   for (int q = threadIdx.x; q < NC * 64 * 8; q += 1024) {
     const int c = q >> 3, ch = q & 7;
     *(uint4*)(dZT + (size_t)c * lddzt + m0 + ch * 8) = *(const uint4*)&sT[c][ch * 8];
@@ -930,26 +950,25 @@ __global__ __launch_bounds__(256) void mlp_bias_kernel(BiasArgs a) {
 }
 
 // The uploads' mean minibatch losses (what each worker reports next to its gradient), one
-// wavefront per upload in a single workgroup, then the mailbox stamp.  Runs right after the
+// thread per upload over the loss sums of its blocks of 64 rows, then the mailbox stamp.  Runs right after the
 // loss kernel so that the host can prepare the next round under this round's backward pass.
 // Local SGD: lossacc carries the sum over the job's steps; only the last step publishes.
-__global__ __launch_bounds__(1024) void mlp_loss_kernel(const float* rowloss, int B, int Bp, int K, uint32_t stamp,
+__global__ __launch_bounds__(128) void mlp_loss_kernel(const float* rowloss, int B, int Bp, int K, uint32_t stamp,
                                                        LossMailbox* mailbox, float* lossacc, int first, int last,
                                                        int U) {
   __shared__ float s_loss[ABS_MAX_WORKERS];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int up = wave; up < K; up += 16) {
+  const int up = threadIdx.x;
+  if (up < K) {                          // rowloss: the loss sums of the upload's blocks of 64 rows
+    const int nb = Bp / 64;
     float s = 0.f;
-    for (int b = lane; b < B; b += 64) s += rowloss[(size_t)up * Bp + b];
-    s = wave_sum(s) / (float)B;
-    if (lane == 0) {
-      if (lossacc) {
-        s += first ? 0.f : lossacc[up];
-        lossacc[up] = s;
-        s /= (float)U;
-      }
-      s_loss[up] = s;
+    for (int q = 0; q < nb; ++q) s += rowloss[(size_t)up * nb + q];
+    s /= (float)B;
+    if (lossacc) {
+      s += first ? 0.f : lossacc[up];
+      lossacc[up] = s;
+      s /= (float)U;
     }
+    s_loss[up] = s;
   }
   __syncthreads();
   if (last) publish_losses(mailbox, s_loss, K, stamp);
@@ -1349,7 +1368,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       }
       hook->end(KK_MLP_SOFTMAX_CE);
       hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
-      mlp_loss_kernel<<<dim3(1), dim3(1024), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox,
+      mlp_loss_kernel<<<dim3(1), dim3(128), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox,
                                                      local ? at<float>(a, p.off_lossacc) : nullptr,
                                                      step == 0, step == U - 1, U);
       hook->end(KK_MLP_LOSS);
