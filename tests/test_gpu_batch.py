@@ -85,3 +85,25 @@ def test_batch_rejects_mixed_shapes_and_mlp():
         lib.Batch([m])
     for s in (a, b, m):
         s.close()
+
+
+def test_batch_of_simulations_on_different_datasets():
+    """Only the shape has to agree: every simulation may bring its own dataset."""
+    base = workloads.scaled_preset(2, M=3000, dims=[32, 5], n_classes=5, N=8, B=12, lr=2e-2)
+    ps = [dict(base, seed_data=base["seed_data"] + 5 * i, seed_sim=base["seed_sim"] + i) for i in range(5)]
+    ds = [workloads.make_inputs(p) for p in ps]
+    sims = [lib.Simulation(p, d) for p, d in zip(ps, ds)]
+    batch = lib.Batch(sims)
+    batch.round(40)
+    got = [(s.model().copy(), s.trace().copy()) for s in sims]
+    batch.close()
+    for s in sims:
+        s.close()
+    for p, d, (m, tr) in zip(ps, ds, got):
+        alone = lib.Simulation(p, d)
+        alone.round(40)
+        assert np.array_equal(alone.model(), m) and np.array_equal(alone.trace(), tr)
+        alone.close()
+        o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False).run(40)
+        if all(int(a) == r["K"] for a, r in zip(tr[:, 1], o.trace)):
+            assert rel_err(m, o.model()) <= 1e-5

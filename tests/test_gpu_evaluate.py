@@ -67,3 +67,8 @@ def test_version_outside_the_ring_is_an_error():
     with pytest.raises(lib.AbsError):
         sim.evaluate(d["X"], d["y"], 21)
     sim.close()
+
+
+def test_mlp_full_width_several_passes():
+    """The 3072-512-10 workload's layer shapes, evaluation set larger than two passes of N * Bp rows."""
+    _check(workloads.scaled_preset(3, M=6400), 10, 9001, 2e-3)
