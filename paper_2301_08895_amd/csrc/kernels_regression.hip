@@ -139,33 +139,60 @@ hipError_t launch_linreg_round(const RegressionArgs& a, const RoundDesc& rd, hip
 }
 
 // ------------------------------------------------------------------ softmax regression
-// Kernel 1 (one wavefront per stacked row): logits of the row at its upload's stale
-// model, softmax cross-entropy, and the row of dZ = c (softmax - onehot).
-// A lane owns float4 chunks lane, lane+64, ... of x; the matching 4 x C block of W is
-// 4C contiguous floats, read as C float4.  Logits are completed by wavefront reductions.
+// Kernel 1 (a workgroup per 4 RPW rows of one upload; a wavefront takes RPW rows, RPW = 4 when the
+// launch has rows to spare, else 1):
+// logits of the row at its upload's stale model, softmax cross-entropy, and the row of
+// dZ = c (softmax - onehot).  A lane owns float4 chunks lane, lane+64, ... of x; the matching
+// 4 x C block of W is 4C contiguous floats, read as C float4 once per chunk and used for the
+// wavefront's RPW rows (a row on its own fetches all of W, ten times its own bytes, from L2).
+// The rows' loads are all issued first.  Logits are completed by wavefront reductions.
 constexpr int kSoftQF = 4;          // float4 chunks per lane  ->  d <= 1024
 constexpr int kDzPitch = 16;        // floats per dZ row (C <= 16)
+constexpr int kRowsToSpare = 8192;  // stacked rows of a launch from which a wavefront takes 4 rows
 
-template <int C>
+template <int C, int RPW>
 __device__ __forceinline__ void softmax_rows_body(const RegressionArgs& a, const RoundDesc& rd) {
-  const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  constexpr int kRowsPerBlock = 4 * RPW;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int B = a.B, d = a.d;
-  if (r >= rd.K * B) return;
-  const int up = r / B;
+  const int bpu = (B + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int up = blockIdx.x / bpu, chunk = blockIdx.x - up * bpu;
+  if (up >= rd.K) return;
   const WorkerDesc w = rd.w[up];
-  const uint64_t row = batch_row(w, a.batch_key, a.shard_rows, (uint32_t)(r - up * B));
-  const float4* xr = (const float4*)(a.X + row * (uint64_t)d);
   const float* Wv = a.ring + (size_t)w.slot * a.slot_stride;
-  const int nchunk = d >> 2;
-  float acc[C];
+  float bz[C];
 #pragma unroll
-  for (int c = 0; c < C; ++c) acc[c] = 0.f;
+  for (int c = 0; c < C; ++c) bz[c] = Wv[(size_t)d * C + c];
+  const int nchunk = d >> 2;
+  // this wavefront's (up to) RPW rows: all their loads first
+  float4 xv[RPW][kSoftQF];
+  uint64_t rows[RPW];
+  int labels[RPW];
+#pragma unroll
+  for (int k = 0; k < RPW; ++k) {
+    const int b = chunk * kRowsPerBlock + wave + 4 * k;
+    rows[k] = 0; labels[k] = 0;
+    if (b < B) {
+      rows[k] = batch_row(w, a.batch_key, a.shard_rows, (uint32_t)b);
+      const float4* xr = (const float4*)(a.X + rows[k] * (uint64_t)d);
+#pragma unroll
+      for (int q = 0; q < kSoftQF; ++q) {
+        const int ch = lane + 64 * q;
+        xv[k][q] = ch < nchunk ? xr[ch] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      labels[k] = ((const int32_t*)a.y)[rows[k]];
+    }
+  }
+  // the lane's 4 x C block of W for each of its chunks is fetched once and used for all RPW rows
+  float accs[RPW][C];
+#pragma unroll
+  for (int k = 0; k < RPW; ++k)
+#pragma unroll
+    for (int c = 0; c < C; ++c) accs[k][c] = 0.f;
 #pragma unroll
   for (int q = 0; q < kSoftQF; ++q) {
     const int ch = lane + 64 * q;
     if (ch < nchunk) {
-      const float4 xv = xr[ch];
       const float4* wp = (const float4*)(Wv + (size_t)ch * 4 * C);
       float wf[4 * C];
 #pragma unroll
@@ -174,39 +201,49 @@ __device__ __forceinline__ void softmax_rows_body(const RegressionArgs& a, const
         wf[4 * i + 0] = t.x; wf[4 * i + 1] = t.y; wf[4 * i + 2] = t.z; wf[4 * i + 3] = t.w;
       }
 #pragma unroll
-      for (int c = 0; c < C; ++c) {
-        acc[c] = fmaf(xv.x, wf[0 * C + c], acc[c]);
-        acc[c] = fmaf(xv.y, wf[1 * C + c], acc[c]);
-        acc[c] = fmaf(xv.z, wf[2 * C + c], acc[c]);
-        acc[c] = fmaf(xv.w, wf[3 * C + c], acc[c]);
-      }
+      for (int k = 0; k < RPW; ++k)
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+          accs[k][c] = fmaf(xv[k][q].x, wf[0 * C + c], accs[k][c]);
+          accs[k][c] = fmaf(xv[k][q].y, wf[1 * C + c], accs[k][c]);
+          accs[k][c] = fmaf(xv[k][q].z, wf[2 * C + c], accs[k][c]);
+          accs[k][c] = fmaf(xv[k][q].w, wf[3 * C + c], accs[k][c]);
+        }
     }
   }
-  const float* bias = Wv + (size_t)d * C;
-  float zmax = -INFINITY;
 #pragma unroll
-  for (int c = 0; c < C; ++c) {
-    acc[c] = wave_sum(acc[c]) + bias[c];
-    zmax = fmaxf(zmax, acc[c]);
-  }
-  const int label = ((const int32_t*)a.y)[row];
-  float ssum = 0.f, zy = 0.f, mine = 0.f;
+  for (int k = 0; k < RPW; ++k) {
+    const int b = chunk * kRowsPerBlock + wave + 4 * k;
+    if (b >= B) break;
+    const int r = up * B + b;
+    float acc[C];
 #pragma unroll
-  for (int c = 0; c < C; ++c) {
-    if (c == label) zy = acc[c] - zmax;
-    acc[c] = expf(acc[c] - zmax);
-    ssum += acc[c];
-  }
+    for (int c = 0; c < C; ++c) acc[c] = accs[k][c];
+    float zmax = -INFINITY;
 #pragma unroll
-  for (int c = 0; c < C; ++c) {
-    const float p = acc[c] / ssum;
-    if (c == lane) mine = w.c * (p - (c == label ? 1.f : 0.f));
-  }
-  if (lane < kDzPitch) a.dz[(size_t)r * kDzPitch + lane] = lane < C ? mine : 0.f;
-  if (lane == 0) {
-    // -log softmax_y = log(sum exp(z - zmax)) - (z_y - zmax)
-    a.rowloss[r] = logf(ssum) - zy;
-    a.rowidx[r] = (uint32_t)row;
+    for (int c = 0; c < C; ++c) {
+      acc[c] = wave_sum(acc[c]) + bz[c];
+      zmax = fmaxf(zmax, acc[c]);
+    }
+    const int label = labels[k];
+    float ssum = 0.f, zy = 0.f, mine = 0.f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      if (c == label) zy = acc[c] - zmax;
+      acc[c] = expf(acc[c] - zmax);
+      ssum += acc[c];
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      const float p = acc[c] / ssum;
+      if (c == lane) mine = w.c * (p - (c == label ? 1.f : 0.f));
+    }
+    if (lane < kDzPitch) a.dz[(size_t)r * kDzPitch + lane] = lane < C ? mine : 0.f;
+    if (lane == 0) {
+      // -log softmax_y = log(sum exp(z - zmax)) - (z_y - zmax)
+      a.rowloss[r] = logf(ssum) - zy;
+      a.rowidx[r] = (uint32_t)rows[k];
+    }
   }
 }
 
@@ -299,20 +336,20 @@ __device__ __forceinline__ void softmax_update_body(const RegressionArgs& a, con
   }
 }
 
-template <int C>
+template <int C, int RPW>
 __global__ __launch_bounds__(256) void softmax_rows_kernel(RegressionArgs a, RoundDesc rd) {
-  softmax_rows_body<C>(a, rd);
+  softmax_rows_body<C, RPW>(a, rd);
 }
 template <int C>
 __global__ __launch_bounds__(1024) void softmax_update_kernel(RegressionArgs a, RoundDesc rd) {
   softmax_update_body<C>(a, rd);
 }
 // Batched forms: blockIdx.y = simulation (see linreg_round_batch_kernel).
-template <int C>
+template <int C, int RPW>
 __global__ __launch_bounds__(256) void softmax_rows_batch_kernel(const RegressionArgs* as, const char* rds,
                                                                  size_t stride) {
   const RegressionArgs a = as[blockIdx.y];
-  softmax_rows_body<C>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
+  softmax_rows_body<C, RPW>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
 }
 template <int C>
 __global__ __launch_bounds__(1024) void softmax_update_batch_kernel(const RegressionArgs* as, const char* rds,
@@ -327,7 +364,8 @@ static hipError_t softmax_round_c(const RegressionArgs& a, const RoundDesc& rd, 
   const int R = rd.K * a.B;
   const double rows = (double)R;
   hook->begin(KK_SOFTMAX_ROWS, rows * a.d * C * 2.0, rows * (a.d + 1) * 4.0);
-  softmax_rows_kernel<C><<<dim3((R + 3) / 4), dim3(256), 0, s>>>(a, rd);
+  if (R >= kRowsToSpare) softmax_rows_kernel<C, 4><<<dim3(rd.K * ((a.B + 15) / 16)), dim3(256), 0, s>>>(a, rd);
+  else                   softmax_rows_kernel<C, 1><<<dim3(rd.K * ((a.B + 3) / 4)), dim3(256), 0, s>>>(a, rd);
   hook->end(KK_SOFTMAX_ROWS);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -359,11 +397,14 @@ hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const cha
     else                linreg_round_batch_kernel<8><<<grid, block, 0, s>>>(d_args, d_rds, stride);
     return hipGetLastError();
   }
-  const int R = Kmax * B, nslice = (d + kUpdF - 1) / kUpdF;
+  const int nslice = (d + kUpdF - 1) / kUpdF;
   switch (C) {
 #define ABS_CASE(c)                                                                                          \
   case c:                                                                                                    \
-    softmax_rows_batch_kernel<c><<<dim3((R + 3) / 4, S), dim3(256), 0, s>>>(d_args, d_rds, stride);          \
+    if ((long)S * Kmax * B >= kRowsToSpare)                                                                  \
+      softmax_rows_batch_kernel<c, 4><<<dim3(Kmax * ((B + 15) / 16), S), dim3(256), 0, s>>>(d_args, d_rds, stride); \
+    else                                                                                                     \
+      softmax_rows_batch_kernel<c, 1><<<dim3(Kmax * ((B + 3) / 4), S), dim3(256), 0, s>>>(d_args, d_rds, stride);  \
     softmax_update_batch_kernel<c><<<dim3(nslice + 1, S), dim3(1024), 0, s>>>(d_args, d_rds, stride);        \
     break;
     ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
