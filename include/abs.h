@@ -206,7 +206,12 @@ void abs_destroy(abs_ctx* ctx);
  *                     borrows the handles: they must outlive it, and stay usable on their own
  *                     (abs_get_model, abs_trace, abs_evaluate, abs_round) between batch calls.
  *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
- *                     count); results are exactly those of abs_round on each handle alone.
+ *                     count).  A simulation's result does not depend on what else is in the
+ *                     batch.  Linear model: bitwise the result of abs_round on the handle alone.
+ *                     Softmax model: the batched round adds up each upload's gradient before
+ *                     Eq. 3 sums the uploads, another rounding order than abs_round's, so models
+ *                     agree with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5
+ *                     that hangs on the last bit of a loss may differ).
  *                     On an error of one simulation the call stops and names it: simulations
  *                     before it in the batch may have completed that round, the failing one and
  *                     those after it have not (a handle that did not complete a round repeats

@@ -368,6 +368,7 @@ struct abs_batch {
   size_t rd_stride = 0;
   LossMailbox* h_box = nullptr;            // pinned, device-visible [S]
   LossMailbox* d_box = nullptr;
+  char* d_slots = nullptr;                 // softmax: per-upload gradient slots and losses of all simulations
   uint64_t rounds = 0;
   std::string err;
 };
@@ -382,6 +383,7 @@ void abs_batch_destroy(abs_batch* b) {
     if (b->d_rds[i]) (void)hipFree(b->d_rds[i]);
   }
   if (b->h_box) (void)hipHostFree(b->h_box);
+  if (b->d_slots) (void)hipFree(b->d_slots);
   delete b;
 }
 
@@ -420,10 +422,18 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
   if (!hip(hipHostMalloc((void**)&b->h_box, (size_t)n * sizeof(LossMailbox), hipHostMallocMapped), "hipHostMalloc")) return ABS_E_HIP;
   std::memset(b->h_box, 0, (size_t)n * sizeof(LossMailbox));
   if (!hip(hipHostGetDevicePointer((void**)&b->d_box, b->h_box, 0), "hipHostGetDevicePointer")) return ABS_E_HIP;
+  // softmax rounds of a batch keep one gradient per upload: N slots and N losses per simulation
+  const size_t slot_floats = (size_t)c0->cfg.N * c0->slot_stride, sim_floats = slot_floats + round_up((size_t)c0->cfg.N, 64);
+  if (c0->cfg.model == ABS_MODEL_SOFTMAX &&
+      !hip(hipMalloc((void**)&b->d_slots, (size_t)n * sim_floats * sizeof(float)), "hipMalloc")) return ABS_E_HIP;
   std::vector<RegressionArgs> args((size_t)n);
   for (int32_t i = 0; i < n; ++i) {
     fill_regression_args(ctxs[i], args[(size_t)i]);
     args[(size_t)i].mailbox = b->d_box + i;          // the batch's own mailboxes
+    if (b->d_slots) {
+      args[(size_t)i].delta = (float*)b->d_slots + (size_t)i * sim_floats;
+      args[(size_t)i].lossbuf = args[(size_t)i].delta + slot_floats;
+    }
   }
   if (!hip(hipMemcpyAsync(b->d_args, args.data(), (size_t)n * sizeof(RegressionArgs), hipMemcpyHostToDevice, b->stream), "hipMemcpyAsync")) return ABS_E_HIP;
   if (!hip(hipStreamSynchronize(b->stream), "hipStreamSynchronize")) return ABS_E_HIP;
@@ -550,7 +560,7 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
     hipError_t e = hipMemcpyAsync(b->d_rds[st.buf], b->h_rds[st.buf], (size_t)S * b->rd_stride, hipMemcpyHostToDevice, b->stream);
     if (e == hipSuccess)
       e = launch_regression_round_batch(b->d_args, b->d_rds[st.buf], b->rd_stride, S, c0.model == ABS_MODEL_SOFTMAX,
-                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->stream);
+                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->d_slots != nullptr, b->stream);
     if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); rc = ABS_E_HIP; break; }
     b->rounds += 1;
     rc = st.run(2 * it + 2);

@@ -65,9 +65,10 @@ hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDes
 
 // One round of S simulations of one shape in a single set of launches (blockIdx.y = simulation):
 // d_args [S] and the S round descriptors (header + uploads, `stride` bytes apart) live in device
-// memory; Kmax = the largest K^t among them.
+// memory; Kmax = the largest K^t among them.  slots: every simulation's `delta` ([N][slot_stride]) and
+// `lossbuf` ([N]) are there, so the softmax round may keep per-upload gradients (the fused form).
 hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
-                                         bool softmax, int d, int C, int B, int Kmax, hipStream_t s);
+                                         bool softmax, int d, int C, int B, int Kmax, bool slots, hipStream_t s);
 
 // ---- held-out evaluation (the read-outs of Section V-B: loss of the global model, accuracy) ----
 // Per-row losses and "argmax is the label" flags go to a scratch of `cap` rows; a single

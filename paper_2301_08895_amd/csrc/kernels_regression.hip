@@ -358,6 +358,315 @@ __global__ __launch_bounds__(1024) void softmax_update_batch_kernel(const Regres
   softmax_update_body<C>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
 }
 
+// ------------------------------------------------------------------ batched softmax rounds, fused
+// With many simulations per launch there are enough uploads to give each a workgroup of its own,
+// and then the round reads every minibatch row from HBM once.  The upload's stale model sits in
+// LDS, transposed ([class][feature]); the rows pass through LDS in tiles of 16, the next tile in
+// flight in registers meanwhile.  Both products of a tile run on the fp32 matrix cores
+// (16x16x4 tiles, classes padded to 16):
+//   (1) logits Z = X_tile W: the eight wavefronts split the features, their partial 16 x 16 tiles
+//       are added through LDS, and 256 threads (row, class) finish softmax, loss and the rows of
+//       dZ = c (softmax - onehot), with reductions over the 16 classes inside a DPP row;
+//   (2) G += X_tile^T dZ: a wavefront owns blocks of 16 features, whose 16 x 16 gradient tiles
+//       stay in its accumulators for the whole upload.
+// The upload's gradient goes to a scratch slot; a second kernel adds the K^t slots in arrival
+// order (Eq. 3) and writes w^{t+1} and the losses.
+constexpr int kFuseThreads = 512, kFuseWaves = 8, kFuseMaxB = 1024;
+constexpr size_t kLdsPerCu = 160 * 1024;
+typedef float f32x4_ __attribute__((ext_vector_type(4)));
+// loads known to be from global memory (a pointer read from memory is generic to the compiler)
+template <class T>
+__device__ __forceinline__ T load_global(const T* p) { return *(const __attribute__((address_space(1))) T*)p; }
+__device__ __forceinline__ float4 load_global_f4(const float* p) {
+  const f32x4_ v = *(const __attribute__((address_space(1))) f32x4_*)p;
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
+// Reductions over the 16 lanes of a DPP row by four lane permutations (lane ^ 1, lane ^ 2, mirror
+// of 8, mirror of 16); every lane ends with the result.  All lanes of the wavefront must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_perm(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_perm<0xB1>(v);      // quad_perm [1,0,3,2]
+  v += dpp_perm<0x4E>(v);      // quad_perm [2,3,0,1]
+  v += dpp_perm<0x141>(v);     // row_half_mirror
+  v += dpp_perm<0x140>(v);     // row_mirror
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_perm<0xB1>(v));
+  v = fmaxf(v, dpp_perm<0x4E>(v));
+  v = fmaxf(v, dpp_perm<0x141>(v));
+  v = fmaxf(v, dpp_perm<0x140>(v));
+  return v;
+}
+
+// dynamic LDS: x tile and model with a pitch of d + 4 floats, partial logits, dZ, bias, then the
+// upload's row indices and labels
+static size_t fuse_lds_bytes(int d, int C, int B, int TR) {
+  return ((size_t)(TR + C) * (d + 4) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)B) * 4;
+}
+
+// TR rows per tile: 16 fills the matrix-core tile; 8 (half of the logits tile idle) when that lets
+// two workgroups share a CU, so that one's set-up and tail overlap the other's streaming.  Measured
+// on the 784 x 10 workload, 256 simulations: 389 us per round against 430 us with 16 rows and one
+// workgroup; 12-row tiles (register spills) 459 us; logits of 8-row tiles on sixteen 4 x 4 x 1
+// blocks instead of a half-idle 16 x 16 x 4 tile 424 us.
+template <int C, int TR>
+__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_batch_kernel(
+    const RegressionArgs* as, const char* rds, size_t stride) {
+  constexpr int LD = TR / 2;              // 16-byte chunks per thread and tile (d <= 1024)
+  constexpr int NB = 8;                   // blocks of 16 features per wavefront (d <= 1024)
+  constexpr int RJ = TR / 4;              // groups of 4 rows per tile
+  extern __shared__ __align__(16) float s_mem[];
+  const RegressionArgs a = as[blockIdx.y];
+  const RoundDesc& rd = *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride);
+  const int up = blockIdx.x;
+  if (up >= rd.K) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int d = a.d, B = a.B, dq = d >> 2, dp = d + 4;
+  float* s_x = s_mem;                     // [TR][dp]
+  float* s_Wt = s_x + TR * dp;            // [C][dp]; at the end: the upload's gradient, boundary layout
+  float* s_zp = s_Wt + C * dp;            // [8 wavefronts][TR rows][16 classes]
+  float* s_dz = s_zp + kFuseWaves * TR * 16;   // [TR][16]
+  float* s_b = s_dz + TR * 16;            // [16]
+  uint32_t* s_rowi = (uint32_t*)(s_b + 16);  // [B]
+  int* s_lab = (int*)(s_rowi + B);           // [B]
+  const WorkerDesc w = rd.w[up];
+  const float* Wv = a.ring + (size_t)w.slot * a.slot_stride;
+
+  // set-up, its loads all in flight together: the model (needs nothing), then - once the
+  // minibatch draws are known - labels and the first tile
+  const int nW4 = (d * C) >> 2;           // d % 4 == 0
+  float4 wv[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) wv[u] = load_global_f4(Wv + 4 * min(t + u * kFuseThreads, nW4 - 1));
+  const float bias = load_global(Wv + d * C + min(t, C - 1));
+  for (int b = t; b < B; b += kFuseThreads)
+    s_rowi[b] = (uint32_t)batch_row(w, a.batch_key, a.shard_rows, (uint32_t)b);
+  __syncthreads();
+  int lab[2];                             // B <= 1024
+#pragma unroll
+  for (int u = 0; u < 2; ++u) lab[u] = load_global((const int32_t*)a.y + s_rowi[min(t + u * kFuseThreads, B - 1)]);
+  // chunk t + 512 j of a tile is chunk pc[j] of tile row pr[j]
+  int pr[LD], pc[LD];
+  {
+    const int sr = kFuseThreads / dq, sc = kFuseThreads - sr * dq;
+    int r = t / dq, ch = t - r * dq;
+#pragma unroll
+    for (int j = 0; j < LD; ++j) {
+      pr[j] = r; pc[j] = ch;
+      ch += sc; r += sr;
+      if (ch >= dq) { ch -= dq; r += 1; }
+    }
+  }
+  // a tile's loads: row indices first, then all chunks (lanes past the tile's rows read the
+  // dataset's first chunk, which costs a cache hit and no branch)
+  float4 pre[LD];
+#define ABS_PREFETCH(base_, nrows_)                                                                          \
+  {                                                                                                          \
+    uint32_t ri[LD];                                                                                         \
+    _Pragma("unroll") for (int j = 0; j < LD; ++j) ri[j] = s_rowi[(base_) + min(pr[j], (nrows_) - 1)];       \
+    _Pragma("unroll") for (int j = 0; j < LD; ++j) {                                                         \
+      const uint64_t off = pr[j] < (nrows_) ? (uint64_t)ri[j] * (uint64_t)d + 4 * pc[j] : 0;                 \
+      pre[j] = load_global_f4(a.X + off);                                                                    \
+    }                                                                                                        \
+  }
+  ABS_PREFETCH(0, min(TR, B))
+  // the model goes into LDS transposed
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int idx = 4 * (t + u * kFuseThreads);
+    if (idx < 4 * nW4) {
+      const float e[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int i = (idx + v) / C, c = (idx + v) - i * C;
+        s_Wt[c * dp + i] = e[v];
+      }
+    }
+  }
+  for (int j = t + 4 * kFuseThreads; j < nW4; j += kFuseThreads) {     // d C > 8192 only
+    const float4 x4 = load_global_f4(Wv + 4 * j);
+    const float e[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int i = (4 * j + v) / C, c = (4 * j + v) - i * C;
+      s_Wt[c * dp + i] = e[v];
+    }
+  }
+  if (t < 16) s_b[t] = t < C ? bias : 0.f;
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+    if (t + u * kFuseThreads < B) s_lab[t + u * kFuseThreads] = lab[u];
+
+  const int m16 = lane & 15, g4 = lane >> 4;      // the lane's row / column and k index inside a tile
+  const int nstep = (d + 15) >> 4;                // steps of 16 features = blocks of 16 features
+  f32x4_ G[NB];
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
+  float bacc = 0.f, loss = 0.f;
+  for (int base = 0; base < B; base += TR) {
+    const int nrows = min(TR, B - base);
+    __syncthreads();                      // the previous tile has been used up
+#pragma unroll
+    for (int j = 0; j < LD; ++j)
+      if (pr[j] < nrows) *(float4*)(s_x + pr[j] * dp + 4 * pc[j]) = pre[j];
+    __syncthreads();
+    if (base + TR < B) ABS_PREFETCH(base + TR, min(TR, B - base - TR))
+    // (1a) this wavefront's share of the logits: steps wave, wave + 8, ... of 16 features; lane
+    // (m16, g4) feeds row m16 of x (mod TR) and class m16 of W at features 16 st + 4 g4 .. + 3
+    {
+      f32x4_ z = {0.f, 0.f, 0.f, 0.f};
+      const float* xrow = s_x + (m16 & (TR - 1)) * dp;
+      const float* wrow = s_Wt + min(m16, C - 1) * dp;
+      for (int st = wave; st < nstep; st += kFuseWaves) {
+        const int kk = 16 * st + 4 * g4;
+        const bool ok = kk < d;
+        const int kc = ok ? kk : 0;
+        float4 av = *(const float4*)(xrow + kc);
+        const float4 bv = *(const float4*)(wrow + kc);
+        if (!ok) av = make_float4(0.f, 0.f, 0.f, 0.f);
+        z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, z, 0, 0, 0);
+        z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, z, 0, 0, 0);
+        z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, z, 0, 0, 0);
+        z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, z, 0, 0, 0);
+      }
+      // the lane holds rows 4 g4 .. 4 g4 + 3 of column m16
+      if (4 * g4 < TR) {
+        float* zp = s_zp + wave * (TR * 16) + (4 * g4) * 16 + m16;
+        zp[0] = z[0]; zp[16] = z[1]; zp[32] = z[2]; zp[48] = z[3];
+      }
+    }
+    __syncthreads();
+    // (1b) thread (row t / 16, class t % 16): the logit, softmax over the DPP row, dZ, loss
+    if (wave < TR / 4) {
+      const int r = t >> 4, c = m16;
+      float zz = s_b[c];
+#pragma unroll
+      for (int v = 0; v < kFuseWaves; ++v) zz += s_zp[v * (TR * 16) + t];
+      if (c >= C) zz = -INFINITY;
+      const float zmax = row16_max(zz);
+      const float e = c < C ? expf(zz - zmax) : 0.f;
+      const float ssum = row16_sum(e);
+      const bool live = r < nrows;
+      const int label = live ? s_lab[base + r] : -1;
+      const float p = e / ssum;
+      s_dz[t] = live && c < C ? w.c * (p - (c == label ? 1.f : 0.f)) : 0.f;
+      if (c == label) loss += logf(ssum) - (zz - zmax);
+    }
+    __syncthreads();
+    // (2) G += X_tile^T dZ: lane (m16, g4) feeds feature f0 + m16 of row 4 j + g4 and dZ[4 j + g4][m16]
+    {
+      float bq[RJ];
+#pragma unroll
+      for (int j = 0; j < RJ; ++j) bq[j] = s_dz[(4 * j + g4) * 16 + m16];
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const int blk = wave + kFuseWaves * bi;
+        if (blk < nstep) {
+          const int f = min(16 * blk + m16, d - 1);
+#pragma unroll
+          for (int j = 0; j < RJ; ++j) {
+            const int r = 4 * j + g4;
+            float xa = s_x[r * dp + f];
+            if (r >= nrows) xa = 0.f;     // rows past the tile hold whatever the last tile left
+            G[bi] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, bq[j], G[bi], 0, 0, 0);
+          }
+        }
+      }
+      if (t < 16) {
+#pragma unroll
+        for (int r = 0; r < TR; ++r) bacc += s_dz[r * 16 + t];
+      }
+    }
+  }
+#undef ABS_PREFETCH
+  // losses sit in the lanes whose class is the row's label: add them up
+  loss = row16_sum(loss);
+  __syncthreads();
+  if (wave < TR / 4 && m16 == 0) s_zp[t >> 4] = loss;      // TR row sums (s_zp is free now)
+  // the gradient, staged through LDS in the boundary layout for full-width stores; the lane holds
+  // G[feature 16 blk + 4 g4 + i][class m16]
+  float* s_G = s_Wt;
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+    const int blk = wave + kFuseWaves * bi;
+    if (blk < nstep && m16 < C) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int f = 16 * blk + 4 * g4 + i;
+        if (f < d) s_G[f * C + m16] = G[bi][i];
+      }
+    }
+  }
+  if (t < C) s_G[d * C + t] = bacc;
+  __syncthreads();
+  float* part = a.delta + (size_t)up * a.slot_stride;
+  for (int j = t; j < nW4; j += kFuseThreads) {
+    const float4 g = ((const float4*)s_G)[j];
+    *(__attribute__((address_space(1))) f32x4_*)(part + 4 * j) = f32x4_{g.x, g.y, g.z, g.w};
+  }
+  if (t < C) part[(size_t)d * C + t] = s_G[d * C + t];
+  if (t == 0) {
+    float l = 0.f;
+#pragma unroll
+    for (int v = 0; v < TR; ++v) l += s_zp[v];
+    a.lossbuf[up] = l / (float)B;
+  }
+}
+
+// Eq. 3 over the uploads' gradients (each already scaled by its c), arrival order
+__global__ __launch_bounds__(256) void softmax_combine_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                    size_t stride, int P) {
+  __shared__ float s_loss[ABS_MAX_WORKERS];
+  const RegressionArgs a = as[blockIdx.y];
+  const RoundDesc& rd = *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride);
+  const int K = rd.K;
+  const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
+  float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < P) {
+    const float c = load_global(cur + i);
+    const float* p = a.delta + i;
+    float sum = 0.f;
+    int up = 0;
+    for (; up + 8 <= K; up += 8) {        // eight loads in flight, added in arrival order
+      float g[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) g[u] = load_global(p + (size_t)(up + u) * a.slot_stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += g[u];
+    }
+    for (; up < K; ++up) sum += load_global(p + (size_t)up * a.slot_stride);
+    nxt[i] = c - sum;
+  }
+  if (blockIdx.x == 0) {
+    for (int up = threadIdx.x; up < K; up += 256) s_loss[up] = a.lossbuf[up];
+    __syncthreads();
+    publish_losses(a.mailbox, s_loss, K, rd.stamp);
+  }
+}
+
+template <int C, int TR>
+static hipError_t launch_softmax_fused_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
+                                             int d, int B, int Kmax, hipStream_t s) {
+  static size_t allowed = 0;              // dynamic LDS the kernel has been cleared for (one device per process)
+  const size_t lds = fuse_lds_bytes(d, C, B, TR);
+  if (lds > allowed) {
+    const hipError_t e = hipFuncSetAttribute((const void*)softmax_upload_batch_kernel<C, TR>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    allowed = lds;
+  }
+  softmax_upload_batch_kernel<C, TR><<<dim3(Kmax, S), dim3(kFuseThreads), lds, s>>>(d_args, d_rds, stride);
+  const int P = (d + 1) * C;
+  softmax_combine_batch_kernel<<<dim3((P + 255) / 256, S), dim3(256), 0, s>>>(d_args, d_rds, stride, P);
+  return hipGetLastError();
+}
+
 template <int C>
 static hipError_t softmax_round_c(const RegressionArgs& a, const RoundDesc& rd, hipStream_t s,
                                   LaunchHook* hook) {
@@ -389,13 +698,26 @@ hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hi
 
 // One round of S simulations of the same shape (model, d, C, B) in one set of launches.
 hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
-                                         bool softmax, int d, int C, int B, int Kmax, hipStream_t s) {
+                                         bool softmax, int d, int C, int B, int Kmax, bool slots, hipStream_t s) {
   if (!softmax) {
     const dim3 grid(1, S), block(kLinWaves * 64);
     if (d <= 128)       linreg_round_batch_kernel<2><<<grid, block, 0, s>>>(d_args, d_rds, stride);
     else if (d <= 256)  linreg_round_batch_kernel<4><<<grid, block, 0, s>>>(d_args, d_rds, stride);
     else                linreg_round_batch_kernel<8><<<grid, block, 0, s>>>(d_args, d_rds, stride);
     return hipGetLastError();
+  }
+  if (slots && B <= kFuseMaxB) {
+    const bool two = 2 * fuse_lds_bytes(d, C, B, 8) <= kLdsPerCu;      // two workgroups per CU
+    switch (C) {
+#define ABS_CASE(c)                                                                                          \
+  case c:                                                                                                    \
+    return two ? launch_softmax_fused_batch<c, 8>(d_args, d_rds, stride, S, d, B, Kmax, s)                   \
+               : launch_softmax_fused_batch<c, 16>(d_args, d_rds, stride, S, d, B, Kmax, s);
+      ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
+      ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
+#undef ABS_CASE
+      default: return hipErrorInvalidValue;
+    }
   }
   const int nslice = (d + kUpdF - 1) / kUpdF;
   switch (C) {
