@@ -424,7 +424,7 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
   if (!hip(hipHostGetDevicePointer((void**)&b->d_box, b->h_box, 0), "hipHostGetDevicePointer")) return ABS_E_HIP;
   // softmax rounds of a batch keep one gradient per upload: N slots and N losses per simulation
   const size_t slot_floats = (size_t)c0->cfg.N * c0->slot_stride, sim_floats = slot_floats + round_up((size_t)c0->cfg.N, 64);
-  if (c0->cfg.model == ABS_MODEL_SOFTMAX &&
+  if (regression_batch_uses_slots(c0->cfg.model == ABS_MODEL_SOFTMAX, c0->cfg.B) &&
       !hip(hipMalloc((void**)&b->d_slots, (size_t)n * sim_floats * sizeof(float)), "hipMalloc")) return ABS_E_HIP;
   std::vector<RegressionArgs> args((size_t)n);
   for (int32_t i = 0; i < n; ++i) {
@@ -443,8 +443,9 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
 
 // The host part of a batched round (select, descriptor, mailbox, Eq. 4-6 per simulation) is
 // independent per simulation, so large batches spread it over a few threads that live for the
-// duration of the call: thread k owns simulations k, k + T, ...  A round has two parallel phases
-// around the launch; workers spin on a phase counter (a round lasts tens of microseconds).
+// duration of the call: thread k owns simulations lo + k, lo + k + T, ... of the group [lo, hi) in
+// hand.  A round of a group has two parallel phases around the launch; workers spin on a phase
+// counter (a round lasts tens of microseconds).
 namespace {
 struct BatchRoundState {
   abs_batch* b;
@@ -452,7 +453,9 @@ struct BatchRoundState {
   std::vector<std::vector<Upload>> sel;
   std::vector<uint32_t> stamp;
   std::vector<int> kmax, rc, bad_sim;          // per thread
-  std::atomic<int> phase{0};                   // 2 r + 1: prepare round r, 2 r + 2: finish round r, -1: exit
+  std::atomic<int> phase{0};                   // bumped for every parallel phase; `kind` says which
+  int kind = 0;                                // 0: prepare, 1: finish, -1: exit (written before the bump)
+  int lo = 0, hi = 0;                          // the group of simulations this phase is about
   std::atomic<int> done{0};
   std::atomic<bool> abort{false};
   int buf = 0;
@@ -469,7 +472,7 @@ struct BatchRoundState {
   }
   void prepare(int k) {                        // select the uploads, write the descriptors
     int km = 0;
-    for (int i = k; i < S; i += T) {
+    for (int i = lo + k; i < hi; i += T) {
       abs_ctx* ctx = b->ctx[(size_t)i];
       const int r = ctx->sched->select(sel[(size_t)i], ctx->err);
       if (r != ABS_OK) { if (rc[(size_t)k] == ABS_OK) { rc[(size_t)k] = r; bad_sim[(size_t)k] = i; } continue; }
@@ -482,7 +485,7 @@ struct BatchRoundState {
     kmax[(size_t)k] = km;
   }
   void finish(int k) {                         // wait for the losses, apply Eq. 4-6
-    for (int i = k; i < S; i += T) {
+    for (int i = lo + k; i < hi; i += T) {
       const volatile LossMailbox* box = b->h_box + i;
       for (uint64_t spin = 1; box->stamp != stamp[(size_t)i]; ++spin) {
         if (abort.load(std::memory_order_relaxed)) return;
@@ -509,19 +512,21 @@ struct BatchRoundState {
         __builtin_ia32_pause();
 #endif
       }
-      if (p < 0) return;
+      if (kind < 0) return;
       seen = p;
-      if (p & 1) prepare(k); else finish(k);
+      if (kind == 0) prepare(k); else finish(k);
       done.fetch_add(1, std::memory_order_release);
     }
   }
-  // run one phase on all threads (this one is thread 0); returns the first failing simulation's code
-  int run(int p) {
+  // run one phase for simulations [lo_, hi_) on all threads (this one is thread 0); returns the
+  // first failing simulation's code
+  int run(int kind_, int lo_, int hi_) {
     done.store(0, std::memory_order_relaxed);
-    phase.store(p, std::memory_order_release);
-    if (p & 1) prepare(0); else finish(0);
+    kind = kind_; lo = lo_; hi = hi_;
+    phase.fetch_add(1, std::memory_order_release);
+    if (kind_ == 0) prepare(0); else finish(0);
     for (uint64_t spin = 1; done.load(std::memory_order_acquire) != T - 1; ++spin) {
-      if (!(p & 1) && (spin & 0x3FFF) == 0 && !abort.load()) stream_failed();   // the others may still wait for mailboxes
+      if (kind_ == 1 && (spin & 0x3FFF) == 0 && !abort.load()) stream_failed();   // the others may still wait for mailboxes
 #if defined(__x86_64__)
       __builtin_ia32_pause();
 #endif
@@ -550,22 +555,52 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   st.bad_sim.assign((size_t)st.T, -1);
   std::vector<std::thread> pool;
   for (int k = 1; k < st.T; ++k) pool.emplace_back([&st, k] { st.worker(k); });
-  int rc = ABS_OK;
-  for (int32_t it = 0; it < n_rounds && rc == ABS_OK; ++it) {
-    st.buf = (int)(b->rounds & 1);
-    rc = st.run(2 * it + 1);
-    if (rc != ABS_OK) break;
+  // Large batches advance as two groups, one round apart in time: while the device works on one
+  // group's round the host finishes and prepares the other's (Eq. 5 makes a simulation's next
+  // selection wait for its own losses, not for the other group's).
+  // A linear round is one workgroup per simulation and lasts as long for 32 of them as for 256:
+  // halves only pay from two workgroups per CU on.
+  const bool softmax = c0.model == ABS_MODEL_SOFTMAX;
+  const int G = S >= (softmax ? 64 : 512) ? 2 : 1;
+  const int lo[2] = {0, S / 2}, hi[2] = {G == 2 ? S / 2 : S, S};
+  bool inflight[2] = {false, false};
+  auto finish = [&](int g) {
+    inflight[g] = false;
+    return st.run(1, lo[g], hi[g]);
+  };
+  auto start = [&](int g) {
+    int r = st.run(0, lo[g], hi[g]);
+    if (r != ABS_OK) return r;
     int Kmax = 0;
     for (int k = 0; k < st.T; ++k) Kmax = std::max(Kmax, st.kmax[(size_t)k]);
-    hipError_t e = hipMemcpyAsync(b->d_rds[st.buf], b->h_rds[st.buf], (size_t)S * b->rd_stride, hipMemcpyHostToDevice, b->stream);
+    const size_t off = (size_t)lo[g] * b->rd_stride, n = (size_t)(hi[g] - lo[g]);
+    hipError_t e = hipMemcpyAsync(b->d_rds[st.buf] + off, b->h_rds[st.buf] + off, n * b->rd_stride, hipMemcpyHostToDevice, b->stream);
     if (e == hipSuccess)
-      e = launch_regression_round_batch(b->d_args, b->d_rds[st.buf], b->rd_stride, S, c0.model == ABS_MODEL_SOFTMAX,
+      e = launch_regression_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
                                         c0.dims[0], c0.dims[1], c0.B, Kmax, b->d_slots != nullptr, b->stream);
-    if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); rc = ABS_E_HIP; break; }
-    b->rounds += 1;
-    rc = st.run(2 * it + 2);
+    if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); return (int)ABS_E_HIP; }
+    inflight[g] = true;
+    return (int)ABS_OK;
+  };
+  int rc = ABS_OK;
+  for (int32_t it = 0; it < n_rounds && rc == ABS_OK; ++it) {
+    st.buf = (int)(it & 1);
+    for (int g = 0; g < G && rc == ABS_OK; ++g) {
+      if (inflight[g]) rc = finish(g);
+      if (rc == ABS_OK) rc = start(g);
+    }
+    if (rc == ABS_OK) b->rounds += 1;
   }
-  st.phase.store(-1, std::memory_order_release);
+  // rounds still on the device are completed also after an error (their uploads are selected and
+  // their kernels enqueued); the first error is the one reported
+  for (int g = 0; g < G; ++g) {
+    if (!inflight[g]) continue;
+    const std::string first = b->err;
+    const int r = finish(g);
+    if (rc == ABS_OK) rc = r; else b->err = first;
+  }
+  st.kind = -1;
+  st.phase.fetch_add(1, std::memory_order_release);
   for (std::thread& t : pool) t.join();
   return rc;
 }

@@ -696,6 +696,8 @@ hipError_t launch_softmax_round(const RegressionArgs& a, const RoundDesc& rd, hi
   }
 }
 
+bool regression_batch_uses_slots(bool softmax, int B) { return softmax && B <= kFuseMaxB; }
+
 // One round of S simulations of the same shape (model, d, C, B) in one set of launches.
 hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
                                          bool softmax, int d, int C, int B, int Kmax, bool slots, hipStream_t s) {
@@ -706,7 +708,7 @@ hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const cha
     else                linreg_round_batch_kernel<8><<<grid, block, 0, s>>>(d_args, d_rds, stride);
     return hipGetLastError();
   }
-  if (slots && B <= kFuseMaxB) {
+  if (slots && regression_batch_uses_slots(softmax, B)) {
     const bool two = 2 * fuse_lds_bytes(d, C, B, 8) <= kLdsPerCu;      // two workgroups per CU
     switch (C) {
 #define ABS_CASE(c)                                                                                          \

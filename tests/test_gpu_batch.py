@@ -98,6 +98,20 @@ def test_softmax_batch():
          oracle_for=(0,), bitwise_alone=False)
 
 
+def test_batches_that_advance_as_two_halves():
+    """Large batches run as two groups half a round apart (softmax from 64 simulations, linear from
+    512): results must not change, also when a call is split in two."""
+    _run(workloads.scaled_preset(2, M=2000, dims=[12, 3], n_classes=3, N=6, B=9, K0=2, lr=1e-2), 67, 21, 1e-5, 1e-4,
+         oracle_for=(0, 66), bitwise_alone=False)
+    _run(workloads.scaled_preset(1, M=2000, dims=[20, 1], N=5, B=6, K0=2), 515, 11, 1e-5, 1e-4, oracle_for=(0, 514))
+
+
+def test_softmax_batch_of_long_minibatches():
+    """B > 1024: batched softmax rounds run the kernels of abs_round, one column per simulation."""
+    _run(workloads.scaled_preset(2, M=6000, dims=[16, 4], n_classes=4, N=3, B=1030, K0=1, lr=5e-3), 3, 10, 1e-5, 1e-4,
+         oracle_for=(0,))
+
+
 def test_batch_rejects_mixed_shapes_and_mlp():
     d1 = workloads.make_inputs(workloads.scaled_preset(1, M=2000))
     a = lib.Simulation(workloads.scaled_preset(1, M=2000), d1)
