@@ -151,3 +151,32 @@ def test_batch_of_simulations_on_different_datasets():
         o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False).run(40)
         if all(int(a) == r["K"] for a, r in zip(tr[:, 1], o.trace)):
             assert rel_err(m, o.model()) <= 1e-5
+
+
+def test_batch_error_leaves_every_simulation_consistent():
+    """One simulation of a large batch runs out of its K replay: the call names it, rounds already on
+    the device are completed (so the simulations end within a round of each other), and every other
+    handle carries on, alone, exactly as if nothing had happened (linear model: bitwise)."""
+    base = dict(workloads.scaled_preset(1, M=2000, dims=[20, 1], N=5, B=6, K0=2), k_mode=2)
+    d = workloads.make_inputs(base)
+    S, bad, T = 515, 300, 12
+    ok_replay = np.tile(np.array([2, 3, 1, 5, 4], np.int32), 4)
+    ps = [dict(base, seed_sim=base["seed_sim"] + 13 * i) for i in range(S)]
+    sims = [lib.Simulation(p, d, k_replay=ok_replay[:7] if i == bad else ok_replay) for i, p in enumerate(ps)]
+    batch = lib.Batch(sims)
+    with pytest.raises(lib.AbsError) as err:
+        batch.round(T)
+    assert f"simulation {bad}" in str(err.value)
+    batch.close()
+    done = np.array([lib.abs_rounds_done(s.handle) for s in sims])
+    assert done[bad] in (6, 7)
+    assert np.all(np.abs(done - done[bad]) <= 1)
+    assert len(set(done[:S // 2])) == 1 and len(set(np.delete(done, bad)[S // 2:])) == 1
+    for i in (0, 1, S // 2 - 1, S // 2, bad - 1, bad + 1, S - 1):
+        sims[i].round(T - int(done[i]))
+        alone = lib.Simulation(ps[i], d, k_replay=ok_replay)
+        alone.round(T)
+        assert np.array_equal(alone.model(), sims[i].model()) and np.array_equal(alone.trace(), sims[i].trace())
+        alone.close()
+    for s in sims:
+        s.close()
