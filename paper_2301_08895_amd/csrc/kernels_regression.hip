@@ -7,6 +7,7 @@
 // aggregate.  All reductions have a fixed order (no floating-point atomics), so a
 // round is bitwise reproducible.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include "kernels.h"
 
 namespace abs_impl {
@@ -653,13 +654,16 @@ __global__ __launch_bounds__(256) void softmax_combine_batch_kernel(const Regres
 template <int C, int TR>
 static hipError_t launch_softmax_fused_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
                                              int d, int B, int Kmax, hipStream_t s) {
-  static size_t allowed = 0;              // dynamic LDS the kernel has been cleared for (one device per process)
+  // dynamic LDS the kernel has been cleared for (one device per process; batches may be advanced
+  // from several host threads, so the high-water mark is atomic and the call is idempotent)
+  static std::atomic<size_t> allowed{0};
   const size_t lds = fuse_lds_bytes(d, C, B, TR);
-  if (lds > allowed) {
+  if (lds > allowed.load(std::memory_order_acquire)) {
     const hipError_t e = hipFuncSetAttribute((const void*)softmax_upload_batch_kernel<C, TR>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    allowed = lds;
+    size_t seen = allowed.load(std::memory_order_relaxed);
+    while (seen < lds && !allowed.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
   }
   softmax_upload_batch_kernel<C, TR><<<dim3(Kmax, S), dim3(kFuseThreads), lds, s>>>(d_args, d_rds, stride);
   const int P = (d + 1) * C;
