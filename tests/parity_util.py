@@ -58,3 +58,28 @@ def assert_trace_equal(res, loss_rtol):
 
 def rel_err(got, want):
     return float(np.linalg.norm(got.astype(np.float64) - want) / max(np.linalg.norm(want), 1e-30))
+
+
+def golden_path(name):
+    import os
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+
+
+def golden_lines(name):
+    """Non-comment lines of a fixture under tests/golden/ (hand-worked or published values, each file
+    carrying its citation)."""
+    with open(golden_path(name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def hand_worked_schedule():
+    """The hand-worked run of Algorithm 1 (tests/golden/abs_hand_worked_schedule.txt): its setting as
+    overrides of a workload preset, and the records, finish times in ticks."""
+    unit = 1 << 20
+    setting = dict(N=4, K0=2, k_mode=1, tau_mode=1, tau_cap=1, time_dist=2, n_slow=1, slow_factor=3.0)
+    ints = lambda s: [] if s == "-" else [int(v) for v in s.split(",")]
+    recs = []
+    for t, K, tmax, now, ids, vers, taus, rst, up, rs in golden_lines("abs_hand_worked_schedule.txt"):
+        recs.append(dict(t=int(t), K=int(K), tau_max=int(tmax), now=int(now) * unit, ids=ints(ids), vers=ints(vers),
+                         taus=ints(taus), restart_ids=ints(rst), comm_uploads=int(up), comm_restarts=int(rs)))
+    return setting, recs

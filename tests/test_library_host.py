@@ -12,6 +12,7 @@ import workloads
 import paper_2301_08895_amd as lib
 from oracle import counter_rng as crng
 from oracle.abs_sim import AbsOracle, trace_words
+from parity_util import hand_worked_schedule
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -60,6 +61,25 @@ def test_scheduler_trace_equals_oracle(i, over, T):
     o = _dry_vs_oracle(p, T)
     if over.get("tau_mode", 0) != 2:
         assert sum(r["n_restart"] for r in o.trace) > 0
+
+
+def test_scheduler_equals_the_hand_worked_run():
+    """The C++ scheduler against tests/golden/abs_hand_worked_schedule.txt (pencil-and-paper run of
+    Algorithm 1: ties, a gradient of staleness tau_max + 1, a restart by Eq. 6)."""
+    setting, want = hand_worked_schedule()
+    p = workloads.scaled_preset(1, M=400, B=8, dims=[12, 1], **setting)
+    sim = lib.Simulation(p, None, device_mode=0)
+    sim.round(len(want))
+    got = sim.trace()
+    sim.close()
+    for row, w in zip(got, want):
+        K = w["K"]
+        assert [int(row[0]), int(row[1]), int(row[2])] == [w["t"], K, w["tau_max"]]
+        assert (int(row[3]) & 0xFFFFFFFF) | (int(row[4]) << 32) == w["now"]
+        assert int(row[5]) == len(w["restart_ids"]) and int(row[6]) == w["comm_uploads"] and int(row[8]) == w["comm_restarts"]
+        assert list(row[12:12 + K]) == w["ids"] and list(row[12 + K:12 + 2 * K]) == w["vers"]
+        assert list(row[12 + 2 * K:12 + 3 * K]) == w["taus"]
+        assert list(row[12 + 3 * K:12 + 3 * K + len(w["restart_ids"])]) == w["restart_ids"]
 
 
 def test_draws_equal_oracle():

@@ -6,14 +6,15 @@ import torch
 
 from oracle import counter_rng as crng
 from oracle.bf16 import round_bf16, bits_to_f64
+from parity_util import golden_lines
 
 
 def test_splitmix64_published_vector():
     # Test vector of the public-domain splitmix64 generator for seed 1234567
     # (the values its reference implementation prints; also used by several
     # language runtimes' test suites).
-    want = [6457827717110365317, 3203168211198807973, 9817491932198370423,
-            4593380528125082431, 16408922859458223821]
+    want = [int(row[0]) for row in golden_lines("splitmix64_seed_1234567.txt")]
+    assert len(want) == 5 and want[0] == 6457827717110365317
     assert crng.splitmix64_stream(1234567, 5) == want
 
 

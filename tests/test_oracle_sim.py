@@ -11,6 +11,7 @@ from oracle import counter_rng as crng
 from oracle.abs_sim import (AbsOracle, next_wait_count, over_stale, threshold_floor,
                             trace_words, trace_stride, INT32_MAX)
 from oracle.models import worker_update
+from parity_util import golden_lines, hand_worked_schedule
 
 
 def _small(model=0, **over):
@@ -184,6 +185,36 @@ def test_wait_count_rule_closed_forms():
         want = max([j for j in range(1, 21) if Fraction(j * j) <= 9 * Fraction(float(ratio))] or [1])
         assert next_wait_count(3, 20, 1, float(ratio), 1.0, 3) == want      # = floor(3 sqrt(ratio))
         assert want == min(20, max(1, int(np.floor(3 * np.sqrt(ratio)))))
+
+
+def test_adaptive_rules_equal_the_hand_worked_values():
+    """tests/golden/threshold_and_wait_count_values.txt: Eq. 4 and Eq. 5 evaluated by hand, among
+    them the setting of Section V-B (N = 20, K^0 = 5, a = 0 .. -3)."""
+    n_tau = n_k = 0
+    for row in golden_lines("threshold_and_wait_count_values.txt"):
+        if row[0] == "tau":
+            N, K, a, want = (int(v) for v in row[1:])
+            assert threshold_floor(K, N, a, 0, 10 ** 6) == want, row
+            assert over_stale(want + 1, K, N, a, 0, 10 ** 6) and not over_stale(want, K, N, a, 0, 10 ** 6), row
+            n_tau += 1
+        else:
+            K0, N, Kprev = (int(v) for v in row[1:4])
+            assert next_wait_count(K0, N, Kprev, float(row[4]), float(row[5]), 0) == int(row[6]), row
+            n_k += 1
+    assert n_tau >= 10 and n_k >= 8
+
+
+def test_schedule_equals_the_hand_worked_run():
+    """tests/golden/abs_hand_worked_schedule.txt: seven rounds of Algorithm 1 on four workers worked
+    out with pencil and paper (ties, a gradient of staleness tau_max + 1, a restart by Eq. 6)."""
+    setting, want = hand_worked_schedule()
+    p, d = _small(0, **setting)
+    o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False).run(len(want))
+    assert len(o.trace) == len(want)
+    for got, w in zip(o.trace, want):
+        for key, val in w.items():
+            assert list(got[key]) == val if isinstance(val, list) else got[key] == val, (w["t"], key, got[key], val)
+        assert got["n_restart"] == len(w["restart_ids"]) and got["K_next"] == w["K"]
 
 
 # ---------------------------------------------------------------- invariants
