@@ -83,3 +83,20 @@ def hand_worked_schedule():
         recs.append(dict(t=int(t), K=int(K), tau_max=int(tmax), now=int(now) * unit, ids=ints(ids), vers=ints(vers),
                          taus=ints(taus), restart_ids=ints(rst), comm_uploads=int(up), comm_restarts=int(rs)))
     return setting, recs
+
+
+def hand_worked_updates(sa_penalty):
+    """The hand-worked model updates (tests/golden/abs_hand_worked_updates.txt): the workload's
+    settings and arrays, the models w^1 .. w^3 and the rounds' mean losses."""
+    import workloads
+    p = workloads.scaled_preset(1, M=3, N=3, B=1, dims=[2, 1], K0=2, k_mode=1, tau_mode=2, tau_cap=8, lr=0.5,
+                                time_dist=2, n_slow=1, slow_factor=3.0, sa_penalty=sa_penalty)
+    d = dict(X=np.array([[1, 0], [0, 1], [1, 1]], np.float32), y=np.array([1, 2, 0], np.float32),
+             w0=np.zeros(2, np.float32))
+    models, losses = {}, {}
+    for row in golden_lines("abs_hand_worked_updates.txt"):
+        if row[0] == "w" and int(row[1]) == sa_penalty:
+            models[int(row[2])] = np.array([float(row[3]), float(row[4])])
+        elif row[0] == "loss":
+            losses[int(row[1])] = float(row[2])
+    return p, d, models, losses

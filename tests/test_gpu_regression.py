@@ -80,3 +80,22 @@ def test_get_model_versions_and_errors():
     with pytest.raises(lib.AbsError):
         sim.model(11)
     sim.close()
+
+
+@pytest.mark.parametrize("sa", [0, 1])
+def test_linear_round_equals_the_hand_worked_updates(sa):
+    """The HIP path against values worked out by hand (tests/golden/abs_hand_worked_updates.txt): three
+    rounds on three rows, one gradient taken at a model two rounds old, plain and staleness-aware
+    step.  Every intermediate is a dyadic fraction, so fp32 reproduces the models exactly."""
+    import paper_2301_08895_amd as lib
+    from parity_util import hand_worked_updates
+    p, d, models, losses = hand_worked_updates(sa)
+    sim = lib.Simulation(p, d)
+    for t in range(3):
+        sim.round(1)
+        assert np.array_equal(sim.model().astype(np.float64), models[t + 1]), (t, sim.model(), models[t + 1])
+    tr = sim.trace()
+    sim.close()
+    assert [list(r[12:14]) for r in tr] == [[1, 2], [1, 2], [0, 1]] and list(tr[2][16:18]) == [2, 0]
+    for t, l in losses.items():
+        assert np.int32(tr[t][10]).view(np.float32) == np.float32(l)

@@ -11,7 +11,7 @@ from oracle import counter_rng as crng
 from oracle.abs_sim import (AbsOracle, next_wait_count, over_stale, threshold_floor,
                             trace_words, trace_stride, INT32_MAX)
 from oracle.models import worker_update
-from parity_util import golden_lines, hand_worked_schedule
+from parity_util import golden_lines, hand_worked_schedule, hand_worked_updates
 
 
 def _small(model=0, **over):
@@ -215,6 +215,19 @@ def test_schedule_equals_the_hand_worked_run():
         for key, val in w.items():
             assert list(got[key]) == val if isinstance(val, list) else got[key] == val, (w["t"], key, got[key], val)
         assert got["n_restart"] == len(w["restart_ids"]) and got["K_next"] == w["K"]
+
+
+@pytest.mark.parametrize("sa", [0, 1])
+def test_updates_equal_the_hand_worked_run(sa):
+    """tests/golden/abs_hand_worked_updates.txt: Eq. 2 / Eq. 3 on three rows by hand, with a gradient
+    taken at a model two rounds old, plain and with the staleness-aware step."""
+    p, d, models, losses = hand_worked_updates(sa)
+    o = AbsOracle(p, d["X"], d["y"], d["w0"]).run(3)
+    assert [r["ids"] for r in o.trace] == [[1, 2], [1, 2], [0, 1]] and o.trace[2]["taus"] == [2, 0]
+    for v, w in models.items():
+        assert np.array_equal(o.model(v), w), (v, o.model(v), w)         # every value is a dyadic fraction
+    for t, l in losses.items():
+        assert o.trace[t]["loss"] == l
 
 
 # ---------------------------------------------------------------- invariants
