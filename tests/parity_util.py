@@ -100,3 +100,15 @@ def hand_worked_updates(sa_penalty):
         elif row[0] == "loss":
             losses[int(row[1])] = float(row[2])
     return p, d, models, losses
+
+
+def softmax_hand_worked_first_round():
+    """tests/golden/softmax_hand_worked_first_round.txt: settings, arrays and w^1."""
+    import workloads
+    p = workloads.scaled_preset(2, M=2, N=2, B=1, dims=[4, 4], n_classes=4, K0=2, k_mode=1, tau_mode=2, tau_cap=4,
+                                lr=1.0, time_dist=2)
+    d = dict(X=np.array([[1, 2, 0, 0], [-1, 0, 0, 0]], np.float32), y=np.array([1, 3], np.int32),
+             w0=np.zeros(20, np.float32))
+    w1 = np.array([float(r[0]) for r in golden_lines("softmax_hand_worked_first_round.txt")])
+    assert w1.size == 20
+    return p, d, w1

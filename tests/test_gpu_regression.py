@@ -99,3 +99,21 @@ def test_linear_round_equals_the_hand_worked_updates(sa):
     assert [list(r[12:14]) for r in tr] == [[1, 2], [1, 2], [0, 1]] and list(tr[2][16:18]) == [2, 0]
     for t, l in losses.items():
         assert np.int32(tr[t][10]).view(np.float32) == np.float32(l)
+
+
+def test_softmax_first_round_equals_the_hand_worked_values():
+    """The HIP path (unbatched and batched kernels) against tests/golden/softmax_hand_worked_first_round.txt."""
+    import paper_2301_08895_amd as lib
+    from parity_util import softmax_hand_worked_first_round
+    p, d, w1 = softmax_hand_worked_first_round()
+    sim = lib.Simulation(p, d)
+    sim.round(1)
+    assert np.allclose(sim.model(), w1, rtol=0, atol=1e-7)
+    assert abs(float(np.int32(sim.trace()[0][10]).view(np.float32)) - np.log(4.0)) < 1e-6
+    sim.close()
+    sim = lib.Simulation(p, d)
+    batch = lib.Batch([sim])
+    batch.round(1)
+    batch.close()
+    assert np.allclose(sim.model(), w1, rtol=0, atol=1e-7)
+    sim.close()

@@ -11,7 +11,7 @@ from oracle import counter_rng as crng
 from oracle.abs_sim import (AbsOracle, next_wait_count, over_stale, threshold_floor,
                             trace_words, trace_stride, INT32_MAX)
 from oracle.models import worker_update
-from parity_util import golden_lines, hand_worked_schedule, hand_worked_updates
+from parity_util import golden_lines, hand_worked_schedule, hand_worked_updates, softmax_hand_worked_first_round
 
 
 def _small(model=0, **over):
@@ -228,6 +228,15 @@ def test_updates_equal_the_hand_worked_run(sa):
         assert np.array_equal(o.model(v), w), (v, o.model(v), w)         # every value is a dyadic fraction
     for t, l in losses.items():
         assert o.trace[t]["loss"] == l
+
+
+def test_softmax_first_round_equals_the_hand_worked_values():
+    """tests/golden/softmax_hand_worked_first_round.txt: from W = 0 every class has probability 1/C, so
+    the gradient of Eq. 3's first round is an exact fraction; loss log C."""
+    p, d, w1 = softmax_hand_worked_first_round()
+    o = AbsOracle(p, d["X"], d["y"], d["w0"]).run(1)
+    assert np.allclose(o.model(1), w1, rtol=0, atol=1e-15)
+    assert abs(o.trace[0]["loss"] - np.log(4.0)) < 1e-12
 
 
 # ---------------------------------------------------------------- invariants
