@@ -112,3 +112,21 @@ def softmax_hand_worked_first_round():
     w1 = np.array([float(r[0]) for r in golden_lines("softmax_hand_worked_first_round.txt")])
     assert w1.size == 20
     return p, d, w1
+
+
+def mlp_hand_worked_first_round():
+    """tests/golden/mlp_hand_worked_first_round.txt: settings, arrays (X as bf16 bit patterns) and w^1."""
+    import workloads
+    p = workloads.scaled_preset(3, M=2, N=2, B=1, dims=[8, 2, 4], n_classes=4, K0=2, k_mode=1, tau_mode=2, tau_cap=4,
+                                lr=1.0, time_dist=2, n_slow=0)
+    X = np.zeros((2, 8), np.float32)
+    X[0, :2] = (1, 2)
+    X[1, :2] = (-1, 3)
+    w0 = np.zeros(30, np.float32)
+    w0[0] = 1.0          # W_1[0][0]
+    w0[3] = 1.0          # W_1[1][1]
+    w0[17] = -1.0        # b_1[1]
+    d = dict(X=(X.view(np.uint32) >> 16).astype(np.uint16), y=np.array([1, 3], np.int32), w0=w0)
+    w1 = np.array([float(r[0]) for r in golden_lines("mlp_hand_worked_first_round.txt")])
+    assert w1.size == 30
+    return p, d, w1

@@ -62,3 +62,18 @@ def test_run_to_run_bitwise_determinism():
         outs.append((sim.model().copy(), sim.trace().copy()))
         sim.close()
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_mlp_first_round_equals_the_hand_worked_values():
+    """The HIP path against tests/golden/mlp_hand_worked_first_round.txt (ReLU forward, H^T dZ, update,
+    an untouched hidden layer; every value survives the bf16 narrowing exactly)."""
+    import paper_2301_08895_amd as lib
+    from parity_util import mlp_hand_worked_first_round
+    p, d, w1 = mlp_hand_worked_first_round()
+    sim = lib.Simulation(p, d)
+    sim.round(1)
+    got = sim.model()
+    loss = float(np.int32(sim.trace()[0][10]).view(np.float32))
+    sim.close()
+    assert np.allclose(got, w1, rtol=0, atol=1e-7), (got, w1)
+    assert abs(loss - np.log(4.0)) < 1e-6

@@ -11,7 +11,8 @@ from oracle import counter_rng as crng
 from oracle.abs_sim import (AbsOracle, next_wait_count, over_stale, threshold_floor,
                             trace_words, trace_stride, INT32_MAX)
 from oracle.models import worker_update
-from parity_util import golden_lines, hand_worked_schedule, hand_worked_updates, softmax_hand_worked_first_round
+from parity_util import (golden_lines, hand_worked_schedule, hand_worked_updates, softmax_hand_worked_first_round,
+                         mlp_hand_worked_first_round)
 
 
 def _small(model=0, **over):
@@ -237,6 +238,16 @@ def test_softmax_first_round_equals_the_hand_worked_values():
     o = AbsOracle(p, d["X"], d["y"], d["w0"]).run(1)
     assert np.allclose(o.model(1), w1, rtol=0, atol=1e-15)
     assert abs(o.trace[0]["loss"] - np.log(4.0)) < 1e-12
+
+
+def test_mlp_first_round_equals_the_hand_worked_values():
+    """tests/golden/mlp_hand_worked_first_round.txt: ReLU forward, output-layer gradient H^T dZ and
+    update by hand (exact fractions, also under the bf16 narrowing); the hidden layer must not move."""
+    p, d, w1 = mlp_hand_worked_first_round()
+    for emulate in (True, False):
+        o = AbsOracle(p, d["X"], d["y"], d["w0"], emulate_bf16=emulate).run(1)
+        assert np.allclose(o.model(1), w1, rtol=0, atol=1e-15), emulate
+        assert abs(o.trace[0]["loss"] - np.log(4.0)) < 1e-12
 
 
 # ---------------------------------------------------------------- invariants
