@@ -130,3 +130,18 @@ def mlp_hand_worked_first_round():
     w1 = np.array([float(r[0]) for r in golden_lines("mlp_hand_worked_first_round.txt")])
     assert w1.size == 30
     return p, d, w1
+
+
+def local_sgd_hand_worked():
+    """tests/golden/local_sgd_hand_worked.txt: settings, arrays, models w^1, w^2 and round losses."""
+    import workloads
+    p = workloads.scaled_preset(1, M=2, N=2, B=1, dims=[2, 1], K0=2, k_mode=1, tau_mode=2, tau_cap=4, lr=0.5,
+                                time_dist=2, U=2)
+    d = dict(X=np.array([[1, 0], [0, 1]], np.float32), y=np.array([1, 2], np.float32), w0=np.zeros(2, np.float32))
+    models, losses = {}, {}
+    for row in golden_lines("local_sgd_hand_worked.txt"):
+        if row[0] == "w":
+            models[int(row[1])] = np.array([float(row[2]), float(row[3])])
+        else:
+            losses[int(row[1])] = float(row[2])
+    return p, d, models, losses

@@ -64,3 +64,18 @@ def test_cfg3_shape_local_steps():
     """The 3072-512-10 workload at its real layer and batch shapes (shorter dataset) with U = 2."""
     p = workloads.scaled_preset(3, M=6400, U=2)
     _check(run_pair(p, 8, checkpoints=(1,)), 2e-2, 2e-3)
+
+
+def test_local_sgd_equals_the_hand_worked_run():
+    """The HIP path against tests/golden/local_sgd_hand_worked.txt (two local steps per job, exact in fp32)."""
+    import paper_2301_08895_amd as lib
+    from parity_util import local_sgd_hand_worked
+    p, d, models, losses = local_sgd_hand_worked()
+    sim = lib.Simulation(p, d)
+    for t in range(2):
+        sim.round(1)
+        assert np.array_equal(sim.model().astype(np.float64), models[t + 1]), (t, sim.model())
+    tr = sim.trace()
+    sim.close()
+    for t, l in losses.items():
+        assert np.int32(tr[t][10]).view(np.float32) == np.float32(l)

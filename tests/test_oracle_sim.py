@@ -12,7 +12,7 @@ from oracle.abs_sim import (AbsOracle, next_wait_count, over_stale, threshold_fl
                             trace_words, trace_stride, INT32_MAX)
 from oracle.models import worker_update
 from parity_util import (golden_lines, hand_worked_schedule, hand_worked_updates, softmax_hand_worked_first_round,
-                         mlp_hand_worked_first_round)
+                         mlp_hand_worked_first_round, local_sgd_hand_worked)
 
 
 def _small(model=0, **over):
@@ -248,6 +248,17 @@ def test_mlp_first_round_equals_the_hand_worked_values():
         o = AbsOracle(p, d["X"], d["y"], d["w0"], emulate_bf16=emulate).run(1)
         assert np.allclose(o.model(1), w1, rtol=0, atol=1e-15), emulate
         assert abs(o.trace[0]["loss"] - np.log(4.0)) < 1e-12
+
+
+def test_local_sgd_equals_the_hand_worked_run():
+    """tests/golden/local_sgd_hand_worked.txt: U = 2 local steps per job, uploads w^{t,0} - w^{t,U},
+    Eq. 3 over the uploads, average local loss; exact in binary."""
+    p, d, models, losses = local_sgd_hand_worked()
+    o = AbsOracle(p, d["X"], d["y"], d["w0"]).run(2)
+    for v, w in models.items():
+        assert np.array_equal(o.model(v), w), (v, o.model(v), w)
+    for t, l in losses.items():
+        assert o.trace[t]["loss"] == l
 
 
 # ---------------------------------------------------------------- invariants
