@@ -206,7 +206,7 @@ def main():
         import_traffic(*args.traffic_import)
         return
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (one simulated parameter server per device); "
+        print("bench.py: this library runs on ONE GPU only (one simulated parameter server per device); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
 
