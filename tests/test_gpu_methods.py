@@ -31,3 +31,22 @@ def test_method(base, tol, loss_rtol, name):
         assert np.all(tr[:, 1] == 1)
     if name in ("sync_sgd", "local_sgd"):
         assert np.all(tr[:, 1] == p["N"])
+
+
+def test_compare_tool_readouts(capsys):
+    """The read-out tool end to end on a shortened cfg 2: per-method table, and the sweep of Eq. 4's
+    constant a (Section V-B) run as one batch of simulations."""
+    from paper_2301_08895_amd import compare
+    assert compare.main(["--config", "2", "--M", "6000", "--methods", "abs,adasync", "--rounds", "60", "--every", "30",
+                         "--eval-rows", "512", "--target", "5.0"]) == 0
+    out = capsys.readouterr().out
+    assert "adasync" in out and "first read-out with held-out loss" in out
+    assert compare.main(["--config", "2", "--M", "6000", "--sweep-a", "0,-2", "--seeds", "3", "--rounds", "60",
+                         "--every", "30", "--eval-rows", "512", "--target", "5.0"]) == 0
+    out = capsys.readouterr().out
+    assert "means over 3 seeds" in out and "a =  -2: 3/3 seeds" in out
+    # a smaller a means a tighter staleness bound, hence at least as many restarts (same seeds, same times)
+    rows = compare.sweep_a(dict(workloads.preset(2), M=6000), [0, -3], 2, 60, 60, 256, None)
+    r0 = sum(r["restarts"] for r in rows if r["a"] == 0)
+    r3 = sum(r["restarts"] for r in rows if r["a"] == -3)
+    assert r3 >= r0
