@@ -249,11 +249,16 @@ class Simulation:
             raise RuntimeError("no GPU: libabs has no CPU path (use device_mode=0 for schedule-only runs)")
         self.torch = torch
         dev = torch.device(device)
-        X = inputs["X"]
-        xt = torch.from_numpy(X.view(np.int16) if X.dtype == np.uint16 else X)
-        self.d_X = xt.to(dev)
-        self.d_y = torch.from_numpy(inputs["y"]).to(dev)
-        self.d_w0 = torch.from_numpy(inputs["w0"]).to(dev)
+        # simulations created from the same `inputs` dict share one device copy of the dataset
+        # (a sweep over seeds or settings reads one dataset); the library only reads these buffers
+        shared = inputs.setdefault("_device_copies", {})
+        X, y, w0 = inputs["X"], inputs["y"], inputs["w0"]
+        hit = shared.get(device)
+        if hit is None or hit[0] is not X or hit[1] is not y or hit[2] is not w0:
+            xt = torch.from_numpy(X.view(np.int16) if X.dtype == np.uint16 else X)
+            hit = (X, y, w0, xt.to(dev), torch.from_numpy(y).to(dev), torch.from_numpy(w0).to(dev))
+            shared[device] = hit
+        self.d_X, self.d_y, self.d_w0 = hit[3:]
         self.P = int(inputs["w0"].size)
         self.ws_bytes = abs_workspace_size(self.cfg)
         self.d_ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=dev)
