@@ -88,3 +88,40 @@ def test_whole_job_properties(i):
     dry.close()
     keep = np.ones(tr.shape[1], bool); keep[10] = False
     assert np.array_equal(tr[:, keep], tr2[:, keep])
+
+
+@pytest.mark.parametrize("i,S,T", [(2, 64, 40), (1, 512, 60)])
+def test_batched_rounds_at_full_size(i, S, T):
+    """The batches bench.py times (--batch S): the workload at its full shape, S simulation seeds on
+    one dataset, advanced as two halves.  Sampled simulations against the oracle, every trace against
+    the invariants of Eq. 4-6."""
+    from oracle.abs_sim import AbsOracle, trace_words
+    from parity_util import LOSS_WORD, KNEXT_WORD
+    p = workloads.preset(i)
+    d = workloads.make_inputs(p)
+    ps = [dict(p, seed_sim=p["seed_sim"] + 7919 * k) for k in range(S)]
+    sims = [lib.Simulation(q, d) for q in ps]
+    batch = lib.Batch(sims)
+    batch.round(T)
+    batch.close()
+    got = [(s.model().copy(), s.trace().copy()) for s in sims]
+    for s in sims:
+        s.close()
+    for q, (w, tr) in zip(ps, got):
+        assert np.all(np.isfinite(w))
+        _trace_properties(q, tr)
+    checked = 0
+    for k in (0, S // 2 - 1, S // 2, S - 1):
+        o = AbsOracle(ps[k], d["X"], d["y"], d["w0"], keep_models=False).run(T)
+        want = np.stack([trace_words(r, p["N"]) for r in o.trace])
+        w, tr = got[k]
+        if np.any(tr[:, KNEXT_WORD] != want[:, KNEXT_WORD]):
+            continue                      # an adaptive-K decision flipped on a last-bit loss difference
+        keep = np.ones(tr.shape[1], bool)
+        keep[LOSS_WORD] = False
+        assert np.array_equal(tr[:, keep], want[:, keep])
+        e = rel_err(w, o.model())
+        print(f"simulation {k}: rel err {e:.3e}", flush=True)
+        assert e <= FP32_TOL
+        checked += 1
+    assert checked >= 2
