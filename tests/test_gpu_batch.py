@@ -180,3 +180,39 @@ def test_batch_error_leaves_every_simulation_consistent():
         alone.close()
     for s in sims:
         s.close()
+
+
+def test_softmax_batch_random_shapes():
+    """Seeded random shapes (features, classes, workers, minibatch, batch size) of batched softmax
+    rounds: batch-of-one bitwise, oracle to the parity bar."""
+    rng = np.random.default_rng(20240607)
+    for case in range(10):
+        d_ = int(rng.integers(1, 257)) * 4
+        C = int(rng.integers(2, 17))
+        N = int(rng.integers(1, 17))
+        B = int(rng.choice([1, 3, 7, 8, 9, 15, 16, 17, 31, 40, 64, 100, 130, 257]))
+        S = int(rng.choice([1, 2, 5, 33, 70]))
+        p = workloads.scaled_preset(2, M=max(N * 20, 600), dims=[d_, C], n_classes=C, N=N, B=B,
+                                    K0=int(rng.integers(1, N + 1)), tau_cap=int(rng.integers(1, 5)),
+                                    lr=float(0.2 / d_), sa_penalty=int(rng.integers(0, 2)))
+        print(f"case {case}: d={d_} C={C} N={N} B={B} S={S}", flush=True)
+        d = workloads.make_inputs(p)
+        ps = [dict(p, seed_sim=p["seed_sim"] + 31 * k) for k in range(S)]
+        sims = [lib.Simulation(q, d) for q in ps]
+        batch = lib.Batch(sims)
+        batch.round(8)
+        batch.close()
+        got = [(s.model().copy(), s.trace().copy()) for s in sims]
+        for s in sims:
+            s.close()
+        for k in sorted({0, S - 1}):
+            one = lib.Simulation(ps[k], d)
+            b1 = lib.Batch([one])
+            b1.round(8)
+            b1.close()
+            assert np.array_equal(one.model(), got[k][0]) and np.array_equal(one.trace(), got[k][1]), (case, k)
+            one.close()
+            o = AbsOracle(ps[k], d["X"], d["y"], d["w0"], keep_models=False).run(8)
+            want = np.stack([trace_words(r, N) for r in o.trace])
+            if _same_schedule(got[k][1], want):
+                assert rel_err(got[k][0], o.model()) <= 1e-5, (case, k)
