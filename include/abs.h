@@ -201,14 +201,15 @@ void abs_destroy(abs_ctx* ctx);
  * one launch: a batch advances n simulations of one shape together, every round of all of them
  * in one set of launches (one workgroup column per simulation).
  *  abs_batch_create   ctxs: n handles (1 <= n <= 4096) created with the same model (linear or
- *                     softmax), dims, N, B and stream, U = 1, profile = 0; seeds, K0, a, tau
+ *                     softmax), dims, N, B, U and stream, profile = 0; seeds, K0, a, tau
  *                     settings, step sizes, time models and datasets may differ.  The batch
  *                     borrows the handles: they must outlive it, and stay usable on their own
  *                     (abs_get_model, abs_trace, abs_evaluate, abs_round) between batch calls.
  *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
  *                     count).  A simulation's result does not depend on what else is in the
- *                     batch.  Linear model: bitwise the result of abs_round on the handle alone.
- *                     Softmax model: the batched round adds up each upload's gradient before
+ *                     batch.  Linear model, and both models with U > 1 (local SGD): bitwise the
+ *                     result of abs_round on the handle alone.
+ *                     Softmax model with U = 1: the batched round adds up each upload's gradient before
  *                     Eq. 3 sums the uploads, another rounding order than abs_round's, so models
  *                     agree with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5
  *                     that hangs on the last bit of a loss may differ).

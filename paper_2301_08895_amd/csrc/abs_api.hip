@@ -399,11 +399,10 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
     for (int32_t j = 0; j < i; ++j) if (ctxs[j] == c) return bad("a handle appears twice in the batch");
     if (!c->cfg.device_mode) return bad("schedule-only handles cannot be batched");
     if (c->cfg.model == ABS_MODEL_MLP) return bad("MLP rounds fill the GPU on their own: batches are for the regression models");
-    if (c->cfg.U != 1) return bad("batched rounds take U = 1");
     if (c->cfg.profile) return bad("batched rounds are not profiled per kernel (profile must be 0)");
     if (c->cfg.model != c0->cfg.model || c->cfg.dims[0] != c0->cfg.dims[0] || c->cfg.dims[1] != c0->cfg.dims[1] ||
-        c->cfg.B != c0->cfg.B || c->cfg.N != c0->cfg.N || c->stream != c0->stream)
-      return bad("all simulations of a batch need the same model, dims, N, B and stream");
+        c->cfg.B != c0->cfg.B || c->cfg.N != c0->cfg.N || c->cfg.U != c0->cfg.U || c->stream != c0->stream)
+      return bad("all simulations of a batch need the same model, dims, N, B, U and stream");
   }
   std::unique_ptr<abs_batch, void (*)(abs_batch*)> b(new abs_batch, abs_batch_destroy);
   b->ctx.assign(ctxs, ctxs + n);
@@ -424,7 +423,7 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
   if (!hip(hipHostGetDevicePointer((void**)&b->d_box, b->h_box, 0), "hipHostGetDevicePointer")) return ABS_E_HIP;
   // softmax rounds of a batch keep one gradient per upload: N slots and N losses per simulation
   const size_t slot_floats = (size_t)c0->cfg.N * c0->slot_stride, sim_floats = slot_floats + round_up((size_t)c0->cfg.N, 64);
-  if (regression_batch_uses_slots(c0->cfg.model == ABS_MODEL_SOFTMAX, c0->cfg.B) &&
+  if (c0->cfg.U == 1 && regression_batch_uses_slots(c0->cfg.model == ABS_MODEL_SOFTMAX, c0->cfg.B) &&
       !hip(hipMalloc((void**)&b->d_slots, (size_t)n * sim_floats * sizeof(float)), "hipMalloc")) return ABS_E_HIP;
   std::vector<RegressionArgs> args((size_t)n);
   for (int32_t i = 0; i < n; ++i) {
@@ -575,7 +574,10 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
     for (int k = 0; k < st.T; ++k) Kmax = std::max(Kmax, st.kmax[(size_t)k]);
     const size_t off = (size_t)lo[g] * b->rd_stride, n = (size_t)(hi[g] - lo[g]);
     hipError_t e = hipMemcpyAsync(b->d_rds[st.buf] + off, b->h_rds[st.buf] + off, n * b->rd_stride, hipMemcpyHostToDevice, b->stream);
-    if (e == hipSuccess)
+    if (e == hipSuccess && c0.U > 1)
+      e = launch_regression_local_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
+                                              c0.dims[0], c0.dims[1], Kmax, b->stream);
+    else if (e == hipSuccess)
       e = launch_regression_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
                                         c0.dims[0], c0.dims[1], c0.B, Kmax, b->d_slots != nullptr, b->stream);
     if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); return (int)ABS_E_HIP; }

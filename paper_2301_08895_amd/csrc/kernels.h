@@ -69,6 +69,9 @@ hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDes
 // `lossbuf` ([N]) are there, so the softmax round may keep per-upload gradients (the fused form).
 hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
                                          bool softmax, int d, int C, int B, int Kmax, bool slots, hipStream_t s);
+// the same for local SGD (U > 1 in every simulation's arguments; their `delta` / `lossbuf` exist)
+hipError_t launch_regression_local_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
+                                               bool softmax, int d, int C, int Kmax, hipStream_t s);
 // whether batched rounds of this shape use the per-upload slots (else they need not be allocated)
 bool regression_batch_uses_slots(bool softmax, int B);
 

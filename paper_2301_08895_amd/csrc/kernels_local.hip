@@ -30,13 +30,14 @@ constexpr int kLocWaves = 4;
 constexpr int kLinDMax = 512;
 
 // ---- linear least squares: private w in LDS; a lane owns features lane, lane+64, ...
-__global__ __launch_bounds__(kLocWaves * 64) void linreg_local_kernel(RegressionArgs a, RoundDesc rd) {
+__device__ __forceinline__ void linreg_local_body(const RegressionArgs& a, const RoundDesc& rd) {
   __shared__ float s_w[kLinDMax];
   __shared__ float s_g[kLocWaves][kLinDMax];
   __shared__ float s_l[kLocWaves];
   constexpr int Q = kLinDMax / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int up = blockIdx.x, d = a.d, B = a.B;
+  if (up >= rd.K) return;
   const WorkerDesc w = rd.w[up];
   const float* start = a.ring + (size_t)w.slot * a.slot_stride;
   const float* y = (const float*)a.y;
@@ -86,6 +87,16 @@ __global__ __launch_bounds__(kLocWaves * 64) void linreg_local_kernel(Regression
   }
 }
 
+__global__ __launch_bounds__(kLocWaves * 64) void linreg_local_kernel(RegressionArgs a, RoundDesc rd) {
+  linreg_local_body(a, rd);
+}
+// Batched forms: blockIdx.y = simulation, arguments and round descriptors from device tables.
+__global__ __launch_bounds__(kLocWaves * 64) void linreg_local_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                           size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  linreg_local_body(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
+}
+
 // ---- softmax regression: private W, b in LDS.  Per batch of up to 256 rows: (1) a
 // wavefront per row computes the row of dZ = c (softmax - onehot) from the LDS model,
 // (2) every thread owns features t, t + 256, ... and adds x^T dZ over the batch's rows;
@@ -94,13 +105,14 @@ constexpr int kSoftDMax = 1024;
 constexpr int kRowBatch = 256;
 
 template <int C>
-__global__ __launch_bounds__(256) void softmax_local_kernel(RegressionArgs a, RoundDesc rd) {
+__device__ __forceinline__ void softmax_local_body(const RegressionArgs& a, const RoundDesc& rd) {
   __shared__ float s_W[(kSoftDMax + 1) * C];
   __shared__ float s_dz[kRowBatch][C];
   __shared__ uint32_t s_row[kRowBatch];
   __shared__ float s_l[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, t = threadIdx.x;
   const int up = blockIdx.x, d = a.d, B = a.B;
+  if (up >= rd.K) return;
   const WorkerDesc w = rd.w[up];
   const float* start = a.ring + (size_t)w.slot * a.slot_stride;
   const int P = (d + 1) * C;
@@ -183,8 +195,19 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(RegressionArgs a, Ro
   if (t == 0) a.lossbuf[up] = (s_l[0] + s_l[1] + s_l[2] + s_l[3]) / (float)(B * a.U);
 }
 
+template <int C>
+__global__ __launch_bounds__(256) void softmax_local_kernel(RegressionArgs a, RoundDesc rd) {
+  softmax_local_body<C>(a, rd);
+}
+template <int C>
+__global__ __launch_bounds__(256) void softmax_local_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                  size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  softmax_local_body<C>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride));
+}
+
 // ---- Eq. 3 over the uploads' changes: w^{t+1} = w^t - (1/K) sum_a delta_a, arrival order
-__global__ __launch_bounds__(256) void delta_update_kernel(RegressionArgs a, RoundDesc rd, int P) {
+__device__ __forceinline__ void delta_update_body(const RegressionArgs& a, const RoundDesc& rd, int P) {
   __shared__ float s_loss[ABS_MAX_WORKERS];
   const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
   float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
@@ -199,6 +222,15 @@ __global__ __launch_bounds__(256) void delta_update_kernel(RegressionArgs a, Rou
     __syncthreads();
     publish_losses(a.mailbox, s_loss, rd.K, rd.stamp);
   }
+}
+
+__global__ __launch_bounds__(256) void delta_update_kernel(RegressionArgs a, RoundDesc rd, int P) {
+  delta_update_body(a, rd, P);
+}
+__global__ __launch_bounds__(256) void delta_update_batch_kernel(const RegressionArgs* as, const char* rds,
+                                                                 size_t stride, int P) {
+  const RegressionArgs a = as[blockIdx.y];
+  delta_update_body(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), P);
 }
 
 }  // namespace
@@ -225,6 +257,27 @@ hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDes
   hook->begin(KK_DELTA_UPDATE, (double)rd.K * P, ((double)rd.K + 2.0) * P * 4.0);
   delta_update_kernel<<<dim3((P + 255) / 256), dim3(256), 0, s>>>(a, rd, P);
   hook->end(KK_DELTA_UPDATE);
+  return hipGetLastError();
+}
+
+// One local-SGD round of S simulations of one shape (U > 1; blockIdx.y = simulation).
+hipError_t launch_regression_local_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
+                                               bool softmax, int d, int C, int Kmax, hipStream_t s) {
+  if (!softmax) {
+    linreg_local_batch_kernel<<<dim3(Kmax, S), dim3(kLocWaves * 64), 0, s>>>(d_args, d_rds, stride);
+  } else {
+    switch (C) {
+#define ABS_CASE(c) case c: softmax_local_batch_kernel<c><<<dim3(Kmax, S), dim3(256), 0, s>>>(d_args, d_rds, stride); break;
+      ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
+      ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
+#undef ABS_CASE
+      default: return hipErrorInvalidValue;
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int P = softmax ? (d + 1) * C : d;
+  delta_update_batch_kernel<<<dim3((P + 255) / 256, S), dim3(256), 0, s>>>(d_args, d_rds, stride, P);
   return hipGetLastError();
 }
 

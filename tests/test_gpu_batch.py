@@ -106,6 +106,20 @@ def test_batches_that_advance_as_two_halves():
     _run(workloads.scaled_preset(1, M=2000, dims=[20, 1], N=5, B=6, K0=2), 515, 11, 1e-5, 1e-4, oracle_for=(0, 514))
 
 
+def test_local_sgd_batches():
+    """U > 1 in batched rounds: the local-SGD kernels with one column of workgroups per simulation,
+    bitwise the unbatched rounds (also as two halves)."""
+    _run(workloads.scaled_preset(1, M=3000, dims=[40, 1], N=6, B=8, K0=2, U=3), 9, 30, 1e-5, 1e-4)
+    _run(workloads.scaled_preset(2, M=3000, dims=[24, 5], n_classes=5, N=7, B=6, K0=3, U=4, lr=1e-2), 66, 16,
+         1e-5, 1e-4, oracle_for=(0, 65))
+    a = lib.Simulation(workloads.scaled_preset(1, M=2000, U=2), workloads.make_inputs(workloads.scaled_preset(1, M=2000, U=2)))
+    b = lib.Simulation(workloads.scaled_preset(1, M=2000), workloads.make_inputs(workloads.scaled_preset(1, M=2000)))
+    with pytest.raises(lib.AbsError):
+        lib.Batch([a, b])                      # U must agree
+    a.close()
+    b.close()
+
+
 def test_softmax_batch_of_long_minibatches():
     """B > 1024: batched softmax rounds run the kernels of abs_round, one column per simulation."""
     _run(workloads.scaled_preset(2, M=6000, dims=[16, 4], n_classes=4, N=3, B=1030, K0=1, lr=5e-3), 3, 10, 1e-5, 1e-4,
