@@ -576,7 +576,7 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
     hipError_t e = hipMemcpyAsync(b->d_rds[st.buf] + off, b->h_rds[st.buf] + off, n * b->rd_stride, hipMemcpyHostToDevice, b->stream);
     if (e == hipSuccess && c0.U > 1)
       e = launch_regression_local_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
-                                              c0.dims[0], c0.dims[1], Kmax, b->stream);
+                                              c0.dims[0], c0.dims[1], c0.B, c0.U, Kmax, b->stream);
     else if (e == hipSuccess)
       e = launch_regression_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
                                         c0.dims[0], c0.dims[1], c0.B, Kmax, b->d_slots != nullptr, b->stream);

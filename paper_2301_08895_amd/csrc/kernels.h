@@ -71,7 +71,15 @@ hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const cha
                                          bool softmax, int d, int C, int B, int Kmax, bool slots, hipStream_t s);
 // the same for local SGD (U > 1 in every simulation's arguments; their `delta` / `lossbuf` exist)
 hipError_t launch_regression_local_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
-                                               bool softmax, int d, int C, int Kmax, hipStream_t s);
+                                               bool softmax, int d, int C, int B, int U, int Kmax, hipStream_t s);
+// Softmax local steps on the matrix cores (a workgroup per upload streams the job's U B rows through
+// LDS, its private model there too): usable when softmax_local_fused_ok.  a1 / rd1: one simulation's
+// arguments by value (then d_args == nullptr), else S simulations from device tables.  Writes the
+// uploads' changes and mean local losses to `delta` / `lossbuf`; Eq. 3 over them is the caller's.
+bool softmax_local_fused_ok(int B, int U);
+hipError_t launch_softmax_local_fused(const RegressionArgs* a1, const RoundDesc* rd1, const RegressionArgs* d_args,
+                                      const char* d_rds, size_t stride, int S, int d, int C, int B, int U, int Kmax,
+                                      hipStream_t s);
 // whether batched rounds of this shape use the per-upload slots (else they need not be allocated)
 bool regression_batch_uses_slots(bool softmax, int B);
 

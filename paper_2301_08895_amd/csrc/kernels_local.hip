@@ -242,6 +242,9 @@ hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDes
   hook->begin(KK_LOCAL_STEPS, rows * a.d * (softmax ? a.C : 1) * 4.0, rows * (a.d + 1) * 4.0);
   if (!softmax) {
     linreg_local_kernel<<<dim3(rd.K), dim3(kLocWaves * 64), 0, s>>>(a, rd);
+  } else if (softmax_local_fused_ok(a.B, a.U)) {
+    const hipError_t e = launch_softmax_local_fused(&a, &rd, nullptr, nullptr, 0, 1, a.d, a.C, a.B, a.U, rd.K, s);
+    if (e != hipSuccess) return e;
   } else {
     switch (a.C) {
 #define ABS_CASE(c) case c: softmax_local_kernel<c><<<dim3(rd.K), dim3(256), 0, s>>>(a, rd); break;
@@ -262,9 +265,12 @@ hipError_t launch_regression_local_round(const RegressionArgs& a, const RoundDes
 
 // One local-SGD round of S simulations of one shape (U > 1; blockIdx.y = simulation).
 hipError_t launch_regression_local_round_batch(const RegressionArgs* d_args, const char* d_rds, size_t stride, int S,
-                                               bool softmax, int d, int C, int Kmax, hipStream_t s) {
+                                               bool softmax, int d, int C, int B, int U, int Kmax, hipStream_t s) {
   if (!softmax) {
     linreg_local_batch_kernel<<<dim3(Kmax, S), dim3(kLocWaves * 64), 0, s>>>(d_args, d_rds, stride);
+  } else if (softmax_local_fused_ok(B, U)) {
+    const hipError_t e = launch_softmax_local_fused(nullptr, nullptr, d_args, d_rds, stride, S, d, C, B, U, Kmax, s);
+    if (e != hipSuccess) return e;
   } else {
     switch (C) {
 #define ABS_CASE(c) case c: softmax_local_batch_kernel<c><<<dim3(Kmax, S), dim3(256), 0, s>>>(d_args, d_rds, stride); break;

@@ -372,7 +372,10 @@ __global__ __launch_bounds__(1024) void softmax_update_batch_kernel(const Regres
 //       stay in its accumulators for the whole upload.
 // The upload's gradient goes to a scratch slot; a second kernel adds the K^t slots in arrival
 // order (Eq. 3) and writes w^{t+1} and the losses.
-constexpr int kFuseThreads = 512, kFuseWaves = 8, kFuseMaxB = 1024;
+// LOCAL (U > 1 local steps per job, Eq. 2): the same stream of tiles runs over the job's U B rows;
+// at the end of every step the gradient is applied to the model in LDS, which is the worker's
+// private copy, and the upload is w^{t,0} - w^{t,U} with the mean of the local losses.
+constexpr int kFuseThreads = 512, kFuseWaves = 8, kFuseMaxB = 1024, kFuseMaxLocalRows = 2048;
 constexpr size_t kLdsPerCu = 160 * 1024;
 typedef float f32x4_ __attribute__((ext_vector_type(4)));
 // loads known to be from global memory (a pointer read from memory is generic to the compiler)
@@ -406,8 +409,8 @@ __device__ __forceinline__ float row16_max(float v) {
 
 // dynamic LDS: x tile and model with a pitch of d + 4 floats, partial logits, dZ, bias, then the
 // upload's row indices and labels
-static size_t fuse_lds_bytes(int d, int C, int B, int TR) {
-  return ((size_t)(TR + C) * (d + 4) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)B) * 4;
+static size_t fuse_lds_bytes(int d, int C, int rows, int TR) {
+  return ((size_t)(TR + C) * (d + 4) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)rows) * 4;
 }
 
 // TR rows per tile: 16 fills the matrix-core tile; 8 (half of the logits tile idle) when that lets
@@ -415,26 +418,23 @@ static size_t fuse_lds_bytes(int d, int C, int B, int TR) {
 // on the 784 x 10 workload, 256 simulations: 389 us per round against 430 us with 16 rows and one
 // workgroup; 12-row tiles (register spills) 459 us; logits of 8-row tiles on sixteen 4 x 4 x 1
 // blocks instead of a half-idle 16 x 16 x 4 tile 424 us.
-template <int C, int TR>
-__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_batch_kernel(
-    const RegressionArgs* as, const char* rds, size_t stride) {
+template <int C, int TR, bool LOCAL>
+__device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, const RoundDesc& rd, int up) {
   constexpr int LD = TR / 2;              // 16-byte chunks per thread and tile (d <= 1024)
   constexpr int NB = 8;                   // blocks of 16 features per wavefront (d <= 1024)
   constexpr int RJ = TR / 4;              // groups of 4 rows per tile
   extern __shared__ __align__(16) float s_mem[];
-  const RegressionArgs a = as[blockIdx.y];
-  const RoundDesc& rd = *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride);
-  const int up = blockIdx.x;
   if (up >= rd.K) return;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int d = a.d, B = a.B, dq = d >> 2, dp = d + 4;
+  const int total = LOCAL ? a.U * B : B;  // rows of the job: draw i of its counter stream is row i
   float* s_x = s_mem;                     // [TR][dp]
-  float* s_Wt = s_x + TR * dp;            // [C][dp]; at the end: the upload's gradient, boundary layout
+  float* s_Wt = s_x + TR * dp;            // [C][dp]; one step: at the end the upload's gradient, boundary layout
   float* s_zp = s_Wt + C * dp;            // [8 wavefronts][TR rows][16 classes]
   float* s_dz = s_zp + kFuseWaves * TR * 16;   // [TR][16]
   float* s_b = s_dz + TR * 16;            // [16]
-  uint32_t* s_rowi = (uint32_t*)(s_b + 16);  // [B]
-  int* s_lab = (int*)(s_rowi + B);           // [B]
+  uint32_t* s_rowi = (uint32_t*)(s_b + 16);  // [total]
+  int* s_lab = (int*)(s_rowi + total);       // [total]
   const WorkerDesc w = rd.w[up];
   const float* Wv = a.ring + (size_t)w.slot * a.slot_stride;
 
@@ -445,12 +445,14 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
 #pragma unroll
   for (int u = 0; u < 4; ++u) wv[u] = load_global_f4(Wv + 4 * min(t + u * kFuseThreads, nW4 - 1));
   const float bias = load_global(Wv + d * C + min(t, C - 1));
-  for (int b = t; b < B; b += kFuseThreads)
+  for (int b = t; b < total; b += kFuseThreads)
     s_rowi[b] = (uint32_t)batch_row(w, a.batch_key, a.shard_rows, (uint32_t)b);
   __syncthreads();
-  int lab[2];                             // B <= 1024
+  constexpr int NLAB = LOCAL ? kFuseMaxLocalRows / kFuseThreads : kFuseMaxB / kFuseThreads;
+  int lab[NLAB];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) lab[u] = load_global((const int32_t*)a.y + s_rowi[min(t + u * kFuseThreads, B - 1)]);
+  for (int u = 0; u < NLAB; ++u)
+    lab[u] = load_global((const int32_t*)a.y + s_rowi[min(t + u * kFuseThreads, total - 1)]);
   // chunk t + 512 j of a tile is chunk pc[j] of tile row pr[j]
   int pr[LD], pc[LD];
   {
@@ -500,8 +502,8 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
   }
   if (t < 16) s_b[t] = t < C ? bias : 0.f;
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-    if (t + u * kFuseThreads < B) s_lab[t + u * kFuseThreads] = lab[u];
+  for (int u = 0; u < NLAB; ++u)
+    if (t + u * kFuseThreads < total) s_lab[t + u * kFuseThreads] = lab[u];
 
   const int m16 = lane & 15, g4 = lane >> 4;      // the lane's row / column and k index inside a tile
   const int nstep = (d + 15) >> 4;                // steps of 16 features = blocks of 16 features
@@ -509,14 +511,16 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
   float bacc = 0.f, loss = 0.f;
-  for (int base = 0; base < B; base += TR) {
+  // off: the tile's first row in the job's stream of rows; base: the same inside its step
+  for (int off = 0, base = 0; off < total;) {
     const int nrows = min(TR, B - base);
+    const int noff = off + nrows, nbase = base + nrows == B ? 0 : base + nrows;
     __syncthreads();                      // the previous tile has been used up
 #pragma unroll
     for (int j = 0; j < LD; ++j)
       if (pr[j] < nrows) *(float4*)(s_x + pr[j] * dp + 4 * pc[j]) = pre[j];
     __syncthreads();
-    if (base + TR < B) ABS_PREFETCH(base + TR, min(TR, B - base - TR))
+    if (noff < total) ABS_PREFETCH(noff, min(TR, B - nbase))
     // (1a) this wavefront's share of the logits: steps wave, wave + 8, ... of 16 features; lane
     // (m16, g4) feeds row m16 of x (mod TR) and class m16 of W at features 16 st + 4 g4 .. + 3
     {
@@ -553,7 +557,7 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
       const float e = c < C ? expf(zz - zmax) : 0.f;
       const float ssum = row16_sum(e);
       const bool live = r < nrows;
-      const int label = live ? s_lab[base + r] : -1;
+      const int label = live ? s_lab[off + r] : -1;
       const float p = e / ssum;
       s_dz[t] = live && c < C ? w.c * (p - (c == label ? 1.f : 0.f)) : 0.f;
       if (c == label) loss += logf(ssum) - (zz - zmax);
@@ -583,12 +587,48 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
         for (int r = 0; r < TR; ++r) bacc += s_dz[r * 16 + t];
       }
     }
+    if (LOCAL && nbase == 0) {
+      // end of a local step (Eq. 2): the step's gradient onto the private model; the lane holds
+      // G[feature 16 blk + 4 g4 + i][class m16].  The next tile's barriers order this before
+      // anybody reads the model again.
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const int blk = wave + kFuseWaves * bi, f0 = 16 * blk + 4 * g4;
+        if (f0 < d && m16 < C) {          // d % 4 == 0: all four features or none
+          float4* q = (float4*)(s_Wt + m16 * dp + f0);
+          float4 v = *q;
+          v.x -= G[bi][0]; v.y -= G[bi][1]; v.z -= G[bi][2]; v.w -= G[bi][3];
+          *q = v;
+        }
+        G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
+      }
+      if (t < 16) { s_b[t] -= bacc; bacc = 0.f; }
+    }
+    off = noff; base = nbase;
   }
 #undef ABS_PREFETCH
   // losses sit in the lanes whose class is the row's label: add them up
   loss = row16_sum(loss);
   __syncthreads();
   if (wave < TR / 4 && m16 == 0) s_zp[t >> 4] = loss;      // TR row sums (s_zp is free now)
+  float* part = a.delta + (size_t)up * a.slot_stride;
+  if (LOCAL) {
+    // the upload: what the U steps changed, w^{t,0} - w^{t,U}, and the mean of the local losses
+    __syncthreads();
+    const int P = (d + 1) * C;
+    for (int idx = t; idx < P; idx += kFuseThreads) {
+      const int i = idx / C, c = idx - i * C;
+      const float now = i < d ? s_Wt[c * dp + i] : s_b[c];
+      part[idx] = load_global(Wv + idx) - now;
+    }
+    if (t == 0) {
+      float l = 0.f;
+#pragma unroll
+      for (int v = 0; v < TR; ++v) l += s_zp[v];
+      a.lossbuf[up] = l / (float)total;
+    }
+    return;
+  }
   // the gradient, staged through LDS in the boundary layout for full-width stores; the lane holds
   // G[feature 16 blk + 4 g4 + i][class m16]
   float* s_G = s_Wt;
@@ -605,7 +645,6 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
   }
   if (t < C) s_G[d * C + t] = bacc;
   __syncthreads();
-  float* part = a.delta + (size_t)up * a.slot_stride;
   for (int j = t; j < nW4; j += kFuseThreads) {
     const float4 g = ((const float4*)s_G)[j];
     *(__attribute__((address_space(1))) f32x4_*)(part + 4 * j) = f32x4_{g.x, g.y, g.z, g.w};
@@ -617,6 +656,23 @@ __global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_
     for (int v = 0; v < TR; ++v) l += s_zp[v];
     a.lossbuf[up] = l / (float)B;
   }
+}
+
+template <int C, int TR>
+__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_batch_kernel(
+    const RegressionArgs* as, const char* rds, size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  softmax_upload_body<C, TR, false>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), blockIdx.x);
+}
+template <int C, int TR>
+__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_local_fused_kernel(RegressionArgs a, RoundDesc rd) {
+  softmax_upload_body<C, TR, true>(a, rd, blockIdx.x);
+}
+template <int C, int TR>
+__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_local_fused_batch_kernel(
+    const RegressionArgs* as, const char* rds, size_t stride) {
+  const RegressionArgs a = as[blockIdx.y];
+  softmax_upload_body<C, TR, true>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), blockIdx.x);
 }
 
 // Eq. 3 over the uploads' gradients (each already scaled by its c), arrival order
@@ -669,6 +725,49 @@ static hipError_t launch_softmax_fused_batch(const RegressionArgs* d_args, const
   const int P = (d + 1) * C;
   softmax_combine_batch_kernel<<<dim3((P + 255) / 256, S), dim3(256), 0, s>>>(d_args, d_rds, stride, P);
   return hipGetLastError();
+}
+
+// The local steps of the uploads of one simulation (d_args == nullptr: arguments by value) or of S
+// simulations; the caller adds the uploads' changes afterwards (Eq. 3).
+template <int C, int TR>
+static hipError_t launch_softmax_local_fused_c(const RegressionArgs* a1, const RoundDesc* rd1, const RegressionArgs* d_args,
+                                               const char* d_rds, size_t stride, int S, int d, int rows, int Kmax,
+                                               hipStream_t s) {
+  static std::atomic<size_t> allowed1{0}, allowedS{0};
+  const size_t lds = fuse_lds_bytes(d, C, rows, TR);
+  const bool single = d_args == nullptr;
+  std::atomic<size_t>& allowed = single ? allowed1 : allowedS;
+  if (lds > allowed.load(std::memory_order_acquire)) {
+    const hipError_t e = single ? hipFuncSetAttribute((const void*)softmax_local_fused_kernel<C, TR>,
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                : hipFuncSetAttribute((const void*)softmax_local_fused_batch_kernel<C, TR>,
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    size_t seen = allowed.load(std::memory_order_relaxed);
+    while (seen < lds && !allowed.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
+  }
+  if (single) softmax_local_fused_kernel<C, TR><<<dim3(Kmax), dim3(kFuseThreads), lds, s>>>(*a1, *rd1);
+  else        softmax_local_fused_batch_kernel<C, TR><<<dim3(Kmax, S), dim3(kFuseThreads), lds, s>>>(d_args, d_rds, stride);
+  return hipGetLastError();
+}
+
+bool softmax_local_fused_ok(int B, int U) { return B <= kFuseMaxB && (long)B * U <= kFuseMaxLocalRows; }
+
+hipError_t launch_softmax_local_fused(const RegressionArgs* a1, const RoundDesc* rd1, const RegressionArgs* d_args,
+                                      const char* d_rds, size_t stride, int S, int d, int C, int B, int U, int Kmax,
+                                      hipStream_t s) {
+  const int rows = B * U;
+  const bool two = 2 * fuse_lds_bytes(d, C, rows, 8) <= kLdsPerCu;      // two workgroups per CU
+  switch (C) {
+#define ABS_CASE(c)                                                                                              \
+  case c:                                                                                                        \
+    return two ? launch_softmax_local_fused_c<c, 8>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s)         \
+               : launch_softmax_local_fused_c<c, 16>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s);
+    ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
+    ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
+#undef ABS_CASE
+    default: return hipErrorInvalidValue;
+  }
 }
 
 template <int C>
