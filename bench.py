@@ -117,7 +117,7 @@ def cpu_baseline(p, inputs, budget_s: float):
     grads = rounds = 0
     while True:
         rec = o.round()
-        grads += rec["K"]
+        grads += rec["K"] * p.get("U", 1)
         rounds += 1
         el = time.perf_counter() - t0
         if el >= budget_s or rounds >= p["T"]:
@@ -161,7 +161,7 @@ def bench_batch(args, p, inputs, warmup, steps):
     grads = 0
     for sim in sims:
         tr = sim.trace(warmup, warmup + steps)
-        grads += int(tr[:, 1].sum())
+        grads += int(tr[:, 1].sum()) * p.get("U", 1)
         assert np.all(np.isfinite(sim.model())), "non-finite parameters after the timed run"
     batch.close()
     for sim in sims:
@@ -176,7 +176,8 @@ def bench_batch(args, p, inputs, warmup, steps):
         "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{p['name']}_x{S}_simulations", "N": p["N"], "B": p["B"], "dims": p["dims"],
-                   "K0": p["K0"], "tau_cap": p["tau_cap"], "a": p["a"], "lr": p["lr"], "simulations": S},
+                   "K0": p["K0"], "tau_cap": p["tau_cap"], "a": p["a"], "lr": p["lr"], "U": p.get("U", 1),
+                   "simulations": S},
         "samples_per_sec": value * p["B"], "rounds_per_sec": steps * S / elapsed,
         "roofline": {"bound": "hbm", "kernel": "whole round (all launches and the host, wall clock)",
                      "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
@@ -197,6 +198,8 @@ def main():
                     help="counter runs only: wait for all N workers every round (the steady state)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="counter runs only: end with a plain 1 GiB device copy to calibrate FETCH/WRITE_SIZE")
+    ap.add_argument("--local-steps", type=int, default=1, metavar="U",
+                    help="local SGD: U minibatch steps per job (Eq. 2); a worker gradient is one such step")
     ap.add_argument("--batch", type=int, default=0,
                     help="configs 1-2: advance this many independent simulations (seeds) per launch")
     ap.add_argument("--traffic-import", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
@@ -218,6 +221,9 @@ def main():
     p = workloads.preset(args.config)
     if args.fixed_k:
         p["k_mode"], p["K0"] = 1, p["N"]
+    if args.local_steps != 1:
+        p["U"] = args.local_steps
+        p["name"] += f"_U{args.local_steps}"
     dw, ds = DEFAULT_STEPS[args.config]
     warmup = dw if args.warmup is None else args.warmup
     steps = ds if args.steps is None else args.steps
@@ -244,7 +250,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
     assert np.all(np.isfinite(final)), "non-finite parameters after the timed run"
-    grads = int(tr[:, 1].sum())
+    grads = int(tr[:, 1].sum()) * p.get("U", 1)
     value = grads / elapsed
 
     # per-kernel time inside the timed region (HIP events on the launch stream)
@@ -297,7 +303,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": p["name"], "N": p["N"], "B": p["B"], "dims": p["dims"], "K0": p["K0"],
                    "tau_cap": p["tau_cap"], "a": p["a"], "lr": p["lr"], "sa_penalty": p["sa_penalty"],
-                   "K_first": int(tr[0, 1]), "K_last": int(tr[-1, 1])},
+                   "U": p.get("U", 1), "K_first": int(tr[0, 1]), "K_last": int(tr[-1, 1])},
         "samples_per_sec": value * p["B"],
         "rounds_per_sec": steps / elapsed,
         "kernels": kernels,
