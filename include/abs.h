@@ -208,20 +208,19 @@ void abs_destroy(abs_ctx* ctx);
  *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
  *                     count).  A simulation's result does not depend on what else is in the
  *                     batch.  Linear model, and both models with U > 1 (local SGD): bitwise the
- *                     result of abs_round on the handle alone.
- *                     Softmax model with U = 1: the batched round adds up each upload's gradient before
- *                     Eq. 3 sums the uploads, another rounding order than abs_round's, so models
- *                     agree with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5
- *                     that hangs on the last bit of a loss may differ).
+ *                     result of abs_round on the handle alone.  Softmax model with U = 1 and
+ *                     B <= 1024: the batched round adds up each upload's gradient before Eq. 3
+ *                     sums the uploads, another rounding order than abs_round's, so models agree
+ *                     with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5 that
+ *                     hangs on the last bit of a loss may differ).
  *                     Large batches (softmax: 64 simulations and more, linear: 512 and more)
- *                     advance as two halves, half a round apart, so
- *                     that the host's part of one overlaps the device's part of the other; at
- *                     return every simulation has done its n_rounds.  On an error of one
- *                     simulation the call stops and names it; rounds already on the device are
- *                     completed first, so the other simulations end on that round, the one before
- *                     or (the other half) the one after: abs_rounds_done tells.  A handle that did
- *                     not complete a round repeats it, with the same result, the next time it is
- *                     advanced.
+ *                     advance as two halves, half a round apart, so that the host's part of one
+ *                     overlaps the device's part of the other; at return every simulation has
+ *                     done its n_rounds.  On an error of one simulation the call stops and names
+ *                     it; rounds already on the device are completed first, so the other
+ *                     simulations end on that round, the one before or (the other half) the one
+ *                     after: abs_rounds_done tells.  A handle that did not complete a round
+ *                     repeats it, with the same result, the next time it is advanced.
  *  abs_batch_last_error  text of the last error (b == NULL: of the last failed abs_batch_create
  *                     on this thread).
  */
