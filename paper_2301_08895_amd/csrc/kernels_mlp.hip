@@ -1217,7 +1217,9 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
   hook->begin(KK_MLP_UPDATE, n * (u.nsplit + 1), n * (4.0 * (u.nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
   const dim3 block(256);
   const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
-  if (vec && p.d[l + 1] >= 256) mlp_update_kernel<256><<<dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
+  // wide tiles (fewer, longer stores) only where they still give every CU a workgroup
+  const bool wide = p.d[l + 1] >= 256 && ((p.d[l + 1] + 255) / 256) * ((p.d[l] + 63) / 64) * batch >= 256;
+  if (vec && wide) mlp_update_kernel<256><<<dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
   else if (vec) mlp_update_kernel<64><<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
   else     mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, 0, s>>>(u);
   hook->end(KK_MLP_UPDATE);
