@@ -103,9 +103,11 @@ int Scheduler::complete(const std::vector<Upload>& sel, const float* worker_loss
     if (!std::isfinite(loss_t)) { err = "non-finite minibatch loss"; return ABS_E_NONFINITE; }
     if (t_ == 0) loss0_ = loss_t;
   }
-  std::vector<char> in_sel((size_t)N_, 0);
+  std::vector<char>& in_sel = in_sel_;
+  in_sel.assign((size_t)N_, 0);
   for (const Upload& u : sel) in_sel[(size_t)u.id] = 1;
-  std::vector<int32_t> restart;
+  std::vector<int32_t>& restart = restart_;
+  restart.clear();
   for (int n = 0; n < N_; ++n)
     if (!in_sel[(size_t)n] && over_stale(tau_[(size_t)n], K)) restart.push_back(n);
 

@@ -56,6 +56,8 @@ class Scheduler {
   std::vector<uint32_t> job_;
   std::vector<uint64_t> fin_;
   std::vector<int32_t> order_;
+  std::vector<char> in_sel_;          // scratch of complete(): aggregated or restarted this round
+  std::vector<int32_t> restart_;      // scratch of complete(): the restart set, ascending
   std::vector<int32_t> trace_;
 };
 
