@@ -407,10 +407,17 @@ __device__ __forceinline__ float row16_max(float v) {
   return v;
 }
 
-// dynamic LDS: x tile and model with a pitch of d + 4 floats, partial logits, dZ, bias, then the
-// upload's row indices and labels
+// Row pitch (floats) of the x tile and the model in LDS, chosen for the bank pattern of the matrix
+// cores' operand reads (64 banks).  The logits product reads 16 bytes per lane from tile rows m16
+// at 4 g4 floats: with 16 rows, a pitch of 4 modulo 64 gives every row its own four banks; with 8
+// rows any pitch of 8 modulo 16 does.  The gradient product reads one float per lane, 16 features
+// of four rows: those rows must be a multiple of 16 banks apart, which rows 2 g4 + j of an 8-row
+// tile are at a pitch of 8 modulo 16.  (At least d + 1, so that the model's region can hold the
+// gradient with its bias row at the end.)
+__host__ __device__ inline int fuse_pitch(int d, int TR) { return TR == 16 ? d + 4 : d + (23 - d % 16) % 16 + 1; }
+// dynamic LDS: x tile and model, partial logits, dZ, bias, then the upload's row indices and labels
 static size_t fuse_lds_bytes(int d, int C, int rows, int TR) {
-  return ((size_t)(TR + C) * (d + 4) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)rows) * 4;
+  return ((size_t)(TR + C) * fuse_pitch(d, TR) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)rows) * 4;
 }
 
 // TR rows per tile: 16 fills the matrix-core tile; 8 (half of the logits tile idle) when that lets
@@ -426,7 +433,7 @@ __device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, con
   extern __shared__ __align__(16) float s_mem[];
   if (up >= rd.K) return;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int d = a.d, B = a.B, dq = d >> 2, dp = d + 4;
+  const int d = a.d, B = a.B, dq = d >> 2, dp = fuse_pitch(d, TR);
   const int total = LOCAL ? a.U * B : B;  // rows of the job: draw i of its counter stream is row i
   float* s_x = s_mem;                     // [TR][dp]
   float* s_Wt = s_x + TR * dp;            // [C][dp]; one step: at the end the upload's gradient, boundary layout
@@ -563,11 +570,14 @@ __device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, con
       if (c == label) loss += logf(ssum) - (zz - zmax);
     }
     __syncthreads();
-    // (2) G += X_tile^T dZ: lane (m16, g4) feeds feature f0 + m16 of row 4 j + g4 and dZ[4 j + g4][m16]
+    // (2) G += X_tile^T dZ: in step j lane (m16, g4) feeds feature f0 + m16 of tile row r(j, g4) and
+    // dZ[r][m16]; which four rows a step takes is free: 4 j + g4 for 16-row tiles, 2 g4 + j for
+    // 8-row tiles (bank pattern, see fuse_pitch)
     {
+      const int r_g4 = TR == 16 ? g4 : RJ * g4, r_j = TR == 16 ? 4 : 1;
       float bq[RJ];
 #pragma unroll
-      for (int j = 0; j < RJ; ++j) bq[j] = s_dz[(4 * j + g4) * 16 + m16];
+      for (int j = 0; j < RJ; ++j) bq[j] = s_dz[(r_g4 + r_j * j) * 16 + m16];
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
         const int blk = wave + kFuseWaves * bi;
@@ -575,7 +585,7 @@ __device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, con
           const int f = min(16 * blk + m16, d - 1);
 #pragma unroll
           for (int j = 0; j < RJ; ++j) {
-            const int r = 4 * j + g4;
+            const int r = r_g4 + r_j * j;
             float xa = s_x[r * dp + f];
             if (r >= nrows) xa = 0.f;     // rows past the tile hold whatever the last tile left
             G[bi] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, bq[j], G[bi], 0, 0, 0);
