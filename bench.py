@@ -193,6 +193,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--profile-every", type=int, default=8, metavar="n",
+                    help="bracket the kernels of every n-th round with HIP events (1: of every round)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time (0: skip)")
     ap.add_argument("--fixed-k", action="store_true",
                     help="counter runs only: wait for all N workers every round (the steady state)")
@@ -232,7 +234,7 @@ def main():
     if args.batch:
         return bench_batch(args, p, inputs, warmup, steps)
 
-    sim = lib.Simulation(p, inputs, profile=0 if args.no_profile else 1)
+    sim = lib.Simulation(p, inputs, profile=0 if args.no_profile else max(1, args.profile_every))
     sim.round(warmup)
     torch.cuda.synchronize()
     stats0 = {s["name"]: s for s in sim.kernel_stats()}
@@ -256,12 +258,12 @@ def main():
     # per-kernel time inside the timed region (HIP events on the launch stream)
     kern = []
     for name, s1 in stats1.items():
-        s0 = stats0.get(name, dict(launches=0, total_ms=0.0, flops=0.0, bytes=0.0))
-        n = s1["launches"] - s0["launches"]
+        s0 = stats0.get(name, dict(timed_launches=0, total_ms=0.0, timed_flops=0.0, timed_bytes=0.0))
+        n = s1["timed_launches"] - s0["timed_launches"]      # the launches of the bracketed rounds
         if n <= 0:
             continue
         kern.append(dict(name=name, launches=n, ms=s1["total_ms"] - s0["total_ms"],
-                         flops=s1["flops"] - s0["flops"], bytes=s1["bytes"] - s0["bytes"]))
+                         flops=s1["timed_flops"] - s0["timed_flops"], bytes=s1["timed_bytes"] - s0["timed_bytes"]))
     roofline = None
     if kern and not args.no_profile:
         dom = max(kern, key=lambda k: k["ms"])
@@ -306,6 +308,7 @@ def main():
                    "U": p.get("U", 1), "K_first": int(tr[0, 1]), "K_last": int(tr[-1, 1])},
         "samples_per_sec": value * p["B"],
         "rounds_per_sec": steps / elapsed,
+        "profile_every": 0 if args.no_profile else max(1, args.profile_every),
         "kernels": kernels,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -81,6 +81,8 @@ typedef struct abs_ctx abs_ctx;   /* opaque: one simulation */
  *             used to plan or check the event trace on a machine without a GPU.
  *  profile    1: bracket every kernel with events and accumulate per-kernel time
  *             (read with abs_kernel_stats); costs a few microseconds per launch.
+ *             n > 1: the same in every n-th round only (rounds t with t mod n = 0), a
+ *             uniform sample of the job at 1/n of the cost.
  *  U          local SGD steps per job (Eq. 2), 1 <= U <= 64.  With U > 1 every upload is
  *             the change w^{t,0} - w^{t,U} of a private copy of the model after U steps
  *             on fresh minibatches (worker part of Algorithm 1) and the reported loss is
@@ -178,14 +180,18 @@ int abs_trace(abs_ctx* ctx, int64_t round_lo, int64_t round_hi, int32_t* h_out,
 /* Rounds completed so far. */
 int64_t abs_rounds_done(const abs_ctx* ctx);
 
-/* Per-kernel accounting: launches always; total_ms only with profile = 1.  flops and
- * bytes are the algorithmic work of the launches so far (not counter readings). */
+/* Per-kernel accounting: launches always; total_ms only with profile >= 1, over the
+ * launches of the bracketed rounds (timed_*).  flops and bytes are the algorithmic work
+ * of the launches so far (not counter readings). */
 typedef struct abs_kernel_stat {
   char    name[48];
   int64_t launches;
   double  total_ms;
   double  flops;
   double  bytes;
+  int64_t timed_launches;   /* the launches that total_ms covers (= launches with profile = 1) */
+  double  timed_flops;      /* ... and their algorithmic work */
+  double  timed_bytes;
 } abs_kernel_stat;
 int abs_kernel_stats(abs_ctx* ctx, abs_kernel_stat* h_out, int32_t cap, int32_t* n_out);
 

@@ -39,7 +39,8 @@ class AbsConfig(C.Structure):
 
 class AbsKernelStat(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double),
-                ("flops", C.c_double), ("bytes", C.c_double)]
+                ("flops", C.c_double), ("bytes", C.c_double), ("timed_launches", C.c_int64),
+                ("timed_flops", C.c_double), ("timed_bytes", C.c_double)]
 
 
 def library_path() -> str:
@@ -208,7 +209,8 @@ def abs_kernel_stats(handle: int):
     n = C.c_int32()
     _check(_lib.abs_kernel_stats(handle, buf, 32, C.byref(n)), handle)
     return [dict(name=buf[i].name.decode(), launches=buf[i].launches, total_ms=buf[i].total_ms,
-                 flops=buf[i].flops, bytes=buf[i].bytes) for i in range(n.value)]
+                 flops=buf[i].flops, bytes=buf[i].bytes, timed_launches=buf[i].timed_launches,
+                 timed_flops=buf[i].timed_flops, timed_bytes=buf[i].timed_bytes) for i in range(n.value)]
 
 
 def abs_last_error(handle=None) -> str:

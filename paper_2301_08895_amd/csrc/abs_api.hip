@@ -54,6 +54,7 @@ bool validate(const abs_config& c, std::string& why) {
   if (c.n_slow > 0 && !(c.slow_factor > 0.0)) return bad("slow_factor must be positive");
   if (c.U < 0 || c.U > 64) return bad("U must be in [1, 64]");
   if (c.reserved != 0) return bad("reserved must be 0");
+  if (c.profile < 0) return bad("profile must be 0, 1 or a sampling period n > 1");
   if (c.device_mode == 0 && !(c.k_mode == ABS_K_FIXED || c.k_mode == ABS_K_REPLAY))
     return bad("schedule-only mode needs k_mode 1 or 2 (there are no losses to adapt K with)");
   switch (c.model) {
@@ -95,7 +96,10 @@ void reg_plan(const abs_config& c, RegPlan& p) {
   p.total = o;
 }
 
-struct Stat { int64_t launches = 0; double ms = 0, flops = 0, bytes = 0; };
+struct Stat {
+  int64_t launches = 0; double ms = 0, flops = 0, bytes = 0;
+  int64_t timed_launches = 0; double timed_flops = 0, timed_bytes = 0;   // the launches bracketed by events
+};
 
 }  // namespace
 
@@ -126,12 +130,16 @@ struct abs_ctx : public LaunchHook {
   std::vector<hipEvent_t> ev;
   std::vector<int> ev_kind;
   size_t ev_used = 0;
+  bool timing = false;                 // this round's launches are bracketed (profile: every round or every n-th)
 
   void begin(int kind, double flops, double bytes) override {
     stats[kind].launches += 1;
     stats[kind].flops += flops;
     stats[kind].bytes += bytes;
-    if (cfg.profile) {
+    if (timing) {
+      stats[kind].timed_launches += 1;
+      stats[kind].timed_flops += flops;
+      stats[kind].timed_bytes += bytes;
       if (ev_used + 2 > ev.size()) {
         for (int i = 0; i < 2; ++i) { hipEvent_t e; (void)hipEventCreate(&e); ev.push_back(e); }
       }
@@ -139,7 +147,7 @@ struct abs_ctx : public LaunchHook {
     }
   }
   void end(int kind) override {
-    if (cfg.profile) {
+    if (timing) {
       (void)hipEventRecord(ev[ev_used + 1], stream);
       ev_kind.push_back(kind);
       ev_used += 2;
@@ -326,6 +334,7 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       continue;
     }
     fill_round_desc(ctx, sel, t, rd);
+    ctx->timing = cfg.profile == 1 || (cfg.profile > 1 && t % cfg.profile == 0);
     hipError_t e;
     if (cfg.model == ABS_MODEL_MLP) {
       e = launch_mlp_round(ctx->margs, rd, ctx->stream, ctx);
@@ -689,6 +698,9 @@ int abs_kernel_stats(abs_ctx* ctx, abs_kernel_stat* h_out, int32_t cap, int32_t*
     h_out[n].total_ms = ctx->stats[k].ms;
     h_out[n].flops = ctx->stats[k].flops;
     h_out[n].bytes = ctx->stats[k].bytes;
+    h_out[n].timed_launches = ctx->stats[k].timed_launches;
+    h_out[n].timed_flops = ctx->stats[k].timed_flops;
+    h_out[n].timed_bytes = ctx->stats[k].timed_bytes;
     ++n;
   }
   *n_out = n;

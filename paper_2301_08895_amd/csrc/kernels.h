@@ -129,6 +129,7 @@ struct MlpPlan {
   size_t off_dz[8], off_dzt[8];   // dZ_l [Mp][ld_l], dZ_l^T [dp_l][ldm], l = 1 .. L
   size_t off_rowloss, off_partial;
   size_t off_colsum[8];           // column sums of dZ_l per block of 64 rows, fp32 [Mp / 64][dp_l], l = 1 .. L
+  size_t off_maskbits[8];         // ReLU mask of H_l, one bit per element in the tile kernel's accumulator order, l = 1 .. L-1
   size_t partial_floats;
   // local SGD (U > 1): the uploads' private models (same slot layouts as the two rings),
   // their running mean losses, and the averaged change of Eq. 3

@@ -135,6 +135,10 @@ struct GemmArgs {
   int mt, nt, nsplit, rows_per_xcd;   // tile grid (see the block -> tile mapping in the kernel)
   const uint16_t* maskT; size_t ldmaskT; // EPI_DGRAD: H_l^T [Ndim][ldmaskT]; the gradient passes where H_l > 0
   float* colsum; size_t ldcs;         // EPI_DGRAD: column sums of the bf16 results per block of 64 rows, [Mdim / 64][ldcs]
+  // 256 x 256 tile kernel only: the ReLU mask as one bit per element in the kernel's own accumulator
+  // order (16 bytes per lane and tile: [tile][wavefront][lane][4 words], word mi, bit (4 ni + rg) 4 + rr).
+  // EPI_RELU writes it when set; EPI_DGRAD reads it instead of maskT when set.
+  uint32_t* maskbits;
 };
 
 // 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
@@ -612,12 +616,20 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
   float* outf = g.outf;
   if (EPI == EPI_WGRAD) outf += (size_t)zsplit * g.split_stride;
+  // the tile's ReLU mask bits of this lane (EPI_RELU collects them, EPI_DGRAD has them from the forward pass)
+  uint32_t mbits[4] = {0u, 0u, 0u, 0u};
+  uint32_t* const mbits_at =
+      g.maskbits ? g.maskbits + ((((size_t)(m0 / TM3) * g.nt + n0 / TN3) * 8 + wave) * 64 + lane) * 4 : nullptr;
+  if (EPI == EPI_DGRAD && mbits_at) {
+    const uint4 q = *(const uint4*)mbits_at;
+    mbits[0] = q.x; mbits[1] = q.y; mbits[2] = q.z; mbits[3] = q.w;
+  }
   uint16_t* const sT = smem + wave * (2 * 64 * kEpiPitch3);     // [64 n][72]
   uint16_t* const sN = sT + 64 * kEpiPitch3;                    // [64 m][72]
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     float cs[2] = {0.f, 0.f};             // EPI_DGRAD: column sums over this half's 64 rows
-    if (EPI == EPI_DGRAD) {
+    if (EPI == EPI_DGRAD && !mbits_at) {
       // the ReLU mask of this half, H_l^T [64 n][64 m], fetched as whole 128-byte rows into sT;
       // every lane later replaces the 4 entries it read by its 4 results
       const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
@@ -642,19 +654,23 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
           const int mbase = m0 + wm * 128 + half * 64 + ml;
           uint16_t h[4];
           uint2 hm = make_uint2(0, 0);
-          if (EPI == EPI_DGRAD) hm = *(const uint2*)&sT[nl * kEpiPitch3 + ml];
+          if (EPI == EPI_DGRAD && !mbits_at) hm = *(const uint2*)&sT[nl * kEpiPitch3 + ml];
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
             const int m = mbase + rr;
             float v = acc[mi][ni][rg * 4 + rr];
             if (EPI == EPI_RELU) {
               v = fmaxf(v + bv, 0.f);
+              // (the mask is taken from the narrowed value, as the transposed copy would give it)
+              if ((f32_to_bf16(v) & 0x7FFFu) != 0) mbits[mi] |= 1u << (((ni * 4 + rg) * 4) + rr);
             } else if (EPI == EPI_LOGITS) {
               v += bv;
               outf[(size_t)m * g.ldof + n] = v;
             } else if (EPI == EPI_DGRAD) {
               const uint32_t pair = rr < 2 ? hm.x : hm.y;
-              v = ((pair >> ((rr & 1) * 16)) & 0x7FFFu) ? v : 0.f;
+              const bool pass = mbits_at ? ((mbits[mi] >> (((ni * 4 + rg) * 4) + rr)) & 1u) != 0
+                                         : ((pair >> ((rr & 1) * 16)) & 0x7FFFu) != 0;
+              v = pass ? v : 0.f;
             } else {
               outf[(size_t)m * g.ldof + n] = v;
             }
@@ -696,6 +712,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
       }
     }
   }
+  if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
 }
 
 // ------------------------------------------------------------------ softmax cross-entropy
@@ -1142,6 +1159,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   }
   p.off_rowloss = take(Mp * 4);
   for (int l = 1; l <= L; ++l) p.off_colsum[l] = take(Mp / 64 * p.dp[l] * 4);
+  for (int l = 1; l < L; ++l) p.off_maskbits[l] = take(round_up(Mp, 256) * round_up((size_t)p.dp[l], 256) / 8);
   p.off_partial = take(p.partial_floats * 4);
   if (p.U > 1) {
     p.off_priv = take((size_t)c.N * p.slot_stride * 4);
@@ -1231,8 +1249,9 @@ inline bool gemm_is_big(bool gather, bool per_upload, const GemmArgs& g, int Mdi
          (!gather || g.a_kvalid == g.ksteps_total * BK) && (Mdim / TM3) * (Ndim / TN3) * nsplit >= 128;
 }
 
+// Returns whether the product went to the 256 x 256 tile kernel (only that one knows maskbits).
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
-void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
+bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   g.nsplit = nsplit;
   const bool big = gemm_is_big(GATHER, PER_UPLOAD, g, Mdim, Ndim, nsplit);
   if (big) {
@@ -1240,7 +1259,7 @@ void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     g.nt = Ndim / TN3;
     g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
     mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd);
-    return;
+    return true;
   }
   // widest column tile that still gives every CU a workgroup (narrower tiles otherwise)
   int tn = 64;
@@ -1256,13 +1275,18 @@ void launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   if (tn == 256)      mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
   else if (tn == 128) mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
   else                mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
+  return false;
 }
 
 // Forward pass over `rows` stacked rows (rowidx gives the rows of Xsrc): H_l and H_l^T for the
 // hidden layers, fp32 logits; the model of the rows of upload a is slot rd.w[a].slot of the
 // ring given by wbase / sbase (own: slot a of the private models).
-void mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd, int rows, double arows,
-                 const float* wbase, const uint16_t* sbase, bool own, hipStream_t s, LaunchHook* hook) {
+// Returns the set of hidden layers l (bit l) whose ReLU mask bits were written (want_bits and the
+// layer's product ran on the 256 x 256 tile kernel).
+unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd, int rows, double arows,
+                     const float* wbase, const uint16_t* sbase, bool own, bool want_bits, hipStream_t s,
+                     LaunchHook* hook) {
+  unsigned have_bits = 0;
   const MlpPlan& p = a.plan;
   const int L = p.L;
   const uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
@@ -1282,8 +1306,10 @@ void mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd, in
       g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = p.ldm;
       const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
       hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
-      if (l == 0) launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s);
-      else        launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      if (want_bits) g.maskbits = at<uint32_t>(a, p.off_maskbits[l + 1]);
+      const bool big = l == 0 ? launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s)
+                              : launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      if (big && want_bits) have_bits |= 1u << (l + 1);
       hook->end(kind);
     } else {
       g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
@@ -1292,6 +1318,7 @@ void mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd, in
       hook->end(KK_MLP_FWD_LOGITS);
     }
   }
+  return have_bits;
 }
 
 }  // namespace
@@ -1352,7 +1379,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     }
 
     // ---- forward at the uploads' model versions
-    mlp_forward(a, a.X, rd, rows, arows, wbase, sbase, own, s, hook);
+    const unsigned have_bits = mlp_forward(a, a.X, rd, rows, arows, wbase, sbase, own, true, s, hook);
 
     // ---- loss and output gradient, already scaled by the uploads' coefficients
     {
@@ -1386,6 +1413,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       g.rows_per_upload = p.Bp;
       g.ksteps_total = g.ksteps_per_split = p.dp[l + 1] / BK;
       g.maskT = at<uint16_t>(a, p.off_ht[l]); g.ldmaskT = p.ldm;
+      if ((have_bits >> l) & 1u) g.maskbits = at<uint32_t>(a, p.off_maskbits[l]);   // the 128-row kernel ignores it
       g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.ld[l];
       g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = p.ldm;
       g.colsum = at<float>(a, p.off_colsum[l]); g.ldcs = (size_t)p.dp[l];
@@ -1488,7 +1516,7 @@ hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, h
     mlp_eval_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, (const int32_t*)e.y, row0, n, rows);
     hook->end(KK_EVAL);
     mlp_forward(a, (const uint16_t*)e.X, rd, rows, (double)n, at<float>(a, p.off_ring), at<uint16_t>(a, p.off_shadow),
-                false, s, hook);
+                false, false, s, hook);
     hook->begin(KK_EVAL, 8.0 * n * p.d[p.L], 4.0 * n * p.d[p.L]);
     const dim3 grid((n + 3) / 4), block(256);
     const float* Z = at<float>(a, p.off_z);

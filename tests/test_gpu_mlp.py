@@ -77,3 +77,24 @@ def test_mlp_first_round_equals_the_hand_worked_values():
     sim.close()
     assert np.allclose(got, w1, rtol=0, atol=1e-7), (got, w1)
     assert abs(loss - np.log(4.0)) < 1e-6
+
+
+def test_sampled_kernel_timing_changes_nothing():
+    """profile = n brackets the kernels of every n-th round only: same results bit for bit, and the
+    statistics say which launches the measured time covers."""
+    import paper_2301_08895_amd as lib
+    p = workloads.scaled_preset(3, M=2048, dims=[128, 64, 10], N=4, B=32, n_slow=1)
+    d = workloads.make_inputs(p)
+    runs = {}
+    for prof in (0, 1, 4):
+        sim = lib.Simulation(p, d, profile=prof)
+        sim.round(21)
+        runs[prof] = (sim.model().copy(), sim.trace().copy(), sim.kernel_stats())
+        sim.close()
+    for prof in (1, 4):
+        assert np.array_equal(runs[prof][0], runs[0][0]) and np.array_equal(runs[prof][1], runs[0][1])
+    for s0, s1, s4 in zip(*(runs[k][2] for k in (0, 1, 4))):
+        assert s0["launches"] == s1["launches"] == s4["launches"] and s0["timed_launches"] == 0 and s0["total_ms"] == 0
+        assert s1["timed_launches"] == s1["launches"] and s1["timed_flops"] == s1["flops"] and s1["total_ms"] > 0
+        per_round = s4["launches"] // 21
+        assert s4["timed_launches"] == 6 * per_round and s4["total_ms"] > 0      # rounds 0, 4, ..., 20
