@@ -1261,11 +1261,13 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd);
     return true;
   }
-  // widest column tile that still gives every CU a workgroup (narrower tiles otherwise)
+  // widest column tile that still fills the GPU: 256-wide tiles only with two workgroups per CU
+  // (the kernel is built for two: one's loads cover the other's barriers), 128-wide with one
   int tn = 64;
   for (int cand : {256, 128}) {
     if (Ndim % cand) continue;
-    if ((Mdim / TM) * (Ndim / cand) * nsplit >= 256 || Ndim % (cand / 2)) { tn = cand; break; }
+    const int need = cand == 256 ? 512 : 256;
+    if ((Mdim / TM) * (Ndim / cand) * nsplit >= need || Ndim % (cand / 2)) { tn = cand; break; }
   }
   g.mt = Mdim / TM;
   g.nt = Ndim / tn;
