@@ -377,6 +377,9 @@ __global__ __launch_bounds__(1024) void softmax_update_batch_kernel(const Regres
 // private copy, and the upload is w^{t,0} - w^{t,U} with the mean of the local losses.
 constexpr int kFuseThreads = 512, kFuseWaves = 8, kFuseMaxB = 1024, kFuseMaxLocalRows = 2048;
 constexpr size_t kLdsPerCu = 160 * 1024;
+constexpr int kWreg = 0;                  // in place of TR: 16-row tiles with the model in registers (below)
+constexpr int kWregNB = 7;                // its blocks of 16 features per wavefront
+constexpr int kWregMaxD = 16 * kWregNB * kFuseWaves;
 typedef float f32x4_ __attribute__((ext_vector_type(4)));
 // loads known to be from global memory (a pointer read from memory is generic to the compiler)
 template <class T>
@@ -417,6 +420,7 @@ __device__ __forceinline__ float row16_max(float v) {
 __host__ __device__ inline int fuse_pitch(int d, int TR) { return TR == 16 ? d + 4 : d + (23 - d % 16) % 16 + 1; }
 // dynamic LDS: x tile and model, partial logits, dZ, bias, then the upload's row indices and labels
 static size_t fuse_lds_bytes(int d, int C, int rows, int TR) {
+  if (TR == kWreg) return ((size_t)16 * (d + 4) + (kFuseWaves + 1) * 256 + 16 + 2 * (size_t)rows) * 4;   // no model
   return ((size_t)(TR + C) * fuse_pitch(d, TR) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)rows) * 4;
 }
 
@@ -668,21 +672,232 @@ __device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, con
   }
 }
 
+// The same round with the model in registers instead of LDS, for d <= 896: the split of the logits
+// product over the wavefronts is static (wavefront w always takes the blocks of 16 features w,
+// w + 8, ...), so lane (m16, g4) only ever needs W[16 blk + 4 g4 + v][class m16] of its own
+// blocks - exactly the elements of the gradient it accumulates.  Without the model, a full
+// 16-row tile (no idle half in the logits product) and two workgroups fit a CU's LDS; a local
+// step (Eq. 2) is a subtraction between two sets of registers.
+// Its x tile has pitch d + 4: the 16 rows start 4 banks apart, and rows 4 g4 + j of the gradient
+// product 16 banks apart.
+
+template <int C, bool LOCAL>
+__device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a, const RoundDesc& rd, int up) {
+  constexpr int TR = 16, NB = kWregNB;
+  constexpr int LD = kWregMaxD / 4 / 32;  // 16-byte chunks per thread and tile: 32 threads per tile row
+  extern __shared__ __align__(16) float s_mem[];
+  if (up >= rd.K) return;
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int d = a.d, B = a.B, dq = d >> 2, dp = d + 4;
+  const int total = LOCAL ? a.U * B : B;  // rows of the job: draw i of its counter stream is row i
+  float* s_x = s_mem;                     // [16][dp]; at the end the upload in the boundary layout
+  float* s_zp = s_x + TR * dp;            // [8 wavefronts][16 rows][16 classes]
+  float* s_dz = s_zp + kFuseWaves * 256;  // [16][16]
+  float* s_b = s_dz + 256;                // [16]
+  uint32_t* s_rowi = (uint32_t*)(s_b + 16);  // [total]
+  int* s_lab = (int*)(s_rowi + total);       // [total]
+  const WorkerDesc w = rd.w[up];
+  const float* Wv = a.ring + (size_t)w.slot * a.slot_stride;
+  const int m16 = lane & 15, g4 = lane >> 4;      // the lane's row / column and k index inside a tile
+  const int nstep = (d + 15) >> 4;                // steps of 16 features = blocks of 16 features
+
+  // set-up, its loads all in flight together: the lane's part of the model, then - once the
+  // minibatch draws are known - labels and the first tile
+  f32x4_ wreg[NB];
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+    const int f0 = 16 * (wave + kFuseWaves * bi) + 4 * g4;
+    const bool ok = f0 < d && m16 < C;    // d % 4 == 0: all four features or none
+    const float* src = Wv + (ok ? f0 * C + m16 : 0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float x = load_global(src + (ok ? v * C : 0));
+      wreg[bi][v] = ok ? x : 0.f;
+    }
+  }
+  const float bias = load_global(Wv + d * C + min(t, C - 1));
+  for (int b = t; b < total; b += kFuseThreads)
+    s_rowi[b] = (uint32_t)batch_row(w, a.batch_key, a.shard_rows, (uint32_t)b);
+  __syncthreads();
+  constexpr int NLAB = LOCAL ? kFuseMaxLocalRows / kFuseThreads : kFuseMaxB / kFuseThreads;
+  int lab[NLAB];
+#pragma unroll
+  for (int u = 0; u < NLAB; ++u)
+    lab[u] = load_global((const int32_t*)a.y + s_rowi[min(t + u * kFuseThreads, total - 1)]);
+  // a tile's loads: thread t takes chunks t % 32 + 32 j of tile row t / 32 (threads past the tile's
+  // rows read its last row again)
+  const int prow = t >> 5, pch = t & 31;
+  float4 pre[LD];
+#define ABS_PREFETCH(base_, nrows_)                                                                          \
+  {                                                                                                          \
+    const uint32_t ri = s_rowi[(base_) + min(prow, (nrows_) - 1)];                                           \
+    const float* src = a.X + (uint64_t)ri * (uint64_t)d + 4 * pch;                                           \
+    _Pragma("unroll") for (int j = 0; j < LD; ++j)                                                           \
+      if (pch + 32 * j < dq) pre[j] = load_global_f4(src + 128 * j);                                         \
+  }
+  ABS_PREFETCH(0, min(TR, B))
+  if (t < 16) s_b[t] = t < C ? bias : 0.f;
+#pragma unroll
+  for (int u = 0; u < NLAB; ++u)
+    if (t + u * kFuseThreads < total) s_lab[t + u * kFuseThreads] = lab[u];
+
+  f32x4_ G[NB];
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
+  float bacc = 0.f, loss = 0.f;
+  // off: the tile's first row in the job's stream of rows; base: the same inside its step
+  for (int off = 0, base = 0; off < total;) {
+    const int nrows = min(TR, B - base);
+    const int noff = off + nrows, nbase = base + nrows == B ? 0 : base + nrows;
+    __syncthreads();                      // the previous tile has been used up
+    if (prow < nrows) {
+#pragma unroll
+      for (int j = 0; j < LD; ++j)
+        if (pch + 32 * j < dq) *(float4*)(s_x + prow * dp + 4 * (pch + 32 * j)) = pre[j];
+    }
+    __syncthreads();
+    if (noff < total) ABS_PREFETCH(noff, min(TR, B - nbase))
+    // (1a) this wavefront's share of the logits: lane (m16, g4) feeds row m16 of x and its own
+    // model elements (class m16) at features 16 blk + 4 g4 .. + 3; two accumulators in turn
+    {
+      f32x4_ z0 = {0.f, 0.f, 0.f, 0.f}, z1 = {0.f, 0.f, 0.f, 0.f};
+      const float* xrow = s_x + m16 * dp;
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const int kk = 16 * (wave + kFuseWaves * bi) + 4 * g4;
+        // no branch but around the last block: a block past d multiplies zeros
+        if (bi < NB - 1 || 16 * (wave + kFuseWaves * bi) < d) {
+          float4 av = *(const float4*)(xrow + kk);     // past d: the pad, the next row, allocated LDS
+          if (kk >= d) av = make_float4(0.f, 0.f, 0.f, 0.f);
+          f32x4_& z = (bi & 1) ? z1 : z0;
+          z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, wreg[bi][0], z, 0, 0, 0);
+          z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, wreg[bi][1], z, 0, 0, 0);
+          z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, wreg[bi][2], z, 0, 0, 0);
+          z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, wreg[bi][3], z, 0, 0, 0);
+        }
+      }
+      // the lane holds rows 4 g4 .. 4 g4 + 3 of column m16
+      float* zp = s_zp + wave * 256 + (4 * g4) * 16 + m16;
+      zp[0] = z0[0] + z1[0]; zp[16] = z0[1] + z1[1]; zp[32] = z0[2] + z1[2]; zp[48] = z0[3] + z1[3];
+    }
+    __syncthreads();
+    // (1b) thread (row t / 16, class t % 16): the logit, softmax over the DPP row, dZ, loss
+    if (wave < TR / 4) {
+      const int r = t >> 4, c = m16;
+      float zz = s_b[c];
+#pragma unroll
+      for (int v = 0; v < kFuseWaves; ++v) zz += s_zp[v * 256 + t];
+      if (c >= C) zz = -INFINITY;
+      const float zmax = row16_max(zz);
+      const float e = c < C ? expf(zz - zmax) : 0.f;
+      const float ssum = row16_sum(e);
+      const bool live = r < nrows;
+      const int label = live ? s_lab[off + r] : -1;
+      const float p = e / ssum;
+      s_dz[t] = live && c < C ? w.c * (p - (c == label ? 1.f : 0.f)) : 0.f;
+      if (c == label) loss += logf(ssum) - (zz - zmax);
+    }
+    __syncthreads();
+    // (2) G += X_tile^T dZ: in step j lane (m16, g4) feeds feature f0 + m16 of tile row 4 g4 + j
+    // and dZ[4 g4 + j][m16].  Features past d read on into allocated LDS (at most 16 NB 8 floats
+    // past a row's start, less than what follows the tile); their gradient elements are never used.
+    {
+      float bq[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bq[j] = s_dz[(4 * g4 + j) * 16 + m16];
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const int blk = wave + kFuseWaves * bi;
+        if (bi < NB - 1 || blk < nstep) {
+          const int f = 16 * blk + m16;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int r = 4 * g4 + j;
+            float xa = s_x[r * dp + f];
+            if (r >= nrows) xa = 0.f;     // rows past the tile hold whatever the last tile left
+            G[bi] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, bq[j], G[bi], 0, 0, 0);
+          }
+        }
+      }
+      if (t < 16) {
+#pragma unroll
+        for (int r = 0; r < TR; ++r) bacc += s_dz[r * 16 + t];
+      }
+    }
+    if (LOCAL && nbase == 0) {
+      // end of a local step (Eq. 2): the step's gradient onto the private model; G[bi][i] and
+      // wreg[bi][i] are the same element (feature 16 blk + 4 g4 + i, class m16)
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        if (16 * (wave + kFuseWaves * bi) + 4 * g4 < d) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) wreg[bi][i] -= G[bi][i];
+        }
+        G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
+      }
+      if (t < 16) { s_b[t] -= bacc; bacc = 0.f; }
+    }
+    off = noff; base = nbase;
+  }
+#undef ABS_PREFETCH
+  // losses sit in the lanes whose class is the row's label: add them up
+  loss = row16_sum(loss);
+  __syncthreads();
+  if (wave < TR / 4 && m16 == 0) s_zp[t >> 4] = loss;      // TR row sums (s_zp is free now)
+  // the upload, staged through LDS in the boundary layout for full-width accesses: the gradient,
+  // or (local steps) the model after the U steps
+  float* s_G = s_x;
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+    const int f0 = 16 * (wave + kFuseWaves * bi) + 4 * g4;
+    if (f0 < d && m16 < C) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s_G[(f0 + i) * C + m16] = LOCAL ? wreg[bi][i] : G[bi][i];
+    }
+  }
+  if (t < C) s_G[d * C + t] = LOCAL ? s_b[t] : bacc;
+  __syncthreads();
+  float* part = a.delta + (size_t)up * a.slot_stride;
+  const int nW4 = (d * C) >> 2;           // d % 4 == 0
+  for (int j = t; j < nW4; j += kFuseThreads) {
+    float4 g = ((const float4*)s_G)[j];
+    if (LOCAL) {                          // what the U steps changed: w^{t,0} - w^{t,U}
+      const float4 w0 = load_global_f4(Wv + 4 * j);
+      g = make_float4(w0.x - g.x, w0.y - g.y, w0.z - g.z, w0.w - g.w);
+    }
+    *(__attribute__((address_space(1))) f32x4_*)(part + 4 * j) = f32x4_{g.x, g.y, g.z, g.w};
+  }
+  if (t < C) part[(size_t)d * C + t] = LOCAL ? load_global(Wv + d * C + t) - s_G[d * C + t] : s_G[d * C + t];
+  if (t == 0) {
+    float l = 0.f;
+#pragma unroll
+    for (int v = 0; v < TR; ++v) l += s_zp[v];
+    a.lossbuf[up] = l / (float)total;
+  }
+}
+
+// TR == kWreg selects the form with the model in registers
+template <int C, int TR, bool LOCAL>
+__device__ __forceinline__ void softmax_upload_any(const RegressionArgs& a, const RoundDesc& rd, int up) {
+  if constexpr (TR == kWreg) softmax_upload_wreg_body<C, LOCAL>(a, rd, up);
+  else softmax_upload_body<C, TR, LOCAL>(a, rd, up);
+}
+
 template <int C, int TR>
-__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_upload_batch_kernel(
+__global__ __launch_bounds__(kFuseThreads, TR == 16 ? 2 : 4) void softmax_upload_batch_kernel(
     const RegressionArgs* as, const char* rds, size_t stride) {
   const RegressionArgs a = as[blockIdx.y];
-  softmax_upload_body<C, TR, false>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), blockIdx.x);
+  softmax_upload_any<C, TR, false>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), blockIdx.x);
 }
 template <int C, int TR>
-__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_local_fused_kernel(RegressionArgs a, RoundDesc rd) {
-  softmax_upload_body<C, TR, true>(a, rd, blockIdx.x);
+__global__ __launch_bounds__(kFuseThreads, TR == 16 ? 2 : 4) void softmax_local_fused_kernel(RegressionArgs a, RoundDesc rd) {
+  softmax_upload_any<C, TR, true>(a, rd, blockIdx.x);
 }
 template <int C, int TR>
-__global__ __launch_bounds__(kFuseThreads, TR == 8 ? 4 : 2) void softmax_local_fused_batch_kernel(
+__global__ __launch_bounds__(kFuseThreads, TR == 16 ? 2 : 4) void softmax_local_fused_batch_kernel(
     const RegressionArgs* as, const char* rds, size_t stride) {
   const RegressionArgs a = as[blockIdx.y];
-  softmax_upload_body<C, TR, true>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), blockIdx.x);
+  softmax_upload_any<C, TR, true>(a, *(const RoundDesc*)(rds + (size_t)blockIdx.y * stride), blockIdx.x);
 }
 
 // Eq. 3 over the uploads' gradients (each already scaled by its c), arrival order
@@ -761,18 +976,26 @@ static hipError_t launch_softmax_local_fused_c(const RegressionArgs* a1, const R
   return hipGetLastError();
 }
 
+// Which form of the fused kernel: the model in registers where d allows it and two workgroups fit a
+// CU; else 8-row tiles if that makes two workgroups fit; else 16-row tiles, one workgroup.
+static int fuse_form(int d, int C, int rows) {
+  if (d <= kWregMaxD && 2 * fuse_lds_bytes(d, C, rows, kWreg) <= kLdsPerCu) return kWreg;
+  return 2 * fuse_lds_bytes(d, C, rows, 8) <= kLdsPerCu ? 8 : 16;
+}
+
 bool softmax_local_fused_ok(int B, int U) { return B <= kFuseMaxB && (long)B * U <= kFuseMaxLocalRows; }
 
 hipError_t launch_softmax_local_fused(const RegressionArgs* a1, const RoundDesc* rd1, const RegressionArgs* d_args,
                                       const char* d_rds, size_t stride, int S, int d, int C, int B, int U, int Kmax,
                                       hipStream_t s) {
   const int rows = B * U;
-  const bool two = 2 * fuse_lds_bytes(d, C, rows, 8) <= kLdsPerCu;      // two workgroups per CU
+  const int form = fuse_form(d, C, rows);
   switch (C) {
 #define ABS_CASE(c)                                                                                              \
   case c:                                                                                                        \
-    return two ? launch_softmax_local_fused_c<c, 8>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s)         \
-               : launch_softmax_local_fused_c<c, 16>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s);
+    return form == kWreg ? launch_softmax_local_fused_c<c, kWreg>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s) \
+           : form == 8   ? launch_softmax_local_fused_c<c, 8>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s)     \
+                         : launch_softmax_local_fused_c<c, 16>(a1, rd1, d_args, d_rds, stride, S, d, rows, Kmax, s);
     ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
     ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
 #undef ABS_CASE
@@ -822,12 +1045,13 @@ hipError_t launch_regression_round_batch(const RegressionArgs* d_args, const cha
     return hipGetLastError();
   }
   if (slots && regression_batch_uses_slots(softmax, B)) {
-    const bool two = 2 * fuse_lds_bytes(d, C, B, 8) <= kLdsPerCu;      // two workgroups per CU
+    const int form = fuse_form(d, C, B);
     switch (C) {
 #define ABS_CASE(c)                                                                                          \
   case c:                                                                                                    \
-    return two ? launch_softmax_fused_batch<c, 8>(d_args, d_rds, stride, S, d, B, Kmax, s)                   \
-               : launch_softmax_fused_batch<c, 16>(d_args, d_rds, stride, S, d, B, Kmax, s);
+    return form == kWreg ? launch_softmax_fused_batch<c, kWreg>(d_args, d_rds, stride, S, d, B, Kmax, s)     \
+           : form == 8   ? launch_softmax_fused_batch<c, 8>(d_args, d_rds, stride, S, d, B, Kmax, s)         \
+                         : launch_softmax_fused_batch<c, 16>(d_args, d_rds, stride, S, d, B, Kmax, s);
       ABS_CASE(2) ABS_CASE(3) ABS_CASE(4) ABS_CASE(5) ABS_CASE(6) ABS_CASE(7) ABS_CASE(8) ABS_CASE(9)
       ABS_CASE(10) ABS_CASE(11) ABS_CASE(12) ABS_CASE(13) ABS_CASE(14) ABS_CASE(15) ABS_CASE(16)
 #undef ABS_CASE
