@@ -379,7 +379,7 @@ constexpr int kFuseThreads = 512, kFuseWaves = 8, kFuseMaxB = 1024, kFuseMaxLoca
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kWreg = 0;                  // in place of TR: 16-row tiles with the model in registers (below)
 constexpr int kWregNB = 7;                // its blocks of 16 features per wavefront
-constexpr int kWregMaxD = 16 * kWregNB * kFuseWaves;
+constexpr int kWregMaxD = 16 * kWregNB * kFuseWaves - 4;     // d + 1 features in its blocks, d % 4 == 0
 typedef float f32x4_ __attribute__((ext_vector_type(4)));
 // loads known to be from global memory (a pointer read from memory is generic to the compiler)
 template <class T>
@@ -420,7 +420,7 @@ __device__ __forceinline__ float row16_max(float v) {
 __host__ __device__ inline int fuse_pitch(int d, int TR) { return TR == 16 ? d + 4 : d + (23 - d % 16) % 16 + 1; }
 // dynamic LDS: x tile and model, partial logits, dZ, bias, then the upload's row indices and labels
 static size_t fuse_lds_bytes(int d, int C, int rows, int TR) {
-  if (TR == kWreg) return ((size_t)16 * (d + 4) + (kFuseWaves + 1) * 256 + 16 + 2 * (size_t)rows) * 4;   // no model
+  if (TR == kWreg) return ((size_t)16 * (d + 4) + (kFuseWaves + 1) * 256 + 2 * (size_t)rows) * 4;   // no model, no bias
   return ((size_t)(TR + C) * fuse_pitch(d, TR) + (kFuseWaves + 1) * TR * 16 + 16 + 2 * (size_t)rows) * 4;
 }
 
@@ -672,50 +672,41 @@ __device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, con
   }
 }
 
-// The same round with the model in registers instead of LDS, for d <= 896: the split of the logits
-// product over the wavefronts is static (wavefront w always takes the blocks of 16 features w,
-// w + 8, ...), so lane (m16, g4) only ever needs W[16 blk + 4 g4 + v][class m16] of its own
+// The same round with the model in registers instead of LDS, for d + 1 <= 896: the split of the
+// logits product over the wavefronts is static (wavefront w always takes the blocks of 16 features
+// w, w + 8, ...), so lane (m16, g4) only ever needs W[16 blk + 4 g4 + v][class m16] of its own
 // blocks - exactly the elements of the gradient it accumulates.  Without the model, a full
 // 16-row tile (no idle half in the logits product) and two workgroups fit a CU's LDS; a local
 // step (Eq. 2) is a subtraction between two sets of registers.
-// Its x tile has pitch d + 4: the 16 rows start 4 banks apart, and rows 4 g4 + j of the gradient
+// The bias is feature d of x~ = [x, 1]: the model's slot holds it right behind W, and the tile's
+// pad column holds the 1, so both products and the local step cover it without extra code.
+// The x tile has pitch d + 4: the 16 rows start 4 banks apart, and rows 4 g4 + j of the gradient
 // product 16 banks apart.
-
 template <int C, bool LOCAL>
 __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a, const RoundDesc& rd, int up) {
   constexpr int TR = 16, NB = kWregNB;
-  constexpr int LD = kWregMaxD / 4 / 32;  // 16-byte chunks per thread and tile: 32 threads per tile row
+  constexpr int LD = 16 * NB * kFuseWaves / 4 / 32;  // 16-byte chunks per thread and tile: 32 threads per tile row
   extern __shared__ __align__(16) float s_mem[];
   if (up >= rd.K) return;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int d = a.d, B = a.B, dq = d >> 2, dp = d + 4;
   const int total = LOCAL ? a.U * B : B;  // rows of the job: draw i of its counter stream is row i
-  float* s_x = s_mem;                     // [16][dp]; at the end the upload in the boundary layout
+  float* s_x = s_mem;                     // [16][dp]; first the model, at the end the upload, boundary layout
   float* s_zp = s_x + TR * dp;            // [8 wavefronts][16 rows][16 classes]
   float* s_dz = s_zp + kFuseWaves * 256;  // [16][16]
-  float* s_b = s_dz + 256;                // [16]
-  uint32_t* s_rowi = (uint32_t*)(s_b + 16);  // [total]
-  int* s_lab = (int*)(s_rowi + total);       // [total]
+  uint32_t* s_rowi = (uint32_t*)(s_dz + 256);  // [total]
+  int* s_lab = (int*)(s_rowi + total);         // [total]
   const WorkerDesc w = rd.w[up];
   const float* Wv = a.ring + (size_t)w.slot * a.slot_stride;
   const int m16 = lane & 15, g4 = lane >> 4;      // the lane's row / column and k index inside a tile
-  const int nstep = (d + 15) >> 4;                // steps of 16 features = blocks of 16 features
+  const int P = (d + 1) * C, nP4 = P >> 2;        // the model with its bias row: (d + 1) x C
 
-  // set-up, its loads all in flight together: the lane's part of the model, then - once the
+  // set-up, its loads all in flight together: the model (needs nothing), then - once the
   // minibatch draws are known - labels and the first tile
-  f32x4_ wreg[NB];
+  float4 wv[4];
 #pragma unroll
-  for (int bi = 0; bi < NB; ++bi) {
-    const int f0 = 16 * (wave + kFuseWaves * bi) + 4 * g4;
-    const bool ok = f0 < d && m16 < C;    // d % 4 == 0: all four features or none
-    const float* src = Wv + (ok ? f0 * C + m16 : 0);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const float x = load_global(src + (ok ? v * C : 0));
-      wreg[bi][v] = ok ? x : 0.f;
-    }
-  }
-  const float bias = load_global(Wv + d * C + min(t, C - 1));
+  for (int u = 0; u < 4; ++u) wv[u] = load_global_f4(Wv + 4 * min(t + u * kFuseThreads, nP4 - 1));
+  const float wtail = load_global(Wv + min(4 * nP4 + t, P - 1));
   for (int b = t; b < total; b += kFuseThreads)
     s_rowi[b] = (uint32_t)batch_row(w, a.batch_key, a.shard_rows, (uint32_t)b);
   __syncthreads();
@@ -736,15 +727,34 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
       if (pch + 32 * j < dq) pre[j] = load_global_f4(src + 128 * j);                                         \
   }
   ABS_PREFETCH(0, min(TR, B))
-  if (t < 16) s_b[t] = t < C ? bias : 0.f;
+  // the model passes through the tile's place in LDS (boundary layout) into the lanes' registers
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (t + u * kFuseThreads < nP4) ((float4*)s_x)[t + u * kFuseThreads] = wv[u];
+  for (int j = t + 4 * kFuseThreads; j < nP4; j += kFuseThreads) ((float4*)s_x)[j] = load_global_f4(Wv + 4 * j);
+  if (4 * nP4 + t < P) s_x[4 * nP4 + t] = wtail;
 #pragma unroll
   for (int u = 0; u < NLAB; ++u)
     if (t + u * kFuseThreads < total) s_lab[t + u * kFuseThreads] = lab[u];
+  __syncthreads();
+  f32x4_ wreg[NB];
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+    const int f0 = 16 * (wave + kFuseWaves * bi) + 4 * g4;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {         // d % 4 == 0: of the bias row's four only the first exists
+      const bool ok = m16 < C && (f0 < d || (f0 == d && v == 0));
+      const float x = s_x[ok ? (f0 + v) * C + m16 : 0];
+      wreg[bi][v] = ok ? x : 0.f;
+    }
+  }
+  __syncthreads();
+  if (t < TR) *(float4*)(s_x + t * dp + d) = make_float4(1.f, 0.f, 0.f, 0.f);   // the 1 of x~; tiles never write here
 
   f32x4_ G[NB];
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
-  float bacc = 0.f, loss = 0.f;
+  float loss = 0.f;
   // off: the tile's first row in the job's stream of rows; base: the same inside its step
   for (int off = 0, base = 0; off < total;) {
     const int nrows = min(TR, B - base);
@@ -757,7 +767,7 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
     }
     __syncthreads();
     if (noff < total) ABS_PREFETCH(noff, min(TR, B - nbase))
-    // (1a) this wavefront's share of the logits: lane (m16, g4) feeds row m16 of x and its own
+    // (1a) this wavefront's share of the logits: lane (m16, g4) feeds row m16 of x~ and its own
     // model elements (class m16) at features 16 blk + 4 g4 .. + 3; two accumulators in turn
     {
       f32x4_ z0 = {0.f, 0.f, 0.f, 0.f}, z1 = {0.f, 0.f, 0.f, 0.f};
@@ -766,9 +776,9 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
       for (int bi = 0; bi < NB; ++bi) {
         const int kk = 16 * (wave + kFuseWaves * bi) + 4 * g4;
         // no branch but around the last block: a block past d multiplies zeros
-        if (bi < NB - 1 || 16 * (wave + kFuseWaves * bi) < d) {
-          float4 av = *(const float4*)(xrow + kk);     // past d: the pad, the next row, allocated LDS
-          if (kk >= d) av = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (bi < NB - 1 || 16 * (wave + kFuseWaves * bi) <= d) {
+          float4 av = *(const float4*)(xrow + kk);     // past d + 3: the next row, allocated LDS
+          if (kk > d) av = make_float4(0.f, 0.f, 0.f, 0.f);
           f32x4_& z = (bi & 1) ? z1 : z0;
           z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, wreg[bi][0], z, 0, 0, 0);
           z = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, wreg[bi][1], z, 0, 0, 0);
@@ -784,9 +794,9 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
     // (1b) thread (row t / 16, class t % 16): the logit, softmax over the DPP row, dZ, loss
     if (wave < TR / 4) {
       const int r = t >> 4, c = m16;
-      float zz = s_b[c];
+      float zz = s_zp[t];
 #pragma unroll
-      for (int v = 0; v < kFuseWaves; ++v) zz += s_zp[v * 256 + t];
+      for (int v = 1; v < kFuseWaves; ++v) zz += s_zp[v * 256 + t];
       if (c >= C) zz = -INFINITY;
       const float zmax = row16_max(zz);
       const float e = c < C ? expf(zz - zmax) : 0.f;
@@ -798,8 +808,8 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
       if (c == label) loss += logf(ssum) - (zz - zmax);
     }
     __syncthreads();
-    // (2) G += X_tile^T dZ: in step j lane (m16, g4) feeds feature f0 + m16 of tile row 4 g4 + j
-    // and dZ[4 g4 + j][m16].  Features past d read on into allocated LDS (at most 16 NB 8 floats
+    // (2) G += X~_tile^T dZ: in step j lane (m16, g4) feeds feature f0 + m16 of tile row 4 g4 + j
+    // and dZ[4 g4 + j][m16].  Features past d + 3 read on into allocated LDS (at most 16 NB 8 floats
     // past a row's start, less than what follows the tile); their gradient elements are never used.
     {
       float bq[4];
@@ -808,7 +818,7 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
         const int blk = wave + kFuseWaves * bi;
-        if (bi < NB - 1 || blk < nstep) {
+        if (bi < NB - 1 || 16 * blk <= d) {
           const int f = 16 * blk + m16;
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -819,23 +829,18 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
           }
         }
       }
-      if (t < 16) {
-#pragma unroll
-        for (int r = 0; r < TR; ++r) bacc += s_dz[r * 16 + t];
-      }
     }
     if (LOCAL && nbase == 0) {
       // end of a local step (Eq. 2): the step's gradient onto the private model; G[bi][i] and
       // wreg[bi][i] are the same element (feature 16 blk + 4 g4 + i, class m16)
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
-        if (16 * (wave + kFuseWaves * bi) + 4 * g4 < d) {
+        if (16 * (wave + kFuseWaves * bi) + 4 * g4 <= d) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) wreg[bi][i] -= G[bi][i];
         }
         G[bi] = f32x4_{0.f, 0.f, 0.f, 0.f};
       }
-      if (t < 16) { s_b[t] -= bacc; bacc = 0.f; }
     }
     off = noff; base = nbase;
   }
@@ -850,16 +855,15 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) {
     const int f0 = 16 * (wave + kFuseWaves * bi) + 4 * g4;
-    if (f0 < d && m16 < C) {
+    if (m16 < C) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s_G[(f0 + i) * C + m16] = LOCAL ? wreg[bi][i] : G[bi][i];
+      for (int i = 0; i < 4; ++i)
+        if (f0 < d || (f0 == d && i == 0)) s_G[(f0 + i) * C + m16] = LOCAL ? wreg[bi][i] : G[bi][i];
     }
   }
-  if (t < C) s_G[d * C + t] = LOCAL ? s_b[t] : bacc;
   __syncthreads();
   float* part = a.delta + (size_t)up * a.slot_stride;
-  const int nW4 = (d * C) >> 2;           // d % 4 == 0
-  for (int j = t; j < nW4; j += kFuseThreads) {
+  for (int j = t; j < nP4; j += kFuseThreads) {
     float4 g = ((const float4*)s_G)[j];
     if (LOCAL) {                          // what the U steps changed: w^{t,0} - w^{t,U}
       const float4 w0 = load_global_f4(Wv + 4 * j);
@@ -867,7 +871,7 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
     }
     *(__attribute__((address_space(1))) f32x4_*)(part + 4 * j) = f32x4_{g.x, g.y, g.z, g.w};
   }
-  if (t < C) part[(size_t)d * C + t] = LOCAL ? load_global(Wv + d * C + t) - s_G[d * C + t] : s_G[d * C + t];
+  if (4 * nP4 + t < P) part[4 * nP4 + t] = LOCAL ? wtail - s_G[4 * nP4 + t] : s_G[4 * nP4 + t];
   if (t == 0) {
     float l = 0.f;
 #pragma unroll
