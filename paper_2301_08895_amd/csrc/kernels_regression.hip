@@ -381,6 +381,7 @@ constexpr int kWreg = 0;                  // in place of TR: 16-row tiles with t
 constexpr int kWregNB = 7;                // its blocks of 16 features per wavefront
 constexpr int kWregMaxD = 16 * kWregNB * kFuseWaves - 4;     // d + 1 features in its blocks, d % 4 == 0
 typedef float f32x4_ __attribute__((ext_vector_type(4)));
+typedef float f32x2_ __attribute__((ext_vector_type(2)));
 // loads known to be from global memory (a pointer read from memory is generic to the compiler)
 template <class T>
 __device__ __forceinline__ T load_global(const T* p) { return *(const __attribute__((address_space(1))) T*)p; }
@@ -790,21 +791,32 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
       float* zp = s_zp + wave * 256 + (4 * g4) * 16 + m16;
       zp[0] = z0[0] + z1[0]; zp[16] = z0[1] + z1[1]; zp[32] = z0[2] + z1[2]; zp[48] = z0[3] + z1[3];
     }
+    // the row's label, fetched ahead of the barrier (thread (row t / 16, class t % 16) of (1b))
+    const int label = wave < TR / 4 && (t >> 4) < nrows ? s_lab[off + (t >> 4)] : -1;
     __syncthreads();
     // (1b) thread (row t / 16, class t % 16): the logit, softmax over the DPP row, dZ, loss
     if (wave < TR / 4) {
-      const int r = t >> 4, c = m16;
-      float zz = s_zp[t];
-#pragma unroll
-      for (int v = 1; v < kFuseWaves; ++v) zz += s_zp[v * 256 + t];
+      const int c = m16;
+      // the eight partial logits, all requests in flight before the first addition (the compiler
+      // would wait for each pair in turn)
+      static_assert(kFuseWaves == 8, "eight partial tiles");
+      f32x2_ q0, q1, q2, q3;
+      asm volatile(
+          "ds_read2st64_b32 %0, %4 offset1:4\n\t"
+          "ds_read2st64_b32 %1, %4 offset0:8 offset1:12\n\t"
+          "ds_read2st64_b32 %2, %4 offset0:16 offset1:20\n\t"
+          "ds_read2st64_b32 %3, %4 offset0:24 offset1:28\n\t"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(q0), "=&v"(q1), "=&v"(q2), "=&v"(q3)
+          : "v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(s_zp + t))
+          : "memory");
+      float zz = ((((((q0.x + q0.y) + q1.x) + q1.y) + q2.x) + q2.y) + q3.x) + q3.y;
       if (c >= C) zz = -INFINITY;
       const float zmax = row16_max(zz);
       const float e = c < C ? expf(zz - zmax) : 0.f;
       const float ssum = row16_sum(e);
-      const bool live = r < nrows;
-      const int label = live ? s_lab[off + r] : -1;
       const float p = e / ssum;
-      s_dz[t] = live && c < C ? w.c * (p - (c == label ? 1.f : 0.f)) : 0.f;
+      s_dz[t] = (t >> 4) < nrows && c < C ? w.c * (p - (c == label ? 1.f : 0.f)) : 0.f;
       if (c == label) loss += logf(ssum) - (zz - zmax);
     }
     __syncthreads();
