@@ -702,8 +702,9 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
   const int m16 = lane & 15, g4 = lane >> 4;      // the lane's row / column and k index inside a tile
   const int P = (d + 1) * C, nP4 = P >> 2;        // the model with its bias row: (d + 1) x C
 
-  // set-up, its loads all in flight together: the model (needs nothing), then - once the
-  // minibatch draws are known - labels and the first tile
+  // set-up: the model is asked for first and has arrived by the time the minibatch draws are
+  // known; it passes through the tile's place in LDS (boundary layout) into the lanes' registers
+  // while the labels and the first tile are on their way
   float4 wv[4];
 #pragma unroll
   for (int u = 0; u < 4; ++u) wv[u] = load_global_f4(Wv + 4 * min(t + u * kFuseThreads, nP4 - 1));
@@ -711,6 +712,11 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
   for (int b = t; b < total; b += kFuseThreads)
     s_rowi[b] = (uint32_t)batch_row(w, a.batch_key, a.shard_rows, (uint32_t)b);
   __syncthreads();
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (t + u * kFuseThreads < nP4) ((float4*)s_x)[t + u * kFuseThreads] = wv[u];
+  for (int j = t + 4 * kFuseThreads; j < nP4; j += kFuseThreads) ((float4*)s_x)[j] = load_global_f4(Wv + 4 * j);
+  if (4 * nP4 + t < P) s_x[4 * nP4 + t] = wtail;
   constexpr int NLAB = LOCAL ? kFuseMaxLocalRows / kFuseThreads : kFuseMaxB / kFuseThreads;
   int lab[NLAB];
 #pragma unroll
@@ -728,15 +734,6 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
       if (pch + 32 * j < dq) pre[j] = load_global_f4(src + 128 * j);                                         \
   }
   ABS_PREFETCH(0, min(TR, B))
-  // the model passes through the tile's place in LDS (boundary layout) into the lanes' registers
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (t + u * kFuseThreads < nP4) ((float4*)s_x)[t + u * kFuseThreads] = wv[u];
-  for (int j = t + 4 * kFuseThreads; j < nP4; j += kFuseThreads) ((float4*)s_x)[j] = load_global_f4(Wv + 4 * j);
-  if (4 * nP4 + t < P) s_x[4 * nP4 + t] = wtail;
-#pragma unroll
-  for (int u = 0; u < NLAB; ++u)
-    if (t + u * kFuseThreads < total) s_lab[t + u * kFuseThreads] = lab[u];
   __syncthreads();
   f32x4_ wreg[NB];
 #pragma unroll
@@ -751,6 +748,9 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
   }
   __syncthreads();
   if (t < TR) *(float4*)(s_x + t * dp + d) = make_float4(1.f, 0.f, 0.f, 0.f);   // the 1 of x~; tiles never write here
+#pragma unroll
+  for (int u = 0; u < NLAB; ++u)
+    if (t + u * kFuseThreads < total) s_lab[t + u * kFuseThreads] = lab[u];
 
   f32x4_ G[NB];
 #pragma unroll
