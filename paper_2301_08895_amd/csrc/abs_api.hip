@@ -370,7 +370,9 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
 // ---- batched simulations: S handles of one shape advance together, one set of launches per round
 struct abs_batch {
   std::vector<abs_ctx*> ctx;
-  hipStream_t stream = nullptr;
+  hipStream_t stream = nullptr;            // the handles' stream
+  hipStream_t stream2 = nullptr;           // the library's own, for the second group of a large batch
+  hipEvent_t ev_in = nullptr, ev_out = nullptr;   // order stream2 after / before the handles' stream
   RegressionArgs* d_args = nullptr;        // device [S]
   char* h_rds[2] = {nullptr, nullptr};     // pinned host, S descriptors, alternating by round
   char* d_rds[2] = {nullptr, nullptr};     // device copies
@@ -386,6 +388,9 @@ namespace { thread_local std::string g_batch_error; }
 void abs_batch_destroy(abs_batch* b) {
   if (!b) return;
   if (b->stream || !b->ctx.empty()) (void)hipStreamSynchronize(b->stream);
+  if (b->stream2) { (void)hipStreamSynchronize(b->stream2); (void)hipStreamDestroy(b->stream2); }
+  if (b->ev_in) (void)hipEventDestroy(b->ev_in);
+  if (b->ev_out) (void)hipEventDestroy(b->ev_out);
   if (b->d_args) (void)hipFree(b->d_args);
   for (int i = 0; i < 2; ++i) {
     if (b->h_rds[i]) (void)hipHostFree(b->h_rds[i]);
@@ -423,6 +428,9 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
     return false;
   };
   if (!hip(hipMalloc((void**)&b->d_args, (size_t)n * sizeof(RegressionArgs)), "hipMalloc")) return ABS_E_HIP;
+  if (!hip(hipStreamCreateWithFlags(&b->stream2, hipStreamNonBlocking), "hipStreamCreateWithFlags")) return ABS_E_HIP;
+  if (!hip(hipEventCreateWithFlags(&b->ev_in, hipEventDisableTiming), "hipEventCreateWithFlags")) return ABS_E_HIP;
+  if (!hip(hipEventCreateWithFlags(&b->ev_out, hipEventDisableTiming), "hipEventCreateWithFlags")) return ABS_E_HIP;
   for (int i = 0; i < 2; ++i) {
     if (!hip(hipHostMalloc((void**)&b->h_rds[i], (size_t)n * b->rd_stride, hipHostMallocDefault), "hipHostMalloc")) return ABS_E_HIP;
     if (!hip(hipMalloc((void**)&b->d_rds[i], (size_t)n * b->rd_stride), "hipMalloc")) return ABS_E_HIP;
@@ -471,7 +479,8 @@ struct BatchRoundState {
   // Thread 0, now and then while mailboxes are awaited: has the stream failed?  (A stream that has
   // drained has written every mailbox, so only a runtime error ends the wait.)
   bool stream_failed() {
-    const hipError_t q = hipStreamQuery(b->stream);
+    hipError_t q = hipStreamQuery(b->stream);
+    if (q == hipSuccess || q == hipErrorNotReady) q = hipStreamQuery(b->stream2);
     if (q == hipSuccess || q == hipErrorNotReady) return false;
     b->err = std::string("hipStreamQuery: ") + hipGetErrorString(q);
     rc[0] = ABS_E_HIP; bad_sim[0] = -1;
@@ -568,9 +577,18 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   // selection wait for its own losses, not for the other group's).
   // A linear round is one workgroup per simulation and lasts as long for 32 of them as for 256:
   // halves only pay from two workgroups per CU on.
+  // The second group's copies and kernels go to a stream of their own (ordered after what the
+  // handles' stream held at entry, and before what it gets after the call), so that the device
+  // fills the tail of one group's kernel with the head of the other's.
   const bool softmax = c0.model == ABS_MODEL_SOFTMAX;
   const int G = S >= (softmax ? 64 : 512) ? 2 : 1;
   const int lo[2] = {0, S / 2}, hi[2] = {G == 2 ? S / 2 : S, S};
+  const hipStream_t gstream[2] = {b->stream, b->stream2};
+  if (G == 2 && n_rounds > 0) {
+    hipError_t e = hipEventRecord(b->ev_in, b->stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(b->stream2, b->ev_in, 0);
+    if (e != hipSuccess) { b->err = std::string("hipStreamWaitEvent: ") + hipGetErrorString(e); return ABS_E_HIP; }
+  }
   bool inflight[2] = {false, false};
   auto finish = [&](int g) {
     inflight[g] = false;
@@ -582,13 +600,13 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
     int Kmax = 0;
     for (int k = 0; k < st.T; ++k) Kmax = std::max(Kmax, st.kmax[(size_t)k]);
     const size_t off = (size_t)lo[g] * b->rd_stride, n = (size_t)(hi[g] - lo[g]);
-    hipError_t e = hipMemcpyAsync(b->d_rds[st.buf] + off, b->h_rds[st.buf] + off, n * b->rd_stride, hipMemcpyHostToDevice, b->stream);
+    hipError_t e = hipMemcpyAsync(b->d_rds[st.buf] + off, b->h_rds[st.buf] + off, n * b->rd_stride, hipMemcpyHostToDevice, gstream[g]);
     if (e == hipSuccess && c0.U > 1)
       e = launch_regression_local_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
-                                              c0.dims[0], c0.dims[1], c0.B, c0.U, Kmax, b->stream);
+                                              c0.dims[0], c0.dims[1], c0.B, c0.U, Kmax, gstream[g]);
     else if (e == hipSuccess)
       e = launch_regression_round_batch(b->d_args + lo[g], b->d_rds[st.buf] + off, b->rd_stride, (int)n, softmax,
-                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->d_slots != nullptr, b->stream);
+                                        c0.dims[0], c0.dims[1], c0.B, Kmax, b->d_slots != nullptr, gstream[g]);
     if (e != hipSuccess) { b->err = std::string("launch: ") + hipGetErrorString(e); return (int)ABS_E_HIP; }
     inflight[g] = true;
     return (int)ABS_OK;
@@ -613,6 +631,11 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   st.kind = -1;
   st.phase.fetch_add(1, std::memory_order_release);
   for (std::thread& t : pool) t.join();
+  if (G == 2 && n_rounds > 0) {
+    hipError_t e = hipEventRecord(b->ev_out, b->stream2);
+    if (e == hipSuccess) e = hipStreamWaitEvent(b->stream, b->ev_out, 0);
+    if (e != hipSuccess && rc == ABS_OK) { b->err = std::string("hipStreamWaitEvent: ") + hipGetErrorString(e); rc = ABS_E_HIP; }
+  }
   return rc;
 }
 
