@@ -219,14 +219,18 @@ void abs_destroy(abs_ctx* ctx);
  *                     sums the uploads, another rounding order than abs_round's, so models agree
  *                     with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5 that
  *                     hangs on the last bit of a loss may differ).
- *                     Large batches (softmax: 64 simulations and more, linear: 512 and more)
- *                     advance as two halves, half a round apart, so that the host's part of one
- *                     overlaps the device's part of the other; at return every simulation has
- *                     done its n_rounds.  On an error of one simulation the call stops and names
- *                     it; rounds already on the device are completed first, so the other
- *                     simulations end on that round, the one before or (the other half) the one
- *                     after: abs_rounds_done tells.  A handle that did not complete a round
- *                     repeats it, with the same result, the next time it is advanced.
+ *                     Large batches (softmax: 16 simulations and more, linear: 512 and more)
+ *                     advance as two to four groups, staggered in time, so that the host's part
+ *                     of one overlaps the device's part of the others; the first group's work
+ *                     goes to the handles' stream, the others' to streams the batch owns, which
+ *                     start after everything the handles' stream held at the call and which
+ *                     that stream waits for before it runs anything enqueued after the call.
+ *                     At return every simulation has done its n_rounds.  On an error of one
+ *                     simulation the call stops and names it; rounds already on the device are
+ *                     completed first, so the other simulations end on that round, the one
+ *                     before or (another group) the one after: abs_rounds_done tells.  A
+ *                     handle that did not complete a round repeats it, with the same result,
+ *                     the next time it is advanced.
  *  abs_batch_last_error  text of the last error (b == NULL: of the last failed abs_batch_create
  *                     on this thread).
  */

@@ -91,16 +91,25 @@ def test_softmax_batch():
     _run(workloads.scaled_preset(2, M=6000), 6, 40, 1e-5, 1e-4, bitwise_alone=False)
     _run(workloads.scaled_preset(2, M=4000, dims=[52, 3], n_classes=3, N=6, B=10, K0=2, tau_cap=2, lr=5e-3), 9, 50,
          1e-5, 1e-4, bitwise_alone=False)
-    # 16 classes and 1024 features (16-row tiles), a ragged last tile; 8 features (fewer chunks than lanes)
+    # the widest model the register-resident form takes (all 56 blocks of 16 features in use)
+    _run(workloads.scaled_preset(2, M=3000, dims=[892, 10], N=5, B=37, lr=2e-4), 3, 10, 1e-5, 1e-4,
+         oracle_for=(0,), bitwise_alone=False)
+    # wider ones keep the model in LDS: 8-row tiles with two workgroups per CU (1000 x 4) ...
+    _run(workloads.scaled_preset(2, M=3000, dims=[1000, 4], n_classes=4, N=4, B=21, lr=2e-4), 3, 10, 1e-5, 1e-4,
+         oracle_for=(0,), bitwise_alone=False)
+    # ... or 16-row tiles (16 classes and 1024 features), a ragged last tile; 8 features (fewer chunks than lanes)
     _run(workloads.scaled_preset(2, M=4000, dims=[1024, 16], n_classes=16, N=4, B=70, lr=2e-4), 3, 12, 1e-5, 1e-4,
          oracle_for=(0,), bitwise_alone=False)
     _run(workloads.scaled_preset(2, M=2000, dims=[8, 2], n_classes=2, N=16, B=5, lr=2e-2), 20, 30, 1e-5, 1e-4,
          oracle_for=(0,), bitwise_alone=False)
 
 
-def test_batches_that_advance_as_two_halves():
-    """Large batches run as two groups half a round apart (softmax from 64 simulations, linear from
-    512): results must not change, also when a call is split in two."""
+def test_batches_that_advance_as_groups():
+    """Large batches run as two to four groups staggered in time, each on its own stream (softmax:
+    two from 16 simulations, three from 64, four from 128; linear: two from 512): results must not
+    change, also when a call is split in two."""
+    _run(workloads.scaled_preset(2, M=2000, dims=[20, 4], n_classes=4, N=5, B=17, K0=2, lr=1e-2), 131, 14, 1e-5, 1e-4,
+         oracle_for=(0, 130), bitwise_alone=False)
     _run(workloads.scaled_preset(2, M=2000, dims=[12, 3], n_classes=3, N=6, B=9, K0=2, lr=1e-2), 67, 21, 1e-5, 1e-4,
          oracle_for=(0, 66), bitwise_alone=False)
     _run(workloads.scaled_preset(1, M=2000, dims=[20, 1], N=5, B=6, K0=2), 515, 11, 1e-5, 1e-4, oracle_for=(0, 514))
@@ -108,7 +117,7 @@ def test_batches_that_advance_as_two_halves():
 
 def test_local_sgd_batches():
     """U > 1 in batched rounds: the local-SGD kernels with one column of workgroups per simulation,
-    bitwise the unbatched rounds (also as two halves)."""
+    bitwise the unbatched rounds (also as groups)."""
     _run(workloads.scaled_preset(1, M=3000, dims=[40, 1], N=6, B=8, K0=2, U=3), 9, 30, 1e-5, 1e-4)
     _run(workloads.scaled_preset(2, M=3000, dims=[24, 5], n_classes=5, N=7, B=6, K0=3, U=4, lr=1e-2), 66, 16,
          1e-5, 1e-4, oracle_for=(0, 65))
