@@ -219,7 +219,7 @@ void abs_destroy(abs_ctx* ctx);
  *                     sums the uploads, another rounding order than abs_round's, so models agree
  *                     with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5 that
  *                     hangs on the last bit of a loss may differ).
- *                     Large batches (softmax: 16 simulations and more, linear: 512 and more)
+ *                     Large batches (softmax: 16 simulations and more, linear: 256 and more)
  *                     advance as two to four groups, staggered in time, so that the host's part
  *                     of one overlaps the device's part of the others; the first group's work
  *                     goes to the handles' stream, the others' to streams the batch owns, which
