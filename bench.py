@@ -140,15 +140,12 @@ def _flops_at_full_k(p, kind):
 
 
 def bench_batch(args, p, inputs, warmup, steps):
-    """S independent simulations (different simulation seeds) of a regression workload, advanced
-    together by abs_batch_round: the sweep shape of the paper's experiments."""
+    """S independent simulations (different simulation seeds) of a workload, advanced together by
+    abs_batch_round: the sweep shape of the paper's experiments."""
     import numpy as np
     import torch
     import paper_2301_08895_amd as lib
 
-    if p["model"] == 2:
-        print("bench.py: --batch is for the regression workloads (configs 1 and 2)", file=sys.stderr)
-        sys.exit(2)
     S = args.batch
     sims = [lib.Simulation(dict(p, seed_sim=p["seed_sim"] + 7919 * i), inputs) for i in range(S)]
     batch = lib.Batch(sims)
@@ -167,21 +164,30 @@ def bench_batch(args, p, inputs, warmup, steps):
     for sim in sims:
         sim.close()
     value = grads / elapsed
-    d = p["dims"][0]
-    # algorithmic bytes: every aggregated gradient reads B rows of d features and B targets once
-    ach = grads * p["B"] * (d + 1) * 4.0 / elapsed / 1e9
+    mlp = p["model"] == 2
+    if mlp:
+        # algorithmic flops of a worker gradient: forward and weight gradient of every layer, input
+        # gradient of every layer but the first
+        dm = p["dims"]
+        per = sum((2 if l == 0 else 3) * 2.0 * p["B"] * dm[l] * dm[l + 1] for l in range(len(dm) - 1))
+        roof = {"bound": "mfma", "kernel": "whole round (all launches and the host, wall clock)",
+                "achieved": grads * per / elapsed / 1e12, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": grads * per / elapsed / 1e12 / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
+    else:
+        # algorithmic bytes: every aggregated gradient reads B rows of d features and B targets once
+        ach = grads * p["B"] * (p["dims"][0] + 1) * 4.0 / elapsed / 1e9
+        roof = {"bound": "hbm", "kernel": "whole round (all launches and the host, wall clock)",
+                "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None}
     cpu = cpu_baseline(p, inputs, args.cpu_budget) if args.cpu_budget > 0 else None
     print(json.dumps({
         "metric": "worker_gradients_per_sec", "value": value, "unit": "worker-gradients/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if mlp else "f32", "data": "synthetic",
         "config": {"workload": f"{p['name']}_x{S}_simulations", "N": p["N"], "B": p["B"], "dims": p["dims"],
                    "K0": p["K0"], "tau_cap": p["tau_cap"], "a": p["a"], "lr": p["lr"], "U": p.get("U", 1),
                    "simulations": S},
         "samples_per_sec": value * p["B"], "rounds_per_sec": steps * S / elapsed,
-        "roofline": {"bound": "hbm", "kernel": "whole round (all launches and the host, wall clock)",
-                     "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                     "traffic": None},
+        "roofline": roof,
         "cpu_baseline": cpu,
     }))
 

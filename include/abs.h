@@ -204,11 +204,11 @@ void abs_destroy(abs_ctx* ctx);
 /*
  * Batched simulations.  The paper's results are sweeps over seeds and hyper-parameters (a, K^0,
  * the step size; Section V), and a single round of the small workloads is too little work for
- * one launch: a batch advances n simulations of one shape together, every round of all of them
- * in one set of launches (one workgroup column per simulation).
- *  abs_batch_create   ctxs: n handles (1 <= n <= 4096) created with the same model (linear or
- *                     softmax), dims, N, B, U and stream, profile = 0; seeds, K0, a, tau
- *                     settings, step sizes, time models and datasets may differ.  The batch
+ * one launch: a batch advances n simulations of one shape together, for the regression models
+ * every round of all of them in one set of launches (one workgroup column per simulation).
+ *  abs_batch_create   ctxs: n handles (1 <= n <= 4096) created with the same model, dims, N, B, U
+ *                     and stream, profile = 0; seeds, K0, a, tau settings, step sizes, time
+ *                     models and datasets may differ.  The batch
  *                     borrows the handles: they must outlive it, and stay usable on their own
  *                     (abs_get_model, abs_trace, abs_evaluate, abs_round) between batch calls.
  *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
@@ -218,7 +218,11 @@ void abs_destroy(abs_ctx* ctx);
  *                     B <= 1024: the batched round adds up each upload's gradient before Eq. 3
  *                     sums the uploads, another rounding order than abs_round's, so models agree
  *                     with abs_round to fp32 rounding (and an adaptive-K decision of Eq. 5 that
- *                     hangs on the last bit of a loss may differ).
+ *                     hangs on the last bit of a loss may differ).  MLP model: every simulation
+ *                     keeps its own launches (a round of it is a chain of kernels, not one);
+ *                     up to four of them run side by side, each on a stream and a host thread
+ *                     of its own, bitwise the result of abs_round, and an error of one does not
+ *                     stop the others (the first failing simulation is the one reported).
  *                     Large batches (softmax: 16 simulations and more, linear: 256 and more)
  *                     advance as two to four groups, staggered in time, so that the host's part
  *                     of one overlaps the device's part of the others; the first group's work

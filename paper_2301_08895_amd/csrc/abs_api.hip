@@ -413,7 +413,6 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
     if (!c) return bad("NULL handle in the batch");
     for (int32_t j = 0; j < i; ++j) if (ctxs[j] == c) return bad("a handle appears twice in the batch");
     if (!c->cfg.device_mode) return bad("schedule-only handles cannot be batched");
-    if (c->cfg.model == ABS_MODEL_MLP) return bad("MLP rounds fill the GPU on their own: batches are for the regression models");
     if (c->cfg.profile) return bad("batched rounds are not profiled per kernel (profile must be 0)");
     if (c->cfg.model != c0->cfg.model || c->cfg.dims[0] != c0->cfg.dims[0] || c->cfg.dims[1] != c0->cfg.dims[1] ||
         c->cfg.B != c0->cfg.B || c->cfg.N != c0->cfg.N || c->cfg.U != c0->cfg.U || c->stream != c0->stream)
@@ -428,12 +427,15 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
     g_batch_error = std::string(what) + ": " + hipGetErrorString(e);
     return false;
   };
-  if (!hip(hipMalloc((void**)&b->d_args, (size_t)n * sizeof(RegressionArgs)), "hipMalloc")) return ABS_E_HIP;
   if (!hip(hipEventCreateWithFlags(&b->ev_in, hipEventDisableTiming), "hipEventCreateWithFlags")) return ABS_E_HIP;
   for (int i = 0; i < kBatchGroups - 1; ++i) {
     if (!hip(hipStreamCreateWithFlags(&b->own[i], hipStreamNonBlocking), "hipStreamCreateWithFlags")) return ABS_E_HIP;
     if (!hip(hipEventCreateWithFlags(&b->ev_out[i], hipEventDisableTiming), "hipEventCreateWithFlags")) return ABS_E_HIP;
   }
+  // MLP simulations keep their own launches, workspaces and mailboxes: the batch only runs them
+  // side by side (abs_batch_round)
+  if (c0->cfg.model == ABS_MODEL_MLP) { *out = b.release(); return ABS_OK; }
+  if (!hip(hipMalloc((void**)&b->d_args, (size_t)n * sizeof(RegressionArgs)), "hipMalloc")) return ABS_E_HIP;
   for (int i = 0; i < 2; ++i) {
     if (!hip(hipHostMalloc((void**)&b->h_rds[i], (size_t)n * b->rd_stride, hipHostMallocDefault), "hipHostMalloc")) return ABS_E_HIP;
     if (!hip(hipMalloc((void**)&b->d_rds[i], (size_t)n * b->rd_stride), "hipMalloc")) return ABS_E_HIP;
@@ -561,10 +563,49 @@ struct BatchRoundState {
 };
 }  // namespace
 
+// MLP simulations of a batch: a round of one is a chain of launches that leaves much of the device
+// idle unless the layers are wide (3072-512-10: one workgroup per CU in its largest product), so up
+// to kBatchGroups simulations run side by side, each through abs_round on a stream of its own and a
+// host thread of its own; further simulations follow on the stream that gets free.
+static int batch_round_mlp(abs_batch* b, int32_t n_rounds) {
+  const int S = (int)b->ctx.size(), T = std::min(S, kBatchGroups);
+  hipError_t e = T > 1 ? hipEventRecord(b->ev_in, b->stream) : hipSuccess;
+  for (int k = 1; k < T && e == hipSuccess; ++k) e = hipStreamWaitEvent(b->own[k - 1], b->ev_in, 0);
+  if (e != hipSuccess) { b->err = std::string("hipStreamWaitEvent: ") + hipGetErrorString(e); return ABS_E_HIP; }
+  std::vector<int> rc((size_t)S, ABS_OK);
+  auto work = [&](int k) {
+    const hipStream_t s = k == 0 ? b->stream : b->own[k - 1];
+    for (int i = k; i < S; i += T) {
+      abs_ctx* c = b->ctx[(size_t)i];
+      const hipStream_t keep = c->stream;
+      c->stream = s;
+      rc[(size_t)i] = abs_round(c, n_rounds);
+      c->stream = keep;
+    }
+  };
+  std::vector<std::thread> pool;
+  for (int k = 1; k < T; ++k) pool.emplace_back(work, k);
+  work(0);
+  for (std::thread& t : pool) t.join();
+  for (int k = 1; k < T && e == hipSuccess; ++k) {
+    e = hipEventRecord(b->ev_out[k - 1], b->own[k - 1]);
+    if (e == hipSuccess) e = hipStreamWaitEvent(b->stream, b->ev_out[k - 1], 0);
+  }
+  for (int i = 0; i < S; ++i)
+    if (rc[(size_t)i] != ABS_OK) {
+      b->err = "simulation " + std::to_string(i) + ": " + b->ctx[(size_t)i]->err;
+      return rc[(size_t)i];
+    }
+  if (e != hipSuccess) { b->err = std::string("hipStreamWaitEvent: ") + hipGetErrorString(e); return ABS_E_HIP; }
+  b->rounds += (uint64_t)n_rounds;
+  return ABS_OK;
+}
+
 int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   if (!b || n_rounds < 0) return ABS_E_ARG;
   const int S = (int)b->ctx.size();
   const abs_config& c0 = b->ctx[0]->cfg;
+  if (c0.model == ABS_MODEL_MLP) return batch_round_mlp(b, n_rounds);
   BatchRoundState st;
   st.b = b;
   st.S = S;

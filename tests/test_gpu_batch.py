@@ -135,7 +135,7 @@ def test_softmax_batch_of_long_minibatches():
          oracle_for=(0,))
 
 
-def test_batch_rejects_mixed_shapes_and_mlp():
+def test_batch_rejects_mixed_shapes_and_models():
     d1 = workloads.make_inputs(workloads.scaled_preset(1, M=2000))
     a = lib.Simulation(workloads.scaled_preset(1, M=2000), d1)
     p2 = workloads.scaled_preset(1, M=2000, B=16)
@@ -147,9 +147,39 @@ def test_batch_rejects_mixed_shapes_and_mlp():
     pm = workloads.scaled_preset(3, M=2048, dims=[128, 64, 10], N=4, B=32, n_slow=1)
     m = lib.Simulation(pm, workloads.make_inputs(pm))
     with pytest.raises(lib.AbsError):
-        lib.Batch([m])
+        lib.Batch([a, m])                      # one model kind per batch
     for s in (a, b, m):
         s.close()
+
+
+def test_mlp_batch():
+    """MLP simulations of a batch run side by side, each through its own rounds on a stream of the
+    batch: bitwise the unbatched runs, also with more simulations than streams and over two calls."""
+    base = workloads.scaled_preset(3, M=4096, dims=[256, 128, 10], N=6, B=32, n_slow=1, K0=2, tau_cap=3)
+    d = workloads.make_inputs(base)
+    S, T = 6, 14
+    ps = [dict(base, seed_sim=base["seed_sim"] + 101 * i, lr=base["lr"] * (1 + 0.25 * (i % 3)), sa_penalty=i % 2)
+          for i in range(S)]
+    sims = [lib.Simulation(p, d) for p in ps]
+    batch = lib.Batch(sims)
+    batch.round(T // 2)
+    mid = [s.model().copy() for s in sims]
+    batch.round(T - T // 2)
+    got = [(s.model().copy(), s.trace().copy()) for s in sims]
+    batch.close()
+    for s in sims:
+        s.close()
+    assert len({m.tobytes() for m in mid}) == S
+    for i, p in enumerate(ps):
+        alone = lib.Simulation(p, d)
+        alone.round(T)
+        assert np.array_equal(alone.model(), got[i][0]), f"simulation {i} differs from its unbatched run"
+        assert np.array_equal(alone.trace(), got[i][1])
+        alone.close()
+    o = AbsOracle(ps[1], d["X"], d["y"], d["w0"], keep_models=False).run(T)
+    want = np.stack([trace_words(r, ps[1]["N"]) for r in o.trace])
+    if _same_schedule(got[1][1], want):
+        assert rel_err(got[1][0], o.model()) <= 2e-2
 
 
 def test_batch_of_simulations_on_different_datasets():
