@@ -67,7 +67,7 @@ def sweep_a(p: dict, values, seeds: int, rounds: int, every: int, eval_rows: int
     train, Xe, ye = workloads.make_split(base, eval_rows)
     runs = [(av, sd, lib.Simulation(dict(base, a=av, seed_sim=base["seed_sim"] + 7919 * sd), train))
             for av in values for sd in range(seeds)]
-    batch = lib.Batch([r[2] for r in runs]) if base["model"] != 2 and len(runs) > 1 else None
+    batch = lib.Batch([r[2] for r in runs]) if len(runs) > 1 else None
     rows, done = [], 0
     while done < rounds:
         n = min(every, rounds - done)

@@ -50,3 +50,7 @@ def test_compare_tool_readouts(capsys):
     r0 = sum(r["restarts"] for r in rows if r["a"] == 0)
     r3 = sum(r["restarts"] for r in rows if r["a"] == -3)
     assert r3 >= r0
+    # the sweep of an MLP workload runs its simulations side by side (a batch of MLP handles)
+    pm = workloads.scaled_preset(3, M=4096, dims=[256, 128, 10], N=6, B=32, n_slow=1, K0=2, tau_cap=3)
+    rows = compare.sweep_a(pm, [0, -1], 2, 12, 12, 256, None)
+    assert len(rows) == 4 and all(np.isfinite(r["eval_loss"]) for r in rows)
