@@ -39,7 +39,8 @@ def test_linear_local_steps(over, T):
     (dict(U=2, M=4000, dims=[1024, 16], n_classes=16, N=4, B=300, lr=2e-4), 20),    # two row batches
     (dict(U=5, M=2000, dims=[8, 2], n_classes=2, N=16, B=5, sa_penalty=1, lr=2e-2), 80),
     (dict(U=9, M=4000, dims=[16, 4], n_classes=4, N=3, B=250, lr=5e-3), 12),     # U B > 2048: the wavefront-per-row kernel
-    (dict(U=2, M=6000, dims=[784, 10], N=4, B=1000, K0=2, lr=1e-3), 6),           # 2000 rows per job, 8-row tiles
+    (dict(U=2, M=6000, dims=[784, 10], N=4, B=1000, K0=2, lr=1e-3), 6),           # 2000 rows per job
+    (dict(U=2, M=3000, dims=[1000, 4], n_classes=4, N=4, B=21, lr=2e-4), 10),     # model in LDS, 8-row tiles
 ])
 def test_softmax_local_steps(over, T):
     p = workloads.scaled_preset(2, **over)
