@@ -615,8 +615,6 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   st.kmax.assign((size_t)st.T, 0);
   st.rc.assign((size_t)st.T, ABS_OK);
   st.bad_sim.assign((size_t)st.T, -1);
-  std::vector<std::thread> pool;
-  for (int k = 1; k < st.T; ++k) pool.emplace_back([&st, k] { st.worker(k); });
   // Large batches advance as G groups, staggered in time: while the device works on one group's
   // round the host finishes and prepares another's (Eq. 5 makes a simulation's next selection wait
   // for its own losses, not for the other groups').
@@ -641,6 +639,8 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
     for (int g = 1; g < G && e == hipSuccess; ++g) e = hipStreamWaitEvent(gstream[g], b->ev_in, 0);
     if (e != hipSuccess) { b->err = std::string("hipStreamWaitEvent: ") + hipGetErrorString(e); return ABS_E_HIP; }
   }
+  std::vector<std::thread> pool;            // from here on every path joins them
+  for (int k = 1; k < st.T; ++k) pool.emplace_back([&st, k] { st.worker(k); });
   bool inflight[kBatchGroups] = {};
   auto finish = [&](int g) {
     inflight[g] = false;
