@@ -251,8 +251,8 @@ __device__ __forceinline__ void softmax_rows_body(const RegressionArgs& a, const
 // Kernel 2: G = X^T dZ over all K*B stacked rows, sliced by feature, then the update
 // w^{t+1} = w^t - G written into the next ring slot.  A workgroup owns 8 features; its
 // 1024 threads are 8 features x 128 row groups; the 128 partial sums are combined through
-// LDS in group order.  The last workgroup reduces the bias gradient and the per-upload
-// losses.
+// LDS in group order.  One more workgroup, the first, reduces the per-upload losses and the
+// bias gradient.
 constexpr int kUpdF = 8, kUpdG = 128;
 
 template <int C>
@@ -262,10 +262,12 @@ __device__ __forceinline__ void softmax_update_body(const RegressionArgs& a, con
   const int B = a.B, d = a.d, R = rd.K * B;
   const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
   float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
-  const int nslice = (d + kUpdF - 1) / kUpdF;
-  if ((int)blockIdx.x < nslice) {
+  // workgroup 0 (the first to be dispatched) publishes the losses, so that the host prepares the
+  // next round while the others still work; workgroups 1 .. are the feature slices
+  const int slice = (int)blockIdx.x - 1;
+  if (slice >= 0) {
     const int f = threadIdx.x % kUpdF, g = threadIdx.x / kUpdF;
-    const int i = blockIdx.x * kUpdF + f;
+    const int i = slice * kUpdF + f;
     float acc[C];
 #pragma unroll
     for (int c = 0; c < C; ++c) acc[c] = 0.f;
@@ -298,7 +300,7 @@ __device__ __forceinline__ void softmax_update_body(const RegressionArgs& a, con
     __syncthreads();
     if ((int)threadIdx.x < kUpdF * C) {
       const int ff = threadIdx.x / C, c = threadIdx.x % C;
-      const int ii = blockIdx.x * kUpdF + ff;
+      const int ii = slice * kUpdF + ff;
       if (ii < d) {
         float G = 0.f;
 #pragma unroll 8
@@ -308,6 +310,19 @@ __device__ __forceinline__ void softmax_update_body(const RegressionArgs& a, con
     }
     return;
   }
+  // per-upload mean minibatch loss (the "average local loss" each worker uploads)
+  {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int up = wave; up < rd.K; up += 16) {
+      float s = 0.f;
+      for (int b = lane; b < B; b += 64) s += a.rowloss[up * B + b];
+      s = wave_sum(s);
+      if (lane == 0) s_loss[up] = s / (float)B;
+    }
+    __syncthreads();
+    publish_losses(a.mailbox, s_loss, rd.K, rd.stamp);
+  }
+  __syncthreads();
   // bias gradient: column sums of dZ (16 columns x 64 row groups), then b^{t+1}
   {
     const int c = threadIdx.x % 16, g = threadIdx.x / 16;
@@ -322,18 +337,6 @@ __device__ __forceinline__ void softmax_update_body(const RegressionArgs& a, con
       for (int gg = 0; gg < 64; ++gg) G += red[gg * 16 + threadIdx.x];
       nxt[(size_t)d * C + threadIdx.x] = cur[(size_t)d * C + threadIdx.x] - G;
     }
-  }
-  // per-upload mean minibatch loss (the "average local loss" each worker uploads)
-  {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int up = wave; up < rd.K; up += 16) {
-      float s = 0.f;
-      for (int b = lane; b < B; b += 64) s += a.rowloss[up * B + b];
-      s = wave_sum(s);
-      if (lane == 0) s_loss[up] = s / (float)B;
-    }
-    __syncthreads();
-    publish_losses(a.mailbox, s_loss, rd.K, rd.stamp);
   }
 }
 
