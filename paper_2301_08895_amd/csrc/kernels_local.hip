@@ -211,16 +211,16 @@ __device__ __forceinline__ void delta_update_body(const RegressionArgs& a, const
   __shared__ float s_loss[ABS_MAX_WORKERS];
   const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
   float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
+  if (blockIdx.x == 0) {                  // first: the host prepares the next round meanwhile
+    for (int up = threadIdx.x; up < rd.K; up += 256) s_loss[up] = a.lossbuf[up];
+    __syncthreads();
+    publish_losses(a.mailbox, s_loss, rd.K, rd.stamp);
+  }
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < P) {
     float s = 0.f;
     for (int up = 0; up < rd.K; ++up) s += a.delta[(size_t)up * a.slot_stride + i];
     nxt[i] = cur[i] - s / (float)rd.K;
-  }
-  if (blockIdx.x == 0) {
-    for (int up = threadIdx.x; up < rd.K; up += 256) s_loss[up] = a.lossbuf[up];
-    __syncthreads();
-    publish_losses(a.mailbox, s_loss, rd.K, rd.stamp);
   }
 }
 

@@ -97,14 +97,7 @@ __device__ __forceinline__ void linreg_round_body(const RegressionArgs& a, const
 #pragma unroll
   for (int q = 0; q < Q; ++q) s_g[wave][lane + 64 * q] = g[q];
   __syncthreads();
-  const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
-  float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    float G = 0.f;
-#pragma unroll
-    for (int w = 0; w < kLinWaves; ++w) G += s_g[w][i];
-    nxt[i] = cur[i] - G;
-  }
+  // the losses first: the host prepares the next round while the update is written
   for (int up = threadIdx.x; up < K; up += blockDim.x) {   // thread `up` owns column `up` of s_loss
     float l = 0.f;
 #pragma unroll
@@ -113,6 +106,14 @@ __device__ __forceinline__ void linreg_round_body(const RegressionArgs& a, const
   }
   __syncthreads();
   publish_losses(a.mailbox, &s_loss[0][0], K, rd.stamp);
+  const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
+  float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    float G = 0.f;
+#pragma unroll
+    for (int w = 0; w < kLinWaves; ++w) G += s_g[w][i];
+    nxt[i] = cur[i] - G;
+  }
 }
 template <int Q>
 __global__ __launch_bounds__(kLinWaves * 64) void linreg_round_kernel(RegressionArgs a, RoundDesc rd) {
@@ -928,6 +929,11 @@ __global__ __launch_bounds__(256) void softmax_combine_batch_kernel(const Regres
   const int K = rd.K;
   const float* cur = a.ring + (size_t)rd.slot_cur * a.slot_stride;
   float* nxt = a.ring + (size_t)rd.slot_next * a.slot_stride;
+  if (blockIdx.x == 0) {                  // first: the host prepares the next round meanwhile
+    for (int up = threadIdx.x; up < K; up += 256) s_loss[up] = a.lossbuf[up];
+    __syncthreads();
+    publish_losses(a.mailbox, s_loss, K, rd.stamp);
+  }
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < P) {
     const float c = load_global(cur + i);
@@ -943,11 +949,6 @@ __global__ __launch_bounds__(256) void softmax_combine_batch_kernel(const Regres
     }
     for (; up < K; ++up) sum += load_global(p + (size_t)up * a.slot_stride);
     nxt[i] = c - sum;
-  }
-  if (blockIdx.x == 0) {
-    for (int up = threadIdx.x; up < K; up += 256) s_loss[up] = a.lossbuf[up];
-    __syncthreads();
-    publish_losses(a.mailbox, s_loss, K, rd.stamp);
   }
 }
 
