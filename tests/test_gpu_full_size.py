@@ -125,3 +125,25 @@ def test_batched_rounds_at_full_size(i, S, T):
         assert e <= FP32_TOL
         checked += 1
     assert checked >= 2
+
+
+def test_mlp_batch_at_full_size():
+    """cfg 3 at its full shape, three simulations side by side (bench.py --config 3 --batch S): every
+    one bitwise its unbatched run."""
+    p = workloads.preset(3)
+    d = workloads.make_inputs(p)
+    ps = [dict(p, seed_sim=p["seed_sim"] + 7919 * k) for k in range(3)]
+    T = 8
+    sims = [lib.Simulation(q, d) for q in ps]
+    batch = lib.Batch(sims)
+    batch.round(T)
+    batch.close()
+    got = [(s.model().copy(), s.trace().copy()) for s in sims]
+    for s in sims:
+        s.close()
+    for q, (w, tr) in zip(ps, got):
+        alone = lib.Simulation(q, d)
+        alone.round(T)
+        assert np.array_equal(alone.model(), w) and np.array_equal(alone.trace(), tr)
+        alone.close()
+        _trace_properties(q, tr)
