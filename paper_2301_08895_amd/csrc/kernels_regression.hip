@@ -365,10 +365,11 @@ __global__ __launch_bounds__(1024) void softmax_update_batch_kernel(const Regres
 
 // ------------------------------------------------------------------ batched softmax rounds, fused
 // With many simulations per launch there are enough uploads to give each a workgroup of its own,
-// and then the round reads every minibatch row from HBM once.  The upload's stale model sits in
-// LDS, transposed ([class][feature]); the rows pass through LDS in tiles of TR = 8 or 16, the next
-// tile in flight in registers meanwhile.  Both products of a tile run on the fp32 matrix cores
-// (16x16x4 tiles, classes padded to 16):
+// and then the round reads every minibatch row from HBM once.  Two forms.  This one, for wide models
+// (d + 1 > 896): the upload's stale model sits in LDS, transposed ([class][feature]).  The other,
+// further down and the usual one: the model sits in registers.  In both the rows pass through LDS
+// in tiles (here TR = 8 or 16 rows), the next tile in flight in registers meanwhile, and both
+// products of a tile run on the fp32 matrix cores (16x16x4 tiles, classes padded to 16):
 //   (1) logits Z = X_tile W: the eight wavefronts split the features, their partial 16 x 16 tiles
 //       are added through LDS, and 16 TR threads (row, class) finish softmax, loss and the rows of
 //       dZ = c (softmax - onehot), with reductions over the 16 classes inside a DPP row;
