@@ -223,7 +223,7 @@ void abs_destroy(abs_ctx* ctx);
  *                     up to four of them run side by side, each on a stream and a host thread
  *                     of its own, bitwise the result of abs_round, and an error of one does not
  *                     stop the others (the first failing simulation is the one reported).
- *                     Large batches (softmax: 16 simulations and more, linear: 32 and more)
+ *                     Batches (softmax: 4 simulations and more, linear: 32 and more)
  *                     advance as two to four groups, staggered in time, so that the host's part
  *                     of one overlaps the device's part of the others; the first group's work
  *                     goes to the handles' stream, the others' to streams the batch owns, which

@@ -624,10 +624,10 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   // handles' stream held at entry, and before what it gets after the call), so that the device
   // fills the tail of one group's kernel with the head of another's.
   const bool softmax = c0.model == ABS_MODEL_SOFTMAX;
-  // (softmax, 784 x 10, N = 16: 16 simulations 6.1 -> 7.1 M worker-gradients/s with two groups,
+  // (softmax, 784 x 10, N = 16: 8 simulations 3.7 -> 4.0, 16: 6.1 -> 7.1 M worker-gradients/s with two groups,
   // 64: 9.0 -> 17.5 M with three, 128 and more: 12.5 -> 20 M with four; linear, d = 100, N = 8:
   // 32 simulations 6.1 -> 7.0 M with two, 128: 13.0 -> 20.6 M, 1024: 38.4 -> 47.7 M, four groups lose)
-  const int G = softmax ? (S >= 128 ? 4 : S >= 64 ? 3 : S >= 16 ? 2 : 1) : (S >= 32 ? 2 : 1);
+  const int G = softmax ? (S >= 128 ? 4 : S >= 64 ? 3 : S >= 4 ? 2 : 1) : (S >= 32 ? 2 : 1);
   int lo[kBatchGroups], hi[kBatchGroups];
   hipStream_t gstream[kBatchGroups];
   for (int g = 0; g < G; ++g) {

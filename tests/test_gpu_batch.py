@@ -106,7 +106,7 @@ def test_softmax_batch():
 
 def test_batches_that_advance_as_groups():
     """Large batches run as two to four groups staggered in time, each on its own stream (softmax:
-    two from 16 simulations, three from 64, four from 128; linear: two from 32): results must not
+    two from 4 simulations, three from 64, four from 128; linear: two from 32): results must not
     change, also when a call is split in two."""
     _run(workloads.scaled_preset(2, M=2000, dims=[20, 4], n_classes=4, N=5, B=17, K0=2, lr=1e-2), 131, 14, 1e-5, 1e-4,
          oracle_for=(0, 130), bitwise_alone=False)
