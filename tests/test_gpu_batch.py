@@ -94,6 +94,9 @@ def test_softmax_batch():
     # the widest model the register-resident form takes (all 56 blocks of 16 features in use)
     _run(workloads.scaled_preset(2, M=3000, dims=[892, 10], N=5, B=37, lr=2e-4), 3, 10, 1e-5, 1e-4,
          oracle_for=(0,), bitwise_alone=False)
+    # all 16 class columns in use
+    _run(workloads.scaled_preset(2, M=3000, dims=[320, 16], n_classes=16, N=6, B=23, lr=5e-4), 4, 10, 1e-5, 1e-4,
+         oracle_for=(0,), bitwise_alone=False)
     # wider ones keep the model in LDS: 8-row tiles with two workgroups per CU (1000 x 4) ...
     _run(workloads.scaled_preset(2, M=3000, dims=[1000, 4], n_classes=4, N=4, B=21, lr=2e-4), 3, 10, 1e-5, 1e-4,
          oracle_for=(0,), bitwise_alone=False)

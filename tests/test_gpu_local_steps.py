@@ -41,6 +41,7 @@ def test_linear_local_steps(over, T):
     (dict(U=9, M=4000, dims=[16, 4], n_classes=4, N=3, B=250, lr=5e-3), 12),     # U B > 2048: the wavefront-per-row kernel
     (dict(U=2, M=6000, dims=[784, 10], N=4, B=1000, K0=2, lr=1e-3), 6),           # 2000 rows per job
     (dict(U=2, M=3000, dims=[1000, 4], n_classes=4, N=4, B=21, lr=2e-4), 10),     # model in LDS, 8-row tiles
+    (dict(U=3, M=3000, dims=[256, 16], n_classes=16, N=5, B=19, lr=1e-3), 12),    # all 16 class columns in use
 ])
 def test_softmax_local_steps(over, T):
     p = workloads.scaled_preset(2, **over)
