@@ -691,7 +691,6 @@ __device__ __forceinline__ void softmax_upload_body(const RegressionArgs& a, con
 template <int C, bool LOCAL>
 __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a, const RoundDesc& rd, int up) {
   constexpr int TR = 16, NB = kWregNB;
-  constexpr int LD = 16 * NB * kFuseWaves / 4 / 32;  // 16-byte chunks per thread and tile: 32 threads per tile row
   extern __shared__ __align__(16) float s_mem[];
   if (up >= rd.K) return;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -727,16 +726,18 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
 #pragma unroll
   for (int u = 0; u < NLAB; ++u)
     lab[u] = load_global((const int32_t*)a.y + s_rowi[min(t + u * kFuseThreads, total - 1)]);
-  // a tile's loads: thread t takes chunks t % 32 + 32 j of tile row t / 32 (threads past the tile's
-  // rows read its last row again)
-  const int prow = t >> 5, pch = t & 31;
-  float4 pre[LD];
+  // A wavefront loads, stores and reads only the feature columns of its own blocks (both products
+  // of wavefront w touch features 16 blk .. + 15 of blk = w, w + 8, ... and nothing else), so the
+  // tile in LDS needs no workgroup barrier: lane l takes the 16 bytes at chunk l % 4 of the block's
+  // 64 bytes in tile row l / 4 (lanes past the tile's rows read its last row again)
+  const int prow = lane >> 2, pch = lane & 3;
+  float4 pre[NB];
 #define ABS_PREFETCH(base_, nrows_)                                                                          \
   {                                                                                                          \
     const uint32_t ri = s_rowi[(base_) + min(prow, (nrows_) - 1)];                                           \
-    const float* src = a.X + (uint64_t)ri * (uint64_t)d + 4 * pch;                                           \
-    _Pragma("unroll") for (int j = 0; j < LD; ++j)                                                           \
-      if (pch + 32 * j < dq) pre[j] = load_global_f4(src + 128 * j);                                         \
+    const float* src = a.X + (uint64_t)ri * (uint64_t)d + 16 * wave + 4 * pch;                               \
+    _Pragma("unroll") for (int bi = 0; bi < NB; ++bi)                                                        \
+      if (16 * (wave + kFuseWaves * bi) + 4 * pch < d) pre[bi] = load_global_f4(src + 128 * bi);             \
   }
   ABS_PREFETCH(0, min(TR, B))
   __syncthreads();
@@ -756,6 +757,7 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
 #pragma unroll
   for (int u = 0; u < NLAB; ++u)
     if (t + u * kFuseThreads < total) s_lab[t + u * kFuseThreads] = lab[u];
+  __syncthreads();
 
   f32x4_ G[NB];
 #pragma unroll
@@ -765,13 +767,19 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
   for (int off = 0, base = 0; off < total;) {
     const int nrows = min(TR, B - base);
     const int noff = off + nrows, nbase = base + nrows == B ? 0 : base + nrows;
-    __syncthreads();                      // the previous tile has been used up
-    if (prow < nrows) {
+    // the tile's columns of this wavefront into LDS (its own gradient product of the previous tile
+    // was their last reader), then the next tile's loads
+    {
+      float* xdst = s_x + prow * dp + 16 * wave + 4 * pch;
 #pragma unroll
-      for (int j = 0; j < LD; ++j)
-        if (pch + 32 * j < dq) *(float4*)(s_x + prow * dp + 4 * (pch + 32 * j)) = pre[j];
+      for (int bi = 0; bi < NB; ++bi)
+        if (16 * (wave + kFuseWaves * bi) + 4 * pch < d) *(float4*)(xdst + 128 * bi) = pre[bi];
     }
-    __syncthreads();
+    // other lanes of this wavefront read what this lane wrote: LDS serves a wavefront's requests in
+    // order, the compiler must keep them in order too
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (noff < total) ABS_PREFETCH(noff, min(TR, B - nbase))
     // (1a) this wavefront's share of the logits: lane (m16, g4) feeds row m16 of x~ and its own
     // model elements (class m16) at features 16 blk + 4 g4 .. + 3; two accumulators in turn
