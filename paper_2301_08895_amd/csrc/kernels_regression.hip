@@ -694,7 +694,7 @@ __device__ __forceinline__ void softmax_upload_wreg_body(const RegressionArgs& a
   extern __shared__ __align__(16) float s_mem[];
   if (up >= rd.K) return;
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int d = a.d, B = a.B, dq = d >> 2, dp = d + 4;
+  const int d = a.d, B = a.B, dp = d + 4;
   const int total = LOCAL ? a.U * B : B;  // rows of the job: draw i of its counter stream is row i
   float* s_x = s_mem;                     // [16][dp]; first the model, at the end the upload, boundary layout
   float* s_zp = s_x + TR * dp;            // [8 wavefronts][16 rows][16 classes]
