@@ -238,6 +238,31 @@ def test_batch_error_leaves_every_simulation_consistent():
         s.close()
 
 
+def test_mlp_batch_error_does_not_stop_the_others():
+    """MLP simulations of a batch advance independently: the one that runs out of its K replay is
+    reported, all the others complete their rounds."""
+    base = dict(workloads.scaled_preset(3, M=4096, dims=[256, 128, 10], N=6, B=32, n_slow=1, K0=2, tau_cap=3), k_mode=2)
+    d = workloads.make_inputs(base)
+    S, bad, T = 6, 2, 10
+    replay = np.tile(np.array([2, 3, 1, 6, 4], np.int32), 2)
+    ps = [dict(base, seed_sim=base["seed_sim"] + 7 * i) for i in range(S)]
+    sims = [lib.Simulation(p, d, k_replay=replay[:4] if i == bad else replay) for i, p in enumerate(ps)]
+    batch = lib.Batch(sims)
+    with pytest.raises(lib.AbsError) as err:
+        batch.round(T)
+    assert f"simulation {bad}" in str(err.value)
+    batch.close()
+    done = [lib.abs_rounds_done(s.handle) for s in sims]
+    assert done[bad] == 4 and all(n == T for i, n in enumerate(done) if i != bad)
+    for i in (0, S - 1):
+        alone = lib.Simulation(ps[i], d, k_replay=replay)
+        alone.round(T)
+        assert np.array_equal(alone.model(), sims[i].model()) and np.array_equal(alone.trace(), sims[i].trace())
+        alone.close()
+    for s in sims:
+        s.close()
+
+
 def test_softmax_batch_random_shapes():
     """Seeded random shapes (features, classes, workers, minibatch, batch size) of batched softmax
     rounds: batch-of-one bitwise, oracle to the parity bar."""
