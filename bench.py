@@ -199,8 +199,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
-    ap.add_argument("--profile-every", type=int, default=8, metavar="n",
-                    help="bracket the kernels of every n-th round with HIP events (1: of every round)")
+    ap.add_argument("--profile-every", type=int, default=None, metavar="n",
+                    help="bracket the kernels of every n-th round with HIP events (1: of every round; "
+                         "default: 8, and 1 for runs shorter than 64 rounds so that the roofline figure "
+                         "rests on every timed round)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time (0: skip)")
     ap.add_argument("--fixed-k", action="store_true",
                     help="counter runs only: wait for all N workers every round (the steady state)")
@@ -236,6 +238,8 @@ def main():
     warmup = dw if args.warmup is None else args.warmup
     steps = ds if args.steps is None else args.steps
     inputs = workloads.make_inputs(p)
+    if args.profile_every is None:
+        args.profile_every = 1 if steps < 64 else 8
 
     if args.batch:
         return bench_batch(args, p, inputs, warmup, steps)

@@ -18,6 +18,16 @@
  * by the caller, h_* are HOST pointers owned by the caller.  Every call
  * returns ABS_OK or a negative error code; no exception crosses the boundary.
  * A handle is not thread-safe.
+ *
+ * Which calls carry the paper's method and which are plumbing.  abs_create is the
+ * initialisation of Algorithm 1, abs_round its server loop with the workers' steps
+ * (Eq. 2-6), abs_evaluate the read-outs of Section V-B, abs_batch_* the sweeps of
+ * Section V, abs_draw_* the random draws of Sections II-A and V-A.  Everything else
+ * has no passage behind it and exists because a C library needs it: abs_config_bytes,
+ * abs_workspace_size (the size of the caller's allocation),
+ * abs_get_model, abs_trace, abs_rounds_done, abs_kernel_stats, abs_mlp_round_plan
+ * (reading results and bookkeeping out), abs_last_error, abs_batch_last_error,
+ * abs_destroy, abs_batch_destroy.
  */
 #ifndef ABS_H
 #define ABS_H
@@ -83,7 +93,7 @@ typedef struct abs_ctx abs_ctx;   /* opaque: one simulation */
  *             (read with abs_kernel_stats); costs a few microseconds per launch.
  *             n > 1: the same in every n-th round only (rounds t with t mod n = 0), a
  *             uniform sample of the job at 1/n of the cost.
- *  U          local SGD steps per job (Eq. 2), 1 <= U <= 64.  With U > 1 every upload is
+ *  U          local SGD steps per job (Eq. 2), 1 <= U <= 64; 0 is read as 1.  With U > 1 every upload is
  *             the change w^{t,0} - w^{t,U} of a private copy of the model after U steps
  *             on fresh minibatches (worker part of Algorithm 1) and the reported loss is
  *             the job's mean local loss; 0 is read as 1.
@@ -146,7 +156,9 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
 int abs_round(abs_ctx* ctx, int32_t n_rounds);
 
 /* Copy global model w^version (fp32, boundary layout, n_floats = parameter count)
- * to host memory; version -1 = the latest.  Synchronises the stream. */
+ * to host memory; version -1 = the latest.  Synchronises the stream.  (Plumbing: the
+ * paper's server simply holds w^t; the versions still readable are those of the ring,
+ * t - tau_cap - 2 .. t, ABS_E_VERSION otherwise.) */
 int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats);
 
 /*
@@ -176,6 +188,17 @@ int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y
  */
 int abs_trace(abs_ctx* ctx, int64_t round_lo, int64_t round_hi, int32_t* h_out,
               size_t cap_words, size_t* words_written);
+
+/*
+ * MLP configurations, host only (no device work, no handle): what a round that waits for K uploads
+ * launches, as text - one "product:tile rows x tile columns/split count" item per kernel of the
+ * round's chain (forward, logits, input gradients, weight gradients, updates), in launch order.
+ * Two values of K with the same text run the same kernels with the same tile shapes and split
+ * counts (grid sizes aside).  For tests that want to cover every plan of a shape, and for reading
+ * profiles.  Writes a NUL-terminated string of at most cap bytes to h_out; ABS_E_ARG if cfg is not
+ * a supported MLP configuration, K is outside [1, N] or the text does not fit.
+ */
+int abs_mlp_round_plan(const abs_config* cfg, int32_t K, char* h_out, size_t cap);
 
 /* Rounds completed so far. */
 int64_t abs_rounds_done(const abs_ctx* ctx);

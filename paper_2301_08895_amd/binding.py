@@ -77,6 +77,8 @@ def _load():
     lib.abs_get_model.argtypes = [vp, i64, C.POINTER(C.c_float), sz]
     lib.abs_trace.restype = C.c_int
     lib.abs_trace.argtypes = [vp, i64, i64, C.POINTER(i32), sz, C.POINTER(sz)]
+    lib.abs_mlp_round_plan.restype = C.c_int
+    lib.abs_mlp_round_plan.argtypes = [cfgp, i32, C.c_char_p, sz]
     lib.abs_rounds_done.restype = i64
     lib.abs_rounds_done.argtypes = [vp]
     lib.abs_kernel_stats.restype = C.c_int
@@ -198,6 +200,14 @@ def abs_trace(handle: int, round_lo: int, round_hi: int, N: int) -> np.ndarray:
                           out.size, C.byref(written)), handle)
     assert written.value == out.size
     return out
+
+
+def abs_mlp_round_plan(cfg: AbsConfig, K: int) -> str:
+    buf = C.create_string_buffer(4096)
+    rc = _lib.abs_mlp_round_plan(C.byref(cfg), K, buf, len(buf))
+    if rc != 0:
+        raise AbsError(rc, "abs_mlp_round_plan: not an MLP configuration the library supports, or K outside [1, N]")
+    return buf.value.decode()
 
 
 def abs_rounds_done(handle: int) -> int:

@@ -4,8 +4,10 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <string>
@@ -22,6 +24,21 @@ namespace {
 thread_local std::string g_create_error;
 
 size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+// How long the host waits for a round's losses before it gives the call up with ABS_E_HIP: a round
+// of the largest workload lasts a few milliseconds, so minutes mean the stream is stuck behind
+// something that will not end.  ABS_MAILBOX_TIMEOUT_MS overrides the two minutes.
+double mailbox_timeout_s() {
+  static const double t = [] {
+    const char* e = std::getenv("ABS_MAILBOX_TIMEOUT_MS");
+    const double ms = e ? std::atof(e) : 0.0;
+    return ms > 0.0 ? ms * 1e-3 : 120.0;
+  }();
+  return t;
+}
+double seconds_since(std::chrono::steady_clock::time_point t0) {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+}
 
 size_t param_count(const abs_config& c) {
   if (c.model == ABS_MODEL_LINEAR) return (size_t)c.dims[0];
@@ -52,7 +69,7 @@ bool validate(const abs_config& c, std::string& why) {
   if (c.time_dist == ABS_TIME_PARETO && !(c.time_param > 0.0)) return bad("Pareto needs time_param > 0");
   if (c.n_slow < 0 || c.n_slow > c.N) return bad("n_slow must be in [0, N]");
   if (c.n_slow > 0 && !(c.slow_factor > 0.0)) return bad("slow_factor must be positive");
-  if (c.U < 0 || c.U > 64) return bad("U must be in [1, 64]");
+  if (c.U < 0 || c.U > 64) return bad("U must be in [1, 64] (0 is read as 1)");
   if (c.reserved != 0) return bad("reserved must be 0");
   if (c.profile < 0) return bad("profile must be 0, 1 or a sampling period n > 1");
   if (c.device_mode == 0 && !(c.k_mode == ABS_K_FIXED || c.k_mode == ABS_K_REPLAY))
@@ -154,8 +171,10 @@ struct abs_ctx : public LaunchHook {
     }
   }
   // Spin until the device has stamped the mailbox; every so often ask the runtime whether the
-  // stream has failed or drained without the stamp, so a broken launch cannot hang the host.
+  // stream has failed or drained without the stamp, and give up after mailbox_timeout_s(), so
+  // neither a broken launch nor a stream that never gets to run can hang the host.
   int wait_mailbox(uint32_t stamp) {
+    const auto t0 = std::chrono::steady_clock::now();
     for (uint64_t spin = 1;; ++spin) {
       if (h_box->stamp == stamp) { std::atomic_thread_fence(std::memory_order_acquire); return ABS_OK; }
       if ((spin & 0x3FFF) == 0) {
@@ -166,6 +185,10 @@ struct abs_ctx : public LaunchHook {
           return ABS_E_HIP;
         }
         if (q != hipErrorNotReady) { err = std::string("hipStreamQuery: ") + hipGetErrorString(q); return ABS_E_HIP; }
+        if (seconds_since(t0) > mailbox_timeout_s()) {
+          err = "timed out waiting for the round's losses (the stream has not completed the round)";
+          return ABS_E_HIP;
+        }
       }
 #if defined(__x86_64__)
       __builtin_ia32_pause();
@@ -483,7 +506,14 @@ struct BatchRoundState {
 
   // Thread 0, now and then while mailboxes are awaited: has the stream failed?  (A stream that has
   // drained has written every mailbox, so only a runtime error ends the wait.)
+  std::chrono::steady_clock::time_point wait_t0;   // set by run() at the start of a finish phase
   bool stream_failed() {
+    if (seconds_since(wait_t0) > mailbox_timeout_s()) {
+      b->err = "timed out waiting for the round's losses (a stream has not completed the round)";
+      rc[0] = ABS_E_HIP; bad_sim[0] = -1;
+      abort.store(true);
+      return true;
+    }
     hipError_t q = hipStreamQuery(b->stream);
     for (hipStream_t s : b->own)
       if (q == hipSuccess || q == hipErrorNotReady) q = hipStreamQuery(s);
@@ -545,6 +575,7 @@ struct BatchRoundState {
   // first failing simulation's code
   int run(int kind_, int lo_, int hi_) {
     done.store(0, std::memory_order_relaxed);
+    wait_t0 = std::chrono::steady_clock::now();
     kind = kind_; lo = lo_; hi = hi_;
     phase.fetch_add(1, std::memory_order_release);
     if (kind_ == 0) prepare(0); else finish(0);
@@ -760,6 +791,17 @@ int abs_trace(abs_ctx* ctx, int64_t round_lo, int64_t round_hi, int32_t* h_out, 
   if (words > cap_words) { ctx->err = "trace buffer too small"; return ABS_E_ARG; }
   if (words) std::memcpy(h_out, ctx->sched->trace().data() + (size_t)round_lo * stride, words * sizeof(int32_t));
   if (words_written) *words_written = words;
+  return ABS_OK;
+}
+
+int abs_mlp_round_plan(const abs_config* cfg, int32_t K, char* h_out, size_t cap) {
+  if (!cfg || !h_out || cap == 0) return ABS_E_ARG;
+  h_out[0] = 0;
+  std::string why;
+  if (cfg->model != ABS_MODEL_MLP || !validate(*cfg, why)) return ABS_E_ARG;
+  const std::string plan = mlp_round_plan(*cfg, K);
+  if (plan.empty() || plan.size() + 1 > cap) return ABS_E_ARG;
+  std::memcpy(h_out, plan.c_str(), plan.size() + 1);
   return ABS_OK;
 }
 

@@ -1,6 +1,7 @@
 // Launchers of the HIP kernels (defined in kernels_regression.hip / kernels_mlp.hip).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <string>
 #include "abs_common.h"
 
 namespace abs_impl {
@@ -152,6 +153,10 @@ struct MlpArgs {
 // One-time preparation on the stream: zero the padded buffers, build the bf16 copies of w^0.
 hipError_t mlp_prepare(const MlpArgs& a, hipStream_t s);
 hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s, LaunchHook* hook);
+// What a round of K uploads launches (kernel, tile shape / split count per product), as text; from
+// the launch code itself run in a recording mode that launches nothing.  Empty if cfg is not an
+// MLP configuration the library supports or K is outside [1, N].
+std::string mlp_round_plan(const abs_config& cfg, int K);
 // forward pass of ring slot `slot` over e.n_rows evaluation rows, Mp rows at a time (e.cap >= Mp)
 hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, hipStream_t s, LaunchHook* hook);
 

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <string>
 
 #include "kernels.h"
 
@@ -410,14 +411,15 @@ __device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_bl
 // apart from a pending global->LDS request wait for all of them, and it cannot for the
 // transposing read: a k-step would then start by waiting for the tile it has just requested.
 // Requests issued this way are invisible to that bookkeeping; the loop's own vmcnt(0) and
-// barrier order them against the reads.
+// barrier order them against the reads.  The LDS base travels in m0, which the register
+// allocator hands over through the "{m0}" constraint (it knows the register is written).
 __device__ __forceinline__ void lds_dma16_raw(const uint16_t* gsrc, uint16_t* lds_block) {
   const uint32_t lds = __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_block);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
-               : "v"(gsrc), "s"(lds)
-               : "memory");      // (m0: nothing else in these kernels keeps a value in it)
+               : "v"(gsrc), "{m0}"(lds)
+               : "memory");
 }
 
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG>
@@ -1175,6 +1177,15 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
 // ------------------------------------------------------------------ launches
 namespace {
 
+// Plan recording: with t_plan set, the launch functions below append what they would launch
+// (kernel, tile shape, split count) and launch nothing; mlp_round_plan() uses it so that the
+// description of a round's launches comes from the very code that issues them.
+thread_local std::string* t_plan = nullptr;
+#define ABS_LAUNCH(...) do { if (!t_plan) { __VA_ARGS__; } } while (0)
+void plan_note(const char* what, int a, int b, int c) {
+  if (t_plan) *t_plan += std::string(what) + ":" + std::to_string(a) + "x" + std::to_string(b) + "/" + std::to_string(c) + " ";
+}
+
 struct NullHook : LaunchHook {
   void begin(int, double, double) override {}
   void end(int) override {}
@@ -1237,9 +1248,10 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
   const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
   // wide tiles (fewer, longer stores) only where they still give every CU a workgroup
   const bool wide = p.d[l + 1] >= 256 && ((p.d[l + 1] + 255) / 256) * ((p.d[l] + 63) / 64) * batch >= 256;
-  if (vec && wide) mlp_update_kernel<256><<<dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
-  else if (vec) mlp_update_kernel<64><<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u);
-  else     mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, 0, s>>>(u);
+  plan_note("update", 64, vec && wide ? 256 : vec ? 64 : 1, u.nsplit);
+  if (vec && wide) ABS_LAUNCH(mlp_update_kernel<256><<<dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u));
+  else if (vec) ABS_LAUNCH(mlp_update_kernel<64><<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u));
+  else     ABS_LAUNCH(mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, 0, s>>>(u));
   hook->end(KK_MLP_UPDATE);
 }
 
@@ -1258,7 +1270,9 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     g.mt = Mdim / TM3;
     g.nt = Ndim / TN3;
     g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
-    mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd);
+    plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : TAG == 2 ? "wgrad_x" : "wgrad",
+              TM3, TN3, nsplit);
+    ABS_LAUNCH(mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd));
     return true;
   }
   // widest column tile that still fills the GPU: 256-wide tiles only with two workgroups per CU
@@ -1274,9 +1288,10 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
   const dim3 block(256);
   const dim3 grid1(8 * g.rows_per_xcd * g.nt, 1, 1);
-  if (tn == 256)      mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
-  else if (tn == 128) mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
-  else                mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd);
+  plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : "wgrad", TM, tn, nsplit);
+  if (tn == 256)      ABS_LAUNCH(mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd));
+  else if (tn == 128) ABS_LAUNCH(mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd));
+  else                ABS_LAUNCH(mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd));
   return false;
 }
 
@@ -1363,9 +1378,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     const uint16_t* sbase = own ? pshadow : shadow;
 
     hook->begin(KK_MLP_INDEX, 0, arows * 12.0);
-    mlp_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, a.y, rd, p.B, p.Bp,
-                                                                    a.shard_rows, a.batch_key,
-                                                                    (uint32_t)step * (uint32_t)p.B);
+    ABS_LAUNCH(mlp_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, a.y, rd, p.B, p.Bp,
+                                                                               a.shard_rows, a.batch_key,
+                                                                               (uint32_t)step * (uint32_t)p.B));
     hook->end(KK_MLP_INDEX);
 
     // The first layer's weight gradient reads the minibatch rows straight from the dataset when
@@ -1375,8 +1390,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
                                                                wgrad_split(p, 0, rows, local ? K : 0));
     if (!wg0_direct) {
       hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
-      mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
-                                                                              at<uint16_t>(a, p.off_xgt), p.ldm);
+      plan_note("gather_t", 64, 64, 1);
+      ABS_LAUNCH(mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
+                                                                                         at<uint16_t>(a, p.off_xgt), p.ldm));
       hook->end(KK_MLP_GATHER_T);
     }
 
@@ -1393,15 +1409,15 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       float* rl = at<float>(a, p.off_rowloss);
       const size_t ld = (size_t)p.dp[L], lddz = (size_t)p.ld[L];
       switch (p.dp[L] / 64) {
-        case 1: mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld); break;
-        case 2: mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld); break;
-        default: mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld); break;
+        case 1: ABS_LAUNCH(mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld)); break;
+        case 2: ABS_LAUNCH(mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld)); break;
+        default: ABS_LAUNCH(mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld)); break;
       }
       hook->end(KK_MLP_SOFTMAX_CE);
       hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
-      mlp_loss_kernel<<<dim3(1), dim3(128), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox,
-                                                     local ? at<float>(a, p.off_lossacc) : nullptr,
-                                                     step == 0, step == U - 1, U);
+      ABS_LAUNCH(mlp_loss_kernel<<<dim3(1), dim3(128), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox,
+                                                                local ? at<float>(a, p.off_lossacc) : nullptr,
+                                                                step == 0, step == U - 1, U));
       hook->end(KK_MLP_LOSS);
     }
 
@@ -1478,7 +1494,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
         for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
       }
       hook->begin(KK_MLP_BIAS_LOSS, (double)c * rows / 64, (double)c * rows / 64 * 4.0);
-      mlp_bias_kernel<<<dim3((c + 15) / 16, local ? K : 1), dim3(256), 0, s>>>(b);
+      ABS_LAUNCH(mlp_bias_kernel<<<dim3((c + 15) / 16, local ? K : 1), dim3(256), 0, s>>>(b));
       hook->end(KK_MLP_BIAS_LOSS);
     }
   }
@@ -1495,11 +1511,26 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     d.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
     d.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
     hook->begin(KK_DELTA_UPDATE, 2.0 * K * p.P, (2.0 * K + 1.0) * p.P * 4.0);
-    mlp_delta_kernel<<<dim3((unsigned)((p.P + 255) / 256)), dim3(256), 0, s>>>(d, rd);
+    ABS_LAUNCH(mlp_delta_kernel<<<dim3((unsigned)((p.P + 255) / 256)), dim3(256), 0, s>>>(d, rd));
     hook->end(KK_DELTA_UPDATE);
     for (int l = L - 1; l >= 0; --l) launch_update(a, l, rd, UPD_DELTA, 0, 1, s, hook);
   }
-  return hipGetLastError();
+  return t_plan ? hipSuccess : hipGetLastError();
+}
+
+std::string mlp_round_plan(const abs_config& cfg, int K) {
+  MlpArgs a{};
+  const char* why = nullptr;
+  if (K < 1 || K > cfg.N || !mlp_plan(cfg, a.plan, &why)) return std::string();
+  RoundDesc rd{};
+  rd.K = K;
+  NullHook nh;
+  std::string out;
+  t_plan = &out;
+  (void)launch_mlp_round(a, rd, nullptr, &nh);   // records, launches nothing, touches no memory
+  t_plan = nullptr;
+  if (!out.empty() && out.back() == ' ') out.pop_back();
+  return out;
 }
 
 hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, hipStream_t s, LaunchHook* hook) {

@@ -17,7 +17,10 @@ def run_pair(p, T, checkpoints=(), emulate_bf16=None, inputs=None):
     models = {}
     done = 0
     for cp in sorted(set(checkpoints) | {T}):
-        o.run(cp - done)
+        while o.t < cp:                  # long stretches in pieces, so that a log shows the run is alive
+            o.run(min(250, cp - o.t))
+            if cp - done > 250:
+                print(f"  oracle at round {o.t}", flush=True)
         sim.round(cp - done)
         done = cp
         models[cp] = (sim.model(), o.model().copy())
@@ -58,6 +61,113 @@ def assert_trace_equal(res, loss_rtol):
 
 def rel_err(got, want):
     return float(np.linalg.norm(got.astype(np.float64) - want) / max(np.linalg.norm(want), 1e-30))
+
+
+def param_blocks(p):
+    """(name, slice) of every tensor of the boundary layout: W_l [d_in, d_out] then b_l per layer
+    (the linear model: w alone)."""
+    d = p["dims"]
+    if p["model"] == 0:
+        return [("w", slice(0, d[0]))]
+    out, o = [], 0
+    for l in range(len(d) - 1):
+        out.append((f"W{l + 1}", slice(o, o + d[l] * d[l + 1]))); o += d[l] * d[l + 1]
+        out.append((f"b{l + 1}", slice(o, o + d[l + 1]))); o += d[l + 1]
+    return out
+
+
+EPS32 = 2.0 ** -24      # half an ulp of the fp32 the library stores its models in
+# Single elements are held to ELEM x the tolerance, in units of their tensor's largest update.  A ReLU
+# is a discontinuity: a hidden pre-activation that lands within accumulation rounding of zero (cfg 5,
+# first round: |z| = 3e-6 against a root mean square of 2) may fall on either side in fp32 and in fp64,
+# which switches one term of one column of a weight gradient on or off - a few percent of the largest
+# update when a round sums few terms (3.7e-2 measured at K = 1, B = 256), and nothing a norm notices.
+# A mis-computed element is off by its own size, i.e. tens of percent of the largest update.
+ELEM = 5.0
+
+def compare_models(p, got, want, w0, rounds):
+    """Per tensor of the model (every W_l and every b_l separately): the relative error of the tensor,
+    of its update w - w^0, and the largest element error in units of the tensor's largest update.
+    `slack` is what storing `rounds` updates in fp32 may cost (the oracle keeps fp64)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    w0 = np.asarray(w0, np.float64)
+    rows = []
+    for name, sl in param_blocks(p):
+        g, w, z = got[sl], want[sl], w0[sl]
+        upd = w - z
+        diff = np.abs(g - w)
+        walk = EPS32 * (np.sqrt(rounds) + 1.0)
+        rows.append(dict(name=name, finite=bool(np.all(np.isfinite(g))),
+                         nw=float(np.linalg.norm(w)), nu=float(np.linalg.norm(upd)),
+                         mw=float(np.max(np.abs(w))), mu=float(np.max(np.abs(upd))),
+                         err=float(np.linalg.norm(g - w)), emax=float(diff.max()),
+                         slack_norm=walk * float(np.linalg.norm(w)), slack_elem=2.0 * walk * float(np.max(np.abs(w))),
+                         untouched_ok=bool(np.array_equal(g, z))))
+    return rows
+
+
+def assert_models_close(p, got, want, w0, tol, rounds, where=""):
+    """The parity bar, tensor by tensor and element by element.  For every W_l and b_l:
+      * ||g - w|| <= tol ||w||                      the stated tolerance on the parameters,
+      * ||g - w|| <= tol ||w - w0|| + slack         ... and on the update the rounds produced,
+      * max |g - w| <= ELEM tol max |w - w0| + slack   every element, in units of the tensor's largest update;
+    a tensor the oracle leaves unchanged must be unchanged bit for bit.  Returns the worst ratios."""
+    worst = dict(w=0.0, upd=0.0, elem=0.0)
+    for r in compare_models(p, got, want, w0, rounds):
+        tag = f"{where} {r['name']}"
+        assert r["finite"], f"{tag}: non-finite parameters"
+        if r["mu"] == 0.0:
+            assert r["untouched_ok"], f"{tag}: the oracle leaves this tensor unchanged, the library does not"
+            continue
+        assert r["err"] <= tol * r["nw"], f"{tag}: ||g-w||/||w|| = {r['err'] / r['nw']:.3e} > {tol}"
+        assert r["err"] <= tol * r["nu"] + r["slack_norm"], \
+            f"{tag}: update differs, ||g-w||/||w-w0|| = {r['err'] / r['nu']:.3e} > {tol}"
+        assert r["emax"] <= ELEM * tol * r["mu"] + r["slack_elem"], \
+            f"{tag}: element error {r['emax']:.3e} > {ELEM * tol} x largest update {r['mu']:.3e}"
+        worst["w"] = max(worst["w"], r["err"] / r["nw"])
+        worst["upd"] = max(worst["upd"], max(0.0, r["err"] - r["slack_norm"]) / r["nu"])
+        worst["elem"] = max(worst["elem"], max(0.0, r["emax"] - r["slack_elem"]) / r["mu"])
+    return worst
+
+
+def check_models(res, tol, label="", guard=None):
+    """All checkpoints of a run_pair result against the oracle, tensor by tensor.  `guard`, if given,
+    is a bound far inside the stated tolerance that the measured errors must also keep (both sides
+    narrow the same quantities at the same points and differ only in accumulation width and order, so
+    a kernel mistake of any size lands above it while rounding stays below)."""
+    p = res["o"].cfg
+    w0 = res["sim_inputs"]["w0"]
+    for cp, (g, w) in sorted(res["models"].items()):
+        worst = assert_models_close(p, g, w, w0, tol, cp, where=f"{label} round {cp}:")
+        print(f"{label} round {cp}: worst tensor rel {worst['w']:.2e}, update rel {worst['upd']:.2e}, "
+              f"element/max-update {worst['elem']:.2e}", flush=True)
+        if guard is not None:
+            assert max(worst["w"], worst["upd"]) <= guard, f"{label} round {cp}: outside the guard band {guard}: {worst}"
+
+
+def assert_matches_oracle(p, d, model, trace, T, tol, rerun, where=""):
+    """A library run of T rounds (its final model and trace) against a fresh oracle run.  When an
+    adaptive wait count flipped on a last-bit difference of a loss, the rounds up to the flip are
+    compared and `rerun(settings, k_replay) -> (model, trace)` repeats the library run with the
+    oracle's K sequence replayed; the comparison never falls away."""
+    o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False).run(T)
+    want = np.stack([trace_words(r, p["N"]) for r in o.trace])
+    keep = np.ones(want.shape[1], bool)
+    keep[LOSS_WORD] = False
+    flips = np.nonzero(trace[:, KNEXT_WORD] != want[:, KNEXT_WORD])[0]
+    if flips.size:
+        assert p["k_mode"] in (0, 3), f"{where}: K^(t+1) differs although the wait count is not adaptive"
+        first = int(flips[0])
+        keep[KNEXT_WORD] = False
+        assert np.array_equal(trace[:first + 1, keep], want[:first + 1, keep]), f"{where}: trace differs before the flip"
+        print(f"{where}: adaptive-K flip at round {first}; repeating with the oracle's K replayed", flush=True)
+        model, trace = rerun(dict(p, k_mode=2), [r["K"] for r in o.trace])
+    assert np.array_equal(trace[:, keep], want[:, keep]), f"{where}: integer trace differs from the oracle"
+    worst = assert_models_close(p, model, o.model(), d["w0"], tol, T, where=where)
+    print(f"{where}: worst tensor rel {worst['w']:.2e}, update rel {worst['upd']:.2e}, "
+          f"element/max-update {worst['elem']:.2e}", flush=True)
+    return worst
 
 
 def golden_path(name):

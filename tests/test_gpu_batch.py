@@ -7,8 +7,7 @@ import pytest
 
 import workloads
 import paper_2301_08895_amd as lib
-from oracle.abs_sim import AbsOracle, trace_words
-from parity_util import rel_err, LOSS_WORD, KNEXT_WORD
+from parity_util import assert_models_close, assert_matches_oracle, LOSS_WORD, KNEXT_WORD
 
 pytestmark = pytest.mark.gpu
 
@@ -36,6 +35,18 @@ def _same_schedule(tr, want):
         return False
     assert np.array_equal(tr[:, keep], want[:, keep])
     return True
+
+
+def _rerun_as_batch_of_one(d):
+    def rerun(q, k_replay):
+        sim = lib.Simulation(q, d, k_replay=k_replay)
+        one = lib.Batch([sim])
+        one.round(len(k_replay))
+        one.close()
+        out = (sim.model().copy(), sim.trace().copy())
+        sim.close()
+        return out
+    return rerun
 
 
 def _run(base, S, T, tol, loss_rtol, oracle_for=(0, 1), bitwise_alone=True):
@@ -68,15 +79,12 @@ def _run(base, S, T, tol, loss_rtol, oracle_for=(0, 1), bitwise_alone=True):
             plain.round(T)
             if _same_schedule(got[i][1], plain.trace()):
                 compared += 1
-                assert rel_err(got[i][0], plain.model()) <= tol, f"simulation {i} against its unbatched run"
+                assert_models_close(p, got[i][0], plain.model(), d["w0"], tol, T, where=f"simulation {i} against its unbatched run")
             plain.close()
         alone.close()
     assert bitwise_alone or compared >= S // 2
     for i in oracle_for:
-        o = AbsOracle(ps[i], d["X"], d["y"], d["w0"], keep_models=False).run(T)
-        want = np.stack([trace_words(r, ps[i]["N"]) for r in o.trace])
-        if _same_schedule(got[i][1], want):
-            assert rel_err(got[i][0], o.model()) <= tol
+        assert_matches_oracle(ps[i], d, got[i][0], got[i][1], T, tol, _rerun_as_batch_of_one(d), where=f"simulation {i}")
 
 
 def test_linear_batch():
@@ -179,10 +187,7 @@ def test_mlp_batch():
         assert np.array_equal(alone.model(), got[i][0]), f"simulation {i} differs from its unbatched run"
         assert np.array_equal(alone.trace(), got[i][1])
         alone.close()
-    o = AbsOracle(ps[1], d["X"], d["y"], d["w0"], keep_models=False).run(T)
-    want = np.stack([trace_words(r, ps[1]["N"]) for r in o.trace])
-    if _same_schedule(got[1][1], want):
-        assert rel_err(got[1][0], o.model()) <= 2e-2
+    assert_matches_oracle(ps[1], d, got[1][0], got[1][1], T, 2e-2, _rerun_as_batch_of_one(d), where="simulation 1")
 
 
 def test_batch_of_simulations_on_different_datasets():
@@ -204,9 +209,7 @@ def test_batch_of_simulations_on_different_datasets():
         one.close()
         assert np.array_equal(alone.model(), m) and np.array_equal(alone.trace(), tr)
         alone.close()
-        o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False).run(40)
-        if all(int(a) == r["K"] for a, r in zip(tr[:, 1], o.trace)):
-            assert rel_err(m, o.model()) <= 1e-5
+        assert_matches_oracle(p, d, m, tr, 40, 1e-5, _rerun_as_batch_of_one(d), where=f"dataset seed {p['seed_data']}")
 
 
 def test_batch_error_leaves_every_simulation_consistent():
@@ -293,7 +296,5 @@ def test_softmax_batch_random_shapes():
             b1.close()
             assert np.array_equal(one.model(), got[k][0]) and np.array_equal(one.trace(), got[k][1]), (case, k)
             one.close()
-            o = AbsOracle(ps[k], d["X"], d["y"], d["w0"], keep_models=False).run(8)
-            want = np.stack([trace_words(r, N) for r in o.trace])
-            if _same_schedule(got[k][1], want):
-                assert rel_err(got[k][0], o.model()) <= 1e-5, (case, k)
+            assert_matches_oracle(ps[k], d, got[k][0], got[k][1], 8, 1e-5, _rerun_as_batch_of_one(d),
+                                  where=f"case {case} simulation {k}")

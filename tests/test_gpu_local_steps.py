@@ -4,22 +4,14 @@ import numpy as np
 import pytest
 
 import workloads
-from parity_util import run_pair, assert_trace_equal, rel_err
+from parity_util import run_pair, assert_trace_equal, check_models
 
 pytestmark = pytest.mark.gpu
 
 
 def _check(res, tol, loss_rtol):
     assert_trace_equal(res, loss_rtol)
-    T = max(res["models"])
-    for cp, (g, w) in res["models"].items():
-        e = rel_err(g, w)
-        print(f"round {cp}: rel err {e:.3e}", flush=True)
-        assert np.all(np.isfinite(g)) and e <= tol, (cp, e)
-    g, w = res["models"][T]
-    w0 = res["sim_inputs"]["w0"].astype(np.float64)
-    if np.linalg.norm(w - w0) > 0:
-        assert rel_err(g - w0, w - w0) <= max(tol, 1e-4)
+    check_models(res, tol)
 
 
 @pytest.mark.parametrize("over,T", [

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import workloads
-from parity_util import run_pair, assert_trace_equal, rel_err
+from parity_util import run_pair, assert_trace_equal, check_models
 
 pytestmark = pytest.mark.gpu
 
@@ -22,8 +22,7 @@ def test_method(base, tol, loss_rtol, name):
     T = 25 if name in ("sync_sgd", "local_sgd") else 80
     res = run_pair(p, T, checkpoints=(1,))
     assert_trace_equal(res, loss_rtol)
-    for cp, (g, w) in res["models"].items():
-        assert np.all(np.isfinite(g)) and rel_err(g, w) <= tol, (name, cp, rel_err(g, w))
+    check_models(res, tol, label=name)
     tr = res["got"]
     if name in ("adasync", "sa_adasync", "k_async", "asgd", "sync_sgd", "local_sgd"):
         assert np.all(tr[:, 5] == 0)                       # no forced restarts without a threshold

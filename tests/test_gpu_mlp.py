@@ -4,25 +4,18 @@ import numpy as np
 import pytest
 
 import workloads
-from parity_util import run_pair, assert_trace_equal, rel_err
+from parity_util import run_pair, assert_trace_equal, check_models
 
 pytestmark = pytest.mark.gpu
 
 BF16_TOL = 2e-2     # relative, stated for the bf16-input workloads
+BF16_GUARD = 5e-3   # per-tensor norms; measured at most 1.2e-3 (K = 4 at the largest shape), typically 1e-5 .. 3e-4
 
 
 def _check(res, tol=BF16_TOL):
     assert_trace_equal(res, 2e-3)
-    for cp, (g, w) in res["models"].items():
-        e = rel_err(g, w)
-        print(f"round {cp}: rel err {e:.3e}")
-        assert np.all(np.isfinite(g))
-        assert e <= tol, (cp, e)
-    # the update itself (w^T - w^0) must agree too, not only the weights it is small against
-    T = max(res["models"])
-    g, w = res["models"][T]
-    w0 = res["sim_inputs"]["w0"].astype(np.float64)
-    assert rel_err(g - w0, w - w0) <= tol, rel_err(g - w0, w - w0)
+    # every W_l and b_l separately, element by element, weights and updates (w^T - w^0)
+    check_models(res, tol, guard=BF16_GUARD)
 
 
 @pytest.mark.parametrize("over,T", [

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import workloads
-from parity_util import run_pair, assert_trace_equal, rel_err
+from parity_util import run_pair, assert_trace_equal, check_models
 
 pytestmark = pytest.mark.gpu
 
@@ -23,9 +23,7 @@ def test_linear_least_squares(over, T):
     p = workloads.scaled_preset(1, **over)
     res = run_pair(p, T, checkpoints=(1, 10))
     assert_trace_equal(res, 1e-4)
-    for cp, (g, w) in res["models"].items():
-        assert rel_err(g, w) <= FP32_TOL, (cp, rel_err(g, w))
-    assert np.all(np.isfinite(res["models"][T][0]))
+    check_models(res, FP32_TOL)
 
 
 @pytest.mark.parametrize("over,T", [
@@ -38,16 +36,14 @@ def test_softmax_regression(over, T):
     p = workloads.scaled_preset(2, **over)
     res = run_pair(p, T, checkpoints=(1, 10))
     assert_trace_equal(res, 1e-4)
-    for cp, (g, w) in res["models"].items():
-        assert rel_err(g, w) <= FP32_TOL, (cp, rel_err(g, w))
+    check_models(res, FP32_TOL)
 
 
 def test_softmax_full_workload():
     p = workloads.preset(2)
     res = run_pair(p, p["T"])
     assert_trace_equal(res, 1e-4)
-    g, w = res["models"][p["T"]]
-    assert rel_err(g, w) <= FP32_TOL
+    check_models(res, FP32_TOL)
     assert res["got"][-1, 1] == p["N"]          # K has grown to N
 
 
