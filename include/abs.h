@@ -177,6 +177,27 @@ int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y
                  double* h_loss, double* h_accuracy);
 
 /*
+ * abs_evaluate for callers that cannot allocate or synchronise: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The same kernels as abs_evaluate, but their
+ * scratch (the two fp64 sums, one pass's per-row losses and hit flags) is a fixed array of
+ * 256 + 8 ABS_STATIC_EVAL_ROWS bytes that the library itself holds in device memory, one copy per
+ * GPU from the library's load to the end of the process, and the result stays on the device:
+ *  d_out      DEVICE, caller-owned, two doubles: d_out[0] = mean loss, d_out[1] = accuracy (NaN
+ *             for the linear model), the values abs_evaluate returns, bit for bit.
+ * The call enqueues on the handle's stream and returns; it makes no hipMalloc / hipFree /
+ * hipHostMalloc, creates no event or stream, copies nothing to the host and does not wait.  Per-kernel
+ * timing (abs_config.profile) leaves these launches out.
+ * Limits: an MLP handle evaluates N x (B rounded up to 128) rows per pass, and that must not exceed
+ * ABS_STATIC_EVAL_ROWS (ABS_E_WORKSPACE otherwise; the regression models pass 16384 rows at a time);
+ * n_rows itself is not limited.  All handles on a GPU share the one array, which keeps the last
+ * call's contents (the call clears what it accumulates into): two such calls that overlap in time on
+ * one GPU - different streams, different handles - race; calls on one stream are safe.
+ */
+#define ABS_STATIC_EVAL_ROWS 65536
+int abs_evaluate_static(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
+                        double* d_out);
+
+/*
  * Copy trace records of rounds [round_lo, round_hi) to h_out.  One record is
  * ABS_TRACE_HEADER + 3 N int32 words:
  *   0 t   1 K^t   2 floor(tau_max^t) (INT32_MAX: none)   3,4 completion tick lo,hi

@@ -65,6 +65,8 @@ def _load():
     lib.abs_round.argtypes = [vp, i32]
     lib.abs_evaluate.restype = C.c_int
     lib.abs_evaluate.argtypes = [vp, i64, vp, vp, i64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.abs_evaluate_static.restype = C.c_int
+    lib.abs_evaluate_static.argtypes = [vp, i64, vp, vp, i64, vp]
     lib.abs_batch_create.restype = C.c_int
     lib.abs_batch_create.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
     lib.abs_batch_round.restype = C.c_int
@@ -190,6 +192,11 @@ def abs_evaluate(handle: int, version: int, d_X: int, d_y: int, n_rows: int):
     loss, acc = C.c_double(), C.c_double()
     _check(_lib.abs_evaluate(handle, version, d_X, d_y, n_rows, C.byref(loss), C.byref(acc)), handle)
     return loss.value, acc.value
+
+
+def abs_evaluate_static(handle: int, version: int, d_X: int, d_y: int, n_rows: int, d_out: int) -> None:
+    """Enqueue the evaluation; (mean loss, accuracy) land in the two doubles at device address d_out."""
+    _check(_lib.abs_evaluate_static(handle, version, d_X, d_y, n_rows, d_out), handle)
 
 
 def abs_trace(handle: int, round_lo: int, round_hi: int, N: int) -> np.ndarray:

@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <thread>
 #include <vector>
@@ -113,6 +114,41 @@ void reg_plan(const abs_config& c, RegPlan& p) {
   p.total = o;
 }
 
+// Scratch of abs_evaluate_static: the two fp64 sums, then per-row losses and hit flags of one pass
+// (laid out as eval_scratch_bytes() says).  One copy per GPU, held from the library's load to the
+// process's end; the name is a host-side stand-in, device code gets the address that
+// hipGetSymbolAddress reports on the device in question.
+constexpr int kStaticEvalRows = ABS_STATIC_EVAL_ROWS;
+constexpr size_t kStaticScratchBytes = 256 + 2 * ((size_t)kStaticEvalRows * 4);
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
+
+// The device's own address of g_static_scratch, resolved once per device (with that device
+// current: abs_create calls this for the device the handle is created on).
+hipError_t static_scratch_of_current_device(int* dev_out, void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess) return e;
+    g_static_ptr[dev] = p;
+  }
+  *dev_out = dev;
+  *ptr_out = g_static_ptr[dev];
+  return hipSuccess;
+}
+
+struct NoHook : LaunchHook {
+  void begin(int, double, double) override {}
+  void end(int) override {}
+};
+
 struct Stat {
   int64_t launches = 0; double ms = 0, flops = 0, bytes = 0;
   int64_t timed_launches = 0; double timed_flops = 0, timed_bytes = 0;   // the launches bracketed by events
@@ -141,6 +177,8 @@ struct abs_ctx : public LaunchHook {
   MlpArgs margs{};
   LossMailbox* h_box = nullptr;   // pinned, device-visible
   LossMailbox* d_box = nullptr;   // the device's address of h_box
+  int device = -1;                // the GPU the handle was created on
+  void* static_scratch = nullptr; // that GPU's copy of the evaluation scratch (abs_evaluate_static)
   std::string err;
   Stat stats[KK_COUNT];
   // profile mode: one event pair per launch of the current round
@@ -265,6 +303,9 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
   std::memset(c->h_box, 0, sizeof(LossMailbox));
   e = hipHostGetDevicePointer((void**)&c->d_box, c->h_box, 0);
   if (e != hipSuccess) return fail("hipHostGetDevicePointer", e);
+
+  e = static_scratch_of_current_device(&c->device, &c->static_scratch);
+  if (e != hipSuccess) return fail("hipGetSymbolAddress", e);
 
   const uint64_t shard = (uint64_t)(cfg->M / cfg->N);
   const uint64_t bkey = stream_key(cfg->seed, kStreamBatch);
@@ -742,9 +783,10 @@ int abs_get_model(abs_ctx* ctx, int64_t version, float* h_out, size_t n_floats) 
   return ABS_OK;
 }
 
-int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
-                 double* h_loss, double* h_accuracy) {
-  if (!ctx || !h_loss || !h_accuracy) return ABS_E_ARG;
+// Checks the arguments common to both evaluation calls and enqueues the passes: per-row losses and
+// hit flags into `scratch` (layout of eval_scratch_bytes(cap)), their fp64 sums into its first 16 bytes.
+static int enqueue_evaluation(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
+                              char* scratch, LaunchHook* hook, EvalArgs& e) {
   if (!ctx->cfg.device_mode) { ctx->err = "no model in schedule-only mode"; return ABS_E_ARG; }
   if (!d_X || !d_y) { ctx->err = "evaluation set pointers are NULL"; return ABS_E_ARG; }
   if (n_rows < 1 || n_rows > 0xFFFFFFFFll) { ctx->err = "n_rows must be in [1, 2^32)"; return ABS_E_ARG; }
@@ -756,8 +798,6 @@ int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y
   const abs_config& cfg = ctx->cfg;
   const uint32_t slot = (uint32_t)(version % ctx->R);
   const bool mlp = cfg.model == ABS_MODEL_MLP;
-  char* scratch = ctx->ws + (mlp ? ctx->margs.plan.off_eval : ctx->rplan.off_eval);
-  EvalArgs e;
   e.X = d_X; e.y = d_y; e.n_rows = n_rows;
   e.cap = mlp ? ctx->margs.plan.Mp : kEvalChunk;
   e.acc = (double*)scratch;
@@ -765,18 +805,47 @@ int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y
   e.correct = (float*)(scratch + 256 + ((size_t)e.cap * 4 + 255) / 256 * 256);
   hipError_t err;
   if (mlp) {
-    err = launch_mlp_eval(ctx->margs, slot, e, ctx->stream, ctx);
+    err = launch_mlp_eval(ctx->margs, slot, e, ctx->stream, hook);
   } else {
     const float* w = (const float*)(ctx->ws + ctx->off_ring) + (size_t)slot * ctx->slot_stride;
-    err = launch_regression_eval(w, cfg.dims[0], cfg.dims[1], cfg.model == ABS_MODEL_SOFTMAX, e, ctx->stream, ctx);
+    err = launch_regression_eval(w, cfg.dims[0], cfg.dims[1], cfg.model == ABS_MODEL_SOFTMAX, e, ctx->stream, hook);
   }
   if (err != hipSuccess) { ctx->err = std::string("kernel launch: ") + hipGetErrorString(err); return ABS_E_HIP; }
+  return ABS_OK;
+}
+
+int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
+                 double* h_loss, double* h_accuracy) {
+  if (!ctx || !h_loss || !h_accuracy) return ABS_E_ARG;
+  const bool mlp = ctx->cfg.model == ABS_MODEL_MLP;
+  char* scratch = ctx->ws ? ctx->ws + (mlp ? ctx->margs.plan.off_eval : ctx->rplan.off_eval) : nullptr;
+  EvalArgs e;
+  const int rc = enqueue_evaluation(ctx, version, d_X, d_y, n_rows, scratch, ctx, e);
+  if (rc != ABS_OK) return rc;
   double acc[2];
   ABS_HIP(ctx, hipMemcpyAsync(acc, e.acc, sizeof(acc), hipMemcpyDeviceToHost, ctx->stream));
   ABS_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  if (cfg.profile) ctx->harvest();
+  if (ctx->cfg.profile) ctx->harvest();
   *h_loss = acc[0] / (double)n_rows;
-  *h_accuracy = cfg.model == ABS_MODEL_LINEAR ? std::nan("") : acc[1] / (double)n_rows;
+  *h_accuracy = ctx->cfg.model == ABS_MODEL_LINEAR ? std::nan("") : acc[1] / (double)n_rows;
+  return ABS_OK;
+}
+
+int abs_evaluate_static(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
+                        double* d_out) {
+  if (!ctx || !d_out) return ABS_E_ARG;
+  if (ctx->cfg.device_mode && ctx->cfg.model == ABS_MODEL_MLP && ctx->margs.plan.Mp > kStaticEvalRows) {
+    ctx->err = "abs_evaluate_static: a pass of this handle is N x (B rounded up to 128) = " +
+               std::to_string(ctx->margs.plan.Mp) + " rows, more than the " + std::to_string(kStaticEvalRows) +
+               " rows (ABS_STATIC_EVAL_ROWS) the library's fixed scratch holds; use abs_evaluate";
+    return ABS_E_WORKSPACE;
+  }
+  NoHook quiet;      // no per-kernel events here: creating one would allocate
+  EvalArgs e;
+  const int rc = enqueue_evaluation(ctx, version, d_X, d_y, n_rows, (char*)ctx->static_scratch, &quiet, e);
+  if (rc != ABS_OK) return rc;
+  const hipError_t err = launch_eval_finish(e, ctx->cfg.model == ABS_MODEL_LINEAR, d_out, ctx->stream);
+  if (err != hipSuccess) { ctx->err = std::string("kernel launch: ") + hipGetErrorString(err); return ABS_E_HIP; }
   return ABS_OK;
 }
 

@@ -100,6 +100,8 @@ struct EvalArgs {
 inline size_t eval_scratch_bytes(size_t cap) { return 256 + 2 * ((cap * 4 + 255) / 256 * 256); }
 hipError_t launch_eval_clear(const EvalArgs& e, hipStream_t s);
 hipError_t launch_eval_reduce(const EvalArgs& e, int n, hipStream_t s, LaunchHook* hook);
+// d_out[0] = acc[0] / n_rows (mean loss), d_out[1] = acc[1] / n_rows (accuracy; NaN when `linear`)
+hipError_t launch_eval_finish(const EvalArgs& e, bool linear, double* d_out, hipStream_t s);
 // w: the model version to evaluate (fp32, boundary layout); softmax = false: linear least squares
 hipError_t launch_regression_eval(const float* w, int d, int C, bool softmax, const EvalArgs& e,
                                   hipStream_t s, LaunchHook* hook);

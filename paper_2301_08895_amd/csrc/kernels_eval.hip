@@ -77,7 +77,19 @@ __global__ __launch_bounds__(1024) void eval_reduce_kernel(const float* rowloss,
   if (threadIdx.x == 0) { acc[0] += s_l[0]; acc[1] += s_c[0]; }
 }
 
+__global__ void eval_finish_kernel(const double* acc, double n_rows, int linear, double* out) {
+  if (threadIdx.x == 0) {
+    out[0] = acc[0] / n_rows;
+    out[1] = linear ? __longlong_as_double(0x7FF8000000000000ll) : acc[1] / n_rows;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_eval_finish(const EvalArgs& e, bool linear, double* d_out, hipStream_t s) {
+  eval_finish_kernel<<<dim3(1), dim3(64), 0, s>>>(e.acc, (double)e.n_rows, linear ? 1 : 0, d_out);
+  return hipGetLastError();
+}
 
 hipError_t launch_eval_clear(const EvalArgs& e, hipStream_t s) {
   eval_clear_kernel<<<dim3(1), dim3(64), 0, s>>>(e.acc);
