@@ -22,7 +22,7 @@ enum KernelKind {
   KK_MLP_FWD_L1,
   KK_MLP_FWD_HIDDEN,
   KK_MLP_FWD_LOGITS,
-  KK_MLP_SOFTMAX_CE,
+  KK_MLP_LOGITS_CE,
   KK_MLP_LOSS,
   KK_MLP_DGRAD_OUT,
   KK_MLP_DGRAD,

@@ -140,7 +140,51 @@ struct GemmArgs {
   // order (16 bytes per lane and tile: [tile][wavefront][lane][4 words], word mi, bit (4 ni + rg) 4 + rr).
   // EPI_RELU writes it when set; EPI_DGRAD reads it instead of maskT when set.
   uint32_t* maskbits;
+  // GATHER with gen_rows set: the kernel draws the minibatch rows itself (stacked row m = upload
+  // m / rows_per_upload, sample m % rows_per_upload; Section II-A: independent uniform draws from the
+  // worker's shard) instead of reading a_rowidx, and the workgroups of the first column tile leave
+  // them, with their labels, in gen_rowidx / gen_label for the kernels that follow.
+  int gen_rows;
+  int gen_B;                          // samples per upload (rows beyond are padding: label -1)
+  uint64_t gen_shard_rows, gen_batch_key;
+  uint32_t gen_draw0;                 // first draw index of this step (local step u: u B)
+  const int32_t* gen_y;
+  uint32_t* gen_rowidx; int32_t* gen_label;
+  // EPI_DGRAD with pub_mailbox set: the first workgroup publishes the uploads' mean minibatch losses
+  // (sums of pub_nb row blocks each, left by the output-layer kernel) before it starts on its tile.
+  LossMailbox* pub_mailbox; const float* pub_rowloss; int pub_nb; int pub_B;
 };
+
+// Dataset row of stacked row m (and whether it carries a sample).
+__device__ __forceinline__ uint32_t gen_row_of(const GemmArgs& g, const RoundDesc& rd, int m, bool* real) {
+  const int up = m / g.rows_per_upload, b = m - up * g.rows_per_upload;
+  const WorkerDesc w = rd.w[up];
+  uint64_t row = (uint64_t)w.id * g.gen_shard_rows;
+  *real = b < g.gen_B;
+  if (b < g.gen_B) row += draw(job_key(g.gen_batch_key, w.id, w.job), g.gen_draw0 + (uint32_t)b) % g.gen_shard_rows;
+  return (uint32_t)row;
+}
+__device__ __forceinline__ void gen_row_store(const GemmArgs& g, int m, uint32_t row, bool real) {
+  g.gen_rowidx[m] = row;
+  g.gen_label[m] = real ? g.gen_y[row] : -1;
+}
+
+// The uploads' mean minibatch losses (what each worker reports next to its gradient) into the
+// mailbox, then the stamp: thread a < K adds the loss sums of upload a's row blocks in order.  Every
+// wavefront that wrote fences at system scope before the barrier, so the host that sees the stamp
+// sees the losses.  Whole workgroup, uniform call.
+__device__ __forceinline__ void publish_upload_losses(LossMailbox* box, const float* rowloss, int nb, int B,
+                                                      int K, uint32_t stamp) {
+  const int up = threadIdx.x;
+  if (up < K) {
+    float sum = 0.f;
+    for (int q = 0; q < nb; ++q) sum += rowloss[(size_t)up * nb + q];
+    box->loss[up] = sum / (float)B;
+  }
+  if (threadIdx.x < ABS_MAX_WORKERS) __threadfence_system();
+  __syncthreads();
+  if (threadIdx.x == 0) box->stamp = stamp;
+}
 
 // 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
 // 32x32x16 MFMA blocks (TN = 256: 2 x 4 blocks, 128 accumulator registers).  A and B
@@ -185,6 +229,9 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
   const int ks0 = zsplit * g.ksteps_per_split;
   const int ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
 
+  if (EPI == EPI_DGRAD && g.pub_mailbox && blockIdx.x == 0)
+    publish_upload_losses(g.pub_mailbox, g.pub_rowloss, g.pub_nb, g.pub_B, rd.K, rd.stamp);
+
   const uint16_t* Bt = g.Bt;
   uint32_t slot = 0;
   if (PER_UPLOAD) {
@@ -197,10 +244,22 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
   const int st_off = r0 * BK + (((t & 7) ^ ((r0 >> 1) & 7)) << 3);   // swizzled LDS offset of chunk i = 0
   const uint16_t* pa0; const uint16_t* pa1; const uint16_t* pa2; const uint16_t* pa3;
   if (GATHER) {
-    pa0 = g.A + (size_t)g.a_rowidx[m0 + r0] * g.lda + c8;
-    pa1 = g.A + (size_t)g.a_rowidx[m0 + r0 + 32] * g.lda + c8;
-    pa2 = g.A + (size_t)g.a_rowidx[m0 + r0 + 64] * g.lda + c8;
-    pa3 = g.A + (size_t)g.a_rowidx[m0 + r0 + 96] * g.lda + c8;
+    uint32_t ri[4];
+    if (g.gen_rows) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bool real;
+        ri[i] = gen_row_of(g, rd, m0 + r0 + 32 * i, &real);
+        if (n0 == 0 && (t & 7) == 0) gen_row_store(g, m0 + r0 + 32 * i, ri[i], real);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ri[i] = g.a_rowidx[m0 + r0 + 32 * i];
+    }
+    pa0 = g.A + (size_t)ri[0] * g.lda + c8;
+    pa1 = g.A + (size_t)ri[1] * g.lda + c8;
+    pa2 = g.A + (size_t)ri[2] * g.lda + c8;
+    pa3 = g.A + (size_t)ri[3] * g.lda + c8;
   } else {
     pa0 = g.A + (size_t)(m0 + r0) * g.lda + c8;
     pa1 = pa0 + 32 * g.lda; pa2 = pa0 + 64 * g.lda; pa3 = pa0 + 96 * g.lda;
@@ -442,6 +501,9 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const int ks0 = zsplit * g.ksteps_per_split;
   const int ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
 
+  if (EPI == EPI_DGRAD && g.pub_mailbox && blockIdx.x == 0)
+    publish_upload_losses(g.pub_mailbox, g.pub_rowloss, g.pub_nb, g.pub_B, rd.K, rd.stamp);
+
   const uint16_t* Bt = g.Bt;
   uint32_t slot = 0;
   if (PER_UPLOAD) {
@@ -467,10 +529,22 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   uint32_t aidx0 = 0, aidx1 = 0, aidx2 = 0, aidx3 = 0;       // dataset rows of the next tile to request
   if (kATR) {
   } else if (GATHER) {
-    pa0 = g.A + (size_t)g.a_rowidx[m0 + dr] * g.lda + c_even;
-    pa1 = g.A + (size_t)g.a_rowidx[m0 + dr + 8] * g.lda + c_odd;
-    pa2 = g.A + (size_t)g.a_rowidx[m0 + dr + 16] * g.lda + c_even;
-    pa3 = g.A + (size_t)g.a_rowidx[m0 + dr + 24] * g.lda + c_odd;
+    uint32_t ri[4];
+    if (g.gen_rows) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bool real;
+        ri[i] = gen_row_of(g, rd, m0 + dr + 8 * i, &real);
+        if (n0 == 0 && pc == 0) gen_row_store(g, m0 + dr + 8 * i, ri[i], real);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ri[i] = g.a_rowidx[m0 + dr + 8 * i];
+    }
+    pa0 = g.A + (size_t)ri[0] * g.lda + c_even;
+    pa1 = g.A + (size_t)ri[1] * g.lda + c_odd;
+    pa2 = g.A + (size_t)ri[2] * g.lda + c_even;
+    pa3 = g.A + (size_t)ri[3] * g.lda + c_odd;
   } else {
     const uint16_t* base = g.A + (size_t)(m0 + dr) * g.lda;
     pa0 = base + c_even; pa1 = base + 8 * g.lda + c_odd;
@@ -717,83 +791,220 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
 }
 
-// ------------------------------------------------------------------ softmax cross-entropy
-// A wavefront per stacked row (16 wavefronts, 4 rows each, 64 rows per workgroup): the 64 rows'
-// loss sum (rowloss[workgroup]), dZ_L = c_k (softmax - onehot) narrowed
-// to bf16 (zero for padding rows and padding columns), in both orientations.
-template <int NC>   // columns per lane: padded class count / 64
-__global__ __launch_bounds__(1024) void mlp_softmax_ce_kernel(const float* Z, size_t ldz, int C, const int32_t* label,
-                                                            RoundDesc rd, int Bp, uint16_t* dZ, size_t lddz,
-                                                            uint16_t* dZT, size_t lddzt, float* rowloss,
-                                                            float* colsum, size_t ldcs) {
-  __shared__ uint16_t sT[NC * 64][72];
-  __shared__ float s_l[16];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int m0 = blockIdx.x * 64;
-  const float coef = rd.w[m0 / Bp].c;
-  float zin[4][NC];                      // the wavefront's four rows: all loads first
-  int labs[4];
+// ------------------------------------------------------------------ output layer: logits, loss, dZ_L
+// The last layer's product, the softmax cross-entropy and the output gradient in one kernel: the
+// class count is at most 256, so a workgroup that owns 128 stacked rows owns their whole logit rows
+// and nothing of Z_L ever goes to memory.  The product is narrow (few classes) and long (the last
+// hidden width): what bounds it is how many bytes a CU keeps in flight, so the 64-wide k-steps of
+// the A tile (128 rows of H_{L-1}) and the B tile (all classes of W_L^T) go from global memory
+// straight into a ring of LDS stages (global_load_lds_dwordx4, swizzled on the global side as in the
+// large-tile GEMM), kStages - 1 steps ahead of their use, one barrier per step.  Wavefront w owns
+// rows 32 w .. 32 w + 31 and all classes, and multiplies the other way round - W_L^T is the
+// MFMA's row operand, the activations its column operand - so that the 32x32 blocks hold Z_L^T:
+// accumulator register r of lane l is class 32 b + 8 (r / 4) + 4 (l / 32) + r % 4 of row l % 32.
+// All classes of a row then sit in the registers of two lanes (l and l + 32), and its softmax is
+// arithmetic inside a lane plus one exchange, instead of a 32-lane reduction per row and class.
+// Outputs: dZ_L = c_k (softmax - onehot) narrowed to bf16 (zero in padding rows and classes) in
+// both orientations, the 128 rows' loss sum, and the column sums of the narrowed dZ_L (the bias
+// gradient's share of these rows).
+constexpr int kCeRows = 128;             // stacked rows per workgroup of the output-layer kernel
+
+struct LogitsCeArgs {
+  const uint16_t* H; size_t ldh;         // H_{L-1} [rows][ldh]
+  int ksteps;                            // dp_{L-1} / 64
+  const uint16_t* Wt; size_t ldw;        // W_L^T [dp_L][ldw] inside a shadow slot
+  size_t w_slot_stride;
+  const float* bias; size_t bias_slot_stride;
+  int C;                                 // classes (columns >= C are padding)
+  int rows_per_upload, by_upload;
+  const int32_t* label;                  // -1: padding row
+  uint16_t* dZ; size_t lddz;             // [rows][lddz]
+  uint16_t* dZT; size_t lddzt;           // [dp_L][lddzt]
+  float* rowloss;                        // [rows / 128]
+  float* colsum; size_t ldcs;            // [rows / 128][ldcs]
+};
+
+__device__ __forceinline__ void lds_dma16_raw(const uint16_t* gsrc, uint16_t* lds_block);
+
+template <int NB>                        // dp_L = 32 NB: 2, 4 or 8
+__global__ __launch_bounds__(256, 1) void mlp_logits_ce_kernel(LogitsCeArgs a, RoundDesc rd) {
+  constexpr int NP = 32 * NB;            // padded class count
+  constexpr int kStageElems = (kCeRows + NP) * BK;
+  constexpr int kStages = NB == 8 ? 3 : 4;
+  constexpr int kPitchD = NP + 8;        // narrowed dZ tile, bf16 [128][kPitchD], after the main loop ...
+  constexpr int kPitchT = kCeRows + 8;   // ... and its transpose, bf16 [NP][kPitchT], behind it
+  static_assert(kStages * kStageElems >= kCeRows * kPitchD + NP * kPitchT, "staging fits the ring");
+  static_assert(kStages * kStageElems * 2 <= 150 * 1024, "LDS budget");
+  constexpr int kDmaPerWave = 4 + NB;    // requests per wavefront and stage (8 rows of 128 bytes each)
+  __shared__ __attribute__((aligned(16))) uint16_t smem[kStages * kStageElems];
+  __shared__ float s_l[4];
+  __shared__ __attribute__((aligned(16))) float s_bias[NP];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int m0 = blockIdx.x * kCeRows;
+  const int up = m0 / a.rows_per_upload;
+  const uint32_t slot = a.by_upload ? (uint32_t)up : rd.w[up].slot;
+  const float coef = rd.w[up].c;
+  const uint16_t* Wt = a.Wt + (size_t)slot * a.w_slot_stride;
+
+  // requests of this wavefront: its own 32 rows of A (4 requests) and NP / 4 rows of B (NB requests);
+  // lane l of a request fills position l & 7 of row r8 + (l >> 3) with chunk (l & 7) ^ ((row >> 1) & 7)
+  const int lr = lane >> 3, lp = lane & 7;
+  const uint16_t* ga[4]; const uint16_t* gb[NB];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int m = m0 + wave * 4 + i;
-    labs[i] = label[m];
-#pragma unroll
-    for (int q = 0; q < NC; ++q) {
-      const int c = lane + 64 * q;
-      zin[i][q] = c < C ? Z[(size_t)m * ldz + c] : -INFINITY;
-    }
+    const int row = wave * 32 + 8 * i + lr;
+    ga[i] = a.H + (size_t)(m0 + row) * a.ldh + ((lp ^ ((row >> 1) & 7)) << 3);
   }
-  float lsum = 0.f;                      // lane 0: loss of the wavefront's rows
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int ml = wave * 4 + i, m = m0 + ml;
-    const int lab = labs[i];
-    float z[NC];
-    float zmax = -INFINITY;
-#pragma unroll
-    for (int q = 0; q < NC; ++q) {
-      z[q] = zin[i][q];
-      zmax = fmaxf(zmax, z[q]);
-    }
-    zmax = wave_max(zmax);
-    float ssum = 0.f, zy = 0.f;
-#pragma unroll
-    for (int q = 0; q < NC; ++q) {
-      const int c = lane + 64 * q;
-      if (c == lab) zy = z[q] - zmax;
-      z[q] = c < C ? expf(z[q] - zmax) : 0.f;
-      ssum += z[q];
-    }
-    ssum = wave_sum(ssum);
-    zy = wave_sum(zy);
-    if (lane == 0) lsum += lab >= 0 ? logf(ssum) - zy : 0.f;
-#pragma unroll
-    for (int q = 0; q < NC; ++q) {
-      const int c = lane + 64 * q;
-      float v = 0.f;
-      if (lab >= 0 && c < C) v = coef * (z[q] / ssum - (c == lab ? 1.f : 0.f));
-      const uint16_t h = f32_to_bf16(v);
-      dZ[(size_t)m * lddz + c] = h;
-      sT[c][ml] = h;
-    }
+  for (int i = 0; i < NB; ++i) {
+    const int row = wave * (NP / 4) + 8 * i + lr;
+    gb[i] = Wt + (size_t)row * a.ldw + ((lp ^ ((row >> 1) & 7)) << 3);
   }
+  uint16_t* const dmaA = smem + (wave * 32) * BK;
+  uint16_t* const dmaB = smem + kCeRows * BK + (wave * (NP / 4)) * BK;
+#define ABS_CE_DMA(ks_)                                                            \
+  {                                                                                \
+    const int k0_ = (ks_) * BK;                                                    \
+    uint16_t* st_ = smem + ((ks_) % kStages) * kStageElems;                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                  \
+      lds_dma16_raw(ga[i] + k0_, st_ + (dmaA - smem) + i * 512);                   \
+    _Pragma("unroll") for (int i = 0; i < NB; ++i)                                 \
+      lds_dma16_raw(gb[i] + k0_, st_ + (dmaB - smem) + i * 512);                   \
+  }
+  f32x16_t acc[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+  const int l32 = lane & 31, lk = lane >> 5;
+  const int sw = (l32 >> 1) & 7;
+  const int fa_row = (wave * 32 + l32) * BK, fb_row = kCeRows * BK + l32 * BK;
+  const int nk = a.ksteps;
+  // what the epilogue needs from memory is requested before the main loop: the label of the lane's
+  // row, and the biases, which wait in LDS (padding classes: -inf, so they drop out of max and sum)
+  const int lab = a.label[m0 + wave * 32 + l32];
+  if (t < NP) s_bias[t] = t < a.C ? (a.bias + (size_t)slot * a.bias_slot_stride)[t] : -INFINITY;
+#pragma unroll
+  for (int st = 0; st < kStages - 1; ++st)
+    if (st < nk) ABS_CE_DMA(st);
+  for (int ks = 0; ks < nk; ++ks) {
+    // this wavefront's requests of step ks have landed once at most those of the steps behind it
+    // (kStages - 2 of them, kDmaPerWave requests each) are still in flight; near the end: all
+    if (ks + kStages - 2 < nk) __builtin_amdgcn_s_waitcnt(0x0F70 | (((kStages - 2) * kDmaPerWave) & 15) |
+                                                          ((((kStages - 2) * kDmaPerWave) >> 4) << 14));
+    else                       __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();                     // everybody's part of step ks is in LDS; everybody is done with step ks - 1
+    if (ks + kStages - 1 < nk) ABS_CE_DMA(ks + kStages - 1);
+    const uint16_t* sS = smem + (ks % kStages) * kStageElems;
+    // fragments of sub-step s + 1 are read while the MFMAs of sub-step s run
+    bf16x8_t fa[2], fb[2][NB];
+#define ABS_CE_FRAGS(set, s_)                                                      \
+  {                                                                                \
+    const int ch_ = ((((s_) << 1) | lk) ^ sw) << 3;                                \
+    fa[set] = *(const bf16x8_t*)&sS[fa_row + ch_];                                 \
+    _Pragma("unroll") for (int b = 0; b < NB; ++b)                                 \
+      fb[set][b] = *(const bf16x8_t*)&sS[fb_row + b * 32 * BK + ch_];              \
+  }
+    ABS_CE_FRAGS(0, 0);
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      if (sub < 3) ABS_CE_FRAGS((sub + 1) & 1, sub + 1);
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[sub & 1][b], fa[sub & 1], acc[b], 0, 0, 0);
+    }
+#undef ABS_CE_FRAGS
+    // issue order: the first fragment set, then per sub-step one read ahead and one read behind each MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 1 + NB, 0);
+#pragma unroll
+    for (int sub = 0; sub < 3; ++sub) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
+  }
+#undef ABS_CE_DMA
+  __syncthreads();                       // all fragment reads done before the ring is reused for staging
+
+  // ---- softmax cross-entropy: the lane's 16 NB classes of row l % 32, its partner holds the rest
+  uint16_t* const sD = smem;             // [128][kPitchD]
+  uint16_t* const sT = smem + kCeRows * kPitchD;       // [NP][kPitchT]
+  const int ml = wave * 32 + l32;
+  float zmax = -INFINITY;
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 bq = *(const float4*)&s_bias[b * 32 + q * 8 + lk * 4];
+      acc[b][q * 4 + 0] += bq.x; acc[b][q * 4 + 1] += bq.y; acc[b][q * 4 + 2] += bq.z; acc[b][q * 4 + 3] += bq.w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) zmax = fmaxf(zmax, acc[b][q * 4 + e]);
+    }
+  zmax = fmaxf(zmax, __shfl_xor(zmax, 32, 64));
+  const int lrel = lab - lk * 4;         // the label relative to this half's class offset
+  float ssum = 0.f, zy = 0.f;
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float dz = acc[b][r] - zmax;
+      zy = (b * 32 + (r >> 2) * 8 + (r & 3) == lrel) ? dz : zy;
+      acc[b][r] = __expf(dz);
+      ssum += acc[b][r];
+    }
+  ssum += __shfl_xor(ssum, 32, 64);
+  zy += __shfl_xor(zy, 32, 64);
+  float lsum = lab >= 0 ? logf(ssum) - zy : 0.f;       // this row's loss (same in both of its lanes)
+  const float cr = lab >= 0 ? coef : 0.f;              // c_k (softmax - onehot), zero for padding rows
+  const float scale = cr / ssum;
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      uint16_t h[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float v = acc[b][q * 4 + e] * scale - ((b * 32 + q * 8 + e == lrel) ? cr : 0.f);
+        h[e] = __builtin_bit_cast(uint16_t, (__bf16)v);
+        sT[(b * 32 + q * 8 + lk * 4 + e) * kPitchT + ml] = h[e];       // (32 lanes: 64 contiguous bytes)
+      }
+      uint2 o;
+      o.x = h[0] | ((uint32_t)h[1] << 16);
+      o.y = h[2] | ((uint32_t)h[3] << 16);
+      *(uint2*)&sD[ml * kPitchD + b * 32 + q * 8 + lk * 4] = o;
+    }
+  // the 32 rows of the wavefront (lanes of a half), then the four wavefronts, always in this order
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o, 64);
   if (lane == 0) s_l[wave] = lsum;
   __syncthreads();
-  if (threadIdx.x == 0) {                // the 64 rows' losses, in wavefront order
-    float l = 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) l += s_l[v];
-    rowloss[blockIdx.x] = l;
+  if (t == 0) a.rowloss[blockIdx.x] = (s_l[0] + s_l[1]) + (s_l[2] + s_l[3]);
+  // row-major copy: 16-byte pieces, NP / 8 per row
+  for (int q = t; q < kCeRows * (NP / 8); q += 256) {
+    const int row = q / (NP / 8), ch = q % (NP / 8);
+    *(uint4*)(a.dZ + (size_t)(m0 + row) * a.lddz + ch * 8) = *(const uint4*)&sD[row * kPitchD + ch * 8];
   }
-  for (int q = threadIdx.x; q < NC * 64 * 8; q += 1024) {
-    const int c = q >> 3, ch = q & 7;
-    *(uint4*)(dZT + (size_t)c * lddzt + m0 + ch * 8) = *(const uint4*)&sT[c][ch * 8];
+  // transposed copy: class n, 16-byte pieces of 8 consecutive rows
+  for (int q = t; q < NP * (kCeRows / 8); q += 256) {
+    const int n = q / (kCeRows / 8), rb8 = (q % (kCeRows / 8)) * 8;
+    *(uint4*)(a.dZT + (size_t)n * a.lddzt + m0 + rb8) = *(const uint4*)&sT[n * kPitchT + rb8];
   }
-  if (threadIdx.x < NC * 64) {            // the bias gradient's share of these 64 rows
+  // the bias gradient's share of these 128 rows: class n's narrowed values added in row order
+  for (int n = t; n < NP; n += 256) {
     float c = 0.f;
-#pragma unroll 8
-    for (int ml = 0; ml < 64; ++ml) c += __uint_as_float((uint32_t)sT[threadIdx.x][ml] << 16);
-    colsum[(size_t)blockIdx.x * ldcs + threadIdx.x] = c;
+#pragma unroll 4
+    for (int p8 = 0; p8 < kCeRows / 8; ++p8) {
+      const uint4 v = *(const uint4*)&sT[n * kPitchT + p8 * 8];
+      c += __uint_as_float(v.x << 16); c += __uint_as_float(v.x & 0xFFFF0000u);
+      c += __uint_as_float(v.y << 16); c += __uint_as_float(v.y & 0xFFFF0000u);
+      c += __uint_as_float(v.z << 16); c += __uint_as_float(v.z & 0xFFFF0000u);
+      c += __uint_as_float(v.w << 16); c += __uint_as_float(v.w & 0xFFFF0000u);
+    }
+    a.colsum[(size_t)blockIdx.x * a.ldcs + n] = c;
   }
 }
 
@@ -922,7 +1133,7 @@ __global__ __launch_bounds__(256) void mlp_update_small_kernel(UpdateArgs u) {
 // ------------------------------------------------------------------ bias update
 // b_j <- b_j - sum over the rows of dZ_l[.][j] (Eq. 2 / Eq. 3 for the biases).  The producers of
 // dZ_l leave the column sums of every block of 64 rows; 16 threads per entry add them (partial
-// row g, g + 16, ... each, then the 16 shares in order).  Global form: all `prow` blocks, model
+// row g, g + 16, ... each, then the 16 shares in order).  Global form: all `prow[l]` blocks, model
 // w_cur -> w_next.  Per-upload form (local SGD, blockIdx.y = upload a): the blocks of a's own
 // rows, model slot cur_index[a] of w_cur -> slot a of w_next.
 struct BiasArgs {
@@ -931,7 +1142,7 @@ struct BiasArgs {
   const float* colsum[ABS_MAX_LAYERS]; size_t ldcs[ABS_MAX_LAYERS];
   size_t b_off[ABS_MAX_LAYERS];
   const float* w_cur; float* w_next;
-  int prow;                                // blocks of 64 rows (per upload in the per-upload form)
+  int prow[ABS_MAX_LAYERS];                // row blocks of colsum[l] (per upload in the per-upload form)
   int batched;
   size_t cur_stride, next_stride;
   uint16_t cur_index[ABS_MAX_WORKERS];
@@ -947,14 +1158,15 @@ __global__ __launch_bounds__(256) void mlp_bias_kernel(BiasArgs a) {
   if (w < ncol) {
     while (w >= a.col_begin[l + 1]) ++l;
     j = w - a.col_begin[l];
-    const float* src = a.colsum[l] + (size_t)(a.batched ? up * a.prow : 0) * a.ldcs[l] + j;
+    const int prow = a.prow[l];
+    const float* src = a.colsum[l] + (size_t)(a.batched ? up * prow : 0) * a.ldcs[l] + j;
     int r = grp;
-    for (; r + 48 < a.prow; r += 64) {       // four loads in flight
+    for (; r + 48 < prow; r += 64) {         // four loads in flight
       const float v0 = src[(size_t)r * a.ldcs[l]], v1 = src[(size_t)(r + 16) * a.ldcs[l]];
       const float v2 = src[(size_t)(r + 32) * a.ldcs[l]], v3 = src[(size_t)(r + 48) * a.ldcs[l]];
       s += v0; s += v1; s += v2; s += v3;
     }
-    for (; r < a.prow; r += 16) s += src[(size_t)r * a.ldcs[l]];
+    for (; r < prow; r += 16) s += src[(size_t)r * a.ldcs[l]];
   }
   s_part[grp][cl] = s;
   __syncthreads();
@@ -968,26 +1180,22 @@ __global__ __launch_bounds__(256) void mlp_bias_kernel(BiasArgs a) {
   }
 }
 
-// The uploads' mean minibatch losses (what each worker reports next to its gradient), one
-// thread per upload over the loss sums of its blocks of 64 rows, then the mailbox stamp.  Runs right after the
-// loss kernel so that the host can prepare the next round under this round's backward pass.
-// Local SGD: lossacc carries the sum over the job's steps; only the last step publishes.
-__global__ __launch_bounds__(128) void mlp_loss_kernel(const float* rowloss, int B, int Bp, int K, uint32_t stamp,
+// Local SGD: the uploads' mean minibatch losses of one local step, one thread per upload over the
+// loss sums of its `nb` row blocks; lossacc carries the sum over the job's steps and the last step
+// publishes the job's average local loss (worker part of Algorithm 1).  (With U = 1 the first
+// workgroup of the input-gradient kernel publishes: publish_upload_losses.)
+__global__ __launch_bounds__(128) void mlp_loss_kernel(const float* rowloss, int B, int nb, int K, uint32_t stamp,
                                                        LossMailbox* mailbox, float* lossacc, int first, int last,
                                                        int U) {
   __shared__ float s_loss[ABS_MAX_WORKERS];
   const int up = threadIdx.x;
-  if (up < K) {                          // rowloss: the loss sums of the upload's blocks of 64 rows
-    const int nb = Bp / 64;
+  if (up < K) {
     float s = 0.f;
     for (int q = 0; q < nb; ++q) s += rowloss[(size_t)up * nb + q];
     s /= (float)B;
-    if (lossacc) {
-      s += first ? 0.f : lossacc[up];
-      lossacc[up] = s;
-      s /= (float)U;
-    }
-    s_loss[up] = s;
+    s += first ? 0.f : lossacc[up];
+    lossacc[up] = s;
+    s_loss[up] = s / (float)U;
   }
   __syncthreads();
   if (last) publish_losses(mailbox, s_loss, K, stamp);
@@ -1160,7 +1368,7 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
     p.off_dzt[l] = take(p.ldm * p.dp[l] * 2);
   }
   p.off_rowloss = take(Mp * 4);
-  for (int l = 1; l <= L; ++l) p.off_colsum[l] = take(Mp / 64 * p.dp[l] * 4);
+  for (int l = 1; l <= L; ++l) p.off_colsum[l] = take(Mp / (l == L ? kCeRows : 64) * p.dp[l] * 4);
   for (int l = 1; l < L; ++l) p.off_maskbits[l] = take(round_up(Mp, 256) * round_up((size_t)p.dp[l], 256) / 8);
   p.off_partial = take(p.partial_floats * 4);
   if (p.U > 1) {
@@ -1295,22 +1503,33 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   return false;
 }
 
-// Forward pass over `rows` stacked rows (rowidx gives the rows of Xsrc): H_l and H_l^T for the
-// hidden layers, fp32 logits; the model of the rows of upload a is slot rd.w[a].slot of the
-// ring given by wbase / sbase (own: slot a of the private models).
+// Forward pass over `rows` stacked rows: H_l and H_l^T for the hidden layers; the model of the rows
+// of upload a is slot rd.w[a].slot of the ring given by wbase / sbase (own: slot a of the private
+// models).  draw0 >= 0 (training): the first layer draws the minibatch rows itself (draw index
+// draw0 + sample) and leaves them in rowidx / label, and the pass stops before the output layer
+// (launch_logits_ce takes over); draw0 < 0 (evaluation): rowidx holds the rows of Xsrc and the fp32
+// logits are written.
 // Returns the set of hidden layers l (bit l) whose ReLU mask bits were written (want_bits and the
 // layer's product ran on the 256 x 256 tile kernel).
 unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd, int rows, double arows,
-                     const float* wbase, const uint16_t* sbase, bool own, bool want_bits, hipStream_t s,
-                     LaunchHook* hook) {
+                     const float* wbase, const uint16_t* sbase, bool own, bool want_bits, long draw0,
+                     hipStream_t s, LaunchHook* hook) {
   unsigned have_bits = 0;
   const MlpPlan& p = a.plan;
   const int L = p.L;
-  const uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
-  for (int l = 0; l < L; ++l) {
+  uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
+  const bool train = draw0 >= 0;
+  for (int l = 0; l < (train ? L - 1 : L); ++l) {
     GemmArgs g{};
-    if (l == 0) { g.A = Xsrc; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0]; }
-    else        { g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.ld[l]; }
+    if (l == 0) {
+      g.A = Xsrc; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx; g.a_kvalid = p.d[0];
+      if (train) {
+        g.gen_rows = 1; g.gen_B = p.B; g.gen_shard_rows = a.shard_rows; g.gen_batch_key = a.batch_key;
+        g.gen_draw0 = (uint32_t)draw0; g.gen_y = a.y; g.gen_rowidx = rowidx; g.gen_label = at<int32_t>(a, p.off_label);
+      }
+    } else {
+      g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.ld[l];
+    }
     g.Bt = sbase + p.wt_off[l]; g.ldb = (size_t)p.ld[l];
     g.bt_slot_stride = p.shadow_stride;
     g.by_upload = own;
@@ -1336,6 +1555,37 @@ unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd
     }
   }
   return have_bits;
+}
+
+// Output layer of a training pass: logits, loss sums per 32 rows, dZ_L in both orientations and its
+// column sums, in one kernel (mlp_logits_ce_kernel).
+void launch_logits_ce(const MlpArgs& a, const RoundDesc& rd, int rows, double arows, const float* wbase,
+                      const uint16_t* sbase, bool own, hipStream_t s, LaunchHook* hook) {
+  const MlpPlan& p = a.plan;
+  const int L = p.L;
+  LogitsCeArgs c{};
+  c.H = at<uint16_t>(a, p.off_h[L - 1]); c.ldh = (size_t)p.ld[L - 1];
+  c.ksteps = p.dp[L - 1] / BK;
+  c.Wt = sbase + p.wt_off[L - 1]; c.ldw = (size_t)p.ld[L - 1];
+  c.w_slot_stride = p.shadow_stride;
+  c.bias = wbase + p.b_off[L - 1]; c.bias_slot_stride = p.slot_stride;
+  c.C = p.d[L];
+  c.rows_per_upload = p.Bp; c.by_upload = own;
+  c.label = at<int32_t>(a, p.off_label);
+  c.dZ = at<uint16_t>(a, p.off_dz[L]); c.lddz = (size_t)p.ld[L];
+  c.dZT = at<uint16_t>(a, p.off_dzt[L]); c.lddzt = p.ldm;
+  c.rowloss = at<float>(a, p.off_rowloss);
+  c.colsum = at<float>(a, p.off_colsum[L]); c.ldcs = (size_t)p.dp[L];
+  hook->begin(KK_MLP_LOGITS_CE, 2.0 * arows * p.d[L - 1] * p.d[L] + arows * p.d[L] * 8.0,
+              arows * (p.d[L - 1] * 2.0 + p.d[L] * 4.0));
+  plan_note("logits_ce", kCeRows, p.dp[L], 1);
+  const dim3 grid(rows / kCeRows), block(256);
+  switch (p.dp[L] / 64) {
+    case 1: ABS_LAUNCH(mlp_logits_ce_kernel<2><<<grid, block, 0, s>>>(c, rd)); break;
+    case 2: ABS_LAUNCH(mlp_logits_ce_kernel<4><<<grid, block, 0, s>>>(c, rd)); break;
+    default: ABS_LAUNCH(mlp_logits_ce_kernel<8><<<grid, block, 0, s>>>(c, rd)); break;
+  }
+  hook->end(KK_MLP_LOGITS_CE);
 }
 
 }  // namespace
@@ -1377,46 +1627,23 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     const float* wbase = own ? priv : ring;
     const uint16_t* sbase = own ? pshadow : shadow;
 
-    hook->begin(KK_MLP_INDEX, 0, arows * 12.0);
-    ABS_LAUNCH(mlp_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, a.y, rd, p.B, p.Bp,
-                                                                               a.shard_rows, a.batch_key,
-                                                                               (uint32_t)step * (uint32_t)p.B));
-    hook->end(KK_MLP_INDEX);
-
     // The first layer's weight gradient reads the minibatch rows straight from the dataset when
     // it runs on the 256 x 256 tile kernel and the rows are whole tiles wide; otherwise it needs
     // the transposed bf16 copy of the gathered rows.
     const bool wg0_direct = p.d[0] % TM3 == 0 && gemm_is_big(false, false, GemmArgs{}, p.dp[0], p.dp[1],
                                                                wgrad_split(p, 0, rows, local ? K : 0));
-    if (!wg0_direct) {
-      hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
-      plan_note("gather_t", 64, 64, 1);
-      ABS_LAUNCH(mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
-                                                                                         at<uint16_t>(a, p.off_xgt), p.ldm));
-      hook->end(KK_MLP_GATHER_T);
-    }
 
-    // ---- forward at the uploads' model versions
-    const unsigned have_bits = mlp_forward(a, a.X, rd, rows, arows, wbase, sbase, own, true, s, hook);
+    // ---- forward at the uploads' model versions; the first layer draws the minibatch rows
+    const unsigned have_bits = mlp_forward(a, a.X, rd, rows, arows, wbase, sbase, own, true,
+                                           (long)step * (long)p.B, s, hook);
 
-    // ---- loss and output gradient, already scaled by the uploads' coefficients
-    {
-      hook->begin(KK_MLP_SOFTMAX_CE, arows * p.d[L] * 8.0, arows * p.d[L] * 8.0);
-      const dim3 grid(rows / 64), block(1024);
-      const float* Z = at<float>(a, p.off_z);
-      uint16_t* dz = at<uint16_t>(a, p.off_dz[L]);
-      uint16_t* dzt = at<uint16_t>(a, p.off_dzt[L]);
-      float* rl = at<float>(a, p.off_rowloss);
-      const size_t ld = (size_t)p.dp[L], lddz = (size_t)p.ld[L];
-      switch (p.dp[L] / 64) {
-        case 1: ABS_LAUNCH(mlp_softmax_ce_kernel<1><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld)); break;
-        case 2: ABS_LAUNCH(mlp_softmax_ce_kernel<2><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld)); break;
-        default: ABS_LAUNCH(mlp_softmax_ce_kernel<4><<<grid, block, 0, s>>>(Z, ld, p.d[L], label, rd, p.Bp, dz, lddz, dzt, p.ldm, rl, at<float>(a, p.off_colsum[L]), ld)); break;
-      }
-      hook->end(KK_MLP_SOFTMAX_CE);
+    // ---- output layer: loss and output gradient, already scaled by the uploads' coefficients
+    launch_logits_ce(a, rd, rows, arows, wbase, sbase, own, s, hook);
+    const int loss_blocks = p.Bp / kCeRows;          // row blocks of the loss sums per upload
+    if (local) {
       hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
-      ABS_LAUNCH(mlp_loss_kernel<<<dim3(1), dim3(128), 0, s>>>(rl, p.B, p.Bp, K, rd.stamp, a.mailbox,
-                                                                local ? at<float>(a, p.off_lossacc) : nullptr,
+      ABS_LAUNCH(mlp_loss_kernel<<<dim3(1), dim3(128), 0, s>>>(at<float>(a, p.off_rowloss), p.B, loss_blocks, K,
+                                                                rd.stamp, a.mailbox, at<float>(a, p.off_lossacc),
                                                                 step == 0, step == U - 1, U));
       hook->end(KK_MLP_LOSS);
     }
@@ -1435,6 +1662,12 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       g.out = l >= 2 ? at<uint16_t>(a, p.off_dz[l]) : nullptr; g.ldo = (size_t)p.ld[l];
       g.outT = at<uint16_t>(a, p.off_dzt[l]); g.ldoT = p.ldm;
       g.colsum = at<float>(a, p.off_colsum[l]); g.ldcs = (size_t)p.dp[l];
+      if (!local && l == L - 1) {
+        // the losses reach the host as the backward pass starts: it selects and enqueues the next
+        // round while the device is still in this one
+        g.pub_mailbox = a.mailbox; g.pub_rowloss = at<float>(a, p.off_rowloss);
+        g.pub_nb = loss_blocks; g.pub_B = p.B;
+      }
       // the product through the output layer contracts over the classes only: bandwidth-bound
       const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
       hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
@@ -1446,6 +1679,13 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     // ---- weight gradients.  U = 1: one contraction over all stacked rows = the K-of-N
     //      reduction, split over row ranges for occupancy, then update + snapshot per layer.
     //      U > 1: split a = the rows of upload a, applied to that upload's private model.
+    if (!wg0_direct) {
+      hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
+      plan_note("gather_t", 64, 64, 1);
+      ABS_LAUNCH(mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
+                                                                                         at<uint16_t>(a, p.off_xgt), p.ldm));
+      hook->end(KK_MLP_GATHER_T);
+    }
     for (int l = L - 1; l >= 0; --l) {
       GemmArgs g{};
       g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = p.ldm;
@@ -1485,12 +1725,12 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       if (!local) {
         b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
         b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
-        b.prow = rows / 64;
+        for (int l = 0; l < L; ++l) b.prow[l] = rows / (l == L - 1 ? kCeRows : 64);
       } else {
         b.batched = 1;
         b.w_cur = wbase; b.cur_stride = p.slot_stride;
         b.w_next = priv; b.next_stride = p.slot_stride;
-        b.prow = p.Bp / 64;
+        for (int l = 0; l < L; ++l) b.prow[l] = p.Bp / (l == L - 1 ? kCeRows : 64);
         for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
       }
       hook->begin(KK_MLP_BIAS_LOSS, (double)c * rows / 64, (double)c * rows / 64 * 4.0);
@@ -1549,7 +1789,7 @@ hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, h
     mlp_eval_index_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(rowidx, label, (const int32_t*)e.y, row0, n, rows);
     hook->end(KK_EVAL);
     mlp_forward(a, (const uint16_t*)e.X, rd, rows, (double)n, at<float>(a, p.off_ring), at<uint16_t>(a, p.off_shadow),
-                false, false, s, hook);
+                false, false, -1, s, hook);
     hook->begin(KK_EVAL, 8.0 * n * p.d[p.L], 4.0 * n * p.d[p.L]);
     const dim3 grid((n + 3) / 4), block(256);
     const float* Z = at<float>(a, p.off_z);
