@@ -338,26 +338,37 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
   return ABS_OK;
 }
 
-// The device's view of round t of one simulation: the K^t uploads in arrival order with the ring
-// slot of their model version and their coefficient in Eq. 3.
-static void fill_round_desc(const abs_ctx* ctx, const std::vector<Upload>& sel, int64_t t, RoundDesc& rd) {
+// The device's view of round t of one simulation: the K^t uploads with the ring slot of their model
+// version and their coefficient in Eq. 3.  Regression models: in arrival order.  MLP: grouped by
+// model version (oldest first, arrival order inside a version), so that the stacked rows of the
+// uploads that computed at the same w^{t - tau} are contiguous - neighbouring tiles of the forward
+// and input-gradient products then share their weight operand (Eq. 2 evaluated per version) - and
+// Eq. 3's sum runs in that order; pos_of[a] = position of the a-th arrival (the trace and the
+// scheduler keep arrival order).
+static void fill_round_desc(const abs_ctx* ctx, const std::vector<Upload>& sel, int64_t t, RoundDesc& rd,
+                            int* pos_of = nullptr) {
   const abs_config& cfg = ctx->cfg;
   const int K = (int)sel.size();
   rd.K = K;
   rd.slot_cur = (uint32_t)(t % ctx->R);
   rd.slot_next = (uint32_t)((t + 1) % ctx->R);
   rd.stamp = (uint32_t)(t + 1);
-  for (int a = 0; a < K; ++a) {
-    const Upload& u = sel[(size_t)a];
+  int order[ABS_MAX_WORKERS];
+  for (int a = 0; a < K; ++a) order[a] = a;
+  if (cfg.model == ABS_MODEL_MLP)
+    std::stable_sort(order, order + K, [&](int x, int y) { return sel[(size_t)x].ver < sel[(size_t)y].ver; });
+  for (int pos = 0; pos < K; ++pos) {
+    const Upload& u = sel[(size_t)order[pos]];
+    if (pos_of) pos_of[order[pos]] = pos;
     // coefficient of this upload in Eq. 3: eta_k / (K^t B), eta_k = eta / max(1, tau_k) under
     // the staleness-aware penalty
     double eta = (double)cfg.lr;
     if (cfg.sa_penalty && u.tau > 1) eta /= (double)u.tau;
-    rd.w[a].id = (uint32_t)u.id;
-    rd.w[a].job = u.job;
-    rd.w[a].slot = (uint32_t)(u.ver % ctx->R);
+    rd.w[pos].id = (uint32_t)u.id;
+    rd.w[pos].job = u.job;
+    rd.w[pos].slot = (uint32_t)(u.ver % ctx->R);
     // (with U > 1 the 1/K^t of Eq. 3 is applied when the uploads' changes are averaged)
-    rd.w[a].c = cfg.U > 1 ? (float)(eta / (double)cfg.B) : (float)(eta / ((double)K * (double)cfg.B));
+    rd.w[pos].c = cfg.U > 1 ? (float)(eta / (double)cfg.B) : (float)(eta / ((double)K * (double)cfg.B));
   }
 }
 
@@ -397,7 +408,8 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       if (rc != ABS_OK) return rc;
       continue;
     }
-    fill_round_desc(ctx, sel, t, rd);
+    int pos_of[ABS_MAX_WORKERS];
+    fill_round_desc(ctx, sel, t, rd, pos_of);
     ctx->timing = cfg.profile == 1 || (cfg.profile > 1 && t % cfg.profile == 0);
     hipError_t e;
     if (cfg.model == ABS_MODEL_MLP) {
@@ -424,7 +436,7 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
       ctx->harvest();
     }
     float losses[ABS_MAX_WORKERS];
-    for (int a = 0; a < K; ++a) losses[a] = ctx->h_box->loss[a];
+    for (int a = 0; a < K; ++a) losses[a] = ctx->h_box->loss[pos_of[a]];
     rc = ctx->sched->complete(sel, losses, true, ctx->err);
     if (rc != ABS_OK) return rc;
   }

@@ -1041,7 +1041,10 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
   constexpr int TPR = TJ / 4;            // threads per row
   constexpr int RPP = 256 / TPR;         // rows per pass
   constexpr int NP = 64 / RPP;           // passes
-  __shared__ __attribute__((aligned(16))) uint16_t tile[64][TJ + 8];
+  // Row pitch TJ + 2: the transposed copy below reads, per wavefront, 8 columns x 8 blocks of 8 rows;
+  // with a pitch of 129 / 33 words the 8 row blocks start 8 banks apart and no two lanes collide
+  // (a pitch of TJ + 8 put them on two banks: the copy was a third of the kernel's time).
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64][TJ + 2];
   update_select_upload(u);
   const int i0 = blockIdx.y * 64, j0 = blockIdx.x * TJ;
   const int jq = (threadIdx.x % TPR) * 4, ir = threadIdx.x / TPR;
@@ -1083,7 +1086,8 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
         hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
         if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
       }
-      *(uint2*)&tile[il][jq] = hh;
+      *(uint32_t*)&tile[il][jq] = hh.x;
+      *(uint32_t*)&tile[il][jq + 2] = hh.y;
     }
   }
   __syncthreads();
