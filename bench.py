@@ -139,6 +139,58 @@ def _flops_at_full_k(p, kind):
     return sum(2.0 * rows * d[l] * d[l + 1] for l in range(1, len(d) - 1)) / max(1, len(d) - 2)
 
 
+def kernel_deltas(stats0, stats1):
+    """Per-kernel time and algorithmic work between two readings of abs_kernel_stats."""
+    kern = []
+    for name, s1 in stats1.items():
+        s0 = stats0.get(name, dict(timed_launches=0, total_ms=0.0, timed_flops=0.0, timed_bytes=0.0))
+        n = s1["timed_launches"] - s0["timed_launches"]      # the launches of the bracketed rounds
+        if n <= 0:
+            continue
+        kern.append(dict(name=name, launches=n, ms=s1["total_ms"] - s0["total_ms"],
+                         flops=s1["timed_flops"] - s0["timed_flops"], bytes=s1["timed_bytes"] - s0["timed_bytes"]))
+    return kern
+
+
+def roofline_of(kern, p, config):
+    """The roofline block for the kernel kind with the largest total time."""
+    if not kern:
+        return None
+    dom = max(kern, key=lambda k: k["ms"])
+    avg_s = dom["ms"] / dom["launches"] * 1e-3
+    if dom["name"] in MFMA_KINDS:
+        ach = dom["flops"] / dom["launches"] / avg_s / 1e12
+        # stored counters were taken at K = N; a launch's traffic scales with its rows
+        traffic = stored_traffic(dom["name"], None) if config == 5 else None
+        if traffic is not None:
+            traffic *= (dom["flops"] / dom["launches"]) / _flops_at_full_k(p, dom["name"])
+        return dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS, traffic=traffic,
+                    avg_launch_us=avg_s * 1e6, launches=dom["launches"])
+    ach = dom["bytes"] / dom["launches"] / avg_s / 1e9
+    return dict(bound="hbm", kernel=dom["name"], achieved=ach, peak=PEAK_HBM_GBS,
+                unit="GB/s", frac=ach / PEAK_HBM_GBS, traffic=None,
+                avg_launch_us=avg_s * 1e6, launches=dom["launches"])
+
+
+def calibrate_mfma(args):
+    """The MFMA-only loop of the library (no memory traffic), constant and random operands: what the
+    matrix cores sustain at the clock the chip settles at.  One JSON line."""
+    import torch
+    import paper_2301_08895_amd as lib
+    wgs, iters = 512, args.calibrate_iters
+    scratch = torch.zeros(wgs * 512, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {"mode": "calibrate_mfma", "workgroups": wgs, "iters": iters, "peak_tflops": PEAK_MFMA_BF16_TFLOPS, "runs": []}
+    for data_mode, label in ((0, "constant operands"), (1, "random bf16 operands")):
+        best = None
+        for _ in range(3):
+            ms, tf = lib.abs_calibrate_mfma(data_mode, iters, wgs, scratch.data_ptr(), stream)
+            best = (ms, tf) if best is None or tf > best[1] else best
+        out["runs"].append({"operands": label, "ms": best[0], "tflops": best[1], "frac_of_peak": best[1] / PEAK_MFMA_BF16_TFLOPS})
+    print(json.dumps(out))
+
+
 def bench_batch(args, p, inputs, warmup, steps):
     """S independent simulations (different simulation seeds) of a workload, advanced together by
     abs_batch_round: the sweep shape of the paper's experiments."""
@@ -212,6 +264,11 @@ def main():
                     help="local SGD: U minibatch steps per job (Eq. 2); a worker gradient is one such step")
     ap.add_argument("--batch", type=int, default=0,
                     help="configs 1-2: advance this many independent simulations (seeds) per launch")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="run the library's MFMA-only loop (constant and random operands), print its rate, exit")
+    ap.add_argument("--calibrate-iters", type=int, default=4000, help="iterations of the MFMA-only loop")
+    ap.add_argument("--full-k-rounds", type=int, default=8,
+                    help="MLP workloads: extra rounds at K = N after the timed region for the roofline_full_k block (0: none)")
     ap.add_argument("--traffic-import", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="write profiles/cfg5_hbm_traffic.txt from two rocprofv3 --pmc counter files and exit")
     args = ap.parse_args()
@@ -223,12 +280,16 @@ def main():
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
 
+    if args.calibrate_mfma:
+        return calibrate_mfma(args)
+
     import numpy as np
     import torch
     import workloads
     import paper_2301_08895_amd as lib
 
     p = workloads.preset(args.config)
+    mlp = p["model"] == 2
     if args.fixed_k:
         p["k_mode"], p["K0"] = 1, p["N"]
     if args.local_steps != 1:
@@ -265,33 +326,30 @@ def main():
     grads = int(tr[:, 1].sum()) * p.get("U", 1)
     value = grads / elapsed
 
-    # per-kernel time inside the timed region (HIP events on the launch stream)
-    kern = []
-    for name, s1 in stats1.items():
-        s0 = stats0.get(name, dict(timed_launches=0, total_ms=0.0, timed_flops=0.0, timed_bytes=0.0))
-        n = s1["timed_launches"] - s0["timed_launches"]      # the launches of the bracketed rounds
-        if n <= 0:
-            continue
-        kern.append(dict(name=name, launches=n, ms=s1["total_ms"] - s0["total_ms"],
-                         flops=s1["timed_flops"] - s0["timed_flops"], bytes=s1["timed_bytes"] - s0["timed_bytes"]))
-    roofline = None
-    if kern and not args.no_profile:
-        dom = max(kern, key=lambda k: k["ms"])
-        avg_s = dom["ms"] / dom["launches"] * 1e-3
-        if dom["name"] in MFMA_KINDS:
-            ach = dom["flops"] / dom["launches"] / avg_s / 1e12
-            # stored counters were taken at K = N; a launch's traffic scales with its rows
-            traffic = stored_traffic(dom["name"], None) if args.config == 5 else None
-            if traffic is not None:
-                traffic *= (dom["flops"] / dom["launches"]) / _flops_at_full_k(p, dom["name"])
-            roofline = dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS,
-                            unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS, traffic=traffic,
-                            avg_launch_us=avg_s * 1e6, launches=dom["launches"])
-        else:
-            ach = dom["bytes"] / dom["launches"] / avg_s / 1e9
-            roofline = dict(bound="hbm", kernel=dom["name"], achieved=ach, peak=PEAK_HBM_GBS,
-                            unit="GB/s", frac=ach / PEAK_HBM_GBS, traffic=None,
-                            avg_launch_us=avg_s * 1e6, launches=dom["launches"])
+    kern = kernel_deltas(stats0, stats1)
+    roofline = roofline_of(kern, p, args.config) if not args.no_profile else None
+
+    # The steady state of the job, K = N, on a few extra rounds of a second handle AFTER the timed
+    # region (the headline figures above are untouched): the wait count grows from K0 to N over the
+    # job (Eq. 5), so a short run only ever sees K = K0, where every product is a quarter the size.
+    roofline_full_k = None
+    if mlp and not args.no_profile and not args.fixed_k and args.full_k_rounds > 0:
+        q = dict(p, k_mode=1, K0=p["N"])
+        sim2 = lib.Simulation(q, inputs, profile=1)
+        sim2.round(3)
+        torch.cuda.synchronize()
+        a0 = {s_["name"]: s_ for s_ in sim2.kernel_stats()}
+        t2 = time.perf_counter()
+        sim2.round(args.full_k_rounds)
+        torch.cuda.synchronize()
+        el2 = time.perf_counter() - t2
+        a1 = {s_["name"]: s_ for s_ in sim2.kernel_stats()}
+        sim2.close()
+        roofline_full_k = roofline_of(kernel_deltas(a0, a1), q, args.config)
+        roofline_full_k.update(note=f"{args.full_k_rounds} extra rounds at fixed K = N = {p['N']} after the timed region; "
+                                    "not part of value / ms_per_step / roofline",
+                               ms_per_round=el2 / args.full_k_rounds * 1e3,
+                               worker_gradients_per_sec=p["N"] * args.full_k_rounds / el2)
     kernels = [dict(name=k["name"], launches=k["launches"], total_ms=round(k["ms"], 3),
                     avg_us=round(k["ms"] / k["launches"] * 1e3, 2),
                     tflops=round(k["flops"] / k["ms"] / 1e9, 1) if k["ms"] > 0 else None,
@@ -321,6 +379,7 @@ def main():
         "profile_every": 0 if args.no_profile else max(1, args.profile_every),
         "kernels": kernels,
         "roofline": roofline,
+        "roofline_full_k": roofline_full_k,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

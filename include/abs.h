@@ -27,7 +27,8 @@
  * abs_workspace_size (the size of the caller's allocation),
  * abs_get_model, abs_trace, abs_rounds_done, abs_kernel_stats, abs_mlp_round_plan
  * (reading results and bookkeeping out), abs_last_error, abs_batch_last_error,
- * abs_destroy, abs_batch_destroy.
+ * abs_destroy, abs_batch_destroy, abs_evaluate_static (abs_evaluate without allocations),
+ * abs_calibrate_mfma (a measurement aid).
  */
 #ifndef ABS_H
 #define ABS_H
@@ -287,6 +288,20 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out);
 int abs_batch_round(abs_batch* b, int32_t n_rounds);
 const char* abs_batch_last_error(const abs_batch* b);
 void abs_batch_destroy(abs_batch* b);
+
+/*
+ * Measurement aid, not part of the method: run nothing but the matrix-core instructions of the large
+ * GEMM tile (MFMA 32x32x16 bf16, 32 per wavefront and iteration, 8 wavefronts per workgroup, operands
+ * in registers, no memory traffic) and report the sustained rate, so that the GEMM kernels' figures
+ * can be read against what the chip's matrix cores deliver at the clock they settle at.
+ *  data_mode   0: all operand elements 1.0;  1: random bf16 values (sign, mantissa, exponent 2^-2..2^0)
+ *  iters       loop iterations per wavefront;  workgroups: grid size (e.g. 512 = two per CU)
+ *  d_scratch   DEVICE, at least workgroups * 512 floats (not written in practice)
+ *  h_ms, h_tflops  HOST: duration of one launch (HIP events on hip_stream) and 2 x 32 x 32 x 16 flops
+ *              per instruction over it.  Synchronises the stream.
+ */
+int abs_calibrate_mfma(int32_t data_mode, int32_t iters, int32_t workgroups, float* d_scratch,
+                       void* hip_stream, double* h_ms, double* h_tflops);
 
 /* Host-side helpers exposing the simulation's counter-based draws (for checking a
  * binding or planning a run; no device work): execution time of job j of worker n in

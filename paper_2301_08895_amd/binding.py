@@ -79,6 +79,8 @@ def _load():
     lib.abs_get_model.argtypes = [vp, i64, C.POINTER(C.c_float), sz]
     lib.abs_trace.restype = C.c_int
     lib.abs_trace.argtypes = [vp, i64, i64, C.POINTER(i32), sz, C.POINTER(sz)]
+    lib.abs_calibrate_mfma.restype = C.c_int
+    lib.abs_calibrate_mfma.argtypes = [i32, i32, i32, vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.abs_mlp_round_plan.restype = C.c_int
     lib.abs_mlp_round_plan.argtypes = [cfgp, i32, C.c_char_p, sz]
     lib.abs_rounds_done.restype = i64
@@ -207,6 +209,15 @@ def abs_trace(handle: int, round_lo: int, round_hi: int, N: int) -> np.ndarray:
                           out.size, C.byref(written)), handle)
     assert written.value == out.size
     return out
+
+
+def abs_calibrate_mfma(data_mode: int, iters: int, workgroups: int, d_scratch: int, hip_stream: int):
+    """(milliseconds, TFLOP/s) of one launch of the MFMA-only loop."""
+    ms, tf = C.c_double(), C.c_double()
+    rc = _lib.abs_calibrate_mfma(data_mode, iters, workgroups, d_scratch, hip_stream, C.byref(ms), C.byref(tf))
+    if rc != 0:
+        raise AbsError(rc, "abs_calibrate_mfma failed")
+    return ms.value, tf.value
 
 
 def abs_mlp_round_plan(cfg: AbsConfig, K: int) -> str:
