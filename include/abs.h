@@ -24,7 +24,7 @@
  * (Eq. 2-6), abs_evaluate the read-outs of Section V-B, abs_batch_* the sweeps of
  * Section V, abs_draw_* the random draws of Sections II-A and V-A.  Everything else
  * has no passage behind it and exists because a C library needs it: abs_config_bytes,
- * abs_workspace_size (the size of the caller's allocation),
+ * abs_workspace_size, abs_batch_workspace_size (sizes of the caller's allocations),
  * abs_get_model, abs_trace, abs_rounds_done, abs_kernel_stats, abs_mlp_round_plan
  * (reading results and bookkeeping out), abs_last_error, abs_batch_last_error,
  * abs_destroy, abs_batch_destroy, abs_evaluate_static (abs_evaluate without allocations),
@@ -251,9 +251,17 @@ void abs_destroy(abs_ctx* ctx);
  * the step size; Section V), and a single round of the small workloads is too little work for
  * one launch: a batch advances n simulations of one shape together, for the regression models
  * every round of all of them in one set of launches (one workgroup column per simulation).
+ *  abs_batch_workspace_size  bytes of device memory a batch of these handles needs (per-simulation
+ *                     kernel arguments, round descriptors, and for softmax rounds one gradient slot
+ *                     per upload: about 0.5 MB per simulation of 784 x 10, N = 16); 0 for MLP handles,
+ *                     and 0 with abs_batch_last_error(NULL) set if the handles cannot form a batch.
  *  abs_batch_create   ctxs: n handles (1 <= n <= 4096) created with the same model, dims, N, B, U
  *                     and stream, profile = 0; seeds, K0, a, tau settings, step sizes, time
- *                     models and datasets may differ.  The batch
+ *                     models and datasets may differ.  d_workspace: DEVICE, caller-owned, at least
+ *                     abs_batch_workspace_size() bytes, 256-byte aligned, used by the batch until
+ *                     abs_batch_destroy (may be NULL when the size is 0).  The library itself
+ *                     allocates only pinned host memory (descriptors, loss mailboxes), three
+ *                     streams and a few events.  The batch
  *                     borrows the handles: they must outlive it, and stay usable on their own
  *                     (abs_get_model, abs_trace, abs_evaluate, abs_round) between batch calls.
  *  abs_batch_round    n_rounds rounds of every simulation (each continues from its own round
@@ -284,7 +292,8 @@ void abs_destroy(abs_ctx* ctx);
  *                     on this thread).
  */
 typedef struct abs_batch abs_batch;
-int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out);
+size_t abs_batch_workspace_size(abs_ctx** ctxs, int32_t n);
+int abs_batch_create(abs_ctx** ctxs, int32_t n, void* d_workspace, size_t workspace_bytes, abs_batch** out);
 int abs_batch_round(abs_batch* b, int32_t n_rounds);
 const char* abs_batch_last_error(const abs_batch* b);
 void abs_batch_destroy(abs_batch* b);

@@ -67,8 +67,10 @@ def _load():
     lib.abs_evaluate.argtypes = [vp, i64, vp, vp, i64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.abs_evaluate_static.restype = C.c_int
     lib.abs_evaluate_static.argtypes = [vp, i64, vp, vp, i64, vp]
+    lib.abs_batch_workspace_size.restype = sz
+    lib.abs_batch_workspace_size.argtypes = [C.POINTER(vp), i32]
     lib.abs_batch_create.restype = C.c_int
-    lib.abs_batch_create.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
+    lib.abs_batch_create.argtypes = [C.POINTER(vp), i32, vp, sz, C.POINTER(vp)]
     lib.abs_batch_round.restype = C.c_int
     lib.abs_batch_round.argtypes = [vp, i32]
     lib.abs_batch_last_error.restype = C.c_char_p
@@ -170,10 +172,17 @@ def abs_get_model(handle: int, version: int, n_floats: int) -> np.ndarray:
     return out
 
 
-def abs_batch_create(handles) -> int:
+def abs_batch_workspace_size(handles) -> int:
+    """Bytes of device memory a batch of these handles needs; 0 for MLP handles, and 0 as well when
+    the handles cannot form a batch (abs_batch_create then says why)."""
+    arr = (C.c_void_p * len(handles))(*handles)
+    return _lib.abs_batch_workspace_size(arr, len(handles))
+
+
+def abs_batch_create(handles, d_workspace: int = 0, workspace_bytes: int = 0) -> int:
     arr = (C.c_void_p * len(handles))(*handles)
     out = C.c_void_p()
-    rc = _lib.abs_batch_create(arr, len(handles), C.byref(out))
+    rc = _lib.abs_batch_create(arr, len(handles), d_workspace or None, workspace_bytes, C.byref(out))
     if rc != 0:
         raise AbsError(rc, _lib.abs_batch_last_error(None).decode())
     return out.value
@@ -337,7 +346,14 @@ class Batch:
 
     def __init__(self, sims):
         self.sims = list(sims)
-        self.handle = abs_batch_create([s.handle for s in self.sims])
+        handles = [s.handle for s in self.sims]
+        self.handle = None
+        self.ws_bytes = abs_batch_workspace_size(handles)
+        self.d_ws, ptr = None, 0
+        if self.ws_bytes:
+            self.d_ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.sims[0].d_X.device)
+            ptr = (self.d_ws.data_ptr() + 255) // 256 * 256
+        self.handle = abs_batch_create(handles, ptr, self.ws_bytes)
 
     def round(self, n: int = 1):
         abs_batch_round(self.handle, n)

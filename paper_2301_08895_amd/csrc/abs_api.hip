@@ -468,36 +468,70 @@ void abs_batch_destroy(abs_batch* b) {
   for (hipStream_t s : b->own) if (s) { (void)hipStreamSynchronize(s); (void)hipStreamDestroy(s); }
   if (b->ev_in) (void)hipEventDestroy(b->ev_in);
   for (hipEvent_t e : b->ev_out) if (e) (void)hipEventDestroy(e);
-  if (b->d_args) (void)hipFree(b->d_args);
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < 2; ++i)
     if (b->h_rds[i]) (void)hipHostFree(b->h_rds[i]);
-    if (b->d_rds[i]) (void)hipFree(b->d_rds[i]);
-  }
   if (b->h_box) (void)hipHostFree(b->h_box);
-  if (b->d_slots) (void)hipFree(b->d_slots);
-  delete b;
+  delete b;          // (the device memory is the caller's workspace)
 }
 
-int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
-  if (out) *out = nullptr;
-  auto bad = [&](const char* m) { g_batch_error = m; return ABS_E_ARG; };
-  if (!ctxs || !out) return bad("NULL argument");
-  if (n < 1 || n > 4096) return bad("a batch holds 1..4096 simulations");
+namespace {
+// Checks that the handles can form a batch; the message of the first problem otherwise.
+const char* batch_problem(abs_ctx** ctxs, int32_t n) {
+  if (!ctxs) return "NULL argument";
+  if (n < 1 || n > 4096) return "a batch holds 1..4096 simulations";
   const abs_ctx* c0 = ctxs[0];
   for (int32_t i = 0; i < n; ++i) {
     const abs_ctx* c = ctxs[i];
-    if (!c) return bad("NULL handle in the batch");
-    for (int32_t j = 0; j < i; ++j) if (ctxs[j] == c) return bad("a handle appears twice in the batch");
-    if (!c->cfg.device_mode) return bad("schedule-only handles cannot be batched");
-    if (c->cfg.profile) return bad("batched rounds are not profiled per kernel (profile must be 0)");
+    if (!c) return "NULL handle in the batch";
+    for (int32_t j = 0; j < i; ++j) if (ctxs[j] == c) return "a handle appears twice in the batch";
+    if (!c->cfg.device_mode) return "schedule-only handles cannot be batched";
+    if (c->cfg.profile) return "batched rounds are not profiled per kernel (profile must be 0)";
     if (c->cfg.model != c0->cfg.model || c->cfg.dims[0] != c0->cfg.dims[0] || c->cfg.dims[1] != c0->cfg.dims[1] ||
         c->cfg.B != c0->cfg.B || c->cfg.N != c0->cfg.N || c->cfg.U != c0->cfg.U || c->stream != c0->stream)
-      return bad("all simulations of a batch need the same model, dims, N, B, U and stream");
+      return "all simulations of a batch need the same model, dims, N, B, U and stream";
+  }
+  return nullptr;
+}
+// Device memory of a batch of n handles shaped like c0, carved from the caller's workspace: the
+// per-simulation kernel arguments, two copies of the round descriptors (alternating by round) and,
+// for softmax rounds that keep one gradient per upload, N slots and N losses per simulation.
+struct BatchPlan { size_t rd_stride, off_args, off_rds[2], off_slots, slot_floats, sim_floats, total; bool slots; };
+BatchPlan batch_plan(const abs_ctx* c0, int32_t n) {
+  BatchPlan p{};
+  p.rd_stride = 16 + (size_t)c0->cfg.N * sizeof(WorkerDesc);
+  if (c0->cfg.model == ABS_MODEL_MLP) return p;      // MLP simulations keep their own launches and workspaces
+  size_t o = 0;
+  p.off_args = o; o = round_up(o + (size_t)n * sizeof(RegressionArgs), 256);
+  for (int i = 0; i < 2; ++i) { p.off_rds[i] = o; o = round_up(o + (size_t)n * p.rd_stride, 256); }
+  p.slot_floats = (size_t)c0->cfg.N * c0->slot_stride;
+  p.sim_floats = p.slot_floats + round_up((size_t)c0->cfg.N, 64);
+  p.slots = c0->cfg.U == 1 && regression_batch_uses_slots(c0->cfg.model == ABS_MODEL_SOFTMAX, c0->cfg.B);
+  p.off_slots = o; if (p.slots) o = round_up(o + (size_t)n * p.sim_floats * sizeof(float), 256);
+  p.total = o;
+  return p;
+}
+}  // namespace
+
+size_t abs_batch_workspace_size(abs_ctx** ctxs, int32_t n) {
+  if (const char* why = batch_problem(ctxs, n)) { g_batch_error = why; return 0; }
+  return batch_plan(ctxs[0], n).total;
+}
+
+int abs_batch_create(abs_ctx** ctxs, int32_t n, void* d_workspace, size_t workspace_bytes, abs_batch** out) {
+  if (out) *out = nullptr;
+  auto bad = [&](const char* m) { g_batch_error = m; return ABS_E_ARG; };
+  if (!out) return bad("NULL argument");
+  if (const char* why = batch_problem(ctxs, n)) return bad(why);
+  const abs_ctx* c0 = ctxs[0];
+  const BatchPlan plan = batch_plan(c0, n);
+  if (plan.total) {
+    if (!d_workspace || ((uintptr_t)d_workspace & 255)) return bad("d_workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < plan.total) { g_batch_error = "workspace smaller than abs_batch_workspace_size()"; return ABS_E_WORKSPACE; }
   }
   std::unique_ptr<abs_batch, void (*)(abs_batch*)> b(new abs_batch, abs_batch_destroy);
   b->ctx.assign(ctxs, ctxs + n);
   b->stream = c0->stream;
-  b->rd_stride = 16 + (size_t)c0->cfg.N * sizeof(WorkerDesc);
+  b->rd_stride = plan.rd_stride;
   auto hip = [&](hipError_t e, const char* what) {
     if (e == hipSuccess) return true;
     g_batch_error = std::string(what) + ": " + hipGetErrorString(e);
@@ -511,25 +545,23 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, abs_batch** out) {
   // MLP simulations keep their own launches, workspaces and mailboxes: the batch only runs them
   // side by side (abs_batch_round)
   if (c0->cfg.model == ABS_MODEL_MLP) { *out = b.release(); return ABS_OK; }
-  if (!hip(hipMalloc((void**)&b->d_args, (size_t)n * sizeof(RegressionArgs)), "hipMalloc")) return ABS_E_HIP;
+  char* ws = (char*)d_workspace;
+  b->d_args = (RegressionArgs*)(ws + plan.off_args);
   for (int i = 0; i < 2; ++i) {
     if (!hip(hipHostMalloc((void**)&b->h_rds[i], (size_t)n * b->rd_stride, hipHostMallocDefault), "hipHostMalloc")) return ABS_E_HIP;
-    if (!hip(hipMalloc((void**)&b->d_rds[i], (size_t)n * b->rd_stride), "hipMalloc")) return ABS_E_HIP;
+    b->d_rds[i] = ws + plan.off_rds[i];
   }
   if (!hip(hipHostMalloc((void**)&b->h_box, (size_t)n * sizeof(LossMailbox), hipHostMallocMapped), "hipHostMalloc")) return ABS_E_HIP;
   std::memset(b->h_box, 0, (size_t)n * sizeof(LossMailbox));
   if (!hip(hipHostGetDevicePointer((void**)&b->d_box, b->h_box, 0), "hipHostGetDevicePointer")) return ABS_E_HIP;
-  // softmax rounds of a batch keep one gradient per upload: N slots and N losses per simulation
-  const size_t slot_floats = (size_t)c0->cfg.N * c0->slot_stride, sim_floats = slot_floats + round_up((size_t)c0->cfg.N, 64);
-  if (c0->cfg.U == 1 && regression_batch_uses_slots(c0->cfg.model == ABS_MODEL_SOFTMAX, c0->cfg.B) &&
-      !hip(hipMalloc((void**)&b->d_slots, (size_t)n * sim_floats * sizeof(float)), "hipMalloc")) return ABS_E_HIP;
+  if (plan.slots) b->d_slots = ws + plan.off_slots;
   std::vector<RegressionArgs> args((size_t)n);
   for (int32_t i = 0; i < n; ++i) {
     fill_regression_args(ctxs[i], args[(size_t)i]);
     args[(size_t)i].mailbox = b->d_box + i;          // the batch's own mailboxes
     if (b->d_slots) {
-      args[(size_t)i].delta = (float*)b->d_slots + (size_t)i * sim_floats;
-      args[(size_t)i].lossbuf = args[(size_t)i].delta + slot_floats;
+      args[(size_t)i].delta = (float*)b->d_slots + (size_t)i * plan.sim_floats;
+      args[(size_t)i].lossbuf = args[(size_t)i].delta + plan.slot_floats;
     }
   }
   if (!hip(hipMemcpyAsync(b->d_args, args.data(), (size_t)n * sizeof(RegressionArgs), hipMemcpyHostToDevice, b->stream), "hipMemcpyAsync")) return ABS_E_HIP;

@@ -163,6 +163,40 @@ def test_batch_rejects_mixed_shapes_and_models():
         s.close()
 
 
+def test_batch_device_memory_comes_from_the_caller():
+    """The batch's device scratch is a workspace of abs_batch_workspace_size() bytes that the caller
+    brings: too small or missing is an error, MLP handles need none."""
+    import torch
+    p = workloads.scaled_preset(2, M=3000, dims=[32, 5], n_classes=5, N=8, B=12, lr=2e-2)
+    d = workloads.make_inputs(p)
+    sims = [lib.Simulation(dict(p, seed_sim=p["seed_sim"] + i), d) for i in range(3)]
+    handles = [s.handle for s in sims]
+    need = lib.abs_batch_workspace_size(handles)
+    assert need > 3 * (16 + 8 * 16) and need % 256 == 0
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    ptr = (ws.data_ptr() + 255) // 256 * 256
+    for args in ((0, 0), (ptr, need - 256), (ptr + 8, need)):
+        with pytest.raises(lib.AbsError) as e:
+            lib.abs_batch_create(handles, *args)
+        assert e.value.code in (-1, -2)
+    b = lib.abs_batch_create(handles, ptr, need)
+    lib.abs_batch_round(b, 5)
+    lib.abs_batch_destroy(b)
+    one = lib.Simulation(dict(p, seed_sim=p["seed_sim"] + 1), d)
+    b1 = lib.Batch([one])
+    b1.round(5)
+    b1.close()
+    assert np.array_equal(one.model(), sims[1].model())
+    for s in sims + [one]:
+        s.close()
+    pm = workloads.scaled_preset(3, M=2048, dims=[128, 64, 10], N=4, B=32, n_slow=1)
+    m = lib.Simulation(pm, workloads.make_inputs(pm))
+    assert lib.abs_batch_workspace_size([m.handle]) == 0
+    bm = lib.abs_batch_create([m.handle])
+    lib.abs_batch_destroy(bm)
+    m.close()
+
+
 def test_mlp_batch():
     """MLP simulations of a batch run side by side, each through its own rounds on a stream of the
     batch: bitwise the unbatched runs, also with more simulations than streams and over two calls."""

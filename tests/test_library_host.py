@@ -134,4 +134,5 @@ def test_batch_and_evaluate_argument_errors_without_a_gpu():
     assert e.value.code == -1 and "schedule-only" in str(e.value)
     with pytest.raises(lib.AbsError):
         lib.abs_batch_create([])
+    assert lib.abs_batch_workspace_size([a.handle, b.handle]) == 0     # no batch, no size
     a.close(); b.close()

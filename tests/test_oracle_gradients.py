@@ -135,3 +135,43 @@ def test_bf16_emulation_is_exact_on_representable_values_and_close_otherwise():
     (_, _), (gW2, gb2) = unpack(cfg, g_emu)
     assert np.allclose(gW2, h1.numpy().T @ dz, rtol=1e-13, atol=1e-18)
     assert np.allclose(gb2, dz.sum(axis=0), rtol=1e-13, atol=1e-18)
+
+
+def test_bf16_rounding_points_of_the_hidden_layers_against_a_library_narrowing():
+    """Every rounding point of the bf16 reading below the output layer, re-derived with torch's own
+    float32 -> bfloat16 conversion on a three-layer network: the input gradient uses the NARROWED
+    weights (dH = dZ Wq^T), it is masked by the narrowed activation (H > 0) and narrowed again before
+    it is used, and each weight gradient is H_{l-1}^T dZ_l of those narrowed factors, summed wide.  A
+    mistake in any of them (wide weights in the input gradient, the mask taken from the pre-activation,
+    a dZ_l used before narrowing, a transposed factor) moves the result by about 2^-8 of its size."""
+    dims = [6, 5, 4, 3]
+    cfg = _cfg(2, dims)
+    rng = np.random.default_rng(11)
+    B, s = 5, 0.37
+    X = round_bf16(rng.standard_normal((B, dims[0])))
+    y = rng.integers(0, dims[-1], B)
+    n = sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(3))
+    w = rng.standard_normal(n) * 0.6
+    g, _ = worker_update(cfg, w, X, y, s, emulate_bf16=True)
+    (W1, b1), (W2, b2), (W3, b3) = unpack(cfg, w)
+    (gW1, gb1), (gW2, gb2), (gW3, gb3) = unpack(cfg, g)
+
+    def narrow(a):                       # torch's conversion, not the oracle's helper
+        return torch.tensor(np.asarray(a)).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+
+    Wq = [narrow(W1), narrow(W2), narrow(W3)]
+    h1 = narrow(np.maximum(X @ Wq[0] + b1, 0.0))
+    h2 = narrow(np.maximum(h1 @ Wq[1] + b2, 0.0))
+    z3 = h2 @ Wq[2] + b3
+    P = scipy.special.softmax(z3, axis=1); P[np.arange(B), y] -= 1.0
+    dz3 = narrow((s / B) * P)
+    dz2 = narrow((dz3 @ Wq[2].T) * (h2 > 0.0))
+    dz1 = narrow((dz2 @ Wq[1].T) * (h1 > 0.0))
+    for got, want in ((gW3, h2.T @ dz3), (gb3, dz3.sum(0)), (gW2, h1.T @ dz2), (gb2, dz2.sum(0)),
+                      (gW1, X.T @ dz1), (gb1, dz1.sum(0))):
+        assert np.allclose(got, want, rtol=1e-12, atol=1e-18)
+    # the variants a wrong reading would give differ by far more than that
+    dz2_wide_w = narrow((dz3 @ W3.T) * (h2 > 0.0))
+    dz2_unnarrowed = (dz3 @ Wq[2].T) * (h2 > 0.0)
+    assert not np.allclose(gW2, h1.T @ dz2_wide_w, rtol=1e-6, atol=0)
+    assert not np.allclose(gW2, h1.T @ dz2_unnarrowed, rtol=1e-6, atol=0)
