@@ -208,6 +208,24 @@ struct abs_ctx : public LaunchHook {
       ev_used += 2;
     }
   }
+  void begin_kernel(int kind, double flops, double bytes, hipEvent_t* e0, hipEvent_t* e1) override {
+    stats[kind].launches += 1;
+    stats[kind].flops += flops;
+    stats[kind].bytes += bytes;
+    *e0 = nullptr; *e1 = nullptr;
+    if (timing) {
+      stats[kind].timed_launches += 1;
+      stats[kind].timed_flops += flops;
+      stats[kind].timed_bytes += bytes;
+      if (ev_used + 2 > ev.size()) {
+        for (int i = 0; i < 2; ++i) { hipEvent_t e; (void)hipEventCreate(&e); ev.push_back(e); }
+      }
+      *e0 = ev[ev_used]; *e1 = ev[ev_used + 1];
+    }
+  }
+  void end_kernel(int kind) override {
+    if (timing) { ev_kind.push_back(kind); ev_used += 2; }
+  }
   // Spin until the device has stamped the mailbox; every so often ask the runtime whether the
   // stream has failed or drained without the stamp, and give up after mailbox_timeout_s(), so
   // neither a broken launch nor a stream that never gets to run can hang the host.

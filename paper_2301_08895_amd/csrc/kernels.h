@@ -10,6 +10,15 @@ namespace abs_impl {
 struct LaunchHook {
   virtual void begin(int kind, double flops, double bytes) = 0;
   virtual void end(int kind) = 0;
+  // The same around a single launch that can carry its own start / stop events (hipExtLaunchKernel):
+  // the kernel's begin and end are then stamped by its dispatch itself, with no marker packets between
+  // the kernels of a round.  *e0 / *e1 come back null when the launch is not to be timed.  The default
+  // falls back on begin / end.
+  virtual void begin_kernel(int kind, double flops, double bytes, hipEvent_t* e0, hipEvent_t* e1) {
+    *e0 = nullptr; *e1 = nullptr;
+    begin(kind, flops, bytes);
+  }
+  virtual void end_kernel(int kind) { end(kind); }
   virtual ~LaunchHook() {}
 };
 

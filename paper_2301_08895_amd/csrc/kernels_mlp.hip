@@ -20,6 +20,7 @@
 // which is why activations and output gradients are stored in both orientations and
 // the weights' bf16 copies in both orientations.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <string>
@@ -1394,6 +1395,15 @@ namespace {
 // description of a round's launches comes from the very code that issues them.
 thread_local std::string* t_plan = nullptr;
 #define ABS_LAUNCH(...) do { if (!t_plan) { __VA_ARGS__; } } while (0)
+// A round's kernels carry their own start / stop events when the round is timed: kbegin() asks the
+// hook for the pair, the next ABS_LAUNCH_K attaches it to its dispatch (null events: a plain launch).
+thread_local hipEvent_t t_ev0 = nullptr, t_ev1 = nullptr;
+void kbegin(LaunchHook* hook, int kind, double flops, double bytes) { hook->begin_kernel(kind, flops, bytes, &t_ev0, &t_ev1); }
+void kend(LaunchHook* hook, int kind) { hook->end_kernel(kind); t_ev0 = t_ev1 = nullptr; }
+#define ABS_LAUNCH_K(kernel, grid, block, stream, ...)                                                    \
+  do {                                                                                                    \
+    if (!t_plan) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, t_ev0, t_ev1, 0, __VA_ARGS__);     \
+  } while (0)
 void plan_note(const char* what, int a, int b, int c) {
   if (t_plan) *t_plan += std::string(what) + ":" + std::to_string(a) + "x" + std::to_string(b) + "/" + std::to_string(c) + " ";
 }
@@ -1455,16 +1465,16 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
     u.wt = shadow + p.wt_off[l];
   }
   const double n = (double)p.d[l] * p.d[l + 1] * batch;
-  hook->begin(KK_MLP_UPDATE, n * (u.nsplit + 1), n * (4.0 * (u.nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
+  kbegin(hook, KK_MLP_UPDATE, n * (u.nsplit + 1), n * (4.0 * (u.nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
   const dim3 block(256);
   const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
   // wide tiles (fewer, longer stores) only where they still give every CU a workgroup
   const bool wide = p.d[l + 1] >= 256 && ((p.d[l + 1] + 255) / 256) * ((p.d[l] + 63) / 64) * batch >= 256;
   plan_note("update", 64, vec && wide ? 256 : vec ? 64 : 1, u.nsplit);
-  if (vec && wide) ABS_LAUNCH(mlp_update_kernel<256><<<dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u));
-  else if (vec) ABS_LAUNCH(mlp_update_kernel<64><<<dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, 0, s>>>(u));
-  else     ABS_LAUNCH(mlp_update_small_kernel<<<dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, 0, s>>>(u));
-  hook->end(KK_MLP_UPDATE);
+  if (vec && wide) ABS_LAUNCH_K((mlp_update_kernel<256>), dim3((p.d[l + 1] + 255) / 256, (p.d[l] + 63) / 64, batch), block, s, u);
+  else if (vec) ABS_LAUNCH_K((mlp_update_kernel<64>), dim3((p.d[l + 1] + 63) / 64, (p.d[l] + 63) / 64, batch), block, s, u);
+  else     ABS_LAUNCH_K(mlp_update_small_kernel, dim3((p.d[l] * p.d[l + 1] + 255) / 256, 1, batch), block, s, u);
+  kend(hook, KK_MLP_UPDATE);
 }
 
 // Whether a product goes to the 256 x 256 tile kernel.
@@ -1484,7 +1494,7 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
     plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : TAG == 2 ? "wgrad_x" : "wgrad",
               TM3, TN3, nsplit);
-    ABS_LAUNCH(mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG><<<dim3(8 * g.rows_per_xcd * g.nt), dim3(512), 0, s>>>(g, rd));
+    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt), dim3(512), s, g, rd);
     return true;
   }
   // widest column tile that still fills the GPU: 256-wide tiles only with two workgroups per CU
@@ -1501,9 +1511,9 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   const dim3 block(256);
   const dim3 grid1(8 * g.rows_per_xcd * g.nt, 1, 1);
   plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : "wgrad", TM, tn, nsplit);
-  if (tn == 256)      ABS_LAUNCH(mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd));
-  else if (tn == 128) ABS_LAUNCH(mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd));
-  else                ABS_LAUNCH(mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG><<<grid1, block, 0, s>>>(g, rd));
+  if (tn == 256)      ABS_LAUNCH_K((mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
+  else if (tn == 128) ABS_LAUNCH_K((mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
+  else                ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
   return false;
 }
 
@@ -1545,17 +1555,17 @@ unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd
       g.out = at<uint16_t>(a, p.off_h[l + 1]); g.ldo = (size_t)p.ld[l + 1];
       g.outT = at<uint16_t>(a, p.off_ht[l + 1]); g.ldoT = p.ldm;
       const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
-      hook->begin(kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+      kbegin(hook, kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
       if (want_bits) g.maskbits = at<uint32_t>(a, p.off_maskbits[l + 1]);
       const bool big = l == 0 ? launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s)
                               : launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
       if (big && want_bits) have_bits |= 1u << (l + 1);
-      hook->end(kind);
+      kend(hook, kind);
     } else {
       g.outf = at<float>(a, p.off_z); g.ldof = (size_t)p.dp[L];
-      hook->begin(KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
+      kbegin(hook, KK_MLP_FWD_LOGITS, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
       launch_gemm<EPI_LOGITS, false, true>(g, rd, rows, p.dp[L], 1, s);
-      hook->end(KK_MLP_FWD_LOGITS);
+      kend(hook, KK_MLP_FWD_LOGITS);
     }
   }
   return have_bits;
@@ -1580,16 +1590,16 @@ void launch_logits_ce(const MlpArgs& a, const RoundDesc& rd, int rows, double ar
   c.dZT = at<uint16_t>(a, p.off_dzt[L]); c.lddzt = p.ldm;
   c.rowloss = at<float>(a, p.off_rowloss);
   c.colsum = at<float>(a, p.off_colsum[L]); c.ldcs = (size_t)p.dp[L];
-  hook->begin(KK_MLP_LOGITS_CE, 2.0 * arows * p.d[L - 1] * p.d[L] + arows * p.d[L] * 8.0,
+  kbegin(hook, KK_MLP_LOGITS_CE, 2.0 * arows * p.d[L - 1] * p.d[L] + arows * p.d[L] * 8.0,
               arows * (p.d[L - 1] * 2.0 + p.d[L] * 4.0));
   plan_note("logits_ce", kCeRows, p.dp[L], 1);
   const dim3 grid(rows / kCeRows), block(256);
   switch (p.dp[L] / 64) {
-    case 1: ABS_LAUNCH(mlp_logits_ce_kernel<2><<<grid, block, 0, s>>>(c, rd)); break;
-    case 2: ABS_LAUNCH(mlp_logits_ce_kernel<4><<<grid, block, 0, s>>>(c, rd)); break;
-    default: ABS_LAUNCH(mlp_logits_ce_kernel<8><<<grid, block, 0, s>>>(c, rd)); break;
+    case 1: ABS_LAUNCH_K((mlp_logits_ce_kernel<2>), grid, block, s, c, rd); break;
+    case 2: ABS_LAUNCH_K((mlp_logits_ce_kernel<4>), grid, block, s, c, rd); break;
+    default: ABS_LAUNCH_K((mlp_logits_ce_kernel<8>), grid, block, s, c, rd); break;
   }
-  hook->end(KK_MLP_LOGITS_CE);
+  kend(hook, KK_MLP_LOGITS_CE);
 }
 
 }  // namespace
@@ -1645,11 +1655,10 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     launch_logits_ce(a, rd, rows, arows, wbase, sbase, own, s, hook);
     const int loss_blocks = p.Bp / kCeRows;          // row blocks of the loss sums per upload
     if (local) {
-      hook->begin(KK_MLP_LOSS, arows, arows * 4.0);
-      ABS_LAUNCH(mlp_loss_kernel<<<dim3(1), dim3(128), 0, s>>>(at<float>(a, p.off_rowloss), p.B, loss_blocks, K,
-                                                                rd.stamp, a.mailbox, at<float>(a, p.off_lossacc),
-                                                                step == 0, step == U - 1, U));
-      hook->end(KK_MLP_LOSS);
+      kbegin(hook, KK_MLP_LOSS, arows, arows * 4.0);
+      ABS_LAUNCH_K(mlp_loss_kernel, dim3(1), dim3(128), s, at<float>(a, p.off_rowloss), p.B, loss_blocks, K, rd.stamp,
+                   a.mailbox, at<float>(a, p.off_lossacc), (int)(step == 0), (int)(step == U - 1), U);
+      kend(hook, KK_MLP_LOSS);
     }
 
     // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
@@ -1674,21 +1683,21 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       }
       // the product through the output layer contracts over the classes only: bandwidth-bound
       const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
-      hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
+      kbegin(hook, kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
       if (l == L - 1) launch_gemm<EPI_DGRAD, false, true, 1>(g, rd, rows, p.dp[l], 1, s);
       else            launch_gemm<EPI_DGRAD, false, true, 0>(g, rd, rows, p.dp[l], 1, s);
-      hook->end(kind);
+      kend(hook, kind);
     }
 
     // ---- weight gradients.  U = 1: one contraction over all stacked rows = the K-of-N
     //      reduction, split over row ranges for occupancy, then update + snapshot per layer.
     //      U > 1: split a = the rows of upload a, applied to that upload's private model.
     if (!wg0_direct) {
-      hook->begin(KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
+      kbegin(hook, KK_MLP_GATHER_T, 0, arows * p.d[0] * 4.0);
       plan_note("gather_t", 64, 64, 1);
-      ABS_LAUNCH(mlp_gather_t_kernel<<<dim3(rows / 64, p.dp[0] / 64), dim3(256), 0, s>>>(a.X, p.d[0], rowidx,
-                                                                                         at<uint16_t>(a, p.off_xgt), p.ldm));
-      hook->end(KK_MLP_GATHER_T);
+      ABS_LAUNCH_K(mlp_gather_t_kernel, dim3(rows / 64, p.dp[0] / 64), dim3(256), s, a.X, p.d[0], (const uint32_t*)rowidx,
+                   at<uint16_t>(a, p.off_xgt), p.ldm);
+      kend(hook, KK_MLP_GATHER_T);
     }
     for (int l = L - 1; l >= 0; --l) {
       GemmArgs g{};
@@ -1701,7 +1710,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1] + kPartialPad;
       g.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
       const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
-      hook->begin(kind, 2.0 * arows * p.d[l] * p.d[l + 1],
+      kbegin(hook, kind, 2.0 * arows * p.d[l] * p.d[l + 1],
                   arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
       if (l == 0 && wg0_direct) {
         g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx;
@@ -1711,7 +1720,7 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       } else {
         launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
       }
-      hook->end(kind);
+      kend(hook, kind);
       launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, nsplit, s, hook);
     }
 
@@ -1737,9 +1746,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
         for (int l = 0; l < L; ++l) b.prow[l] = p.Bp / (l == L - 1 ? kCeRows : 64);
         for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
       }
-      hook->begin(KK_MLP_BIAS_LOSS, (double)c * rows / 64, (double)c * rows / 64 * 4.0);
-      ABS_LAUNCH(mlp_bias_kernel<<<dim3((c + 15) / 16, local ? K : 1), dim3(256), 0, s>>>(b));
-      hook->end(KK_MLP_BIAS_LOSS);
+      kbegin(hook, KK_MLP_BIAS_LOSS, (double)c * rows / 64, (double)c * rows / 64 * 4.0);
+      ABS_LAUNCH_K(mlp_bias_kernel, dim3((c + 15) / 16, local ? K : 1), dim3(256), s, b);
+      kend(hook, KK_MLP_BIAS_LOSS);
     }
   }
 
@@ -1754,9 +1763,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     for (int l = 0; l < L; ++l) { d.b_off[l] = p.b_off[l]; d.b_len[l] = p.d[l + 1]; }
     d.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
     d.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
-    hook->begin(KK_DELTA_UPDATE, 2.0 * K * p.P, (2.0 * K + 1.0) * p.P * 4.0);
-    ABS_LAUNCH(mlp_delta_kernel<<<dim3((unsigned)((p.P + 255) / 256)), dim3(256), 0, s>>>(d, rd));
-    hook->end(KK_DELTA_UPDATE);
+    kbegin(hook, KK_DELTA_UPDATE, 2.0 * K * p.P, (2.0 * K + 1.0) * p.P * 4.0);
+    ABS_LAUNCH_K(mlp_delta_kernel, dim3((unsigned)((p.P + 255) / 256)), dim3(256), s, d, rd);
+    kend(hook, KK_DELTA_UPDATE);
     for (int l = L - 1; l >= 0; --l) launch_update(a, l, rd, UPD_DELTA, 0, 1, s, hook);
   }
   return t_plan ? hipSuccess : hipGetLastError();
