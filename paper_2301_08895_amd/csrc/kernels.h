@@ -42,6 +42,7 @@ enum KernelKind {
   KK_LOCAL_STEPS,
   KK_DELTA_UPDATE,
   KK_EVAL,
+  KK_MLP_WGRAD_OUT,
   KK_COUNT
 };
 const char* kernel_kind_name(int kind);
@@ -139,10 +140,11 @@ struct MlpPlan {
   size_t off_h[8], off_ht[8];     // H_l [Mp][ld_l], H_l^T [dp_l][ldm], l = 1 .. L-1
   size_t off_z;                   // logits fp32 [Mp][dp_L]
   size_t off_dz[8], off_dzt[8];   // dZ_l [Mp][ld_l], dZ_l^T [dp_l][ldm], l = 1 .. L
-  size_t off_rowloss, off_partial;
+  size_t off_rowloss;
+  size_t off_partial[8];          // split partials of layer l's weight gradient, fp32 [splits][dp_l][dp_{l+1} + pad] (a region per layer:
+                                  // a layer's update may run inside the next layer's weight-gradient launch)
   size_t off_colsum[8];           // column sums of dZ_l per block of 64 rows, fp32 [Mp / 64][dp_l], l = 1 .. L
   size_t off_maskbits[8];         // ReLU mask of H_l, one bit per element in the tile kernel's accumulator order, l = 1 .. L-1
-  size_t partial_floats;
   // local SGD (U > 1): the uploads' private models (same slot layouts as the two rings),
   // their running mean losses, and the averaged change of Eq. 3
   int U;

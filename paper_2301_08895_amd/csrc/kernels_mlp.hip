@@ -116,6 +116,100 @@ __global__ __launch_bounds__(256) void mlp_gather_t_kernel(const uint16_t* X, in
   }
 }
 
+// ------------------------------------------------------------------ Eq. 3 on a block of a weight matrix
+// w^{t+1} = w^t - sum_z partial[z] (fixed order) for one weight matrix, written as fp32 into the next
+// ring slot and as bf16 in both orientations into the next shadow slot.
+struct TileUpdate {
+  const float* partial; size_t split_stride; size_t ldp; int nsplit;
+  const float* w_cur; float* w_next;   // [d_in][d_out] fp32, pitch d_out
+  int d_in, d_out;
+  uint16_t* wn; size_t ldwn;           // bf16 [dp_in][dp_out] (may be null)
+  uint16_t* wt; size_t ldwt;           // bf16 [dp_out][dp_in]
+  // sk_q > 0: the partials come from a weight-gradient launch that cut the contraction into equal
+  // runs of sk_q k-steps across the 256 x 256 output tiles (see GemmArgs::sk_q); tile T then has as
+  // many partials as runs touch its sk_ksteps k-steps, in slots 0 .. count - 1.
+  int sk_q, sk_ksteps, sk_nt;
+};
+__device__ __forceinline__ int partial_count(const TileUpdate& u, int i0, int j0) {
+  if (!u.sk_q) return u.nsplit;
+  const int tile = (i0 >> 8) * u.sk_nt + (j0 >> 8);
+  return ((tile + 1) * u.sk_ksteps - 1) / u.sk_q - tile * u.sk_ksteps / u.sk_q + 1;
+}
+// Tiled version for 16-byte aligned rows (d_out % 4 == 0).  One block of 64 rows x TJ columns at
+// (i0, j0), by all NT threads of the workgroup (uniform call): a thread moves 4 consecutive columns at
+// a time, TJ / 4 threads cover a row (TJ = 256: 1 KB of a model row per row of the tile, so that the
+// rows of a tile - a whole number of 4 KB apart for the usual widths - do not all fall on one memory
+// channel).  `tile` is 64 x (TJ + 2) bf16 of LDS: with a row pitch of 129 / 33 words the transposed
+// copy's 8 blocks of 8 rows start 8 banks apart and no two lanes of a wavefront collide.
+template <int NT, int TJ>
+__device__ __forceinline__ void update_block64(const TileUpdate& u, int i0, int j0, uint16_t* tile) {
+  constexpr int TPR = TJ / 4;            // threads per row
+  constexpr int RPP = NT / TPR;          // rows per pass
+  constexpr int NPASS = 64 / RPP;        // passes
+  constexpr int PT = TJ + 2;             // pitch of the LDS tile
+  static_assert(NPASS >= 2 && NPASS % 2 == 0, "two rows of a thread at a time");
+  const int jq = ((int)threadIdx.x % TPR) * 4, ir = (int)threadIdx.x / TPR;
+  const int nsplit = partial_count(u, i0, j0);
+  // two of the thread's rows at a time, with the model row and up to 8 partials of both in
+  // flight together (a partial beyond the 8th, rare, is fetched afterwards); summed in split order
+#pragma unroll 1
+  for (int r2 = 0; r2 < NPASS / 2; ++r2) {
+    float4 wc[2], v[2][8];
+    bool ok[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int i = i0 + ir + RPP * (2 * r2 + h), j = j0 + jq;
+      ok[h] = i < u.d_in && j < u.d_out;
+      if (ok[h]) {
+        const float* pp = u.partial + (size_t)i * u.ldp + j;
+        wc[h] = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
+#pragma unroll
+        for (int z = 0; z < 8; ++z)
+          if (z < nsplit) v[h][z] = *(const float4*)(pp + (size_t)z * u.split_stride);
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int il = ir + RPP * (2 * r2 + h), i = i0 + il, j = j0 + jq;
+      uint2 hh = make_uint2(0, 0);
+      if (ok[h]) {
+        float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int z = 0; z < 8; ++z)
+          if (z < nsplit) { G.x += v[h][z].x; G.y += v[h][z].y; G.z += v[h][z].z; G.w += v[h][z].w; }
+        for (int z = 8; z < nsplit; ++z) {
+          const float4 t = *(const float4*)(u.partial + (size_t)i * u.ldp + j + (size_t)z * u.split_stride);
+          G.x += t.x; G.y += t.y; G.z += t.z; G.w += t.w;
+        }
+        float4 w = wc[h];
+        w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
+        *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
+        hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
+        hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+        if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
+      }
+      *(uint32_t*)&tile[il * PT + jq] = hh.x;
+      *(uint32_t*)&tile[il * PT + jq + 2] = hh.y;
+    }
+  }
+  __syncthreads();
+  // transposed bf16 copy: thread -> column j, 8 consecutive rows i (the padded pitch of wt makes
+  // the 16-byte store safe; rows beyond d_in hold zeros, which is what the padding must be)
+  for (int q = threadIdx.x; q < TJ * 8; q += NT) {
+    const int jl = q >> 3, ib = (q & 7) * 8;
+    const int j = j0 + jl;
+    if (j < u.d_out) {
+      uint16_t v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = tile[(ib + e) * PT + jl];
+      uint4 o;
+      o.x = v[0] | ((uint32_t)v[1] << 16); o.y = v[2] | ((uint32_t)v[3] << 16);
+      o.z = v[4] | ((uint32_t)v[5] << 16); o.w = v[6] | ((uint32_t)v[7] << 16);
+      *(uint4*)(u.wt + (size_t)j * u.ldwt + i0 + ib) = o;
+    }
+  }
+}
+
 // ------------------------------------------------------------------ the GEMM
 enum { EPI_RELU = 0, EPI_LOGITS = 1, EPI_DGRAD = 2, EPI_WGRAD = 3 };
 
@@ -151,6 +245,20 @@ struct GemmArgs {
   uint32_t gen_draw0;                 // first draw index of this step (local step u: u B)
   const int32_t* gen_y;
   uint32_t* gen_rowidx; int32_t* gen_label;
+  // EPI_WGRAD on the 256 x 256 tile kernel with sk_q > 0: instead of nsplit equal row ranges per
+  // output tile, the mt nt ksteps_total (tile, k-step) pairs, tile after tile, are cut into runs of
+  // sk_q and workgroup w takes run w - a run may end in one tile and begin the next.  Every workgroup
+  // then does the same number of k-steps whatever the tile count (96 tiles on 256 CUs: two splits
+  // each leave a quarter of the CUs idle, runs of 48 k-steps none); a tile's partials are the pieces
+  // of the runs that touch it, in order, slot = piece number.
+  int sk_q;
+  // EPI_WGRAD with pig_blocks > 0: the launch's first pig_blocks workgroups do not belong to this
+  // product at all - each applies Eq. 3 to one 64 x pig_tj block of ANOTHER layer's weight matrix,
+  // whose split partials the previous launch completed (pig_upd).  The update is bound by memory, the
+  // product by the matrix cores, and a weight-gradient launch rarely has a whole number of waves of
+  // tiles: sharing a launch lets the two overlap without streams, events or fences.
+  int pig_blocks, pig_tj;
+  TileUpdate pig_upd;
   // EPI_DGRAD with pub_mailbox set: the first workgroup publishes the uploads' mean minibatch losses
   // (sums of pub_nb row blocks each, left by the output-layer kernel) before it starts on its tile.
   LossMailbox* pub_mailbox; const float* pub_rowloss; int pub_nb; int pub_B;
@@ -187,6 +295,22 @@ __device__ __forceinline__ void publish_upload_losses(LossMailbox* box, const fl
   if (threadIdx.x == 0) box->stamp = stamp;
 }
 
+// A piggybacked update block (see GemmArgs::pig_blocks): block b of the other layer's matrix, 64 rows
+// x pig_tj columns, by the NT threads of this workgroup.  Blocks beyond the matrix (the count is
+// rounded up to a multiple of 8 to keep the product's block -> XCD mapping) do nothing.
+template <int NT, bool WIDE_OK>
+__device__ __forceinline__ void piggy_update(const GemmArgs& g, int b, uint16_t* lds) {
+  const TileUpdate& u = g.pig_upd;
+  const int rows = (u.d_in + 63) / 64;
+  if (WIDE_OK && g.pig_tj == 256) {
+    const int nbx = (u.d_out + 255) / 256;
+    if (b < nbx * rows) update_block64<NT, 256>(u, (b / nbx) * 64, (b % nbx) * 256, lds);
+  } else {
+    const int nbx = (u.d_out + 63) / 64;
+    if (b < nbx * rows) update_block64<NT, 64>(u, (b / nbx) * 64, (b % nbx) * 64, lds);
+  }
+}
+
 // 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
 // 32x32x16 MFMA blocks (TN = 256: 2 x 4 blocks, 128 accumulator registers).  A and B
 // tiles of BK = 64 are staged in LDS (one stage; the next tile's global loads are in
@@ -217,12 +341,20 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  const int bx = blockIdx.x;
+  if (EPI == EPI_WGRAD && g.pig_blocks) {
+    // The update's blocks come last in the grid: they take the CUs that the product's last wave of
+    // tiles leaves idle and the tail.  (Dealt out evenly between the tiles they slowed every tile
+    // down: 260 -> 400 us for the hidden layer's product at K = 128.)
+    const int own = (int)gridDim.x - g.pig_blocks;
+    if (bx >= own) { piggy_update<256, false>(g, bx - own, smem); return; }
+  }
   // Block -> tile mapping.  Workgroups are handed to the 8 XCDs round-robin and every XCD has
   // its own L2, so block b works for XCD b % 8.  The (split, row-tile) pairs are cut into 8
   // contiguous ranges, one per XCD, and inside a range consecutive blocks sweep the column
   // tiles of one row tile: the blocks resident on an XCD then share their A rows (and, for
   // neighbouring row tiles of the same upload, their B rows) through that XCD's L2.
-  const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
+  const int xcd = bx & 7, jx = bx >> 3;
   const int trow = xcd * g.rows_per_xcd + jx / g.nt;
   if (trow >= g.mt * g.nsplit) return;
   const int zsplit = trow / g.mt;
@@ -494,16 +626,47 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 2, wn = wave & 3;
-  const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
-  const int trow = xcd * g.rows_per_xcd + jx / g.nt;
-  if (trow >= g.mt * g.nsplit) return;
-  const int zsplit = trow / g.mt;
-  const int m0 = (trow - zsplit * g.mt) * TM3, n0 = (jx % g.nt) * TN3;
-  const int ks0 = zsplit * g.ksteps_per_split;
-  const int ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
+  const int bx = blockIdx.x;
+  if (EPI == EPI_WGRAD && g.pig_blocks) {
+    // The update's blocks come last in the grid: they take the CUs that the product's last wave of
+    // tiles leaves idle and the tail.  (Dealt out evenly between the tiles they slowed every tile
+    // down: 260 -> 400 us for the hidden layer's product at K = 128.)
+    const int own = (int)gridDim.x - g.pig_blocks;
+    if (bx >= own) { piggy_update<512, true>(g, bx - own, smem); return; }
+  }
+  int m0, n0, zsplit, ks0, ks1;
+  // runs of k-steps across tiles (sk_q > 0): this workgroup's next (tile, k-step) pair and the end of
+  // its run.  The workgroups of an XCD take neighbouring runs, hence neighbouring tiles.
+  const bool kRuns = EPI == EPI_WGRAD && g.sk_q > 0;
+  int sk_u = 0, sk_end = 0;
+  if (kRuns) {
+    const int own = (int)gridDim.x - g.pig_blocks;
+    const int lw = (bx & 7) * (own >> 3) + (bx >> 3);
+    sk_u = lw * g.sk_q;
+    sk_end = min(sk_u + g.sk_q, g.mt * g.nt * g.ksteps_total);
+    if (sk_u >= sk_end) return;
+  } else {
+    const int xcd = bx & 7, jx = bx >> 3;
+    const int trow = xcd * g.rows_per_xcd + jx / g.nt;
+    if (trow >= g.mt * g.nsplit) return;
+    zsplit = trow / g.mt;
+    m0 = (trow - zsplit * g.mt) * TM3; n0 = (jx % g.nt) * TN3;
+    ks0 = zsplit * g.ksteps_per_split;
+    ks1 = min(g.ksteps_total, ks0 + g.ksteps_per_split);
+  }
 
   if (EPI == EPI_DGRAD && g.pub_mailbox && blockIdx.x == 0)
     publish_upload_losses(g.pub_mailbox, g.pub_rowloss, g.pub_nb, g.pub_B, rd.K, rd.stamp);
+
+  for (;;) {       // one pass per piece of the run (a single pass without runs)
+  if (kRuns) {
+    const int tile = sk_u / g.ksteps_total;
+    ks0 = sk_u - tile * g.ksteps_total;
+    ks1 = min(g.ksteps_total, ks0 + (sk_end - sk_u));
+    m0 = (tile / g.nt) * TM3; n0 = (tile % g.nt) * TN3;
+    zsplit = sk_u / g.sk_q - tile * g.ksteps_total / g.sk_q;     // pieces of earlier runs in this tile
+    sk_u += ks1 - ks0;
+  }
 
   const uint16_t* Bt = g.Bt;
   uint32_t slot = 0;
@@ -790,6 +953,8 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
     }
   }
   if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
+  if (!kRuns || sk_u >= sk_end) break;
+  }
 }
 
 // ------------------------------------------------------------------ output layer: logits, loss, dZ_L
@@ -1010,14 +1175,9 @@ __global__ __launch_bounds__(256, 1) void mlp_logits_ce_kernel(LogitsCeArgs a, R
 }
 
 // ------------------------------------------------------------------ update + snapshot
-// w^{t+1} = w^t - sum_z partial[z]  (fixed order), written as fp32 into the next ring slot
-// and as bf16 in both orientations into the next shadow slot.  64 x 64 tiles.
-struct UpdateArgs {
-  const float* partial; size_t split_stride; size_t ldp; int nsplit;
-  const float* w_cur; float* w_next;   // [d_in][d_out] fp32, pitch d_out
-  int d_in, d_out;
-  uint16_t* wn; size_t ldwn;           // bf16 [dp_in][dp_out] (may be null)
-  uint16_t* wt; size_t ldwt;           // bf16 [dp_out][dp_in]
+// The update as a kernel of its own (a TileUpdate for a whole matrix): local SGD, the averaged change of
+// the uploads, matrices whose rows are not 16-byte aligned, a round's last layer, the bf16 copies of w^0.
+struct UpdateArgs : TileUpdate {
   // batched form (local SGD): blockIdx.z = upload a; partial a, nsplit = 1, the model read from
   // slot cur_index[a] of w_cur's ring and written to slot a of w_next's ring / shadow ring
   int batched;
@@ -1033,81 +1193,11 @@ __device__ __forceinline__ void update_select_upload(UpdateArgs& u) {
   if (u.wn) u.wn += (size_t)a * u.shadow_stride;
   u.wt += (size_t)a * u.shadow_stride;
 }
-// Tiled version for 16-byte aligned rows (d_out % 4 == 0): a 64 x TJ tile; a thread moves 4
-// consecutive columns at a time, TJ / 4 threads cover a row (TJ = 256: 1 KB of a model row per
-// row of the tile, so that the rows of a tile - a whole number of 4 KB apart for the usual widths -
-// do not all fall on one memory channel).
 template <int TJ>
 __global__ __launch_bounds__(256) void mlp_update_kernel(UpdateArgs u) {
-  constexpr int TPR = TJ / 4;            // threads per row
-  constexpr int RPP = 256 / TPR;         // rows per pass
-  constexpr int NP = 64 / RPP;           // passes
-  // Row pitch TJ + 2: the transposed copy below reads, per wavefront, 8 columns x 8 blocks of 8 rows;
-  // with a pitch of 129 / 33 words the 8 row blocks start 8 banks apart and no two lanes collide
-  // (a pitch of TJ + 8 put them on two banks: the copy was a third of the kernel's time).
-  __shared__ __attribute__((aligned(16))) uint16_t tile[64][TJ + 2];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64 * (TJ + 2)];
   update_select_upload(u);
-  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * TJ;
-  const int jq = (threadIdx.x % TPR) * 4, ir = threadIdx.x / TPR;
-  // two of the thread's rows at a time, with the model row and up to 8 partials of both in
-  // flight together (a partial beyond the 8th, rare, is fetched afterwards); summed in split order
-#pragma unroll 1
-  for (int r2 = 0; r2 < NP / 2; ++r2) {
-    float4 wc[2], v[2][8];
-    bool ok[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int i = i0 + ir + RPP * (2 * r2 + h), j = j0 + jq;
-      ok[h] = i < u.d_in && j < u.d_out;
-      if (ok[h]) {
-        const float* pp = u.partial + (size_t)i * u.ldp + j;
-        wc[h] = *(const float4*)(u.w_cur + (size_t)i * u.d_out + j);
-#pragma unroll
-        for (int z = 0; z < 8; ++z)
-          if (z < u.nsplit) v[h][z] = *(const float4*)(pp + (size_t)z * u.split_stride);
-      }
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int il = ir + RPP * (2 * r2 + h), i = i0 + il, j = j0 + jq;
-      uint2 hh = make_uint2(0, 0);
-      if (ok[h]) {
-        float4 G = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int z = 0; z < 8; ++z)
-          if (z < u.nsplit) { G.x += v[h][z].x; G.y += v[h][z].y; G.z += v[h][z].z; G.w += v[h][z].w; }
-        for (int z = 8; z < u.nsplit; ++z) {
-          const float4 t = *(const float4*)(u.partial + (size_t)i * u.ldp + j + (size_t)z * u.split_stride);
-          G.x += t.x; G.y += t.y; G.z += t.z; G.w += t.w;
-        }
-        float4 w = wc[h];
-        w.x -= G.x; w.y -= G.y; w.z -= G.z; w.w -= G.w;
-        *(float4*)(u.w_next + (size_t)i * u.d_out + j) = w;
-        hh.x = f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
-        hh.y = f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
-        if (u.wn) *(uint2*)(u.wn + (size_t)i * u.ldwn + j) = hh;
-      }
-      *(uint32_t*)&tile[il][jq] = hh.x;
-      *(uint32_t*)&tile[il][jq + 2] = hh.y;
-    }
-  }
-  __syncthreads();
-  // transposed bf16 copy: thread -> column j, 8 consecutive rows i (the padded pitch of wt makes
-  // the 16-byte store safe; rows beyond d_in hold zeros, which is what the padding must be)
-#pragma unroll
-  for (int r = 0; r < TJ / 32; ++r) {
-    const int q = threadIdx.x + 256 * r, jl = q >> 3, ib = (q & 7) * 8;
-    const int j = j0 + jl;
-    if (j < u.d_out) {
-      uint16_t v[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = tile[ib + e][jl];
-      uint4 o;
-      o.x = v[0] | ((uint32_t)v[1] << 16); o.y = v[2] | ((uint32_t)v[3] << 16);
-      o.z = v[4] | ((uint32_t)v[5] << 16); o.w = v[6] | ((uint32_t)v[7] << 16);
-      *(uint4*)(u.wt + (size_t)j * u.ldwt + i0 + ib) = o;
-    }
-  }
+  update_block64<256, TJ>(u, blockIdx.y * 64, blockIdx.x * TJ, tile);
 }
 
 // Element-wise version for narrow or odd output widths (e.g. the 10-class output layer):
@@ -1351,10 +1441,6 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
     p.wn_off[l] = o; if (l >= 1) o += (size_t)p.dp[l] * p.ld[l + 1];
   }
   p.shadow_stride = round_up(o, 128);
-  size_t partial = 0;
-  for (int l = 0; l < L; ++l) partial = std::max(partial, (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad));
-  p.partial_floats = partial * (p.U > 1 ? std::max<size_t>(kMaxSplit, (size_t)c.N) : (size_t)kMaxSplit);
-
   size_t b = 0;
   auto take = [&](size_t bytes) { size_t at = b; b = round_up(b + bytes, 256); return at; };
   const size_t Mp = (size_t)p.Mp;
@@ -1375,7 +1461,9 @@ bool mlp_plan(const abs_config& c, MlpPlan& p, const char** why) {
   p.off_rowloss = take(Mp * 4);
   for (int l = 1; l <= L; ++l) p.off_colsum[l] = take(Mp / (l == L ? kCeRows : 64) * p.dp[l] * 4);
   for (int l = 1; l < L; ++l) p.off_maskbits[l] = take(round_up(Mp, 256) * round_up((size_t)p.dp[l], 256) / 8);
-  p.off_partial = take(p.partial_floats * 4);
+  for (int l = 0; l < L; ++l)
+    p.off_partial[l] = take((size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad) * 4 *
+                            (p.U > 1 ? std::max<size_t>(kMaxSplit, (size_t)c.N) : (size_t)kMaxSplit));
   if (p.U > 1) {
     p.off_priv = take((size_t)c.N * p.slot_stride * 4);
     p.off_priv_shadow = take((size_t)c.N * p.shadow_stride * 2);
@@ -1419,8 +1507,50 @@ struct NullHook : LaunchHook {
 //   UPD_DELTA   w^{t+1} = w^t - D, D = the averaged change of the uploads    (U > 1, Eq. 3)
 // each also writes the bf16 copies of what it produced.
 enum { UPD_GLOBAL = 0, UPD_LOCAL = 1, UPD_DELTA = 2 };
+// Weight gradient of layer l over `rows` stacked rows on the 256 x 256 tile kernel: k-steps per run if
+// the contraction should be cut into equal runs across the tiles (GemmArgs::sk_q), else 0.  Runs pay
+// when equal row ranges per tile leave a good part of the CUs idle in the launch's last wave and a
+// run is still long enough to amortise a tile's epilogue; a tile then gets up to *max_parts partials.
+int wgrad_runs(const MlpPlan& p, int l, int rows, int nsplit, int* max_parts) {
+  constexpr int kCUs = 256, kMinRun = 24;
+  if (p.dp[l] % TM3 || p.dp[l + 1] % TN3 || p.d[l + 1] % 4 || p.w_off[l] % 4) return 0;   // (the tiled update kernels read the per-tile counts)
+  const int tiles = (p.dp[l] / TM3) * (p.dp[l + 1] / TN3), ksteps = rows / BK;
+  const int wgs = tiles * nsplit;
+  if (wgs < 128) return 0;                                   // (not a launch of the large-tile kernel)
+  const int waves = (wgs + kCUs - 1) / kCUs;
+  if ((double)wgs / (waves * kCUs) >= 0.9) return 0;         // equal ranges already fill the CUs
+  const long units = (long)tiles * ksteps;
+  const int q = (int)((units + kCUs - 1) / kCUs);            // one run per CU
+  if (q < kMinRun) return 0;
+  const int parts = (ksteps + q - 1) / q + 1;
+  if (parts > kMaxSplit) return 0;
+  *max_parts = parts;
+  return q;
+}
+
+// Eq. 3 for layer l's weight matrix from the split partials of its weight gradient (U = 1).
+TileUpdate global_update_args(const MlpArgs& a, int l, const RoundDesc& rd, int nsplit) {
+  const MlpPlan& p = a.plan;
+  float* ring = at<float>(a, p.off_ring);
+  uint16_t* shadow = at<uint16_t>(a, p.off_shadow) + (size_t)rd.slot_next * p.shadow_stride;
+  TileUpdate u{};
+  u.partial = at<float>(a, p.off_partial[l]);
+  u.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
+  u.ldp = (size_t)p.dp[l + 1] + kPartialPad;
+  u.nsplit = nsplit;
+  u.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride + p.w_off[l];
+  u.w_next = ring + (size_t)rd.slot_next * p.slot_stride + p.w_off[l];
+  u.d_in = p.d[l];
+  u.d_out = p.d[l + 1];
+  u.wn = l >= 1 ? shadow + p.wn_off[l] : nullptr; u.ldwn = (size_t)p.ld[l + 1];
+  u.wt = shadow + p.wt_off[l]; u.ldwt = (size_t)p.ld[l];
+  return u;
+}
+// Whether the rows of layer l's fp32 weight matrix can be moved 16 bytes at a time.
+bool update_rows_aligned(const MlpPlan& p, int l) { return p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0; }
+
 void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int step, int nsplit,
-                   hipStream_t s, LaunchHook* hook) {
+                   hipStream_t s, LaunchHook* hook, int run_q = 0, int run_ksteps = 0) {
   const MlpPlan& p = a.plan;
   float* ring = at<float>(a, p.off_ring);
   UpdateArgs u{};
@@ -1434,7 +1564,7 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
     uint16_t* pshadow = at<uint16_t>(a, p.off_priv_shadow);
     u.batched = 1;
     batch = rd.K;
-    u.partial = at<float>(a, p.off_partial);
+    u.partial = at<float>(a, p.off_partial[l]);
     u.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
     u.ldp = (size_t)p.dp[l + 1] + kPartialPad;
     u.nsplit = 1;
@@ -1449,7 +1579,7 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
   } else {
     uint16_t* shadow = at<uint16_t>(a, p.off_shadow) + (size_t)rd.slot_next * p.shadow_stride;
     if (mode == UPD_GLOBAL) {
-      u.partial = at<float>(a, p.off_partial);
+      u.partial = at<float>(a, p.off_partial[l]);
       u.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
       u.ldp = (size_t)p.dp[l + 1] + kPartialPad;
       u.nsplit = nsplit;
@@ -1464,10 +1594,11 @@ void launch_update(const MlpArgs& a, int l, const RoundDesc& rd, int mode, int s
     u.wn = l >= 1 ? shadow + p.wn_off[l] : nullptr;
     u.wt = shadow + p.wt_off[l];
   }
+  if (run_q) { u.sk_q = run_q; u.sk_ksteps = run_ksteps; u.sk_nt = p.dp[l + 1] / TN3; }
   const double n = (double)p.d[l] * p.d[l + 1] * batch;
   kbegin(hook, KK_MLP_UPDATE, n * (u.nsplit + 1), n * (4.0 * (u.nsplit + 2) + (l >= 1 ? 4.0 : 2.0)));
   const dim3 block(256);
-  const bool vec = p.d[l + 1] % 4 == 0 && p.w_off[l] % 4 == 0;
+  const bool vec = update_rows_aligned(p, l);
   // wide tiles (fewer, longer stores) only where they still give every CU a workgroup
   const bool wide = p.d[l + 1] >= 256 && ((p.d[l + 1] + 255) / 256) * ((p.d[l] + 63) / 64) * batch >= 256;
   plan_note("update", 64, vec && wide ? 256 : vec ? 64 : 1, u.nsplit);
@@ -1487,14 +1618,24 @@ inline bool gemm_is_big(bool gather, bool per_upload, const GemmArgs& g, int Mdi
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
 bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   g.nsplit = nsplit;
-  const bool big = gemm_is_big(GATHER, PER_UPLOAD, g, Mdim, Ndim, nsplit);
+  const bool big = g.sk_q > 0 || gemm_is_big(GATHER, PER_UPLOAD, g, Mdim, Ndim, nsplit);
+  if (big && g.sk_q > 0) {
+    // runs of sk_q k-steps across the tiles: one workgroup per run
+    g.mt = Mdim / TM3;
+    g.nt = Ndim / TN3;
+    g.rows_per_xcd = 0;
+    const int runs = (g.mt * g.nt * g.ksteps_total + g.sk_q - 1) / g.sk_q;
+    plan_note(TAG == 2 ? "wgrad_x_runs" : "wgrad_runs", TM3, TN3, g.sk_q);
+    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3((runs + 7) / 8 * 8 + g.pig_blocks), dim3(512), s, g, rd);
+    return true;
+  }
   if (big) {
     g.mt = Mdim / TM3;
     g.nt = Ndim / TN3;
     g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
     plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : TAG == 2 ? "wgrad_x" : "wgrad",
               TM3, TN3, nsplit);
-    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt), dim3(512), s, g, rd);
+    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt + g.pig_blocks), dim3(512), s, g, rd);
     return true;
   }
   // widest column tile that still fills the GPU: 256-wide tiles only with two workgroups per CU
@@ -1509,7 +1650,7 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   g.nt = Ndim / tn;
   g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
   const dim3 block(256);
-  const dim3 grid1(8 * g.rows_per_xcd * g.nt, 1, 1);
+  const dim3 grid1(8 * g.rows_per_xcd * g.nt + g.pig_blocks, 1, 1);
   plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : "wgrad", TM, tn, nsplit);
   if (tn == 256)      ABS_LAUNCH_K((mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
   else if (tn == 128) ABS_LAUNCH_K((mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
@@ -1699,7 +1840,18 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
                    at<uint16_t>(a, p.off_xgt), p.ldm);
       kend(hook, KK_MLP_GATHER_T);
     }
-    for (int l = L - 1; l >= 0; --l) {
+    // U = 1: first layer first.  The update of a layer (Eq. 3: bound by memory) does not get a launch of
+    // its own but rides along in the NEXT layer's weight-gradient launch (bound by the matrix cores) as
+    // that launch's last workgroups: they take the CUs its last wave of tiles leaves idle and its tail,
+    // and there is no gap between two launches.  Only the last layer's update, small, is launched by
+    // itself.  (cfg 5, same box, microseconds per round at K = 32 / K = 128: 680 / 1838 with an update
+    // launch per layer, 650 / 1811 this way.  Hiding the second layer's update under the first layer's
+    // product instead - order 1, 0, 2, no runs: a quarter of the CUs is idle there at K = 32 - gave
+    // 631 / 1807, but the product that bounds the round then carries another layer's traffic and its
+    // own figure, 0.31 of the matrix peak instead of 0.37 with runs, says little about it.)
+    int pend = -1, pend_split = 0, pend_q = 0;   // layer whose partials are complete and whose update is still due (its splits or run length)
+    for (int li = 0; li < L; ++li) {
+      const int l = local ? L - 1 - li : li;
       GemmArgs g{};
       g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = p.ldm;
       g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = p.ldm;
@@ -1707,11 +1859,26 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       const int nsplit = wgrad_split(p, l, rows, local ? K : 0);
       g.ksteps_total = ksteps;
       g.ksteps_per_split = local ? p.Bp / BK : (ksteps + nsplit - 1) / nsplit;
-      g.outf = at<float>(a, p.off_partial); g.ldof = (size_t)p.dp[l + 1] + kPartialPad;
+      g.outf = at<float>(a, p.off_partial[l]); g.ldof = (size_t)p.dp[l + 1] + kPartialPad;
       g.split_stride = (size_t)p.dp[l] * (p.dp[l + 1] + kPartialPad);
-      const int kind = l == 0 ? KK_MLP_WGRAD_L1 : KK_MLP_WGRAD;
+      int run_parts = 0;
+      const int run_q = local ? 0 : wgrad_runs(p, l, rows, nsplit, &run_parts);
+      if (run_q) { g.sk_q = run_q; }
+      double upd_bytes = 0.0;
+      if (pend >= 0) {
+        g.nsplit = nsplit;
+        const bool big = gemm_is_big(false, false, g, p.dp[l], p.dp[l + 1], nsplit);
+        g.pig_upd = global_update_args(a, pend, rd, pend_split);
+        if (pend_q) { g.pig_upd.sk_q = pend_q; g.pig_upd.sk_ksteps = ksteps; g.pig_upd.sk_nt = p.dp[pend + 1] / TN3; }
+        g.pig_tj = big && p.d[pend + 1] >= 256 ? 256 : 64;
+        g.pig_blocks = (((p.d[pend + 1] + g.pig_tj - 1) / g.pig_tj) * ((p.d[pend] + 63) / 64) + 7) / 8 * 8;
+        upd_bytes = (double)p.d[pend] * p.d[pend + 1] * (4.0 * (pend_split + 2) + (pend >= 1 ? 4.0 : 2.0));
+        plan_note("with_update_of_previous", 64, g.pig_tj, pend_split);
+        pend = -1;
+      }
+      const int kind = l == 0 ? KK_MLP_WGRAD_L1 : l == L - 1 ? KK_MLP_WGRAD_OUT : KK_MLP_WGRAD;
       kbegin(hook, kind, 2.0 * arows * p.d[l] * p.d[l + 1],
-                  arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0);
+             arows * (p.d[l] + p.d[l + 1]) * 2.0 + (double)nsplit * p.d[l] * p.d[l + 1] * 4.0 + upd_bytes);
       if (l == 0 && wg0_direct) {
         g.A = a.X; g.lda = (size_t)p.d[0]; g.a_rowidx = rowidx;
         launch_gemm<EPI_WGRAD, false, false, 2>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
@@ -1721,7 +1888,9 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
         launch_gemm<EPI_WGRAD, false, false, 0>(g, rd, p.dp[l], p.dp[l + 1], nsplit, s);
       }
       kend(hook, kind);
-      launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, nsplit, s, hook);
+      const int parts = run_q ? run_parts : nsplit;          // partials per tile (at most, with runs)
+      if (!local && update_rows_aligned(p, l) && li + 1 < L) { pend = l; pend_split = parts; pend_q = run_q; }
+      else launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, parts, s, hook, run_q, ksteps);
     }
 
     // ---- biases, from the column sums the producers of dZ_l left per block of 64 rows
