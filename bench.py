@@ -45,10 +45,11 @@ def source_hash():
     return hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:16]
 
 
-def import_traffic(fetch_csv, write_csv):
+def import_traffic(fetch_csv, write_csv, k):
     """Turn two rocprofv3 --pmc runs of `bench.py --config 5 --calibrate-copy` (FETCH_SIZE, then
     WRITE_SIZE; counters in KiB per dispatch) into profiles/cfg5_hbm_traffic.txt: HBM bytes
-    per launch of each GEMM kind, each counter scaled by what it reads for the 1 GiB copy."""
+    per launch of each GEMM kind at K = `k` uploads per round, each counter scaled by what it
+    reads for the 1 GiB copy.  Lines of other K taken from the same kernel source are kept."""
     import csv
     def per_kernel(path, counter):
         acc = {}
@@ -69,23 +70,31 @@ def import_traffic(fetch_csv, write_csv):
             raise SystemExit("no copy kernel in the counter file: run bench.py with --calibrate-copy")
         return COPY_BYTES / big
     ff, fw = copy_factor(fetch), copy_factor(write)
+    kept = []
+    if os.path.exists(TRAFFIC_FILE):
+        old = open(TRAFFIC_FILE).read().splitlines()
+        if f"source_hash {source_hash()}" in old:
+            kept = [l for l in old if "@" in l.split(" ")[0] and not l.split(" ")[0].endswith(f"@{k}")]
     lines = [f"# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),",
-             f"# scaled by the same counters' reading for a {COPY_BYTES >> 20} MiB copy kernel",
-             f"source_hash {source_hash()}", f"fetch_factor {ff:.4f}", f"write_factor {fw:.4f}"]
+             f"# scaled by the same counters' reading for a {COPY_BYTES >> 20} MiB copy kernel;",
+             f"# kind@K = the launches of a round with K uploads (K * B stacked rows)",
+             f"source_hash {source_hash()}"] + kept
     for kind, sym in KIND_SYMBOL.items():
-        f = [v for k, v in fetch.items() if sym in k]
-        w = [v for k, v in write.items() if sym in k]
+        f = [v for n, v in fetch.items() if sym in n]
+        w = [v for n, v in write.items() if sym in n]
         if not f or not w:
             continue
         fb, wb = f[0][0] / f[0][1] * ff, w[0][0] / w[0][1] * fw
-        lines.append(f"{kind} launches {f[0][1]} fetch_bytes {fb:.0f} write_bytes {wb:.0f}")
+        lines.append(f"{kind}@{k} launches {f[0][1]} fetch_bytes {fb:.0f} write_bytes {wb:.0f} "
+                     f"fetch_factor {ff:.4f} write_factor {fw:.4f}")
     open(TRAFFIC_FILE, "w").write("\n".join(lines) + "\n")
     print("\n".join(lines))
 
 
-def stored_traffic(kind, flops_per_launch, flops_per_launch_ref=None):
-    """HBM bytes per launch of `kind` from the stored counters, or None when there are none or
-    the kernel source has changed since they were taken."""
+def stored_traffic(kind, k_avg, k_full):
+    """HBM bytes per launch of `kind` from the stored counters: the line taken at the launches'
+    own K when there is one, else the line at K = N scaled by the rows.  None when there are no
+    counters or the kernel source has changed since they were taken."""
     if not os.path.exists(TRAFFIC_FILE):
         return None
     rows = {}
@@ -93,11 +102,17 @@ def stored_traffic(kind, flops_per_launch, flops_per_launch_ref=None):
         t = line.split()
         if t and not t[0].startswith("#"):
             rows[t[0]] = t[1:]
-    if rows.get("source_hash", [""])[0] != source_hash() or kind not in rows:
+    if rows.get("source_hash", [""])[0] != source_hash():
         return None
-    r = rows[kind]
-    d = dict(zip(r[0::2], r[1::2]))
-    return float(d["fetch_bytes"]) + float(d["write_bytes"])
+    def total(key):
+        r = rows[key]
+        d = dict(zip(r[0::2], r[1::2]))
+        return float(d["fetch_bytes"]) + float(d["write_bytes"])
+    own = f"{kind}@{int(round(k_avg))}"
+    if abs(k_avg - round(k_avg)) < 1e-3 and own in rows:
+        return total(own)
+    full = f"{kind}@{k_full}"
+    return total(full) * k_avg / k_full if full in rows else None
 
 
 # default (warmup, steps) per workload: short enough for a default run of about a minute
@@ -160,10 +175,8 @@ def roofline_of(kern, p, config):
     avg_s = dom["ms"] / dom["launches"] * 1e-3
     if dom["name"] in MFMA_KINDS:
         ach = dom["flops"] / dom["launches"] / avg_s / 1e12
-        # stored counters were taken at K = N; a launch's traffic scales with its rows
-        traffic = stored_traffic(dom["name"], None) if config == 5 else None
-        if traffic is not None:
-            traffic *= (dom["flops"] / dom["launches"]) / _flops_at_full_k(p, dom["name"])
+        k_avg = (dom["flops"] / dom["launches"]) / _flops_at_full_k(p, dom["name"]) * p["N"]
+        traffic = stored_traffic(dom["name"], k_avg, p["N"]) if config == 5 else None
         return dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS,
                     unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS, traffic=traffic,
                     avg_launch_us=avg_s * 1e6, launches=dom["launches"])
@@ -269,11 +282,13 @@ def main():
     ap.add_argument("--calibrate-iters", type=int, default=4000, help="iterations of the MFMA-only loop")
     ap.add_argument("--full-k-rounds", type=int, default=8,
                     help="MLP workloads: extra rounds at K = N after the timed region for the roofline_full_k block (0: none)")
+    ap.add_argument("--traffic-k", type=int, default=128,
+                    help="uploads per round (K) of the run the --traffic-import counter files come from")
     ap.add_argument("--traffic-import", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="write profiles/cfg5_hbm_traffic.txt from two rocprofv3 --pmc counter files and exit")
     args = ap.parse_args()
     if args.traffic_import:
-        import_traffic(*args.traffic_import)
+        import_traffic(*args.traffic_import, args.traffic_k)
         return
     if args.gpus != 1:
         print("bench.py: this library runs on ONE GPU only (one simulated parameter server per device); "
