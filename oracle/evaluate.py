@@ -12,7 +12,8 @@ from __future__ import annotations
 import numpy as np
 
 from .bf16 import round_bf16
-from .models import MODEL_LINEAR, MODEL_MLP, unpack, narrowed_weights, _softmax_ce
+from .models import MODEL_LINEAR, MODEL_MLP, MODEL_CNN, unpack, narrowed_weights, _softmax_ce
+from . import cnn as _cnn
 
 
 def logits(cfg: dict, w: np.ndarray, X: np.ndarray, emulate_bf16: bool = False) -> np.ndarray:
@@ -21,6 +22,8 @@ def logits(cfg: dict, w: np.ndarray, X: np.ndarray, emulate_bf16: bool = False) 
     X = np.asarray(X, dtype=np.float64)
     if cfg["model"] == MODEL_LINEAR:
         return (X @ w)[:, None]
+    if cfg["model"] == MODEL_CNN:
+        return _cnn.logits(cfg, w, X)
     rnd = round_bf16 if emulate_bf16 else (lambda a: a)
     layers = unpack(cfg, w)
     Wq = narrowed_weights(cfg, w, emulate_bf16)

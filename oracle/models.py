@@ -2,11 +2,12 @@
 
 The paper only asks for a smooth per-sample loss f(w; xi) (Eq. 1) and uses
 the minibatch gradient g = (1/B) sum_b grad f(w; xi_b) (Eq. 2, Assumption 3).
-The three models are the synthetic workloads' own:
+The first three models are the synthetic workloads' own, the fourth is Section V-A's:
   linear   f = 1/2 (x.w - y)^2                       (no bias)
   softmax  f = -log softmax(x W + b)_y
   mlp      H_0 = x, Z_l = H_{l-1} W_l + b_l, H_l = relu(Z_l) (l < L),
            softmax cross-entropy on Z_L, relu'(0) = 0.
+  cnn      two convolutional + three dense layers (cnn.py).
 Parameter vector layout: per layer W_l [d_in, d_out] row-major then b_l.
 
 `worker_update` returns s * g and the minibatch mean loss, where s is the
@@ -24,7 +25,10 @@ import numpy as np
 
 from .bf16 import round_bf16
 
+from . import cnn as _cnn
+
 MODEL_LINEAR, MODEL_SOFTMAX, MODEL_MLP = 0, 1, 2
+MODEL_CNN = _cnn.MODEL_CNN      # Section V-A's convolutional network: cnn.py
 
 
 def unpack(cfg: dict, w: np.ndarray):
@@ -32,6 +36,8 @@ def unpack(cfg: dict, w: np.ndarray):
     d = cfg["dims"]
     if cfg["model"] == MODEL_LINEAR:
         return [(w.reshape(d[0], 1), None)]
+    if cfg["model"] == MODEL_CNN:
+        return _cnn.unpack(cfg, w)
     out, o = [], 0
     for l in range(len(d) - 1):
         W = w[o:o + d[l] * d[l + 1]].reshape(d[l], d[l + 1]); o += d[l] * d[l + 1]
@@ -57,7 +63,7 @@ def narrowed_weights(cfg: dict, w: np.ndarray, emulate_bf16: bool):
     (bf16-rounded when emulation is on).  A pure function of the model version,
     so a caller may compute it once per version and hand it to worker_update."""
     w = np.asarray(w, dtype=np.float64)
-    if cfg["model"] == MODEL_LINEAR:
+    if cfg["model"] in (MODEL_LINEAR, MODEL_CNN):
         return None
     return [round_bf16(W) if emulate_bf16 else W for (W, _) in unpack(cfg, w)]
 
@@ -69,6 +75,8 @@ def worker_update(cfg: dict, w: np.ndarray, X: np.ndarray, y: np.ndarray, s: flo
     Wq, if given, must be narrowed_weights(cfg, w, emulate_bf16)."""
     B = X.shape[0]
     model = cfg["model"]
+    if model == MODEL_CNN:
+        return _cnn.worker_update(cfg, w, X, y, s)
     w = np.asarray(w, dtype=np.float64)
     u = np.zeros_like(w)
     if model == MODEL_LINEAR:

@@ -2,7 +2,7 @@
 
 Linear least squares: X ~ N(0,1), w* ~ N(0,1), y = X w* + N(0, 0.01^2), w0 = 0.
 Classification: a Gaussian mixture, class means ~ N(0, I), unit variance,
-labels uniform; softmax starts from w0 = 0, MLP weights W_l ~ N(0, 2/d_in), b = 0.
+labels uniform; softmax starts from w0 = 0, MLP and CNN weights W_l ~ N(0, 2/fan_in), b = 0.
 bf16 datasets are the fp32 draw rounded to nearest-even and handed over as the
 uint16 payload (the dataset *is* bf16 for those workloads).
 """
@@ -10,7 +10,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from .presets import MODEL_LINEAR, MODEL_SOFTMAX, MODEL_MLP, X_BF16
+from .presets import MODEL_LINEAR, MODEL_SOFTMAX, MODEL_MLP, MODEL_CNN, X_BF16, cnn_layer_shapes
 
 
 def to_bf16_bits(x32: np.ndarray) -> np.ndarray:
@@ -56,6 +56,13 @@ def make_inputs(p: dict):
         w0 = np.zeros(d, dtype=np.float32)
     elif p["model"] == MODEL_SOFTMAX:
         w0 = np.zeros(dims[0] * dims[1] + dims[1], dtype=np.float32)
+    elif p["model"] == MODEL_CNN:
+        parts = []
+        for rows, cols in cnn_layer_shapes(p):       # fan-in = rows for both kinds of layer
+            W = irng.standard_normal((rows, cols), dtype=np.float32)
+            W *= np.float32(np.sqrt(2.0 / rows))
+            parts += [W.ravel(), np.zeros(cols, dtype=np.float32)]
+        w0 = np.concatenate(parts).astype(np.float32)
     else:
         parts = []
         for l in range(len(dims) - 1):

@@ -10,7 +10,7 @@ from __future__ import annotations
 import copy
 
 # model ids / dtype ids / time-distribution ids are the integers the C-ABI uses
-MODEL_LINEAR, MODEL_SOFTMAX, MODEL_MLP = 0, 1, 2
+MODEL_LINEAR, MODEL_SOFTMAX, MODEL_MLP, MODEL_CNN = 0, 1, 2, 3
 X_FP32, X_BF16 = 0, 1
 TIME_EXP, TIME_PARETO, TIME_CONST = 0, 1, 2
 K_ADAPTIVE, K_FIXED, K_REPLAY, K_ADAPTIVE_FREE = 0, 1, 2, 3
@@ -46,8 +46,20 @@ PRESETS = [
 ]
 
 
+# Section V-A's setting, as far as the paper states it: 32 x 32 colour images in 10 classes, 50 000 of
+# them, two convolutional + three fully connected layers, B = 32, N = 20 workers, K0 = 5, a = -2
+# (so the threshold starts at N/K0 + a = 2).  The layer shapes are this repository's reading
+# (5 x 5 convolutions with 6 and 16 channels, each followed by ReLU and 2 x 2 max-pooling, then
+# 400 -> 120 -> 84 -> 10); dims = [C0*S*S, C1, C2, F1, F2, C, C0, k].  The step size is picked like
+# the other workloads' (the synthetic images are not normalised).
+CNN_PRESET = _mk(6, "cnn_3x32x32_c6_c16_120_84_10", MODEL_CNN, [3 * 32 * 32, 6, 16, 120, 84, 10, 3, 5], X_FP32,
+                 50_000, 10, N=20, B=32, tau_cap=2, lr=0.003, T=2000)
+
+
 def preset(i: int) -> dict:
-    """Config i in 1..5 (a fresh copy)."""
+    """Config i in 1..5 (a fresh copy); 6 = the convolutional model of Section V-A."""
+    if i == 6:
+        return copy.deepcopy(CNN_PRESET)
     return copy.deepcopy(PRESETS[i - 1])
 
 
@@ -69,4 +81,15 @@ def param_count(p: dict) -> int:
     d = p["dims"]
     if p["model"] == MODEL_LINEAR:
         return d[0]
+    if p["model"] == MODEL_CNN:
+        return sum(r * c + c for r, c in cnn_layer_shapes(p))
     return sum(d[l] * d[l + 1] + d[l + 1] for l in range(len(d) - 1))
+
+
+def cnn_layer_shapes(p: dict):
+    """[(rows, cols)] of the five weight matrices of the convolutional model in the parameter vector:
+    a convolution's matrix has one row per (input channel, kernel row, kernel column)."""
+    d0, C1, C2, F1, F2, C, C0, k = p["dims"]
+    S = int(round((d0 // C0) ** 0.5))
+    S2 = ((S - k + 1) // 2 - k + 1) // 2
+    return [(C0 * k * k, C1), (C1 * k * k, C2), (C2 * S2 * S2, F1), (F1, F2), (F2, C)]
