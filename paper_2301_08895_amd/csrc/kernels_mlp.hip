@@ -311,6 +311,11 @@ __device__ __forceinline__ void piggy_update(const GemmArgs& g, int b, uint16_t*
   }
 }
 
+__device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_block) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
+}
+
 // 256 threads = 2 x 2 wavefronts; a wavefront owns a 64 x (TN/2) sub-tile made of
 // 32x32x16 MFMA blocks (TN = 256: 2 x 4 blocks, 128 accumulator registers).  A and B
 // tiles of BK = 64 are staged in LDS (one stage; the next tile's global loads are in
@@ -318,6 +323,12 @@ __device__ __forceinline__ void piggy_update(const GemmArgs& g, int b, uint16_t*
 // cover each other's barriers).  A tile row is 128 bytes; its 16-byte chunk c is stored at
 // position c ^ ((row >> 1) & 7): the 16 lanes that one cycle of a 128-bit LDS read serves
 // (16 consecutive rows of a fragment) then cover all 64 banks.
+#ifndef ABS_RING64
+#define ABS_RING64 3
+#endif
+#ifndef ABS_RING128
+#define ABS_RING128 2
+#endif
 template <int TN>
 struct GemmCfg {
   static constexpr int WN = TN / 2;            // columns per wavefront
@@ -329,15 +340,22 @@ struct GemmCfg {
 };
 
 // TAG only separates kernel symbols (first layer / other layers) for profilers.
-template <int TN, int EPI, bool GATHER, bool PER_UPLOAD, int TAG>
-__global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
+//
+// RING > 0: the tiles travel global -> LDS by DMA through a ring of RING stages with RING - 1
+// tiles in flight and one barrier per k-step (as in the 256 x 256 kernel, swizzle on the global
+// side).  For products with few tiles per CU, where one tile in flight per workgroup leaves the
+// k-steps waiting for memory latency one after the other.  Needs whole 64-wide k-steps of A
+// (a_kvalid a multiple of BK covering the contraction).
+template <int TN, int EPI, bool GATHER, bool PER_UPLOAD, int TAG, int RING = 0>
+__global__ __launch_bounds__(256, (RING * GemmCfg<TN>::kMainElems * 2 > 80 * 1024) ? 1 : 2)
+void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
   using Cfg = GemmCfg<TN>;
   constexpr int WN = Cfg::WN, NI = Cfg::NI, BCH = Cfg::BCH;
   constexpr bool kStageT = (EPI == EPI_RELU || EPI == EPI_DGRAD);
-  constexpr int kSmem = kStageT && Cfg::kEpiElems > Cfg::kMainElems ? Cfg::kEpiElems : Cfg::kMainElems;
+  constexpr int kMain = (RING ? RING : 1) * Cfg::kMainElems;
+  constexpr int kSmem = kStageT && Cfg::kEpiElems > kMain ? Cfg::kEpiElems : kMain;
+  static_assert(kSmem * 2 <= 160 * 1024, "LDS budget");
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem];
-  uint16_t* const sA = smem;
-  uint16_t* const sB = smem + TM * BK;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -372,8 +390,14 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
     Bt += (size_t)slot * g.bt_slot_stride;
   }
 
-  // staging: thread t moves chunk (row r0 + 32 i, 16-byte column c) of each tile
-  const int r0 = t >> 3, c8 = (t & 7) * 8;
+  // staging.  Register path: thread t moves chunk (row r0 + 32 i, 16-byte column c) of each tile.
+  // DMA path: instruction i of wavefront w fills 8 rows of 128 bytes, lane l row (l >> 3) of them at
+  // chunk position l & 7, fetching logical chunk (l & 7) ^ ((row >> 1) & 7): A rows 32 w + 8 i
+  // (i < 4), B rows (TN / 4) w + 8 i (i < TN / 32); (row >> 1) & 7 is (l >> 4) + 4 (i & 1) for both.
+  constexpr int kRowStep = RING ? 8 : 32;
+  const int r0 = RING ? wave * 32 + (lane >> 3) : t >> 3;
+  const int c8 = (t & 7) * 8;
+  const int c_even = ((t & 7) ^ ((lane >> 4) & 7)) * 8, c_odd = ((t & 7) ^ ((4 + (lane >> 4)) & 7)) * 8;
   const int st_off = r0 * BK + (((t & 7) ^ ((r0 >> 1) & 7)) << 3);   // swizzled LDS offset of chunk i = 0
   const uint16_t* pa0; const uint16_t* pa1; const uint16_t* pa2; const uint16_t* pa3;
   if (GATHER) {
@@ -382,23 +406,28 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         bool real;
-        ri[i] = gen_row_of(g, rd, m0 + r0 + 32 * i, &real);
-        if (n0 == 0 && (t & 7) == 0) gen_row_store(g, m0 + r0 + 32 * i, ri[i], real);
+        ri[i] = gen_row_of(g, rd, m0 + r0 + kRowStep * i, &real);
+        if (n0 == 0 && (t & 7) == 0) gen_row_store(g, m0 + r0 + kRowStep * i, ri[i], real);
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ri[i] = g.a_rowidx[m0 + r0 + 32 * i];
+      for (int i = 0; i < 4; ++i) ri[i] = g.a_rowidx[m0 + r0 + kRowStep * i];
     }
-    pa0 = g.A + (size_t)ri[0] * g.lda + c8;
-    pa1 = g.A + (size_t)ri[1] * g.lda + c8;
-    pa2 = g.A + (size_t)ri[2] * g.lda + c8;
-    pa3 = g.A + (size_t)ri[3] * g.lda + c8;
+    pa0 = g.A + (size_t)ri[0] * g.lda + (RING ? c_even : c8);
+    pa1 = g.A + (size_t)ri[1] * g.lda + (RING ? c_odd : c8);
+    pa2 = g.A + (size_t)ri[2] * g.lda + (RING ? c_even : c8);
+    pa3 = g.A + (size_t)ri[3] * g.lda + (RING ? c_odd : c8);
+  } else if (RING) {
+    const uint16_t* base = g.A + (size_t)(m0 + r0) * g.lda;
+    pa0 = base + c_even; pa1 = base + 8 * g.lda + c_odd;
+    pa2 = base + 16 * g.lda + c_even; pa3 = base + 24 * g.lda + c_odd;
   } else {
     pa0 = g.A + (size_t)(m0 + r0) * g.lda + c8;
     pa1 = pa0 + 32 * g.lda; pa2 = pa0 + 64 * g.lda; pa3 = pa0 + 96 * g.lda;
   }
-  const uint16_t* pb0 = Bt + (size_t)(n0 + r0) * g.ldb + c8;
-  const size_t b_step = 32 * g.ldb;
+  const uint16_t* pb0 = RING ? Bt + (size_t)(n0 + wave * (TN / 4) + (lane >> 3)) * g.ldb
+                             : Bt + (size_t)(n0 + r0) * g.ldb + c8;
+  const size_t b_step = (RING ? 8 : 32) * g.ldb;
   const bool a_ok = !GATHER || c8 < g.a_kvalid;       // refined per k-step below
 
   f32x16_t acc[2][NI];
@@ -429,23 +458,55 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
   }
 #define ABS_STAGE()                                                                       \
   {                                                                                       \
-    *(uint4*)&sA[st_off] = ra0;            *(uint4*)&sA[st_off + 32 * BK] = ra1;          \
-    *(uint4*)&sA[st_off + 64 * BK] = ra2;  *(uint4*)&sA[st_off + 96 * BK] = ra3;          \
-    *(uint4*)&sB[st_off] = rb0;            *(uint4*)&sB[st_off + 32 * BK] = rb1;          \
-    if (BCH > 2) { *(uint4*)&sB[st_off + 64 * BK] = rb2; *(uint4*)&sB[st_off + 96 * BK] = rb3; }   \
-    if (BCH > 4) { *(uint4*)&sB[st_off + 128 * BK] = rb4; *(uint4*)&sB[st_off + 160 * BK] = rb5;   \
-                   *(uint4*)&sB[st_off + 192 * BK] = rb6; *(uint4*)&sB[st_off + 224 * BK] = rb7; } \
+    *(uint4*)&smem[st_off] = ra0;            *(uint4*)&smem[st_off + 32 * BK] = ra1;          \
+    *(uint4*)&smem[st_off + 64 * BK] = ra2;  *(uint4*)&smem[st_off + 96 * BK] = ra3;          \
+    *(uint4*)&smem[TM * BK + st_off] = rb0;            *(uint4*)&smem[TM * BK + st_off + 32 * BK] = rb1;          \
+    if (BCH > 2) { *(uint4*)&smem[TM * BK + st_off + 64 * BK] = rb2; *(uint4*)&smem[TM * BK + st_off + 96 * BK] = rb3; }   \
+    if (BCH > 4) { *(uint4*)&smem[TM * BK + st_off + 128 * BK] = rb4; *(uint4*)&smem[TM * BK + st_off + 160 * BK] = rb5;   \
+                   *(uint4*)&smem[TM * BK + st_off + 192 * BK] = rb6; *(uint4*)&smem[TM * BK + st_off + 224 * BK] = rb7; } \
   }
 
   const int lr = lane & 31, lk = lane >> 5;
   const int fa_row = (wm * 64 + lr) * BK, fb_row = (wn * WN + lr) * BK;
   const int sw = (lr >> 1) & 7;
+  // one request per 8 rows: stage `st_` receives tile `ks_`
+#define ABS_RING_DMA(ks_, st_)                                                            \
+  {                                                                                       \
+    const int k0_ = (ks_) * BK;                                                           \
+    uint16_t* a_ = smem + (st_) * Cfg::kMainElems + wave * 32 * BK;                       \
+    uint16_t* b_ = smem + (st_) * Cfg::kMainElems + TM * BK + wave * (TN / 4) * BK;       \
+    lds_dma16(pa0 + k0_, a_);            lds_dma16(pa1 + k0_, a_ + 8 * BK);               \
+    lds_dma16(pa2 + k0_, a_ + 16 * BK);  lds_dma16(pa3 + k0_, a_ + 24 * BK);              \
+    _Pragma("unroll") for (int i = 0; i < TN / 32; ++i)                                   \
+      lds_dma16(pb0 + i * b_step + ((i & 1) ? c_odd : c_even) + k0_, b_ + i * 8 * BK);    \
+  }
+  constexpr int kDmaPerWave = 4 + TN / 32;
   if (ks0 < ks1) {
-    ABS_FETCH(ks0);
+    if (RING) {
+#pragma unroll
+      for (int j = 0; j < RING - 1; ++j)
+        if (ks0 + j < ks1) ABS_RING_DMA(ks0 + j, j);
+    } else {
+      ABS_FETCH(ks0);
+    }
+    int stage = 0;
     for (int ks = ks0; ks < ks1; ++ks) {
-      ABS_STAGE();
-      __syncthreads();
-      if (ks + 1 < ks1) ABS_FETCH(ks + 1);
+      const uint16_t* sA = smem;
+      if (RING) {
+        // tile ks has landed when at most the RING - 2 tiles behind it are outstanding
+        constexpr int kOut = RING > 2 ? (RING - 2) * kDmaPerWave : 0;
+        if (ks + RING - 2 < ks1) __builtin_amdgcn_s_waitcnt(0x0F70 | (kOut & 15) | ((kOut >> 4) << 14));
+        else                     __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();      // ... for every wavefront; and everybody is done with tile ks - 1
+        if (ks + RING - 1 < ks1) ABS_RING_DMA(ks + RING - 1, stage == 0 ? RING - 1 : stage - 1);
+        sA = smem + stage * Cfg::kMainElems;
+        stage = stage + 1 == RING ? 0 : stage + 1;
+      } else {
+        ABS_STAGE();
+        __syncthreads();
+        if (ks + 1 < ks1) ABS_FETCH(ks + 1);
+      }
+      const uint16_t* sB = sA + TM * BK;
       // fragments of sub-step s+1 are read while the MFMAs of sub-step s run
       bf16x8_t fa[2][2], fb[2][NI];
 #define ABS_FRAGS(set, s_)                                                                        \
@@ -479,10 +540,12 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(GemmArgs g, RoundDesc 
         if (2 * NI > 2 + NI) __builtin_amdgcn_sched_group_barrier(0x008, 2 * NI - (2 + NI), 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 2 * NI, 0);
-      __syncthreads();
+      if (!RING) __syncthreads();
     }
   }
+  if (RING) __syncthreads();      // all fragment reads done before the staging area is reused
 
+#undef ABS_RING_DMA
 #undef ABS_FETCH
 #undef ABS_STAGE
 
@@ -593,11 +656,6 @@ constexpr int kEpiPitch3 = 64 + 8;                   // per wavefront: staging [
 constexpr int kEpiElems3 = 8 * 2 * 64 * kEpiPitch3;   // 147456 B
 constexpr int kSmem3 = 2 * kStage3 > kEpiElems3 ? 2 * kStage3 : kEpiElems3;
 static_assert(kSmem3 * 2 <= 160 * 1024, "LDS budget");
-
-__device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_block) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                   (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
-}
 
 // The same request written out by hand.  The compiler makes every LDS read that it cannot tell
 // apart from a pending global->LDS request wait for all of them, and it cannot for the
@@ -1651,6 +1709,18 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
   const dim3 block(256);
   const dim3 grid1(8 * g.rows_per_xcd * g.nt + g.pig_blocks, 1, 1);
+  // DMA ring: whole k-steps only
+  const bool ring_ok = EPI != EPI_LOGITS && (!GATHER || (g.a_kvalid % BK == 0 && g.a_kvalid >= g.ksteps_total * BK));
+  if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU) {
+    plan_note(EPI == EPI_RELU ? "fwd_ring" : EPI == EPI_DGRAD ? "dgrad_ring" : "wgrad_ring", TM, tn, nsplit);
+    ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64>), grid1, block, s, g, rd);
+    return false;
+  }
+  if (ring_ok && tn == 128 && ABS_RING128) {
+    plan_note(EPI == EPI_RELU ? "fwd_ring" : EPI == EPI_DGRAD ? "dgrad_ring" : "wgrad_ring", TM, tn, nsplit);
+    ABS_LAUNCH_K((mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING128>), grid1, block, s, g, rd);
+    return false;
+  }
   plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : "wgrad", TM, tn, nsplit);
   if (tn == 256)      ABS_LAUNCH_K((mlp_gemm_kernel<256, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
   else if (tn == 128) ABS_LAUNCH_K((mlp_gemm_kernel<128, EPI, GATHER, PER_UPLOAD, TAG>), grid1, block, s, g, rd);
