@@ -116,7 +116,7 @@ def stored_traffic(kind, k_avg, k_full):
 
 
 # default (warmup, steps) per workload: short enough for a default run of about a minute
-DEFAULT_STEPS = {1: (20, 180), 2: (200, 1800), 3: (200, 1800), 4: (200, 4800), 5: (100, 4900)}
+DEFAULT_STEPS = {1: (20, 180), 2: (200, 1800), 3: (200, 1800), 4: (200, 4800), 5: (100, 4900), 6: (100, 1900)}
 
 
 def cpu_baseline(p, inputs, budget_s: float):
@@ -262,7 +262,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest)")
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest); 6: the convolutional model of Section V-A")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--profile-every", type=int, default=None, metavar="n",
                     help="bracket the kernels of every n-th round with HIP events (1: of every round; "

@@ -54,7 +54,7 @@ enum {
   ABS_E_REPLAY = -6      /* k_mode 2: the replay array has no entry for this round      */
 };
 
-enum { ABS_MODEL_LINEAR = 0, ABS_MODEL_SOFTMAX = 1, ABS_MODEL_MLP = 2 };
+enum { ABS_MODEL_LINEAR = 0, ABS_MODEL_SOFTMAX = 1, ABS_MODEL_MLP = 2, ABS_MODEL_CNN = 3 };
 enum { ABS_X_FP32 = 0, ABS_X_BF16 = 1 };
 enum { ABS_K_ADAPTIVE = 0, ABS_K_FIXED = 1, ABS_K_REPLAY = 2, ABS_K_ADAPTIVE_FREE = 3 };
 enum { ABS_TAU_ADAPTIVE = 0, ABS_TAU_FIXED = 1, ABS_TAU_INF = 2 };
@@ -74,6 +74,16 @@ typedef struct abs_ctx abs_ctx;   /* opaque: one simulation */
  *                L = n_layers >= 2, d_0 % 8 == 0, d_L <= 256; X bf16 (uint16
  *                payload) [M, d_0]; bf16 operands, fp32 accumulation and master
  *                weights.
+ *             3: the convolutional network of Section V-A (two convolutional and three
+ *                fully connected layers; the paper gives no shapes, this is the reading):
+ *                n_layers = 5, dims = {C0*S*S, C1, C2, F1, F2, C, C0, k}: k x k convolutions,
+ *                stride 1, no padding, C0 -> C1 -> C2 channels, each followed by ReLU and
+ *                2 x 2 max-pooling (S - k + 1 and the pooled side - k + 1 even), then dense
+ *                layers F0 = C2*S2*S2 -> F1 -> F2 -> C with ReLU between them, softmax
+ *                cross-entropy.  X fp32 [M, C0*S*S], an image stored (channel, row,
+ *                column); y int32 [M]; fp32 throughout.  Model vector: per
+ *                layer W then b; a convolution's W is [C_in*k*k][C_out], row
+ *                (ci*k + u)*k + v; a dense layer's [d_in][d_out].
  *  k_mode     0: Eq. 5, floor'ed, kept non-decreasing;  1: K^t = K0;
  *             2: K^t = k_replay[t] (host array, copied at create);
  *             3: Eq. 5 floor'ed and clamped to [1, N] only.

@@ -115,7 +115,8 @@ def make_config(p: dict, device_mode: int = 1, profile: int = 0, k_replay=None) 
     array, if any, is kept alive on the returned object."""
     c = AbsConfig()
     c.model = p["model"]
-    c.n_layers = len(p["dims"]) - 1
+    # the convolutional model's dims carry its geometry (8 entries); it has five layers
+    c.n_layers = 5 if p["model"] == 3 else len(p["dims"]) - 1
     for i, d in enumerate(p["dims"]):
         c.dims[i] = d
     c.x_dtype = p["x_dtype"]

@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libabs.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 HIP_SOURCES = ["abs_api.hip", "kernels_regression.hip", "kernels_local.hip", "kernels_eval.hip", "kernels_mlp.hip",
-               "calibrate.hip"]
+               "calibrate.hip", "kernels_cnn.hip"]
 CXX_SOURCES = ["sched.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]

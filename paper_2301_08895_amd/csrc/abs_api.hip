@@ -43,6 +43,10 @@ double seconds_since(std::chrono::steady_clock::time_point t0) {
 
 size_t param_count(const abs_config& c) {
   if (c.model == ABS_MODEL_LINEAR) return (size_t)c.dims[0];
+  if (c.model == ABS_MODEL_CNN) {
+    CnnPlan cp; const char* w = nullptr;
+    return cnn_plan(c, cp, &w) ? cp.P : 0;
+  }
   size_t p = 0;
   for (int l = 0; l < c.n_layers; ++l) p += (size_t)c.dims[l] * c.dims[l + 1] + c.dims[l + 1];
   return p;
@@ -95,7 +99,13 @@ bool validate(const abs_config& c, std::string& why) {
       if (!mlp_plan(c, p, &w)) return bad(w ? w : "unsupported MLP configuration");
       break;
     }
-    default: return bad("model must be 0, 1 or 2");
+    case ABS_MODEL_CNN: {
+      CnnPlan p;
+      const char* w = nullptr;
+      if (!cnn_plan(c, p, &w)) return bad(w ? w : "unsupported CNN configuration");
+      break;
+    }
+    default: return bad("model must be 0, 1, 2 or 3");
   }
   return true;
 }
@@ -160,7 +170,8 @@ const char* abs_impl::kernel_kind_name(int kind) {
   static const char* names[KK_COUNT] = {
       "linreg_round", "softmax_rows", "softmax_update", "mlp_index", "mlp_gather_t", "mlp_fwd_l1",
       "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_logits_ce", "mlp_loss", "mlp_dgrad_out", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
-      "mlp_update", "mlp_bias_loss", "local_steps", "delta_update", "evaluate", "mlp_wgrad_out"};
+      "mlp_update", "mlp_bias_loss", "local_steps", "delta_update", "evaluate", "mlp_wgrad_out",
+      "cnn_conv_fwd", "cnn_dense", "cnn_dense_wgrad", "cnn_conv_bwd", "cnn_conv_wgrad"};
   return kind >= 0 && kind < KK_COUNT ? names[kind] : "?";
 }
 
@@ -175,6 +186,7 @@ struct abs_ctx : public LaunchHook {
   int R = 0;
   RegPlan rplan{};
   MlpArgs margs{};
+  CnnArgs cargs{};
   LossMailbox* h_box = nullptr;   // pinned, device-visible
   LossMailbox* d_box = nullptr;   // the device's address of h_box
   int device = -1;                // the GPU the handle was created on
@@ -283,6 +295,11 @@ size_t abs_workspace_size(const abs_config* cfg) {
     mlp_plan(*cfg, p, &w);
     return p.total;
   }
+  if (cfg->model == ABS_MODEL_CNN) {
+    CnnPlan p; const char* w = nullptr;
+    cnn_plan(*cfg, p, &w);
+    return p.total;
+  }
   RegPlan p; reg_plan(*cfg, p);
   return p.total;
 }
@@ -338,6 +355,19 @@ int abs_create(const abs_config* cfg, const void* d_X, const void* d_y, const fl
     c->margs.mailbox = c->d_box;
     c->slot_stride = c->margs.plan.slot_stride;
     c->off_ring = c->margs.plan.off_ring;
+  } else if (cfg->model == ABS_MODEL_CNN) {
+    const char* w = nullptr;
+    cnn_plan(*cfg, c->cargs.plan, &w);
+    c->cargs.ws = c->ws;
+    c->cargs.X = (const float*)d_X;
+    c->cargs.y = (const int32_t*)d_y;
+    c->cargs.shard_rows = shard;
+    c->cargs.batch_key = bkey;
+    c->cargs.mailbox = c->d_box;
+    c->slot_stride = c->cargs.plan.slot_stride;
+    c->off_ring = c->cargs.plan.off_ring;
+    e = cnn_prepare();
+    if (e != hipSuccess) return fail("hipFuncSetAttribute", e);
   } else {
     reg_plan(*cfg, c->rplan);
     c->slot_stride = c->rplan.slot_stride;
@@ -432,6 +462,8 @@ int abs_round(abs_ctx* ctx, int32_t n_rounds) {
     hipError_t e;
     if (cfg.model == ABS_MODEL_MLP) {
       e = launch_mlp_round(ctx->margs, rd, ctx->stream, ctx);
+    } else if (cfg.model == ABS_MODEL_CNN) {
+      e = launch_cnn_round(ctx->cargs, rd, ctx->stream, ctx);
     } else {
       RegressionArgs ra;
       fill_regression_args(ctx, ra);
@@ -494,6 +526,8 @@ void abs_batch_destroy(abs_batch* b) {
 
 namespace {
 // Checks that the handles can form a batch; the message of the first problem otherwise.
+// models whose round is a chain of launches of their own (batches run them side by side on streams)
+bool chain_model(int model) { return model == ABS_MODEL_MLP || model == ABS_MODEL_CNN; }
 const char* batch_problem(abs_ctx** ctxs, int32_t n) {
   if (!ctxs) return "NULL argument";
   if (n < 1 || n > 4096) return "a batch holds 1..4096 simulations";
@@ -517,7 +551,7 @@ struct BatchPlan { size_t rd_stride, off_args, off_rds[2], off_slots, slot_float
 BatchPlan batch_plan(const abs_ctx* c0, int32_t n) {
   BatchPlan p{};
   p.rd_stride = 16 + (size_t)c0->cfg.N * sizeof(WorkerDesc);
-  if (c0->cfg.model == ABS_MODEL_MLP) return p;      // MLP simulations keep their own launches and workspaces
+  if (chain_model(c0->cfg.model)) return p;      // MLP / CNN simulations keep their own launches and workspaces
   size_t o = 0;
   p.off_args = o; o = round_up(o + (size_t)n * sizeof(RegressionArgs), 256);
   for (int i = 0; i < 2; ++i) { p.off_rds[i] = o; o = round_up(o + (size_t)n * p.rd_stride, 256); }
@@ -562,7 +596,7 @@ int abs_batch_create(abs_ctx** ctxs, int32_t n, void* d_workspace, size_t worksp
   }
   // MLP simulations keep their own launches, workspaces and mailboxes: the batch only runs them
   // side by side (abs_batch_round)
-  if (c0->cfg.model == ABS_MODEL_MLP) { *out = b.release(); return ABS_OK; }
+  if (chain_model(c0->cfg.model)) { *out = b.release(); return ABS_OK; }
   char* ws = (char*)d_workspace;
   b->d_args = (RegressionArgs*)(ws + plan.off_args);
   for (int i = 0; i < 2; ++i) {
@@ -739,7 +773,7 @@ int abs_batch_round(abs_batch* b, int32_t n_rounds) {
   if (!b || n_rounds < 0) return ABS_E_ARG;
   const int S = (int)b->ctx.size();
   const abs_config& c0 = b->ctx[0]->cfg;
-  if (c0.model == ABS_MODEL_MLP) return batch_round_mlp(b, n_rounds);
+  if (chain_model(c0.model)) return batch_round_mlp(b, n_rounds);
   BatchRoundState st;
   st.b = b;
   st.S = S;
@@ -859,15 +893,17 @@ static int enqueue_evaluation(abs_ctx* ctx, int64_t version, const void* d_X, co
   }
   const abs_config& cfg = ctx->cfg;
   const uint32_t slot = (uint32_t)(version % ctx->R);
-  const bool mlp = cfg.model == ABS_MODEL_MLP;
+  const bool mlp = cfg.model == ABS_MODEL_MLP, cnn = cfg.model == ABS_MODEL_CNN;
   e.X = d_X; e.y = d_y; e.n_rows = n_rows;
-  e.cap = mlp ? ctx->margs.plan.Mp : kEvalChunk;
+  e.cap = mlp ? ctx->margs.plan.Mp : cnn ? ctx->cargs.plan.N * ctx->cargs.plan.B : kEvalChunk;
   e.acc = (double*)scratch;
   e.rowloss = (float*)(scratch + 256);
   e.correct = (float*)(scratch + 256 + ((size_t)e.cap * 4 + 255) / 256 * 256);
   hipError_t err;
   if (mlp) {
     err = launch_mlp_eval(ctx->margs, slot, e, ctx->stream, hook);
+  } else if (cnn) {
+    err = launch_cnn_eval(ctx->cargs, slot, e, ctx->stream, hook);
   } else {
     const float* w = (const float*)(ctx->ws + ctx->off_ring) + (size_t)slot * ctx->slot_stride;
     err = launch_regression_eval(w, cfg.dims[0], cfg.dims[1], cfg.model == ABS_MODEL_SOFTMAX, e, ctx->stream, hook);
@@ -879,8 +915,8 @@ static int enqueue_evaluation(abs_ctx* ctx, int64_t version, const void* d_X, co
 int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
                  double* h_loss, double* h_accuracy) {
   if (!ctx || !h_loss || !h_accuracy) return ABS_E_ARG;
-  const bool mlp = ctx->cfg.model == ABS_MODEL_MLP;
-  char* scratch = ctx->ws ? ctx->ws + (mlp ? ctx->margs.plan.off_eval : ctx->rplan.off_eval) : nullptr;
+  const bool mlp = ctx->cfg.model == ABS_MODEL_MLP, cnn = ctx->cfg.model == ABS_MODEL_CNN;
+  char* scratch = ctx->ws ? ctx->ws + (mlp ? ctx->margs.plan.off_eval : cnn ? ctx->cargs.plan.off_eval : ctx->rplan.off_eval) : nullptr;
   EvalArgs e;
   const int rc = enqueue_evaluation(ctx, version, d_X, d_y, n_rows, scratch, ctx, e);
   if (rc != ABS_OK) return rc;

@@ -43,6 +43,11 @@ enum KernelKind {
   KK_DELTA_UPDATE,
   KK_EVAL,
   KK_MLP_WGRAD_OUT,
+  KK_CNN_CONV_FWD,
+  KK_CNN_DENSE,
+  KK_CNN_DENSE_WGRAD,
+  KK_CNN_CONV_BWD,
+  KK_CNN_CONV_WGRAD,
   KK_COUNT
 };
 const char* kernel_kind_name(int kind);
@@ -172,5 +177,40 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
 std::string mlp_round_plan(const abs_config& cfg, int K);
 // forward pass of ring slot `slot` over e.n_rows evaluation rows, Mp rows at a time (e.cap >= Mp)
 hipError_t launch_mlp_eval(const MlpArgs& a, uint32_t slot, const EvalArgs& e, hipStream_t s, LaunchHook* hook);
+
+// ---- convolutional model (Section V-A: two convolutional + three dense layers), fp32 ---------
+// Geometry and workspace offsets; filled by cnn_plan().
+struct CnnPlan {
+  int C0, C1, C2, F0, F1, F2, C, k;   // channels, dense widths (F0 = C2 S2 S2), classes, kernel size
+  int S, S1, S2;                      // image side; pooled sides after the first / second convolution
+  int B, N, R;
+  size_t P, slot_stride;              // parameters; floats between ring slots
+  size_t w_off[5], b_off[5];          // W_l / b_l inside a slot (floats): conv1, conv2, dense1..3
+  // byte offsets into the workspace; per stacked row (N B at most):
+  size_t off_ring, off_rowidx, off_label;
+  size_t off_p1, off_a1;              // first pooled map fp32 [C1 S1 S1] and which entry of each window it was
+  size_t off_p2, off_a2;              // second pooled map [F0] (the dense stack's input) and the same
+  size_t off_h1, off_h2;              // dense activations
+  size_t off_dz1, off_dz2, off_dz3;   // dense output gradients (coefficient of Eq. 3 included)
+  size_t off_dp2, off_dp1;            // gradients of the pooled maps (zero where the window is dead)
+  size_t off_lossbuf;                 // [N] mean minibatch loss per upload
+  int U;                              // local steps per job
+  size_t off_priv;                    // U > 1: the uploads' private models [N][slot_stride]
+  size_t off_eval;                    // evaluation scratch for N B rows
+  size_t total;
+};
+bool cnn_plan(const abs_config& cfg, CnnPlan& plan, const char** why);
+struct CnnArgs {
+  CnnPlan plan;
+  char* ws;
+  const float* X;        // fp32 [M, C0 S S], an image row is (channel, row, column)
+  const int32_t* y;
+  uint64_t shard_rows, batch_key;
+  LossMailbox* mailbox;
+};
+hipError_t cnn_prepare();       // once per process: LDS opt-in of the kernels
+hipError_t launch_cnn_round(const CnnArgs& a, const RoundDesc& rd, hipStream_t s, LaunchHook* hook);
+// forward pass of ring slot `slot` over e.n_rows evaluation rows, N B rows at a time (e.cap >= N B)
+hipError_t launch_cnn_eval(const CnnArgs& a, uint32_t slot, const EvalArgs& e, hipStream_t s, LaunchHook* hook);
 
 }  // namespace abs_impl

@@ -70,6 +70,12 @@ def param_blocks(p):
     if p["model"] == 0:
         return [("w", slice(0, d[0]))]
     out, o = [], 0
+    if p["model"] == 3:              # convolutional model: conv1, conv2, dense1..3
+        names = ["Wc1", "Wc2", "Wd1", "Wd2", "Wd3"]
+        for name, (r, c) in zip(names, workloads.presets.cnn_layer_shapes(p)):
+            out.append((name, slice(o, o + r * c))); o += r * c
+            out.append(("b" + name[1:], slice(o, o + c))); o += c
+        return out
     for l in range(len(d) - 1):
         out.append((f"W{l + 1}", slice(o, o + d[l] * d[l + 1]))); o += d[l] * d[l + 1]
         out.append((f"b{l + 1}", slice(o, o + d[l + 1]))); o += d[l + 1]
