@@ -171,7 +171,7 @@ const char* abs_impl::kernel_kind_name(int kind) {
       "linreg_round", "softmax_rows", "softmax_update", "mlp_index", "mlp_gather_t", "mlp_fwd_l1",
       "mlp_fwd_hidden", "mlp_fwd_logits", "mlp_logits_ce", "mlp_loss", "mlp_dgrad_out", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad",
       "mlp_update", "mlp_bias_loss", "local_steps", "delta_update", "evaluate", "mlp_wgrad_out",
-      "cnn_conv_fwd", "cnn_dense", "cnn_dense_wgrad", "cnn_conv_bwd", "cnn_conv_wgrad"};
+      "cnn_conv_fwd", "cnn_dense", "cnn_dense_wgrad", "cnn_conv_bwd", "cnn_conv_wgrad", "cnn_combine"};
   return kind >= 0 && kind < KK_COUNT ? names[kind] : "?";
 }
 

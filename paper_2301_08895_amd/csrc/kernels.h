@@ -48,6 +48,7 @@ enum KernelKind {
   KK_CNN_DENSE_WGRAD,
   KK_CNN_CONV_BWD,
   KK_CNN_CONV_WGRAD,
+  KK_CNN_COMBINE,
   KK_COUNT
 };
 const char* kernel_kind_name(int kind);
@@ -195,7 +196,10 @@ struct CnnPlan {
   size_t off_dp2, off_dp1;            // gradients of the pooled maps (zero where the window is dead)
   size_t off_lossbuf;                 // [N] mean minibatch loss per upload
   int U;                              // local steps per job
-  size_t off_priv;                    // U > 1: the uploads' private models [N][slot_stride]
+  size_t off_rowloss;                 // per-row losses
+  size_t off_priv;                    // [N][slot_stride]: U = 1: the uploads' shares of the dense layers' gradient;
+                                      // U > 1: the uploads' private models
+  size_t off_grow1, off_grow2;        // the rows' shares of the two convolutions' gradients [N B][weights + biases]
   size_t off_eval;                    // evaluation scratch for N B rows
   size_t total;
 };

@@ -34,6 +34,7 @@ namespace abs_impl {
 namespace {
 
 constexpr int kDead = 255;
+constexpr int kMaxCout = 32;
 
 __device__ __forceinline__ uint64_t cnn_batch_row(const WorkerDesc& w, uint64_t batch_key, uint64_t shard_rows,
                                                   uint32_t b) {
@@ -63,19 +64,6 @@ __device__ __forceinline__ const float* slot_of(const CnnDev& d, const RoundDesc
   const uint32_t slot = d.fixed_slot >= 0 ? (uint32_t)d.fixed_slot : rd.w[upload].slot;
   return wsp<const float>(d, d.p.off_ring) + (size_t)slot * d.p.slot_stride;
 }
-// where a weight-gradient kernel reads the model it steps from and writes the stepped model: the
-// round's slots (U = 1), or upload a's stale version / private model (local steps)
-__device__ __forceinline__ void step_models(const CnnDev& d, const RoundDesc& rd, int upload, const float** cur,
-                                            float** next) {
-  if (d.step < 0) {
-    *cur = wsp<const float>(d, d.p.off_ring) + (size_t)rd.slot_cur * d.p.slot_stride;
-    *next = wsp<float>(d, d.p.off_ring) + (size_t)rd.slot_next * d.p.slot_stride;
-  } else {
-    *cur = slot_of(d, rd, upload);
-    *next = wsp<float>(d, d.p.off_priv) + (size_t)upload * d.p.slot_stride;
-  }
-}
-
 // layer 0: dataset rows -> first pooled map; layer 1: first pooled map -> second pooled map (the
 // dense stack's input).
 __global__ __launch_bounds__(256) void cnn_conv_pool_fwd_kernel(CnnDev d, RoundDesc rd, int layer) {
@@ -132,37 +120,48 @@ __global__ __launch_bounds__(256) void cnn_conv_pool_fwd_kernel(CnnDev d, RoundD
   }
 }
 
-// out[b][j] = bias[j] + sum_i in[b][i] W[i][j] for the B rows in LDS; a thread takes 8 rows of one
-// column, so a weight is fetched once per 8 rows and neighbouring threads read neighbouring weights.
+constexpr int kGroup = 8;       // stacked rows per workgroup of the dense stage
+
+// out[b][j] = bias[j] + sum_i in[b][i] W[i][j] for the workgroup's nb <= 8 rows in LDS: a thread
+// takes one column, so a weight is fetched once for all rows and neighbouring threads read
+// neighbouring weights; eight weights of a column are in flight at a time.
 __device__ __forceinline__ void dense_rows(const float* s_in, int Fin, const float* W, const float* bias, int Fout,
-                                           int B, bool relu, float* s_out, float* g_out) {
-  const int groups = (B + 7) / 8;
-  for (int item = threadIdx.x; item < groups * Fout; item += 256) {
-    const int j = item % Fout, b0 = (item / Fout) * 8;
-    float acc[8];
+                                           int nb, bool relu, float* s_out, float* g_out) {
+  for (int j = threadIdx.x; j < Fout; j += blockDim.x) {
+    float acc[kGroup];
     const float bv = bias[j];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) acc[q] = bv;
-    for (int i = 0; i < Fin; ++i) {
+    for (int q = 0; q < kGroup; ++q) acc[q] = bv;
+    int i = 0;
+    for (; i + 8 <= Fin; i += 8) {
+      float wv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) wv[e] = W[(size_t)(i + e) * Fout + j];
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int q = 0; q < kGroup; ++q) acc[q] = fmaf(s_in[q * Fin + i + e], wv[e], acc[q]);
+    }
+    for (; i < Fin; ++i) {
       const float wv = W[(size_t)i * Fout + j];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[q] = fmaf(s_in[min(b0 + q, B - 1) * Fin + i], wv, acc[q]);
+      for (int q = 0; q < kGroup; ++q) acc[q] = fmaf(s_in[q * Fin + i], wv, acc[q]);
     }
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-      if (b0 + q < B) {
+    for (int q = 0; q < kGroup; ++q)
+      if (q < nb) {
         const float v = relu ? fmaxf(acc[q], 0.f) : acc[q];
-        s_out[(b0 + q) * Fout + j] = v;
-        if (g_out) g_out[(size_t)(b0 + q) * Fout + j] = v;
+        s_out[q * Fout + j] = v;
+        if (g_out) g_out[(size_t)q * Fout + j] = v;
       }
   }
 }
 
 // dIn[b][i] = gate(b, i) ? sum_j dOut[b][j] W[i][j] : 0
 template <typename Gate>
-__device__ __forceinline__ void dense_rows_back(const float* s_dout, int Fout, const float* W, int Fin, int B,
+__device__ __forceinline__ void dense_rows_back(const float* s_dout, int Fout, const float* W, int Fin, int nb,
                                                 Gate gate, float* s_din, float* g_din) {
-  for (int item = threadIdx.x; item < B * Fin; item += 256) {
+  for (int item = threadIdx.x; item < nb * Fin; item += blockDim.x) {
     const int b = item / Fin, i = item - b * Fin;
     float acc = 0.f;
     if (gate(b, i)) {
@@ -175,36 +174,39 @@ __device__ __forceinline__ void dense_rows_back(const float* s_dout, int Fout, c
   }
 }
 
-// Training: one workgroup per upload (B rows).  Evaluation (eval_loss != nullptr): one workgroup per
-// block of B rows of the evaluation pass, forward only, per-row loss and hit flag.
-__global__ __launch_bounds__(256) void cnn_dense_kernel(CnnDev d, RoundDesc rd, float* eval_loss, float* eval_hit) {
+// The dense stack for a group of up to 8 rows of one upload (training) or of the evaluation pass:
+// forward at the rows' model version, per-row loss, and (training) back down to the gradient of the
+// second pooled map; every dZ carries the upload's coefficient of Eq. 3.
+__global__ __launch_bounds__(128) void cnn_dense_kernel(CnnDev d, RoundDesc rd, float* eval_loss, float* eval_hit) {
   extern __shared__ float sm[];
   const CnnPlan& p = d.p;
-  const int a = blockIdx.x, t = threadIdx.x;
-  const int r0 = a * p.B;
-  const int B = min(p.B, d.n_rows - r0);
+  const int t = threadIdx.x;
+  const int gpu_ = (p.B + kGroup - 1) / kGroup;            // groups per upload
+  const int a = blockIdx.x / gpu_, g = blockIdx.x - a * gpu_;
+  const int r0 = a * p.B + g * kGroup;
+  const int nb = min(kGroup, min(p.B - g * kGroup, d.n_rows - r0));
+  if (nb <= 0) return;
   float* sH0 = sm;
-  float* sH1 = sH0 + p.B * p.F0;
-  float* sH2 = sH1 + p.B * p.F1;
-  float* sZ = sH2 + p.B * p.F2;
-  float* sD2 = sZ + p.B * p.C;          // dZ of the second dense layer
-  float* sD1 = sD2 + p.B * p.F2;        // dZ of the first dense layer
-  float* sL = sD1 + p.B * p.F1;         // per-row losses
+  float* sH1 = sH0 + kGroup * p.F0;
+  float* sH2 = sH1 + kGroup * p.F1;
+  float* sZ = sH2 + kGroup * p.F2;
+  float* sD2 = sZ + kGroup * p.C;       // dZ of the second dense layer
+  float* sD1 = sD2 + kGroup * p.F2;     // dZ of the first dense layer
   const float* w = slot_of(d, rd, a);
   const float* p2 = wsp<const float>(d, p.off_p2) + (size_t)r0 * p.F0;
-  for (int i = t; i < B * p.F0; i += 256) sH0[i] = p2[i];
+  for (int i = t; i < kGroup * p.F0; i += 128) sH0[i] = i < nb * p.F0 ? p2[i] : 0.f;
   __syncthreads();
   const bool train = eval_loss == nullptr;
-  dense_rows(sH0, p.F0, w + p.w_off[2], w + p.b_off[2], p.F1, B, true, sH1,
+  dense_rows(sH0, p.F0, w + p.w_off[2], w + p.b_off[2], p.F1, nb, true, sH1,
              train ? wsp<float>(d, p.off_h1) + (size_t)r0 * p.F1 : nullptr);
   __syncthreads();
-  dense_rows(sH1, p.F1, w + p.w_off[3], w + p.b_off[3], p.F2, B, true, sH2,
+  dense_rows(sH1, p.F1, w + p.w_off[3], w + p.b_off[3], p.F2, nb, true, sH2,
              train ? wsp<float>(d, p.off_h2) + (size_t)r0 * p.F2 : nullptr);
   __syncthreads();
-  dense_rows(sH2, p.F2, w + p.w_off[4], w + p.b_off[4], p.C, B, false, sZ, nullptr);
+  dense_rows(sH2, p.F2, w + p.w_off[4], w + p.b_off[4], p.C, nb, false, sZ, nullptr);
   __syncthreads();
   const int32_t* label = wsp<const int32_t>(d, p.off_label) + r0;
-  if (t < B) {
+  if (t < nb) {
     // softmax cross-entropy of row t; dZ = c (p - onehot) with the upload's coefficient of Eq. 3
     float* z = sZ + t * p.C;
     const int y = label[t];
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256) void cnn_dense_kernel(CnnDev d, RoundDesc rd, 
         z[c] = v;
         dz3[c] = v;
       }
-      sL[t] = loss;
+      wsp<float>(d, p.off_rowloss)[r0 + t] = loss;
     } else {
       eval_loss[r0 + t] = loss;
       eval_hit[r0 + t] = best == y ? 1.f : 0.f;
@@ -229,43 +231,28 @@ __global__ __launch_bounds__(256) void cnn_dense_kernel(CnnDev d, RoundDesc rd, 
   }
   if (!train) return;
   __syncthreads();
-  if (t == 0) {
-    float sum = 0.f;
-    for (int b = 0; b < B; ++b) sum += sL[b];
-    // the upload's mean minibatch loss; with local steps, the mean over its U steps
-    float* lb = wsp<float>(d, p.off_lossbuf) + a;
-    const float mean = sum / (float)B;
-    *lb = d.step <= 0 ? (d.step < 0 ? mean : mean / (float)d.U) : *lb + mean / (float)d.U;
-  }
-  dense_rows_back(sZ, p.C, w + p.w_off[4], p.F2, B, [&](int b, int i) { return sH2[b * p.F2 + i] > 0.f; }, sD2,
+  dense_rows_back(sZ, p.C, w + p.w_off[4], p.F2, nb, [&](int b, int i) { return sH2[b * p.F2 + i] > 0.f; }, sD2,
                   wsp<float>(d, p.off_dz2) + (size_t)r0 * p.F2);
   __syncthreads();
-  dense_rows_back(sD2, p.F2, w + p.w_off[3], p.F1, B, [&](int b, int i) { return sH1[b * p.F1 + i] > 0.f; }, sD1,
+  dense_rows_back(sD2, p.F2, w + p.w_off[3], p.F1, nb, [&](int b, int i) { return sH1[b * p.F1 + i] > 0.f; }, sD1,
                   wsp<float>(d, p.off_dz1) + (size_t)r0 * p.F1);
   __syncthreads();
   const uint8_t* a2 = wsp<const uint8_t>(d, p.off_a2) + (size_t)r0 * p.F0;
-  dense_rows_back(sD1, p.F1, w + p.w_off[2], p.F0, B, [&](int b, int i) { return a2[b * p.F0 + i] != kDead; }, nullptr,
+  dense_rows_back(sD1, p.F1, w + p.w_off[2], p.F0, nb, [&](int b, int i) { return a2[b * p.F0 + i] != kDead; }, nullptr,
                   wsp<float>(d, p.off_dp2) + (size_t)r0 * p.F0);
 }
 
-// Eq. 3 for the dense layers: element e of the three weight matrices and biases, summed over the
-// stacked rows in row order (every dZ carries its upload's coefficient).
-__global__ __launch_bounds__(256) void cnn_dense_wgrad_update_kernel(CnnDev d, RoundDesc rd, LossMailbox* mailbox) {
+// The dense layers' share of an upload's gradient (blockIdx.y = upload): element e of the three
+// weight matrices and biases summed over the upload's B rows in row order.  U = 1: the sum goes to
+// the upload's slot of G (Eq. 3 adds the slots in arrival order, cnn_combine_kernel); local steps:
+// the upload's private model takes the step at once (Eq. 2).
+__global__ __launch_bounds__(256) void cnn_dense_wgrad_kernel(CnnDev d, RoundDesc rd) {
   const CnnPlan& p = d.p;
-  if (blockIdx.x == 0 && mailbox) {
-    const float* lossbuf = wsp<const float>(d, p.off_lossbuf);
-    if ((int)threadIdx.x < rd.K) mailbox->loss[threadIdx.x] = lossbuf[threadIdx.x];
-    if (threadIdx.x < ABS_MAX_WORKERS) __threadfence_system();
-    __syncthreads();
-    if (threadIdx.x == 0) mailbox->stamp = rd.stamp;
-  }
+  const int a = blockIdx.y;
   const int Fin[3] = {p.F0, p.F1, p.F2}, Fout[3] = {p.F1, p.F2, p.C};
   const size_t in_off[3] = {p.off_p2, p.off_h1, p.off_h2}, dz_off[3] = {p.off_dz1, p.off_dz2, p.off_dz3};
   long e = (long)blockIdx.x * 256 + threadIdx.x;
-  // local steps: blockIdx.y = upload, the sum runs over its own rows only (Eq. 2)
-  const int ra = d.step < 0 ? 0 : (int)blockIdx.y * p.B, rb = d.step < 0 ? d.n_rows : ra + p.B;
-  const float* w_cur; float* w_next;
-  step_models(d, rd, (int)blockIdx.y, &w_cur, &w_next);
+  const int ra = a * p.B, rb = ra + p.B;
   for (int l = 0; l < 3; ++l) {
     const long nw = (long)Fin[l] * Fout[l], n = nw + Fout[l];
     if (e < n) {
@@ -282,7 +269,8 @@ __global__ __launch_bounds__(256) void cnn_dense_wgrad_update_kernel(CnnDev d, R
         for (int r = ra; r < rb; ++r) g += dz[(size_t)r * Fout[l] + j];
         at = p.b_off[2 + l] + (size_t)j;
       }
-      w_next[at] = w_cur[at] - g;
+      float* priv = wsp<float>(d, p.off_priv) + (size_t)a * p.slot_stride;
+      priv[at] = d.step < 0 ? g : slot_of(d, rd, a)[at] - g;
       return;
     }
     e -= n;
@@ -334,55 +322,96 @@ __global__ __launch_bounds__(256) void cnn_conv2_bwd_kernel(CnnDev d, RoundDesc 
   }
 }
 
-// Eq. 3 for a convolution: workgroup q < Cin k k sums filter row q = (ci, u, v) over all rows and
-// pooling windows (a window contributes the input under its maximum), workgroup Cin k k the bias.
-// Thread partial sums are added in thread order.
-constexpr int kMaxCout = 32;
-__global__ __launch_bounds__(256) void cnn_conv_wgrad_update_kernel(CnnDev d, RoundDesc rd, int layer) {
-  __shared__ float sred[kMaxCout][257];
+// A convolution's share of one row's gradient (workgroup = stacked row): the row's input map, the
+// gradient of its pooled map and the windows' maxima in LDS; a thread sums one filter weight
+// (ci, u, v, co) over the pooling windows (a window contributes the input under its maximum), the
+// last Cout entries are the bias.  Result: Grow[r][weights..., biases...], in the model's own order.
+__global__ __launch_bounds__(256) void cnn_conv_wgrad_rows_kernel(CnnDev d, int layer) {
+  extern __shared__ float sm[];
   const CnnPlan& p = d.p;
-  const int t = threadIdx.x, k = p.k;
+  const int r = blockIdx.x, t = threadIdx.x, k = p.k;
   const int Cin = layer ? p.C1 : p.C0, Cout = layer ? p.C2 : p.C1;
   const int Sin = layer ? p.S1 : p.S, Sp = layer ? p.S2 : p.S1;
-  const int n_in = Cin * Sin * Sin, n_out = Cout * Sp * Sp, win = Sp * Sp;
-  const int q = blockIdx.x;
-  const bool bias = q == Cin * k * k;
-  const int ci = q / (k * k), u = (q / k) % k, v = q % k;
-  const float* dP = wsp<const float>(d, layer ? p.off_dp2 : p.off_dp1);
-  const uint8_t* A = wsp<const uint8_t>(d, layer ? p.off_a2 : p.off_a1);
-  const float* P1 = wsp<const float>(d, p.off_p1);
-  const uint32_t* rowidx = wsp<const uint32_t>(d, p.off_rowidx);
-  float acc[kMaxCout];
-#pragma unroll
-  for (int co = 0; co < kMaxCout; ++co) acc[co] = 0.f;
-  const int ra = d.step < 0 ? 0 : (int)blockIdx.y * p.B, nr = d.step < 0 ? d.n_rows : p.B;
-  for (int it = t; it < nr * win; it += 256) {
-    const int r = ra + it / win, w_ = it % win, pi = w_ / Sp, pj = w_ - pi * Sp;
-    const float* in = layer ? P1 + (size_t)r * n_in : d.X + (size_t)rowidx[r] * n_in;
-    const float* g = dP + (size_t)r * n_out + w_;
-    const uint8_t* ar = A + (size_t)r * n_out + w_;
-#pragma unroll
-    for (int co = 0; co < kMaxCout; ++co) {
-      if (co < Cout) {
-        const int m = ar[co * win];
-        if (m != kDead) {
-          const float gv = g[co * win];
-          acc[co] += bias ? gv : in[(ci * Sin + 2 * pi + (m >> 1) + u) * Sin + 2 * pj + (m & 1) + v] * gv;
-        }
-      }
+  const int n_in = Cin * Sin * Sin, n_out = Cout * Sp * Sp, win = Sp * Sp, nW = Cin * k * k * Cout;
+  float* sx = sm;
+  float* sg = sx + n_in;
+  int* sa = (int*)(sg + n_out);
+  const float* in = layer ? wsp<const float>(d, p.off_p1) + (size_t)r * n_in
+                          : d.X + (size_t)wsp<const uint32_t>(d, p.off_rowidx)[r] * n_in;
+  const float* g = wsp<const float>(d, layer ? p.off_dp2 : p.off_dp1) + (size_t)r * n_out;
+  const uint8_t* A = wsp<const uint8_t>(d, layer ? p.off_a2 : p.off_a1) + (size_t)r * n_out;
+  for (int i = t; i < n_in; i += 256) sx[i] = in[i];
+  for (int i = t; i < n_out; i += 256) {
+    const int m = A[i], w_ = i % win, pi = w_ / Sp, pj = w_ - pi * Sp;
+    sg[i] = m == kDead ? 0.f : g[i];
+    // offset of the window's maximum inside an input plane (a dead window contributes 0 x its corner)
+    sa[i] = (2 * pi + (m == kDead ? 0 : (m >> 1))) * Sin + 2 * pj + (m == kDead ? 0 : (m & 1));
+  }
+  __syncthreads();
+  float* out = wsp<float>(d, layer ? p.off_grow2 : p.off_grow1) + (size_t)r * (nW + Cout);
+  for (int e = t; e < nW + Cout; e += 256) {
+    float acc = 0.f;
+    if (e < nW) {
+      const int co = e % Cout, q = e / Cout, ci = q / (k * k), u = (q / k) % k, v = q % k;
+      const float* x0 = sx + (ci * Sin + u) * Sin + v;
+      const float* gg = sg + co * win;
+      const int* aa = sa + co * win;
+      for (int w_ = 0; w_ < win; ++w_) acc = fmaf(x0[aa[w_]], gg[w_], acc);
+    } else {
+      const float* gg = sg + (e - nW) * win;
+      for (int w_ = 0; w_ < win; ++w_) acc += gg[w_];
+    }
+    out[e] = acc;
+  }
+}
+
+// From the rows' and uploads' shares to the stepped model, parameter e per thread:
+//   kPerUpload (blockIdx.y = upload): a convolution parameter's shares of the upload's own rows, added in
+//     row order; with local steps the upload's private model takes the step (Eq. 2; the dense
+//     parameters took theirs in cnn_dense_wgrad_kernel), at U = 1 the sum joins the dense shares in the
+//     upload's slot of G;
+//   kAcrossUploads (U = 1): Eq. 3, w^{t+1} = w^t - the uploads' shares added in arrival order.
+// The first workgroup of kPerUpload / local and of kAcrossUploads turns the row losses into the uploads'
+// mean minibatch losses and, at U = 1, publishes them.
+enum { kPerUpload = 0, kAcrossUploads = 1 };
+__global__ __launch_bounds__(256) void cnn_combine_kernel(CnnDev d, RoundDesc rd, int mode, LossMailbox* mailbox) {
+  const CnnPlan& p = d.p;
+  const bool local = d.step >= 0;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && (local || mode == kAcrossUploads)) {
+    const int a = threadIdx.x;
+    if (a < rd.K) {
+      const float* rl = wsp<const float>(d, p.off_rowloss) + (size_t)a * p.B;
+      float sum = 0.f;
+      for (int b = 0; b < p.B; ++b) sum += rl[b];
+      const float mean = sum / (float)p.B;
+      float* lb = wsp<float>(d, p.off_lossbuf) + a;
+      if (!local) *lb = mean;
+      else *lb = (d.step == 0 ? 0.f : *lb) + mean / (float)d.U;       // mean over the job's U steps
+      if (mailbox) mailbox->loss[a] = mean;
+    }
+    if (mailbox) {
+      if (threadIdx.x < ABS_MAX_WORKERS) __threadfence_system();
+      __syncthreads();
+      if (threadIdx.x == 0) mailbox->stamp = rd.stamp;
     }
   }
-#pragma unroll
-  for (int co = 0; co < kMaxCout; ++co)
-    if (co < Cout) sred[co][t] = acc[co];
-  __syncthreads();
-  if (t < Cout) {
-    float g = 0.f;
-    for (int i = 0; i < 256; ++i) g += sred[t][i];
-    const float* w_cur; float* w_next;
-    step_models(d, rd, (int)blockIdx.y, &w_cur, &w_next);
-    const size_t at = bias ? p.b_off[layer] + t : p.w_off[layer] + (size_t)q * Cout + t;
-    w_next[at] = w_cur[at] - g;
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= p.P) return;
+  const int a = blockIdx.y;
+  float sum = 0.f;
+  if (mode == kPerUpload) {
+    if (e >= p.w_off[2]) return;                       // convolution parameters only
+    const int layer = e >= p.w_off[1] ? 1 : 0;
+    const size_t n = (layer ? p.w_off[2] : p.w_off[1]) - p.w_off[layer], idx = e - p.w_off[layer];
+    const float* G = wsp<const float>(d, layer ? p.off_grow2 : p.off_grow1);
+    for (int r = a * p.B; r < (a + 1) * p.B; ++r) sum += G[(size_t)r * n + idx];
+    float* priv = wsp<float>(d, p.off_priv) + (size_t)a * p.slot_stride;
+    priv[e] = local ? slot_of(d, rd, a)[e] - sum : sum;
+  } else {
+    const float* G = wsp<const float>(d, p.off_priv);
+    for (int k = 0; k < rd.K; ++k) sum += G[(size_t)k * p.slot_stride + e];
+    const float* ring = wsp<const float>(d, p.off_ring);
+    wsp<float>(d, p.off_ring)[(size_t)rd.slot_next * p.slot_stride + e] = ring[(size_t)rd.slot_cur * p.slot_stride + e] - sum;
   }
 }
 
@@ -413,7 +442,11 @@ size_t conv_fwd_lds(const CnnPlan& p, int layer) {
   return ((size_t)Cin * Sin * Sin + (size_t)Cin * p.k * p.k * Cout + Cout) * 4;
 }
 size_t dense_lds(const CnnPlan& p) {
-  return (size_t)p.B * (p.F0 + 2 * p.F1 + 2 * p.F2 + p.C + 1) * 4;
+  return (size_t)kGroup * (p.F0 + 2 * p.F1 + 2 * p.F2 + p.C) * 4;
+}
+size_t conv_wgrad_lds(const CnnPlan& p, int layer) {
+  const int Cin = layer ? p.C1 : p.C0, Cout = layer ? p.C2 : p.C1, Sin = layer ? p.S1 : p.S, Sp = layer ? p.S2 : p.S1;
+  return ((size_t)Cin * Sin * Sin + 2 * (size_t)Cout * Sp * Sp) * 4;
 }
 size_t conv2_bwd_lds(const CnnPlan& p) {
   return ((size_t)p.C2 * 4 * p.S2 * p.S2 + (size_t)p.C1 * p.k * p.k * p.C2) * 4;
@@ -453,7 +486,7 @@ bool cnn_plan(const abs_config& c, CnnPlan& p, const char** why) {
   if (c.x_dtype != ABS_X_FP32) return bad("CNN: X must be fp32");
   p.B = c.B; p.N = c.N; p.R = c.tau_cap + 3;
   if (conv_fwd_lds(p, 0) > 150 * 1024 || conv_fwd_lds(p, 1) > 150 * 1024 || dense_lds(p) > 150 * 1024 ||
-      conv2_bwd_lds(p) > 150 * 1024)
+      conv2_bwd_lds(p) > 150 * 1024 || conv_wgrad_lds(p, 0) > 150 * 1024 || conv_wgrad_lds(p, 1) > 150 * 1024)
     return bad("CNN: a stage does not fit the LDS (smaller B, image or layers)");
   const int kk = p.k * p.k;
   const int rows[5] = {p.C0 * kk, p.C1 * kk, p.F0, p.F1, p.F2}, cols[5] = {p.C1, p.C2, p.F1, p.F2, p.C};
@@ -482,8 +515,11 @@ bool cnn_plan(const abs_config& c, CnnPlan& p, const char** why) {
   p.off_dp2 = off;     off = up(off + Rm * p.F0 * 4);
   p.off_dp1 = off;     off = up(off + Rm * n1 * 4);
   p.off_lossbuf = off; off = up(off + (size_t)p.N * 4);
+  p.off_rowloss = off; off = up(off + Rm * 4);
   p.U = c.U < 1 ? 1 : c.U;
-  p.off_priv = off;    if (p.U > 1) off = up(off + (size_t)p.N * p.slot_stride * 4);
+  p.off_priv = off;    off = up(off + (size_t)p.N * p.slot_stride * 4);
+  p.off_grow1 = off;   off = up(off + Rm * (p.w_off[1] - p.w_off[0]) * 4);
+  p.off_grow2 = off;   off = up(off + Rm * (p.w_off[2] - p.w_off[1]) * 4);
   p.off_eval = off;    off = up(off + eval_scratch_bytes(Rm));
   p.total = off;
   return true;
@@ -496,12 +532,12 @@ hipError_t launch_cnn_round(const CnnArgs& a, const RoundDesc& rd, hipStream_t s
   d.n_rows = rows;
   d.U = p.U;
   const bool local = p.U > 1;
-  const unsigned ups = local ? (unsigned)rd.K : 1u;      // weight-gradient launches: one sum per upload
   const double ar = (double)rows, kk = (double)p.k * p.k;
   const double f1 = 2.0 * ar * p.C1 * 4.0 * p.S1 * p.S1 * p.C0 * kk, f2 = 2.0 * ar * p.C2 * 4.0 * p.S2 * p.S2 * p.C1 * kk;
   const double fd = 2.0 * ar * ((double)p.F0 * p.F1 + (double)p.F1 * p.F2 + (double)p.F2 * p.C);
   const double n1 = (double)p.C1 * p.S1 * p.S1;
   const long n_dense = (long)p.F0 * p.F1 + p.F1 + (long)p.F1 * p.F2 + p.F2 + (long)p.F2 * p.C + p.C;
+  const unsigned groups = (unsigned)(rd.K * ((p.B + kGroup - 1) / kGroup));
   for (int step = 0; step < p.U; ++step) {
     d.step = local ? step : -1;
     hook->begin(KK_CNN_CONV_FWD, f1 + f2, ar * 4.0 * (p.C0 * (double)p.S * p.S + 2.0 * n1 + p.F0));
@@ -509,21 +545,24 @@ hipError_t launch_cnn_round(const CnnArgs& a, const RoundDesc& rd, hipStream_t s
     cnn_conv_pool_fwd_kernel<<<dim3(rows), dim3(256), conv_fwd_lds(p, 1), s>>>(d, rd, 1);
     hook->end(KK_CNN_CONV_FWD);
     hook->begin(KK_CNN_DENSE, 2.0 * fd, ar * 4.0 * (2.0 * p.F0 + 2.0 * p.F1 + 2.0 * p.F2 + p.C));
-    cnn_dense_kernel<<<dim3(rd.K), dim3(256), dense_lds(p), s>>>(d, rd, nullptr, nullptr);
+    cnn_dense_kernel<<<dim3(groups), dim3(128), dense_lds(p), s>>>(d, rd, nullptr, nullptr);
     hook->end(KK_CNN_DENSE);
-    // the second convolution's input gradient needs that layer's filters as they were in the forward
-    // pass: before its weight-gradient launch steps a private model in place
+    // everything that reads a model comes before the kernels that step a private model in place
     hook->begin(KK_CNN_CONV_BWD, 2.0 * ar * n1 * kk * p.C2, ar * 4.0 * (p.F0 + n1));
     cnn_conv2_bwd_kernel<<<dim3(rows), dim3(256), conv2_bwd_lds(p), s>>>(d, rd);
     hook->end(KK_CNN_CONV_BWD);
     hook->begin(KK_CNN_DENSE_WGRAD, fd, (double)n_dense * 8.0 + ar * 4.0 * (p.F0 + 2.0 * p.F1 + 2.0 * p.F2 + p.C));
-    cnn_dense_wgrad_update_kernel<<<dim3((unsigned)((n_dense + 255) / 256), ups), dim3(256), 0, s>>>(
-        d, rd, local ? nullptr : a.mailbox);
+    cnn_dense_wgrad_kernel<<<dim3((unsigned)((n_dense + 255) / 256), (unsigned)rd.K), dim3(256), 0, s>>>(d, rd);
     hook->end(KK_CNN_DENSE_WGRAD);
     hook->begin(KK_CNN_CONV_WGRAD, (f1 + f2) / 4.0, ar * 4.0 * (p.C0 * (double)p.S * p.S + 2.0 * n1 + p.F0));
-    cnn_conv_wgrad_update_kernel<<<dim3(p.C1 * p.k * p.k + 1, ups), dim3(256), 0, s>>>(d, rd, 1);
-    cnn_conv_wgrad_update_kernel<<<dim3(p.C0 * p.k * p.k + 1, ups), dim3(256), 0, s>>>(d, rd, 0);
+    cnn_conv_wgrad_rows_kernel<<<dim3(rows), dim3(256), conv_wgrad_lds(p, 1), s>>>(d, 1);
+    cnn_conv_wgrad_rows_kernel<<<dim3(rows), dim3(256), conv_wgrad_lds(p, 0), s>>>(d, 0);
     hook->end(KK_CNN_CONV_WGRAD);
+    hook->begin(KK_CNN_COMBINE, (double)p.P * rd.K, 4.0 * (ar * (double)p.w_off[2] + (double)rd.K * n_dense + 2.0 * p.P));
+    cnn_combine_kernel<<<dim3((unsigned)((p.w_off[2] + 255) / 256), (unsigned)rd.K), dim3(256), 0, s>>>(d, rd, kPerUpload, nullptr);
+    if (!local)
+      cnn_combine_kernel<<<dim3((unsigned)((p.P + 255) / 256)), dim3(256), 0, s>>>(d, rd, kAcrossUploads, a.mailbox);
+    hook->end(KK_CNN_COMBINE);
   }
   if (local) {
     hook->begin(KK_DELTA_UPDATE, (double)p.P * rd.K, (double)p.P * 4.0 * (2.0 * rd.K + 2.0));
@@ -546,7 +585,8 @@ hipError_t launch_cnn_eval(const CnnArgs& a, uint32_t slot, const EvalArgs& e, h
     hook->begin(KK_EVAL, 0.0, 4.0 * n * p.C0 * p.S * p.S);
     cnn_conv_pool_fwd_kernel<<<dim3(n), dim3(256), conv_fwd_lds(p, 0), s>>>(d, rd, 0);
     cnn_conv_pool_fwd_kernel<<<dim3(n), dim3(256), conv_fwd_lds(p, 1), s>>>(d, rd, 1);
-    cnn_dense_kernel<<<dim3((n + p.B - 1) / p.B), dim3(256), dense_lds(p), s>>>(d, rd, e.rowloss, e.correct);
+    cnn_dense_kernel<<<dim3((unsigned)(((n + p.B - 1) / p.B) * ((p.B + kGroup - 1) / kGroup))), dim3(128), dense_lds(p), s>>>(
+        d, rd, e.rowloss, e.correct);
     hook->end(KK_EVAL);
     err = hipGetLastError();
     if (err == hipSuccess) err = launch_eval_reduce(e, n, s, hook);
@@ -560,6 +600,7 @@ hipError_t cnn_prepare() {
     hipError_t e = hipFuncSetAttribute((const void*)cnn_conv_pool_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)cnn_dense_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)cnn_conv2_bwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)cnn_conv_wgrad_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     return e;
   }();
   return done;
