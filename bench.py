@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16 MFMA
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # fp32 vector ALUs: 256 CUs x 128 lanes x 2 flop x 2.4 GHz
 
 MFMA_KINDS = {"mlp_fwd_l1", "mlp_fwd_hidden", "mlp_dgrad", "mlp_wgrad_l1", "mlp_wgrad"}
 
@@ -179,6 +180,12 @@ def roofline_of(kern, p, config):
         traffic = stored_traffic(dom["name"], k_avg, p["N"]) if config == 5 else None
         return dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_MFMA_BF16_TFLOPS,
                     unit="TFLOP/s", frac=ach / PEAK_MFMA_BF16_TFLOPS, traffic=traffic,
+                    avg_launch_us=avg_s * 1e6, launches=dom["launches"])
+    if dom["name"].startswith("cnn_"):
+        # the convolutional model's kernels are plain fp32 vector arithmetic on data that lives in LDS
+        ach = dom["flops"] / dom["launches"] / avg_s / 1e12
+        return dict(bound="alu", kernel=dom["name"], achieved=ach, peak=PEAK_FP32_VECTOR_TFLOPS,
+                    unit="TFLOP/s", frac=ach / PEAK_FP32_VECTOR_TFLOPS, traffic=None,
                     avg_launch_us=avg_s * 1e6, launches=dom["launches"])
     ach = dom["bytes"] / dom["launches"] / avg_s / 1e9
     return dict(bound="hbm", kernel=dom["name"], achieved=ach, peak=PEAK_HBM_GBS,
