@@ -105,7 +105,7 @@ def sweep_a(p: dict, values, seeds: int, rounds: int, every: int, eval_rows: int
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5")
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5; 6: the convolutional model of Section V-A")
     ap.add_argument("--methods", default="abs,adasync,sa_adasync,k_async,local_sgd")
     ap.add_argument("--rounds", type=int, default=600)
     ap.add_argument("--every", type=int, default=100, help="rounds between read-outs")

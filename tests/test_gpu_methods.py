@@ -11,15 +11,21 @@ SOFTMAX = workloads.scaled_preset(2, M=3000, dims=[16, 4], n_classes=4, N=12, B=
                                   slow_factor=5.0)
 LINEAR = workloads.scaled_preset(1, M=4000, N=8, B=16)
 MLP = workloads.scaled_preset(3, M=4096, dims=[128, 64, 10], N=8, B=32, n_slow=2, lr=1e-3)
+# the convolutional model at a reduced geometry: 2 x 14 x 14 images, 3 x 3 filters, 4 and 5 channels, 20-24-12-4
+CNN = workloads.scaled_preset(6, M=2000, dims=[2 * 14 * 14, 4, 5, 24, 12, 4, 2, 3], n_classes=4, N=8, B=8, K0=2,
+                              tau_cap=2, lr=3e-3, n_slow=2, slow_factor=4.0)
 
 
 @pytest.mark.parametrize("name", workloads.METHODS)
-@pytest.mark.parametrize("base,tol,loss_rtol", [(LINEAR, 1e-5, 1e-4), (SOFTMAX, 1e-5, 1e-4), (MLP, 2e-2, 2e-3)],
-                         ids=["linear", "softmax", "mlp"])
+@pytest.mark.parametrize("base,tol,loss_rtol", [(LINEAR, 1e-5, 1e-4), (SOFTMAX, 1e-5, 1e-4), (MLP, 2e-2, 2e-3),
+                                                (CNN, 1e-4, 1e-4)],
+                         ids=["linear", "softmax", "mlp", "cnn"])
 def test_method(base, tol, loss_rtol, name):
     over = dict(U=3) if name == "local_sgd" else {}
     p = workloads.method_preset(base, name, **over)
     T = 25 if name in ("sync_sgd", "local_sgd") else 80
+    if base is CNN:
+        T = min(T, 30)               # the oracle's convolutions are plain loops
     res = run_pair(p, T, checkpoints=(1,))
     assert_trace_equal(res, loss_rtol)
     check_models(res, tol, label=name)
