@@ -66,12 +66,15 @@ __device__ __forceinline__ const float* slot_of(const CnnDev& d, const RoundDesc
 }
 // layer 0: dataset rows -> first pooled map; layer 1: first pooled map -> second pooled map (the
 // dense stack's input).
+// KS: the filter size when it is 3 or 5 (loops over a filter row unrolled, a row of inputs fetched
+// once for its KS taps), 0: any size.
+template <int KS>
 __global__ __launch_bounds__(256) void cnn_conv_pool_fwd_kernel(CnnDev d, RoundDesc rd, int layer) {
-  extern __shared__ float sm[];
+  extern __shared__ __attribute__((aligned(16))) float sm[];
   const CnnPlan& p = d.p;
   const int r = blockIdx.x, a = r / p.B, t = threadIdx.x;
   const int Cin = layer ? p.C1 : p.C0, Cout = layer ? p.C2 : p.C1;
-  const int Sin = layer ? p.S1 : p.S, Sp = layer ? p.S2 : p.S1, k = p.k;
+  const int Sin = layer ? p.S1 : p.S, Sp = layer ? p.S2 : p.S1, k = KS ? KS : p.k;
   const int n_in = Cin * Sin * Sin, n_w = Cin * k * k * Cout, n_out = Cout * Sp * Sp;
   float* sx = sm;
   float* sw = sx + n_in;
@@ -103,12 +106,26 @@ __global__ __launch_bounds__(256) void cnn_conv_pool_fwd_kernel(CnnDev d, RoundD
       for (int u = 0; u < k; ++u) {
         const float* x0 = sx + (ci * Sin + 2 * pi + u) * Sin + 2 * pj;
         const float* wr = sw + ((ci * k + u) * k) * Cout + co;
-        for (int v = 0; v < k; ++v) {
-          const float wv = wr[v * Cout];
-          a0 = fmaf(x0[v], wv, a0);
-          a1 = fmaf(x0[v + 1], wv, a1);
-          a2 = fmaf(x0[v + Sin], wv, a2);
-          a3 = fmaf(x0[v + Sin + 1], wv, a3);
+        if (KS) {
+          float xa[KS + 1], xb[KS + 1];
+#pragma unroll
+          for (int v = 0; v <= KS; ++v) { xa[v] = x0[v]; xb[v] = x0[v + Sin]; }
+#pragma unroll
+          for (int v = 0; v < KS; ++v) {
+            const float wv = wr[v * Cout];
+            a0 = fmaf(xa[v], wv, a0);
+            a1 = fmaf(xa[v + 1], wv, a1);
+            a2 = fmaf(xb[v], wv, a2);
+            a3 = fmaf(xb[v + 1], wv, a3);
+          }
+        } else {
+          for (int v = 0; v < k; ++v) {
+            const float wv = wr[v * Cout];
+            a0 = fmaf(x0[v], wv, a0);
+            a1 = fmaf(x0[v + 1], wv, a1);
+            a2 = fmaf(x0[v + Sin], wv, a2);
+            a3 = fmaf(x0[v + Sin + 1], wv, a3);
+          }
         }
       }
     float m = a0; int q = 0;
@@ -157,28 +174,46 @@ __device__ __forceinline__ void dense_rows(const float* s_in, int Fin, const flo
   }
 }
 
-// dIn[b][i] = gate(b, i) ? sum_j dOut[b][j] W[i][j] : 0
+// dIn[b][i] = gate(b, i) ? sum_j dOut[b][j] W[i][j] : 0 for the group's rows: a thread takes input
+// feature i for all rows, so a weight row is fetched once.
 template <typename Gate>
 __device__ __forceinline__ void dense_rows_back(const float* s_dout, int Fout, const float* W, int Fin, int nb,
                                                 Gate gate, float* s_din, float* g_din) {
-  for (int item = threadIdx.x; item < nb * Fin; item += blockDim.x) {
-    const int b = item / Fin, i = item - b * Fin;
-    float acc = 0.f;
-    if (gate(b, i)) {
-      const float* wr = W + (size_t)i * Fout;
-      const float* dz = s_dout + b * Fout;
-      for (int j = 0; j < Fout; ++j) acc = fmaf(dz[j], wr[j], acc);
+  for (int i = threadIdx.x; i < Fin; i += blockDim.x) {
+    float acc[kGroup];
+#pragma unroll
+    for (int q = 0; q < kGroup; ++q) acc[q] = 0.f;
+    const float* wr = W + (size_t)i * Fout;
+    int j = 0;
+    for (; j + 4 <= Fout; j += 4) {
+      const float w0 = wr[j], w1 = wr[j + 1], w2 = wr[j + 2], w3 = wr[j + 3];
+#pragma unroll
+      for (int q = 0; q < kGroup; ++q) {
+        const float* dz = s_dout + q * Fout + j;
+        acc[q] = fmaf(dz[0], w0, acc[q]); acc[q] = fmaf(dz[1], w1, acc[q]);
+        acc[q] = fmaf(dz[2], w2, acc[q]); acc[q] = fmaf(dz[3], w3, acc[q]);
+      }
     }
-    if (s_din) s_din[item] = acc;
-    g_din[(size_t)b * Fin + i] = acc;
+    for (; j < Fout; ++j) {
+      const float wv = wr[j];
+#pragma unroll
+      for (int q = 0; q < kGroup; ++q) acc[q] = fmaf(s_dout[q * Fout + j], wv, acc[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < kGroup; ++q)
+      if (q < nb) {
+        const float v = gate(q, i) ? acc[q] : 0.f;
+        if (s_din) s_din[q * Fin + i] = v;
+        g_din[(size_t)q * Fin + i] = v;
+      }
   }
 }
 
 // The dense stack for a group of up to 8 rows of one upload (training) or of the evaluation pass:
 // forward at the rows' model version, per-row loss, and (training) back down to the gradient of the
 // second pooled map; every dZ carries the upload's coefficient of Eq. 3.
-__global__ __launch_bounds__(128) void cnn_dense_kernel(CnnDev d, RoundDesc rd, float* eval_loss, float* eval_hit) {
-  extern __shared__ float sm[];
+__global__ __launch_bounds__(256) void cnn_dense_kernel(CnnDev d, RoundDesc rd, float* eval_loss, float* eval_hit) {
+  extern __shared__ __attribute__((aligned(16))) float sm[];
   const CnnPlan& p = d.p;
   const int t = threadIdx.x;
   const int gpu_ = (p.B + kGroup - 1) / kGroup;            // groups per upload
@@ -194,7 +229,7 @@ __global__ __launch_bounds__(128) void cnn_dense_kernel(CnnDev d, RoundDesc rd, 
   float* sD1 = sD2 + kGroup * p.F2;     // dZ of the first dense layer
   const float* w = slot_of(d, rd, a);
   const float* p2 = wsp<const float>(d, p.off_p2) + (size_t)r0 * p.F0;
-  for (int i = t; i < kGroup * p.F0; i += 128) sH0[i] = i < nb * p.F0 ? p2[i] : 0.f;
+  for (int i = t; i < kGroup * p.F0; i += 256) sH0[i] = i < nb * p.F0 ? p2[i] : 0.f;
   __syncthreads();
   const bool train = eval_loss == nullptr;
   dense_rows(sH0, p.F0, w + p.w_off[2], w + p.b_off[2], p.F1, nb, true, sH1,
@@ -279,16 +314,22 @@ __global__ __launch_bounds__(256) void cnn_dense_wgrad_kernel(CnnDev d, RoundDes
 
 // Gradient of the first pooled map of row r: the second convolution's output gradient is non-zero
 // only where a pooling window had its (positive) maximum.
+// LDS: the output gradient as [row][column][channel] and the filters as [(ci, u, v)][channel], channels
+// padded to a multiple of 4, so that the sum over output channels runs on 16-byte reads.
+template <int KS>
 __global__ __launch_bounds__(256) void cnn_conv2_bwd_kernel(CnnDev d, RoundDesc rd) {
-  extern __shared__ float sm[];
+  extern __shared__ __attribute__((aligned(16))) float sm[];
   const CnnPlan& p = d.p;
-  const int r = blockIdx.x, a = r / p.B, t = threadIdx.x, k = p.k;
-  const int S2c = 2 * p.S2, n_dc = p.C2 * S2c * S2c, n_w = p.C1 * k * k * p.C2;
-  float* sdc = sm;             // [C2][S2c][S2c]
-  float* sw = sdc + n_dc;      // second convolution's filters of this upload's version
+  const int r = blockIdx.x, a = r / p.B, t = threadIdx.x, k = KS ? KS : p.k;
+  const int S2c = 2 * p.S2, Cp = (p.C2 + 3) & ~3, n_dc = S2c * S2c * Cp, n_q = p.C1 * k * k;
+  float* sdc = sm;             // [S2c][S2c][Cp]
+  float* sw = sdc + n_dc;      // [C1 k k][Cp]: second convolution's filters of this upload's version
   const float* w = slot_of(d, rd, a);
   for (int i = t; i < n_dc; i += 256) sdc[i] = 0.f;
-  for (int i = t; i < n_w; i += 256) sw[i] = w[p.w_off[1] + i];
+  for (int i = t; i < n_q * Cp; i += 256) {
+    const int q = i / Cp, co = i - q * Cp;
+    sw[i] = co < p.C2 ? w[p.w_off[1] + (size_t)q * p.C2 + co] : 0.f;
+  }
   __syncthreads();
   const float* dp2 = wsp<const float>(d, p.off_dp2) + (size_t)r * p.F0;
   const uint8_t* a2 = wsp<const uint8_t>(d, p.off_a2) + (size_t)r * p.F0;
@@ -296,7 +337,7 @@ __global__ __launch_bounds__(256) void cnn_conv2_bwd_kernel(CnnDev d, RoundDesc 
     const int q = a2[o];
     if (q != kDead) {
       const int co = o / (p.S2 * p.S2), pi = (o / p.S2) % p.S2, pj = o % p.S2;
-      sdc[(co * S2c + 2 * pi + (q >> 1)) * S2c + 2 * pj + (q & 1)] = dp2[o];
+      sdc[((2 * pi + (q >> 1)) * S2c + 2 * pj + (q & 1)) * Cp + co] = dp2[o];
     }
   }
   __syncthreads();
@@ -307,14 +348,21 @@ __global__ __launch_bounds__(256) void cnn_conv2_bwd_kernel(CnnDev d, RoundDesc 
     float acc = 0.f;
     if (a1[o] != kDead) {
       const int ci = o / (p.S1 * p.S1), y = (o / p.S1) % p.S1, x = o % p.S1;
-      for (int u = 0; u < k; ++u) {
+#pragma unroll
+      for (int u = 0; u < (KS ? KS : k); ++u) {
         const int i = y - u;
         if (i < 0 || i >= S2c) continue;
-        for (int v = 0; v < k; ++v) {
+#pragma unroll
+        for (int v = 0; v < (KS ? KS : k); ++v) {
           const int j = x - v;
           if (j < 0 || j >= S2c) continue;
-          const float* wr = sw + ((ci * k + u) * k + v) * p.C2;
-          for (int co = 0; co < p.C2; ++co) acc = fmaf(sdc[(co * S2c + i) * S2c + j], wr[co], acc);
+          const float4* wr = (const float4*)(sw + ((ci * k + u) * k + v) * Cp);
+          const float4* gr = (const float4*)(sdc + (i * S2c + j) * Cp);
+          for (int c4 = 0; c4 < Cp / 4; ++c4) {
+            const float4 gv = gr[c4], wv = wr[c4];
+            acc = fmaf(gv.x, wv.x, acc); acc = fmaf(gv.y, wv.y, acc);
+            acc = fmaf(gv.z, wv.z, acc); acc = fmaf(gv.w, wv.w, acc);
+          }
         }
       }
     }
@@ -327,7 +375,7 @@ __global__ __launch_bounds__(256) void cnn_conv2_bwd_kernel(CnnDev d, RoundDesc 
 // (ci, u, v, co) over the pooling windows (a window contributes the input under its maximum), the
 // last Cout entries are the bias.  Result: Grow[r][weights..., biases...], in the model's own order.
 __global__ __launch_bounds__(256) void cnn_conv_wgrad_rows_kernel(CnnDev d, int layer) {
-  extern __shared__ float sm[];
+  extern __shared__ __attribute__((aligned(16))) float sm[];
   const CnnPlan& p = d.p;
   const int r = blockIdx.x, t = threadIdx.x, k = p.k;
   const int Cin = layer ? p.C1 : p.C0, Cout = layer ? p.C2 : p.C1;
@@ -449,7 +497,20 @@ size_t conv_wgrad_lds(const CnnPlan& p, int layer) {
   return ((size_t)Cin * Sin * Sin + 2 * (size_t)Cout * Sp * Sp) * 4;
 }
 size_t conv2_bwd_lds(const CnnPlan& p) {
-  return ((size_t)p.C2 * 4 * p.S2 * p.S2 + (size_t)p.C1 * p.k * p.k * p.C2) * 4;
+  const size_t Cp = (size_t)((p.C2 + 3) & ~3);
+  return (Cp * 4 * p.S2 * p.S2 + (size_t)p.C1 * p.k * p.k * Cp) * 4;
+}
+
+void launch_conv_fwd(const CnnDev& d, const RoundDesc& rd, int rows, hipStream_t s) {
+  const CnnPlan& p = d.p;
+  for (int layer = 0; layer < 2; ++layer) {
+    const size_t lds = conv_fwd_lds(p, layer);
+    switch (p.k) {
+      case 3: cnn_conv_pool_fwd_kernel<3><<<dim3(rows), dim3(256), lds, s>>>(d, rd, layer); break;
+      case 5: cnn_conv_pool_fwd_kernel<5><<<dim3(rows), dim3(256), lds, s>>>(d, rd, layer); break;
+      default: cnn_conv_pool_fwd_kernel<0><<<dim3(rows), dim3(256), lds, s>>>(d, rd, layer);
+    }
+  }
 }
 
 CnnDev dev_of(const CnnArgs& a) {
@@ -541,15 +602,18 @@ hipError_t launch_cnn_round(const CnnArgs& a, const RoundDesc& rd, hipStream_t s
   for (int step = 0; step < p.U; ++step) {
     d.step = local ? step : -1;
     hook->begin(KK_CNN_CONV_FWD, f1 + f2, ar * 4.0 * (p.C0 * (double)p.S * p.S + 2.0 * n1 + p.F0));
-    cnn_conv_pool_fwd_kernel<<<dim3(rows), dim3(256), conv_fwd_lds(p, 0), s>>>(d, rd, 0);
-    cnn_conv_pool_fwd_kernel<<<dim3(rows), dim3(256), conv_fwd_lds(p, 1), s>>>(d, rd, 1);
+    launch_conv_fwd(d, rd, rows, s);
     hook->end(KK_CNN_CONV_FWD);
     hook->begin(KK_CNN_DENSE, 2.0 * fd, ar * 4.0 * (2.0 * p.F0 + 2.0 * p.F1 + 2.0 * p.F2 + p.C));
-    cnn_dense_kernel<<<dim3(groups), dim3(128), dense_lds(p), s>>>(d, rd, nullptr, nullptr);
+    cnn_dense_kernel<<<dim3(groups), dim3(256), dense_lds(p), s>>>(d, rd, nullptr, nullptr);
     hook->end(KK_CNN_DENSE);
     // everything that reads a model comes before the kernels that step a private model in place
     hook->begin(KK_CNN_CONV_BWD, 2.0 * ar * n1 * kk * p.C2, ar * 4.0 * (p.F0 + n1));
-    cnn_conv2_bwd_kernel<<<dim3(rows), dim3(256), conv2_bwd_lds(p), s>>>(d, rd);
+    switch (p.k) {
+      case 3: cnn_conv2_bwd_kernel<3><<<dim3(rows), dim3(256), conv2_bwd_lds(p), s>>>(d, rd); break;
+      case 5: cnn_conv2_bwd_kernel<5><<<dim3(rows), dim3(256), conv2_bwd_lds(p), s>>>(d, rd); break;
+      default: cnn_conv2_bwd_kernel<0><<<dim3(rows), dim3(256), conv2_bwd_lds(p), s>>>(d, rd);
+    }
     hook->end(KK_CNN_CONV_BWD);
     hook->begin(KK_CNN_DENSE_WGRAD, fd, (double)n_dense * 8.0 + ar * 4.0 * (p.F0 + 2.0 * p.F1 + 2.0 * p.F2 + p.C));
     cnn_dense_wgrad_kernel<<<dim3((unsigned)((n_dense + 255) / 256), (unsigned)rd.K), dim3(256), 0, s>>>(d, rd);
@@ -583,9 +647,8 @@ hipError_t launch_cnn_eval(const CnnArgs& a, uint32_t slot, const EvalArgs& e, h
     d.X = (const float*)e.X; d.y = (const int32_t*)e.y;
     d.fixed_slot = (int)slot; d.row0 = row0; d.n_rows = n;
     hook->begin(KK_EVAL, 0.0, 4.0 * n * p.C0 * p.S * p.S);
-    cnn_conv_pool_fwd_kernel<<<dim3(n), dim3(256), conv_fwd_lds(p, 0), s>>>(d, rd, 0);
-    cnn_conv_pool_fwd_kernel<<<dim3(n), dim3(256), conv_fwd_lds(p, 1), s>>>(d, rd, 1);
-    cnn_dense_kernel<<<dim3((unsigned)(((n + p.B - 1) / p.B) * ((p.B + kGroup - 1) / kGroup))), dim3(128), dense_lds(p), s>>>(
+    launch_conv_fwd(d, rd, n, s);
+    cnn_dense_kernel<<<dim3((unsigned)(((n + p.B - 1) / p.B) * ((p.B + kGroup - 1) / kGroup))), dim3(256), dense_lds(p), s>>>(
         d, rd, e.rowloss, e.correct);
     hook->end(KK_EVAL);
     err = hipGetLastError();
@@ -597,9 +660,13 @@ hipError_t launch_cnn_eval(const CnnArgs& a, uint32_t slot, const EvalArgs& e, h
 hipError_t cnn_prepare() {
   // stages whose LDS need exceeds the default limit must opt in once per process
   static hipError_t done = [] {
-    hipError_t e = hipFuncSetAttribute((const void*)cnn_conv_pool_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)cnn_dense_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)cnn_conv2_bwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    const void* fns[] = {(const void*)cnn_conv_pool_fwd_kernel<0>, (const void*)cnn_conv_pool_fwd_kernel<3>,
+                         (const void*)cnn_conv_pool_fwd_kernel<5>, (const void*)cnn_dense_kernel,
+                         (const void*)cnn_conv2_bwd_kernel<0>, (const void*)cnn_conv2_bwd_kernel<3>,
+                         (const void*)cnn_conv2_bwd_kernel<5>};
+    hipError_t e = hipSuccess;
+    for (const void* f : fns)
+      if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)cnn_conv_wgrad_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     return e;
   }();

@@ -54,34 +54,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
-__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
-}
-
-// ------------------------------------------------------------------ minibatch rows
-// rowidx[m], label[m] for the stacked rows m = up * Bp + b.  Padding rows (b >= B) point
-// at a valid dataset row so that everything computed from them is finite; their label
-// is -1 and their output gradient is forced to zero.
-__global__ __launch_bounds__(256) void mlp_index_kernel(uint32_t* rowidx, int32_t* label, const int32_t* y,
-                                                       RoundDesc rd, int B, int Bp, uint64_t shard_rows,
-                                                       uint64_t batch_key, uint32_t draw0) {
-  const int m = blockIdx.x * 256 + threadIdx.x;
-  if (m >= rd.K * Bp) return;
-  const int up = m / Bp, b = m - up * Bp;
-  const WorkerDesc w = rd.w[up];
-  uint64_t row = (uint64_t)w.id * shard_rows;
-  if (b < B) row += draw(job_key(batch_key, w.id, w.job), draw0 + (uint32_t)b) % shard_rows;   // draw0 = u * B
-  rowidx[m] = (uint32_t)row;
-  label[m] = b < B ? y[row] : -1;
 }
 
 // ------------------------------------------------------------------ gather + transpose of X
@@ -1844,7 +1821,6 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
   float* priv = local ? at<float>(a, p.off_priv) : nullptr;
   const uint16_t* pshadow = local ? at<uint16_t>(a, p.off_priv_shadow) : nullptr;
   uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
-  int32_t* label = at<int32_t>(a, p.off_label);
 
   for (int step = 0; step < U; ++step) {
     // where the uploads' models live during this step: the ring (by slot) or the private copies
