@@ -198,8 +198,9 @@ int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y
  * The call enqueues on the handle's stream and returns; it makes no hipMalloc / hipFree /
  * hipHostMalloc, creates no event or stream, copies nothing to the host and does not wait.  Per-kernel
  * timing (abs_config.profile) leaves these launches out.
- * Limits: an MLP handle evaluates N x (B rounded up to 128) rows per pass, and that must not exceed
- * ABS_STATIC_EVAL_ROWS (ABS_E_WORKSPACE otherwise; the regression models pass 16384 rows at a time);
+ * Limits: an MLP handle evaluates N x (B rounded up to 128) rows per pass, a handle of the convolutional
+ * model N x B, and that must not exceed ABS_STATIC_EVAL_ROWS (ABS_E_WORKSPACE otherwise; the regression
+ * models pass 16384 rows at a time);
  * n_rows itself is not limited.  All handles on a GPU share the one array, which keeps the last
  * call's contents (the call clears what it accumulates into): two such calls that overlap in time on
  * one GPU - different streams, different handles - race; calls on one stream are safe.

@@ -932,9 +932,12 @@ int abs_evaluate(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y
 int abs_evaluate_static(abs_ctx* ctx, int64_t version, const void* d_X, const void* d_y, int64_t n_rows,
                         double* d_out) {
   if (!ctx || !d_out) return ABS_E_ARG;
-  if (ctx->cfg.device_mode && ctx->cfg.model == ABS_MODEL_MLP && ctx->margs.plan.Mp > kStaticEvalRows) {
-    ctx->err = "abs_evaluate_static: a pass of this handle is N x (B rounded up to 128) = " +
-               std::to_string(ctx->margs.plan.Mp) + " rows, more than the " + std::to_string(kStaticEvalRows) +
+  const long pass_rows = !ctx->cfg.device_mode ? 0
+                         : ctx->cfg.model == ABS_MODEL_MLP ? (long)ctx->margs.plan.Mp
+                         : ctx->cfg.model == ABS_MODEL_CNN ? (long)ctx->cargs.plan.N * ctx->cargs.plan.B : 0;
+  if (pass_rows > kStaticEvalRows) {
+    ctx->err = "abs_evaluate_static: a pass of this handle is N x B (MLP: B rounded up to 128) = " +
+               std::to_string(pass_rows) + " rows, more than the " + std::to_string(kStaticEvalRows) +
                " rows (ABS_STATIC_EVAL_ROWS) the library's fixed scratch holds; use abs_evaluate";
     return ABS_E_WORKSPACE;
   }

@@ -33,6 +33,9 @@ def _both(sim, Xe, ye, n_rows, version=-1):
     (workloads.scaled_preset(2, M=6000), 40, (40_003, 1_001)),            # three passes of 16384 rows, then one
     (workloads.scaled_preset(1, M=4000), 30, (5_001, 77)),                 # linear model: accuracy is NaN
     (workloads.scaled_preset(3, M=4096, dims=[200, 96, 10], N=8, B=40, n_slow=2, lr=1e-3), 12, (1_500, 333)),
+    # the convolutional model: passes of N B = 48 rows
+    (workloads.scaled_preset(6, M=1500, dims=[2 * 14 * 14, 4, 5, 24, 12, 4, 2, 3], n_classes=4, N=6, B=8, K0=2,
+                             tau_cap=2, lr=3e-3), 10, (500, 77)),
 ])
 def test_static_evaluation_equals_abs_evaluate(p, T, rows):
     d, Xe, ye = workloads.make_split(p, max(rows))
