@@ -671,12 +671,16 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   }
   int m0, n0, zsplit, ks0, ks1;
   // runs of k-steps across tiles (sk_q > 0): this workgroup's next (tile, k-step) pair and the end of
-  // its run.  The workgroups of an XCD take neighbouring runs, hence neighbouring tiles.
+  // its run.
   const bool kRuns = EPI == EPI_WGRAD && g.sk_q > 0;
   int sk_u = 0, sk_end = 0;
   if (kRuns) {
     const int own = (int)gridDim.x - g.pig_blocks;
-    const int lw = (bx & 7) * (own >> 3) + (bx >> 3);
+    // Block b runs on XCD b % 8.  When eight runs span a whole number of tiles' k ranges
+    // (8 q = 0 mod k-steps), runs b, b + 8, b + 16, ... start at the same k-step of their tiles: handing
+    // run b to block b puts workgroups on one XCD that walk the same k range in step and share their
+    // A and B panels in that XCD's L2.  Otherwise an XCD takes neighbouring runs (neighbouring tiles).
+    const int lw = (8 * g.sk_q) % g.ksteps_total == 0 ? bx : (bx & 7) * (own >> 3) + (bx >> 3);
     sk_u = lw * g.sk_q;
     sk_end = min(sk_u + g.sk_q, g.mt * g.nt * g.ksteps_total);
     if (sk_u >= sk_end) return;
