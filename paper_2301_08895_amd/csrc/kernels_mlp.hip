@@ -190,6 +190,53 @@ __device__ __forceinline__ void update_block64(const TileUpdate& u, int i0, int 
 // ------------------------------------------------------------------ the GEMM
 enum { EPI_RELU = 0, EPI_LOGITS = 1, EPI_DGRAD = 2, EPI_WGRAD = 3 };
 
+// ------------------------------------------------------------------ bias update
+// b_j <- b_j - sum over the rows of dZ_l[.][j] (Eq. 2 / Eq. 3 for the biases).  The producers of
+// dZ_l leave the column sums of every block of 64 rows (128 for the output layer); 16 threads per entry
+// add them (partial row g, g + 16, ... each, then the 16 shares in order).  A block of 256 threads
+// takes 16 consecutive entries of the concatenated bias vectors.
+struct BiasCore {
+  int L;
+  int col_begin[ABS_MAX_LAYERS + 1];       // prefix of valid columns over the layers
+  const float* colsum[ABS_MAX_LAYERS]; size_t ldcs[ABS_MAX_LAYERS];
+  size_t b_off[ABS_MAX_LAYERS];
+  const float* w_cur; float* w_next;
+  int prow[ABS_MAX_LAYERS];                // row blocks of colsum[l] (per upload in the per-upload form)
+};
+// blk: which 16 entries; first_row_block(l): where the sum over layer l's row blocks starts; cur / nxt:
+// the model read and written.  Threads 0 .. 255 of the workgroup work, all of them meet the barrier.
+template <typename FirstRow>
+__device__ __forceinline__ void bias_block(const BiasCore& a, int blk, FirstRow first_row_block, const float* cur,
+                                           float* nxt, float* lds) {
+  float (*s_part)[17] = (float (*)[17])lds;
+  const int t = threadIdx.x, cl = t & 15, grp = (t >> 4) & 15;
+  const int w = blk * 16 + cl;
+  const int ncol = a.col_begin[a.L];
+  float s = 0.f;
+  int l = 0, j = 0;
+  if (w < ncol && t < 256) {
+    while (w >= a.col_begin[l + 1]) ++l;
+    j = w - a.col_begin[l];
+    const int prow = a.prow[l];
+    const float* src = a.colsum[l] + (size_t)first_row_block(l) * a.ldcs[l] + j;
+    int r = grp;
+    for (; r + 48 < prow; r += 64) {         // four loads in flight
+      const float v0 = src[(size_t)r * a.ldcs[l]], v1 = src[(size_t)(r + 16) * a.ldcs[l]];
+      const float v2 = src[(size_t)(r + 32) * a.ldcs[l]], v3 = src[(size_t)(r + 48) * a.ldcs[l]];
+      s += v0; s += v1; s += v2; s += v3;
+    }
+    for (; r < prow; r += 16) s += src[(size_t)r * a.ldcs[l]];
+  }
+  if (t < 256) s_part[grp][cl] = s;
+  __syncthreads();
+  if (t < 16 && w < ncol) {
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) sum += s_part[g][cl];
+    nxt[a.b_off[l] + j] = cur[a.b_off[l] + j] - sum;
+  }
+}
+
 struct GemmArgs {
   const uint16_t* A;  size_t lda;     // [Mdim][lda], k contiguous
   const uint32_t* a_rowidx;           // GATHER: row m of A is A + a_rowidx[m] * lda
@@ -236,6 +283,10 @@ struct GemmArgs {
   // tiles: sharing a launch lets the two overlap without streams, events or fences.
   int pig_blocks, pig_tj;
   TileUpdate pig_upd;
+  // ... and its very last bias_blocks workgroups the round's bias update (every dZ_l and its column
+  // sums are complete before the first weight-gradient launch).
+  int bias_blocks;
+  BiasCore bias_upd;
   // EPI_DGRAD with pub_mailbox set: the first workgroup publishes the uploads' mean minibatch losses
   // (sums of pub_nb row blocks each, left by the output-layer kernel) before it starts on its tile.
   LossMailbox* pub_mailbox; const float* pub_rowloss; int pub_nb; int pub_B;
@@ -337,11 +388,15 @@ void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int bx = blockIdx.x;
-  if (EPI == EPI_WGRAD && g.pig_blocks) {
+  if (EPI == EPI_WGRAD && (g.pig_blocks | g.bias_blocks)) {
     // The update's blocks come last in the grid: they take the CUs that the product's last wave of
     // tiles leaves idle and the tail.  (Dealt out evenly between the tiles they slowed every tile
-    // down: 260 -> 400 us for the hidden layer's product at K = 128.)
-    const int own = (int)gridDim.x - g.pig_blocks;
+    // down: 260 -> 400 us for the hidden layer's product at K = 128.)  Behind them the bias blocks.
+    const int own = (int)gridDim.x - g.pig_blocks - g.bias_blocks;
+    if (bx >= own + g.pig_blocks) {
+      bias_block(g.bias_upd, bx - own - g.pig_blocks, [](int) { return 0; }, g.bias_upd.w_cur, g.bias_upd.w_next, (float*)smem);
+      return;
+    }
     if (bx >= own) { piggy_update<256, false>(g, bx - own, smem); return; }
   }
   // Block -> tile mapping.  Workgroups are handed to the 8 XCDs round-robin and every XCD has
@@ -662,11 +717,15 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   const int bx = blockIdx.x;
-  if (EPI == EPI_WGRAD && g.pig_blocks) {
+  if (EPI == EPI_WGRAD && (g.pig_blocks | g.bias_blocks)) {
     // The update's blocks come last in the grid: they take the CUs that the product's last wave of
     // tiles leaves idle and the tail.  (Dealt out evenly between the tiles they slowed every tile
-    // down: 260 -> 400 us for the hidden layer's product at K = 128.)
-    const int own = (int)gridDim.x - g.pig_blocks;
+    // down: 260 -> 400 us for the hidden layer's product at K = 128.)  Behind them the bias blocks.
+    const int own = (int)gridDim.x - g.pig_blocks - g.bias_blocks;
+    if (bx >= own + g.pig_blocks) {
+      bias_block(g.bias_upd, bx - own - g.pig_blocks, [](int) { return 0; }, g.bias_upd.w_cur, g.bias_upd.w_next, (float*)smem);
+      return;
+    }
     if (bx >= own) { piggy_update<512, true>(g, bx - own, smem); return; }
   }
   int m0, n0, zsplit, ks0, ks1;
@@ -675,7 +734,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const bool kRuns = EPI == EPI_WGRAD && g.sk_q > 0;
   int sk_u = 0, sk_end = 0;
   if (kRuns) {
-    const int own = (int)gridDim.x - g.pig_blocks;
+    const int own = (int)gridDim.x - g.pig_blocks - g.bias_blocks;
     // Block b runs on XCD b % 8.  When eight runs span a whole number of tiles' k ranges
     // (8 q = 0 mod k-steps), runs b, b + 8, b + 16, ... start at the same k-step of their tiles: handing
     // run b to block b puts workgroups on one XCD that walk the same k range in step and share their
@@ -1264,54 +1323,20 @@ __global__ __launch_bounds__(256) void mlp_update_small_kernel(UpdateArgs u) {
   u.wt[(size_t)j * u.ldwt + i] = h;
 }
 
-// ------------------------------------------------------------------ bias update
-// b_j <- b_j - sum over the rows of dZ_l[.][j] (Eq. 2 / Eq. 3 for the biases).  The producers of
-// dZ_l leave the column sums of every block of 64 rows; 16 threads per entry add them (partial
-// row g, g + 16, ... each, then the 16 shares in order).  Global form: all `prow[l]` blocks, model
-// w_cur -> w_next.  Per-upload form (local SGD, blockIdx.y = upload a): the blocks of a's own
-// rows, model slot cur_index[a] of w_cur -> slot a of w_next.
-struct BiasArgs {
-  int L;
-  int col_begin[ABS_MAX_LAYERS + 1];       // prefix of valid columns over the layers
-  const float* colsum[ABS_MAX_LAYERS]; size_t ldcs[ABS_MAX_LAYERS];
-  size_t b_off[ABS_MAX_LAYERS];
-  const float* w_cur; float* w_next;
-  int prow[ABS_MAX_LAYERS];                // row blocks of colsum[l] (per upload in the per-upload form)
+// The bias update as a launch of its own.  Global form: all `prow[l]` blocks, model w_cur -> w_next.
+// Per-upload form (local SGD, blockIdx.y = upload a): the blocks of a's own rows, model slot
+// cur_index[a] of w_cur -> slot a of w_next.
+struct BiasArgs : BiasCore {
   int batched;
   size_t cur_stride, next_stride;
   uint16_t cur_index[ABS_MAX_WORKERS];
 };
 __global__ __launch_bounds__(256) void mlp_bias_kernel(BiasArgs a) {
-  __shared__ float s_part[16][17];
-  const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const int w = blockIdx.x * 16 + cl;
-  const int ncol = a.col_begin[a.L];
+  __shared__ float s_part[16 * 17];
   const int up = blockIdx.y;
-  float s = 0.f;
-  int l = 0, j = 0;
-  if (w < ncol) {
-    while (w >= a.col_begin[l + 1]) ++l;
-    j = w - a.col_begin[l];
-    const int prow = a.prow[l];
-    const float* src = a.colsum[l] + (size_t)(a.batched ? up * prow : 0) * a.ldcs[l] + j;
-    int r = grp;
-    for (; r + 48 < prow; r += 64) {         // four loads in flight
-      const float v0 = src[(size_t)r * a.ldcs[l]], v1 = src[(size_t)(r + 16) * a.ldcs[l]];
-      const float v2 = src[(size_t)(r + 32) * a.ldcs[l]], v3 = src[(size_t)(r + 48) * a.ldcs[l]];
-      s += v0; s += v1; s += v2; s += v3;
-    }
-    for (; r < prow; r += 16) s += src[(size_t)r * a.ldcs[l]];
-  }
-  s_part[grp][cl] = s;
-  __syncthreads();
-  if (grp == 0 && w < ncol) {
-    float t = 0.f;
-#pragma unroll
-    for (int g = 0; g < 16; ++g) t += s_part[g][cl];
-    const float* cur = a.w_cur + (a.batched ? (size_t)a.cur_index[up] * a.cur_stride : 0);
-    float* nxt = a.w_next + (a.batched ? (size_t)up * a.next_stride : 0);
-    nxt[a.b_off[l] + j] = cur[a.b_off[l] + j] - t;
-  }
+  const float* cur = a.w_cur + (a.batched ? (size_t)a.cur_index[up] * a.cur_stride : 0);
+  float* nxt = a.w_next + (a.batched ? (size_t)up * a.next_stride : 0);
+  bias_block(a, blockIdx.x, [&](int l) { return a.batched ? up * a.prow[l] : 0; }, cur, nxt, s_part);
 }
 
 // Local SGD: the uploads' mean minibatch losses of one local step, one thread per upload over the
@@ -1665,7 +1690,7 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     g.rows_per_xcd = 0;
     const int runs = (g.mt * g.nt * g.ksteps_total + g.sk_q - 1) / g.sk_q;
     plan_note(TAG == 2 ? "wgrad_x_runs" : "wgrad_runs", TM3, TN3, g.sk_q);
-    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3((runs + 7) / 8 * 8 + g.pig_blocks), dim3(512), s, g, rd);
+    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3((runs + 7) / 8 * 8 + g.pig_blocks + g.bias_blocks), dim3(512), s, g, rd);
     return true;
   }
   if (big) {
@@ -1674,7 +1699,7 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
     plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : TAG == 2 ? "wgrad_x" : "wgrad",
               TM3, TN3, nsplit);
-    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt + g.pig_blocks), dim3(512), s, g, rd);
+    ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt + g.pig_blocks + g.bias_blocks), dim3(512), s, g, rd);
     return true;
   }
   // widest column tile that still fills the GPU: 256-wide tiles only with two workgroups per CU
@@ -1689,7 +1714,7 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   g.nt = Ndim / tn;
   g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
   const dim3 block(256);
-  const dim3 grid1(8 * g.rows_per_xcd * g.nt + g.pig_blocks, 1, 1);
+  const dim3 grid1(8 * g.rows_per_xcd * g.nt + g.pig_blocks + g.bias_blocks, 1, 1);
   // DMA ring: whole k-steps only
   const bool ring_ok = EPI != EPI_LOGITS && (!GATHER || (g.a_kvalid % BK == 0 && g.a_kvalid >= g.ksteps_total * BK));
   if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU) {
@@ -1899,10 +1924,29 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     // product instead - order 1, 0, 2, no runs: a quarter of the CUs is idle there at K = 32 - gave
     // 631 / 1807, but the product that bounds the round then carries another layer's traffic and its
     // own figure, 0.31 of the matrix peak instead of 0.37 with runs, says little about it.)
+    // The bias update (column sums of every dZ_l, complete since the backward pass) rides along in the
+    // same way: as the very last workgroups of the last layer's weight-gradient launch.
+    BiasCore bias{};
+    bias.L = L;
+    int bias_cols = 0;
+    for (int l = 0; l < L; ++l) {
+      bias.col_begin[l] = bias_cols; bias_cols += p.d[l + 1];
+      bias.colsum[l] = at<float>(a, p.off_colsum[l + 1]); bias.ldcs[l] = (size_t)p.dp[l + 1];
+      bias.b_off[l] = p.b_off[l];
+      bias.prow[l] = (local ? p.Bp : rows) / (l == L - 1 ? kCeRows : 64);
+    }
+    bias.col_begin[L] = bias_cols;
+    bias.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
+    bias.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
     int pend = -1, pend_split = 0, pend_q = 0;   // layer whose partials are complete and whose update is still due (its splits or run length)
     for (int li = 0; li < L; ++li) {
       const int l = local ? L - 1 - li : li;
       GemmArgs g{};
+      if (!local && li == L - 1) {
+        g.bias_blocks = (bias_cols + 15) / 16;
+        g.bias_upd = bias;
+        plan_note("with_biases", 16, 1, 1);
+      }
       g.A = l == 0 ? at<uint16_t>(a, p.off_xgt) : at<uint16_t>(a, p.off_ht[l]); g.lda = p.ldm;
       g.Bt = at<uint16_t>(a, p.off_dzt[l + 1]); g.ldb = p.ldm;
       const int ksteps = rows / BK;
@@ -1943,30 +1987,19 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       else launch_update(a, l, rd, local ? UPD_LOCAL : UPD_GLOBAL, step, parts, s, hook, run_q, ksteps);
     }
 
-    // ---- biases, from the column sums the producers of dZ_l left per block of 64 rows
-    {
+    // ---- biases (local steps: a launch of its own, per upload; else they rode on the last
+    // weight-gradient launch)
+    if (local) {
       BiasArgs b{};
-      b.L = L;
-      int c = 0;
-      for (int l = 0; l < L; ++l) {
-        b.col_begin[l] = c; c += p.d[l + 1];
-        b.colsum[l] = at<float>(a, p.off_colsum[l + 1]); b.ldcs[l] = (size_t)p.dp[l + 1];
-        b.b_off[l] = p.b_off[l];
-      }
-      b.col_begin[L] = c;
-      if (!local) {
-        b.w_cur = ring + (size_t)rd.slot_cur * p.slot_stride;
-        b.w_next = ring + (size_t)rd.slot_next * p.slot_stride;
-        for (int l = 0; l < L; ++l) b.prow[l] = rows / (l == L - 1 ? kCeRows : 64);
-      } else {
+      (BiasCore&)b = bias;
+      {
         b.batched = 1;
         b.w_cur = wbase; b.cur_stride = p.slot_stride;
         b.w_next = priv; b.next_stride = p.slot_stride;
-        for (int l = 0; l < L; ++l) b.prow[l] = p.Bp / (l == L - 1 ? kCeRows : 64);
         for (int k = 0; k < K; ++k) b.cur_index[k] = (uint16_t)(own ? (uint32_t)k : rd.w[k].slot);
       }
-      kbegin(hook, KK_MLP_BIAS_LOSS, (double)c * rows / 64, (double)c * rows / 64 * 4.0);
-      ABS_LAUNCH_K(mlp_bias_kernel, dim3((c + 15) / 16, local ? K : 1), dim3(256), s, b);
+      kbegin(hook, KK_MLP_BIAS_LOSS, (double)bias_cols * rows / 64, (double)bias_cols * rows / 64 * 4.0);
+      ABS_LAUNCH_K(mlp_bias_kernel, dim3((bias_cols + 15) / 16, K), dim3(256), s, b);
       kend(hook, KK_MLP_BIAS_LOSS);
     }
   }
