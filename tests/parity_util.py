@@ -5,8 +5,15 @@ import numpy as np
 import workloads
 import paper_2301_08895_amd as lib
 from oracle.abs_sim import AbsOracle, trace_words
+from progress import say, tick
 
 LOSS_WORD, KNEXT_WORD = 10, 11
+
+
+def _piece(p):
+    """Rounds per call of the oracle: a few seconds of its work at the workload's size."""
+    per_round = p["N"] * p["B"] * max(int(np.prod(p["dims"][:2])) if "dims" in p else 1, 1)
+    return int(min(250, max(1, 2e10 // per_round)))
 
 
 def run_pair(p, T, checkpoints=(), emulate_bf16=None, inputs=None):
@@ -17,10 +24,9 @@ def run_pair(p, T, checkpoints=(), emulate_bf16=None, inputs=None):
     models = {}
     done = 0
     for cp in sorted(set(checkpoints) | {T}):
-        while o.t < cp:                  # long stretches in pieces, so that a log shows the run is alive
-            o.run(min(250, cp - o.t))
-            if cp - done > 250:
-                print(f"  oracle at round {o.t}", flush=True)
+        while o.t < cp:                  # in pieces, so that the output shows the run is alive
+            o.run(min(_piece(p), cp - o.t))
+            tick(f"  oracle at round {o.t}")
         sim.round(cp - done)
         done = cp
         models[cp] = (sim.model(), o.model().copy())
@@ -31,7 +37,7 @@ def run_pair(p, T, checkpoints=(), emulate_bf16=None, inputs=None):
         # an adaptive wait count decided on float losses flipped: report it and repeat with
         # the oracle's K sequence replayed
         sim.close()
-        print(f"adaptive-K flips at rounds {flips[:8]}; repeating with the oracle's K replayed")
+        say(f"adaptive-K flips at rounds {flips[:8]}; repeating with the oracle's K replayed")
         q = dict(p, k_mode=2)
         sim = lib.Simulation(q, d, k_replay=[r["K"] for r in o.trace])
         done = 0
@@ -148,6 +154,7 @@ def check_models(res, tol, label="", guard=None):
         worst = assert_models_close(p, g, w, w0, tol, cp, where=f"{label} round {cp}:")
         print(f"{label} round {cp}: worst tensor rel {worst['w']:.2e}, update rel {worst['upd']:.2e}, "
               f"element/max-update {worst['elem']:.2e}", flush=True)
+        tick(f"  {label} round {cp} compared")
         if guard is not None:
             assert max(worst["w"], worst["upd"]) <= guard, f"{label} round {cp}: outside the guard band {guard}: {worst}"
 
@@ -157,7 +164,10 @@ def assert_matches_oracle(p, d, model, trace, T, tol, rerun, where=""):
     adaptive wait count flipped on a last-bit difference of a loss, the rounds up to the flip are
     compared and `rerun(settings, k_replay) -> (model, trace)` repeats the library run with the
     oracle's K sequence replayed; the comparison never falls away."""
-    o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False).run(T)
+    o = AbsOracle(p, d["X"], d["y"], d["w0"], keep_models=False)
+    while o.t < T:
+        o.run(min(_piece(p), T - o.t))
+        tick(f"  {where}: oracle at round {o.t}")
     want = np.stack([trace_words(r, p["N"]) for r in o.trace])
     keep = np.ones(want.shape[1], bool)
     keep[LOSS_WORD] = False
@@ -167,7 +177,7 @@ def assert_matches_oracle(p, d, model, trace, T, tol, rerun, where=""):
         first = int(flips[0])
         keep[KNEXT_WORD] = False
         assert np.array_equal(trace[:first + 1, keep], want[:first + 1, keep]), f"{where}: trace differs before the flip"
-        print(f"{where}: adaptive-K flip at round {first}; repeating with the oracle's K replayed", flush=True)
+        say(f"{where}: adaptive-K flip at round {first}; repeating with the oracle's K replayed")
         model, trace = rerun(dict(p, k_mode=2), [r["K"] for r in o.trace])
     assert np.array_equal(trace[:, keep], want[:, keep]), f"{where}: integer trace differs from the oracle"
     worst = assert_models_close(p, model, o.model(), d["w0"], tol, T, where=where)

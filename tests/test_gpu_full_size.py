@@ -9,6 +9,7 @@ import pytest
 import workloads
 import paper_2301_08895_amd as lib
 from parity_util import run_pair, assert_trace_equal, check_models, assert_matches_oracle
+from progress import say
 
 pytestmark = pytest.mark.gpu
 
@@ -27,7 +28,7 @@ def test_mlp_workload_from_the_start(i, T, checkpoints):
     """cfg 3: the whole job; cfg 4-5: its first rounds (the oracle needs seconds per round there)."""
     p = workloads.preset(i)
     d = workloads.make_inputs(p)
-    print(f"{p['name']}: {T} rounds with the adaptive wait count", flush=True)
+    say(f"{p['name']}: {T} rounds with the adaptive wait count")
     res = run_pair(p, T, checkpoints=checkpoints, inputs=d)
     _check(res, BF16_TOL, p["name"])
     if i == 3:
@@ -56,7 +57,7 @@ def test_every_launch_plan_of_the_workload(i):
     budget = {3: 24, 4: 16, 5: 10}[i]
     if len(ks) > budget:
         ks = sorted({ks[round(j * (len(ks) - 1) / (budget - 1))] for j in range(budget)})
-    print(f"{p['name']}: {len(by_plan)} launch plans over K = 1..{p['N']}; rounds at K = {ks}", flush=True)
+    say(f"{p['name']}: {len(by_plan)} launch plans over K = 1..{p['N']}; rounds at K = {ks}")
     for K in ks:
         q = dict(p, k_mode=1, K0=K)
         res = run_pair(q, 1, inputs=d)
