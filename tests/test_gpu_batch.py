@@ -126,6 +126,18 @@ def test_batches_that_advance_as_groups():
     _run(workloads.scaled_preset(1, M=2000, dims=[20, 1], N=5, B=6, K0=2), 515, 11, 1e-5, 1e-4, oracle_for=(0, 514))
 
 
+def test_softmax_batch_of_many_simulations():
+    """Launches of more than a thousand uploads (4 groups of 130 simulations x up to 8 uploads; wait
+    counts differ between the simulations): bitwise the batch of one.  Three tiles with a ragged last
+    one, a single tile per upload, and all feature blocks in use."""
+    _run(workloads.scaled_preset(2, M=2000, dims=[20, 4], n_classes=4, N=8, B=37, K0=2, lr=1e-2), 520, 8, 1e-5, 1e-4,
+         oracle_for=(0, 259, 519), bitwise_alone=False)
+    _run(workloads.scaled_preset(2, M=2000, dims=[36, 10], N=8, B=9, K0=2, lr=1e-2), 520, 6, 1e-5, 1e-4,
+         oracle_for=(7, 518), bitwise_alone=False)
+    _run(workloads.scaled_preset(2, M=3000, dims=[892, 10], N=8, B=16, lr=2e-4), 520, 4, 1e-5, 1e-4,
+         oracle_for=(0, 300), bitwise_alone=False)
+
+
 def test_local_sgd_batches():
     """U > 1 in batched rounds: the local-SGD kernels with one column of workgroups per simulation,
     bitwise the unbatched rounds (also as groups)."""

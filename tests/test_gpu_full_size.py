@@ -126,10 +126,10 @@ def test_whole_job_properties(i):
     assert np.array_equal(tr[:, keep], tr2[:, keep])
 
 
-@pytest.mark.parametrize("i,S,T", [(2, 64, 40), (2, 128, 24), (1, 512, 60)])
+@pytest.mark.parametrize("i,S,T", [(2, 64, 40), (2, 128, 24), (2, 256, 12), (1, 512, 60)])
 def test_batched_rounds_at_full_size(i, S, T):
     """The batches bench.py times (--batch S): the workload at its full shape, S simulation seeds on
-    one dataset, advanced as groups (three, four and two).  Sampled simulations against the oracle,
+    one dataset, advanced as groups (three, four, four and two).  Sampled simulations against the oracle,
     every trace against the invariants of Eq. 4-6."""
     p = workloads.preset(i)
     d = workloads.make_inputs(p)
