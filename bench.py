@@ -372,6 +372,23 @@ def main():
                                     "not part of value / ms_per_step / roofline",
                                ms_per_round=el2 / args.full_k_rounds * 1e3,
                                worker_gradients_per_sec=p["N"] * args.full_k_rounds / el2)
+    # The same warm-up and timed rounds once more on a fresh handle WITHOUT per-kernel events, after
+    # everything above: what the events cost (an event pair on every dispatch keeps consecutive
+    # kernels from following each other directly).  Reported beside the headline, never in its place.
+    no_events = None
+    if not args.no_profile and steps <= 256:
+        sim3 = lib.Simulation(p, inputs, profile=0)
+        sim3.round(warmup)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        sim3.round(steps)
+        torch.cuda.synchronize()
+        el3 = time.perf_counter() - t3
+        tr3 = sim3.trace(warmup, warmup + steps)
+        sim3.close()
+        no_events = dict(value=int(tr3[:, 1].sum()) * p.get("U", 1) / el3, ms_per_step=el3 / steps * 1e3,
+                         note=f"the same {warmup} + {steps} rounds again without per-kernel events, after the timed region; "
+                              "not part of value / ms_per_step / roofline")
     kernels = [dict(name=k["name"], launches=k["launches"], total_ms=round(k["ms"], 3),
                     avg_us=round(k["ms"] / k["launches"] * 1e3, 2),
                     tflops=round(k["flops"] / k["ms"] / 1e9, 1) if k["ms"] > 0 else None,
@@ -402,6 +419,7 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
         "roofline_full_k": roofline_full_k,
+        "no_events": no_events,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
