@@ -33,6 +33,7 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 128;   // rows of C per workgroup
 constexpr int BK = 64;    // contraction elements per main-loop step
@@ -53,6 +54,22 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
+}
+
+// 16-byte store that, on request, does not keep its line in the cache.  The activations and
+// gradients of a large round are hundreds of megabytes that another kernel reads next; kept out of
+// the L2 they no longer evict the operand panels the other workgroups of the XCD still share
+// (a 32768 x 2048 x 2048 forward product 250 -> 230 us).  A small round's outputs fit the caches and
+// are better left there for their reader (8192 rows: the products that follow got 4 % slower).
+#ifndef ABS_STREAM_MIN_BYTES
+#define ABS_STREAM_MIN_BYTES (64u << 20)
+#endif
+__device__ __forceinline__ void store16_stream(uint16_t* p, const uint4& v, bool stream) {
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+  // (written out by hand: when both forms of the store sit in the two arms of a branch the optimiser
+  // merges them into one plain store)
+  if (stream) asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(p), "v"(u32x4_t{v.x, v.y, v.z, v.w}) : "memory");
+  else        *(uint4*)p = v;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -259,6 +276,9 @@ struct GemmArgs {
   // order (16 bytes per lane and tile: [tile][wavefront][lane][4 words], word mi, bit (4 ni + rg) 4 + rr).
   // EPI_RELU writes it when set; EPI_DGRAD reads it instead of maskT when set.
   uint32_t* maskbits;
+  // 256 x 256 tile kernel, bf16 outputs: store them without keeping their lines in the L2 (set by the
+  // launcher for outputs much larger than the L2s: see store16_stream)
+  int stream_out;
   // GATHER with gen_rows set: the kernel draws the minibatch rows itself (stacked row m = upload
   // m / rows_per_upload, sample m % rows_per_upload; Section II-A: independent uniform draws from the
   // worker's shard) instead of reading a_rowidx, and the workgroups of the first column tile leave
@@ -712,6 +732,8 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   // [m][k]; its fragments are read with the transposing LDS read, so no transposed copy of
   // the minibatch is ever written.
   constexpr bool kATR = (EPI == EPI_WGRAD && TAG == 2);
+  // forward / input-gradient products run on 16x16x32 MFMAs, the rest on 32x32x16 (see below)
+  constexpr bool kM16 = (EPI == EPI_RELU || EPI == EPI_DGRAD);
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem3];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -846,6 +868,160 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
     }                                                                             \
   }
 
+  if constexpr (kM16) {
+  // ---- forward and input-gradient products: MFMA 16x16x32.  A wavefront's 128 x 64 sub-tile is
+  // 8 x 4 blocks of 16 x 16 (128 accumulator registers as before); lane l holds row l & 15 and the
+  // 8 k values 8 (l >> 4) .. of an operand block, and accumulator register r of a block is row
+  // 4 (l >> 4) + r, column l & 15.  Per flop this form moves a quarter of the accumulator
+  // registers in and out of the matrix pipe that the 32x32x16 form does; on random operands the
+  // pipes alone sustain 2.18 instead of 1.86 PFLOP/s before the chip lowers its clock.  The
+  // fragments of a 32-wide sub-step are read in halves (rows 0-63, rows 64-127 of A; B once per
+  // sub-step) one half ahead of the MFMAs that use them.
+  f32x4_t acc[8][4];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[a][b][r] = 0.f;
+  const int lr = lane & 15, lk = lane >> 4;
+  const int fa_row = (wm * 128 + lr) * BK, fb_row = TM3 * BK + (wn * 64 + lr) * BK;
+  const int sw = (lr >> 1) & 7;
+  const int ch0 = (lk ^ sw) << 3, ch1 = ((4 | lk) ^ sw) << 3;
+  if (ks0 < ks1) {
+    ABS_DMA(ks0, 0);
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const int stage = (ks - ks0) & 1;
+      __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's part of tile ks is in LDS
+      __syncthreads();                         // ... and everybody's; everybody is done with tile ks-1
+      if (ks + 1 < ks1) ABS_DMA(ks + 1, stage ^ 1);
+      const uint16_t* sS = smem + stage * kStage3;
+      bf16x8_t fa[2][4], fb[2][4];
+#define ABS_LOAD_A(set, s_, h_) _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[set][i] = *(const bf16x8_t*)&sS[fa_row + ((h_) * 4 + i) * 16 * BK + ((s_) ? ch1 : ch0)];
+#define ABS_LOAD_B(set, s_)     _Pragma("unroll") for (int i = 0; i < 4; ++i) fb[set][i] = *(const bf16x8_t*)&sS[fb_row + i * 16 * BK + ((s_) ? ch1 : ch0)];
+#define ABS_MMA(h_, aset, bset)                                                          \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b)                                        \
+      acc[(h_) * 4 + i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[aset][i], fb[bset][b], acc[(h_) * 4 + i][b], 0, 0, 0);
+      ABS_LOAD_B(0, 0); ABS_LOAD_A(0, 0, 0);
+      ABS_LOAD_A(1, 0, 1);                       ABS_MMA(0, 0, 0);
+      ABS_LOAD_B(1, 1); ABS_LOAD_A(0, 1, 0);     ABS_MMA(1, 1, 0);
+      ABS_LOAD_A(1, 1, 1);                       ABS_MMA(0, 0, 1);
+                                                 ABS_MMA(1, 1, 1);
+#undef ABS_LOAD_A
+#undef ABS_LOAD_B
+#undef ABS_MMA
+      // issue order: the first eight fragments, then the reads of the next half spread between
+      // the 16 MFMAs of the current one
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    }
+  }
+  __syncthreads();      // all fragment reads done before the staging area is reused
+
+  // ---- epilogue: bf16 outputs leave through this wavefront's private LDS staging, half of the
+  // wavefront's tile (64 x 64) at a time, staged as [n][m] for the transposed copy and as [m][n]
+  // for the row-major one, so that every global store is 16 bytes per lane and 128 contiguous
+  // bytes per row.  The ReLU mask of the tile is one bit per element in accumulator order:
+  // word a / 2 of a lane, bit (a & 1) 16 + 4 b + r for block (a, b), register r.
+  const int lcol = lane & 15, lrow4 = (lane >> 4) * 4;
+  const float* bias = nullptr;
+  if (EPI == EPI_RELU) bias = g.bias + (size_t)slot * g.bias_slot_stride;
+  uint32_t mbits[4] = {0u, 0u, 0u, 0u};
+  uint32_t* const mbits_at =
+      g.maskbits ? g.maskbits + ((((size_t)(m0 / TM3) * g.nt + n0 / TN3) * 8 + wave) * 64 + lane) * 4 : nullptr;
+  if (EPI == EPI_DGRAD && mbits_at) {
+    const uint4 q = *(const uint4*)mbits_at;
+    mbits[0] = q.x; mbits[1] = q.y; mbits[2] = q.z; mbits[3] = q.w;
+  }
+  uint16_t* const sT = smem + wave * (2 * 64 * kEpiPitch3);     // [64 n][72]
+  uint16_t* const sN = sT + 64 * kEpiPitch3;                    // [64 m][72]
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    float cs[4] = {0.f, 0.f, 0.f, 0.f};   // EPI_DGRAD: column sums over this half's 64 rows
+    if (EPI == EPI_DGRAD && !mbits_at) {
+      // the ReLU mask of this half, H_l^T [64 n][64 m], fetched as whole 128-byte rows into sT;
+      // every lane later replaces the 4 entries it read by its 4 results
+      const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int q = lane + 64 * i, r = q >> 3, ch = (q & 7) * 8;
+        *(uint4*)&sT[r * kEpiPitch3 + ch] = *(const uint4*)(g.maskT + (size_t)(ncol + r) * g.ldmaskT + mrow + ch);
+      }
+    }
+#pragma unroll
+    for (int ah = 0; ah < 4; ++ah) {
+      const int a = half * 4 + ah;
+      const int ml = ah * 16 + lrow4;                           // first of this lane's 4 rows inside the half
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int nl = b * 16 + lcol;
+        const int n = n0 + wn * 64 + nl;
+        float bv = 0.f;
+        if (EPI == EPI_RELU) bv = n < g.n_valid ? bias[n] : 0.f;
+        uint2 hm = make_uint2(0, 0);
+        if (EPI == EPI_DGRAD && !mbits_at) hm = *(const uint2*)&sT[nl * kEpiPitch3 + ml];
+        uint16_t h[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int bit = (a & 1) * 16 + b * 4 + rr;
+          float v = acc[a][b][rr];
+          if (EPI == EPI_RELU) {
+            v = fmaxf(v + bv, 0.f);
+            // (the mask is taken from the narrowed value, as the transposed copy would give it)
+            if ((f32_to_bf16(v) & 0x7FFFu) != 0) mbits[a >> 1] |= 1u << bit;
+          } else {
+            const uint32_t pair = rr < 2 ? hm.x : hm.y;
+            const bool pass = mbits_at ? ((mbits[a >> 1] >> bit) & 1u) != 0
+                                       : ((pair >> ((rr & 1) * 16)) & 0x7FFFu) != 0;
+            v = pass ? v : 0.f;
+          }
+          h[rr] = f32_to_bf16(v);
+          if (EPI == EPI_DGRAD) cs[b] += __uint_as_float((uint32_t)h[rr] << 16);
+          if (g.out) sN[(ml + rr) * kEpiPitch3 + nl] = h[rr];
+        }
+        uint2 o;
+        o.x = h[0] | ((uint32_t)h[1] << 16);
+        o.y = h[2] | ((uint32_t)h[3] << 16);
+        *(uint2*)&sT[nl * kEpiPitch3 + ml] = o;
+      }
+    }
+    if (EPI == EPI_DGRAD) {
+      // the bias gradient's share of these 64 rows (the four quarter-wavefronts hold rows 4 q .. 4 q + 3 of every 16)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        float c = cs[b] + __shfl_xor(cs[b], 16, 64);
+        c += __shfl_xor(c, 32, 64);
+        if (lane < 16)
+          g.colsum[(size_t)((m0 + wm * 128 + half * 64) >> 6) * g.ldcs + n0 + wn * 64 + b * 16 + lcol] = c;
+      }
+    }
+    {
+      const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int q = lane + 64 * i, r = q >> 3, ch = (q & 7) * 8;
+        const uint4 vt = *(const uint4*)&sT[r * kEpiPitch3 + ch];
+        store16_stream(g.outT + (size_t)(ncol + r) * g.ldoT + mrow + ch, vt, g.stream_out != 0);
+        if (g.out) {
+          const uint4 vn = *(const uint4*)&sN[r * kEpiPitch3 + ch];
+          store16_stream(g.out + (size_t)(mrow + r) * g.ldo + ncol + ch, vn, g.stream_out != 0);
+        }
+      }
+    }
+  }
+  if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
+  break;
+  } else {
   f32x16_t acc[4][2];
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
@@ -1052,6 +1228,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   }
   if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
   if (!kRuns || sk_u >= sk_end) break;
+  }      // 32x32x16 path
   }
 }
 
@@ -1697,6 +1874,11 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     g.mt = Mdim / TM3;
     g.nt = Ndim / TN3;
     g.rows_per_xcd = (g.mt * nsplit + 7) / 8;
+    // long products with outputs beyond the caches stream them out (short ones are bound by these very
+    // stores and were slower for it: the output layer's input gradient 75 -> 79 us at 32768 rows; so was
+    // the first layer's forward product, whose gathered rows come from memory anyway: 368 -> 374 us)
+    g.stream_out = (EPI == EPI_RELU || EPI == EPI_DGRAD) && !GATHER && g.ksteps_total >= 16 &&
+                   (size_t)Mdim * (size_t)Ndim * 2 >= ABS_STREAM_MIN_BYTES;
     plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : TAG == 2 ? "wgrad_x" : "wgrad",
               TM3, TN3, nsplit);
     ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt + g.pig_blocks + g.bias_blocks), dim3(512), s, g, rd);
