@@ -61,6 +61,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 // the L2 they no longer evict the operand panels the other workgroups of the XCD still share
 // (a 32768 x 2048 x 2048 forward product 250 -> 230 us).  A small round's outputs fit the caches and
 // are better left there for their reader (8192 rows: the products that follow got 4 % slower).
+#ifndef ABS_ATR16
+#define ABS_ATR16 1
+#endif
+#ifndef ABS_WGRAD16
+#define ABS_WGRAD16 1
+#endif
 #ifndef ABS_STREAM_MIN_BYTES
 #define ABS_STREAM_MIN_BYTES (64u << 20)
 #endif
@@ -733,7 +739,7 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   // the minibatch is ever written.
   constexpr bool kATR = (EPI == EPI_WGRAD && TAG == 2);
   // forward / input-gradient products run on 16x16x32 MFMAs, the rest on 32x32x16 (see below)
-  constexpr bool kM16 = (EPI == EPI_RELU || EPI == EPI_DGRAD);
+  constexpr bool kM16 = (EPI == EPI_RELU || EPI == EPI_DGRAD || (EPI == EPI_WGRAD && ABS_WGRAD16 && (!kATR || ABS_ATR16)));
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem3];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -888,16 +894,40 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const int fa_row = (wm * 128 + lr) * BK, fb_row = TM3 * BK + (wn * 64 + lr) * BK;
   const int sw = (lr >> 1) & 7;
   const int ch0 = (lk ^ sw) << 3, ch1 = ((4 | lk) ^ sw) << 3;
+  // kATR (A stored [k][m], see the 32x32x16 path below): a block's fragment is two transposing reads.
+  // Quarter-wavefront q takes k rows 8 q .. 8 q + 7 of the 32-row sub-step (rows + 0 and + 4 of its
+  // 4 x 16 pieces), all quarters the same 16 columns; the block position is XORed with the row's low
+  // bits as stored.
+  const int t16s = lane & 15, t16r = t16s >> 2;
+  int fa_tr[8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+    fa_tr[a] = (t16r + 8 * lk) * TM3 + (wm * 4 + ((a >> 1) ^ t16r)) * 32 + 16 * (a & 1) + 4 * (t16s & 3);
   if (ks0 < ks1) {
+    if (kATR) ABS_AIDX(ks0);
     ABS_DMA(ks0, 0);
+    if (kATR) ABS_AIDX(min(ks0 + 1, ks1 - 1));
     for (int ks = ks0; ks < ks1; ++ks) {
       const int stage = (ks - ks0) & 1;
       __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's part of tile ks is in LDS
       __syncthreads();                         // ... and everybody's; everybody is done with tile ks-1
       if (ks + 1 < ks1) ABS_DMA(ks + 1, stage ^ 1);
+      if (kATR) ABS_AIDX(min(ks + 2, ks1 - 1));
       const uint16_t* sS = smem + stage * kStage3;
       bf16x8_t fa[2][4], fb[2][4];
-#define ABS_LOAD_A(set, s_, h_) _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[set][i] = *(const bf16x8_t*)&sS[fa_row + ((h_) * 4 + i) * 16 * BK + ((s_) ? ch1 : ch0)];
+#define ABS_LOAD_A(set, s_, h_)                                                                                    \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                                  \
+    if (kATR) {                                                                                                    \
+      typedef short s16x4_ __attribute__((ext_vector_type(4)));                                                    \
+      const uint16_t* q_ = sS + fa_tr[(h_) * 4 + i] + (s_) * 32 * TM3;                                             \
+      union { s16x4_ h[2]; bf16x8_t v; } u_;                                                                       \
+      u_.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_*)(q_));          \
+      u_.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_*)(q_ + 4 * TM3)); \
+      fa[set][i] = u_.v;                                                                                           \
+    } else {                                                                                                       \
+      fa[set][i] = *(const bf16x8_t*)&sS[fa_row + ((h_) * 4 + i) * 16 * BK + ((s_) ? ch1 : ch0)];                  \
+    }                                                                                                              \
+  }
 #define ABS_LOAD_B(set, s_)     _Pragma("unroll") for (int i = 0; i < 4; ++i) fb[set][i] = *(const bf16x8_t*)&sS[fb_row + i * 16 * BK + ((s_) ? ch1 : ch0)];
 #define ABS_MMA(h_, aset, bset)                                                          \
   _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
@@ -911,18 +941,31 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 #undef ABS_LOAD_A
 #undef ABS_LOAD_B
 #undef ABS_MMA
-      // issue order: the first eight fragments, then the reads of the next half spread between
-      // the 16 MFMAs of the current one
-      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      // issue order: the first fragments, then the reads of the next half spread between the
+      // 16 MFMAs of the current one (a transposed A block takes two reads)
+      if (kATR) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        for (int i = 0; i < 12; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      }
       __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
     }
   }
@@ -934,6 +977,19 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   // bytes per row.  The ReLU mask of the tile is one bit per element in accumulator order:
   // word a / 2 of a lane, bit (a & 1) 16 + 4 b + r for block (a, b), register r.
   const int lcol = lane & 15, lrow4 = (lane >> 4) * 4;
+  if constexpr (EPI == EPI_WGRAD) {
+    // this piece's fp32 partial of the tile, straight from the accumulators (64 contiguous bytes per
+    // row and quarter-wavefront)
+    float* const outf = g.outf + (size_t)zsplit * g.split_stride + (size_t)(m0 + wm * 128 + lrow4) * g.ldof + n0 + wn * 64 + lcol;
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) outf[(size_t)(a * 16 + rr) * g.ldof + b * 16] = acc[a][b][rr];
+    if (!kRuns || sk_u >= sk_end) break;
+    continue;
+  }
   const float* bias = nullptr;
   if (EPI == EPI_RELU) bias = g.bias + (size_t)slot * g.bias_slot_stride;
   uint32_t mbits[4] = {0u, 0u, 0u, 0u};
