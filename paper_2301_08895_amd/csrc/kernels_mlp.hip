@@ -1,4 +1,5 @@
-// MLP rounds: bf16 operands on the matrix cores (MFMA 32x32x16), fp32 accumulation,
+// MLP rounds: bf16 operands on the matrix cores (MFMA 16x16x32 in the large-tile kernel, 32x32x16
+// in the others), fp32 accumulation,
 // fp32 master weights.
 //
 // The K^t uploads of a round are stacked into one batch of K^t * Bp rows (Bp = B padded
@@ -61,12 +62,6 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 // the L2 they no longer evict the operand panels the other workgroups of the XCD still share
 // (a 32768 x 2048 x 2048 forward product 250 -> 230 us).  A small round's outputs fit the caches and
 // are better left there for their reader (8192 rows: the products that follow got 4 % slower).
-#ifndef ABS_ATR16
-#define ABS_ATR16 1
-#endif
-#ifndef ABS_WGRAD16
-#define ABS_WGRAD16 1
-#endif
 #ifndef ABS_STREAM_MIN_BYTES
 #define ABS_STREAM_MIN_BYTES (64u << 20)
 #endif
@@ -279,7 +274,8 @@ struct GemmArgs {
   const uint16_t* maskT; size_t ldmaskT; // EPI_DGRAD: H_l^T [Ndim][ldmaskT]; the gradient passes where H_l > 0
   float* colsum; size_t ldcs;         // EPI_DGRAD: column sums of the bf16 results per block of 64 rows, [Mdim / 64][ldcs]
   // 256 x 256 tile kernel only: the ReLU mask as one bit per element in the kernel's own accumulator
-  // order (16 bytes per lane and tile: [tile][wavefront][lane][4 words], word mi, bit (4 ni + rg) 4 + rr).
+  // order (16 bytes per lane and tile: [tile][wavefront][lane][4 words], word a / 2, bit (a & 1) 16 + 4 b + r
+  // for the 16 x 16 block (a, b) of the wavefront's sub-tile and accumulator register r).
   // EPI_RELU writes it when set; EPI_DGRAD reads it instead of maskT when set.
   uint32_t* maskbits;
   // 256 x 256 tile kernel, bf16 outputs: store them without keeping their lines in the L2 (set by the
@@ -696,7 +692,7 @@ void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
 }
 
 // ------------------------------------------------------------------ the large-tile GEMM
-// 256 x 256 tile, 512 threads = 2 x 4 wavefronts of 128 x 64 (4 x 2 MFMA blocks, 128
+// 256 x 256 tile, 512 threads = 2 x 4 wavefronts of 128 x 64 (8 x 4 blocks of MFMA 16x16x32, 128
 // accumulator registers), BK = 64.  On gfx950 the LDS accepts about 64 B/clk of writes
 // against 256 B/clk of reads and the L1 delivers 64 B/clk, so what bounds a bf16 GEMM
 // tile is the bytes staged per flop: a 256 x 256 tile stages 64 KB per 8.4 MFLOP, two
@@ -732,14 +728,11 @@ __device__ __forceinline__ void lds_dma16_raw(const uint16_t* gsrc, uint16_t* ld
 
 template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG>
 __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDesc rd) {
-  constexpr bool kStageT = (EPI == EPI_RELU || EPI == EPI_DGRAD);
   // TAG 2 (first-layer weight gradient): the A operand is the dataset itself, rows gathered by
   // a_rowidx and the contraction running over those rows, i.e. A arrives as [k][m] instead of
   // [m][k]; its fragments are read with the transposing LDS read, so no transposed copy of
   // the minibatch is ever written.
   constexpr bool kATR = (EPI == EPI_WGRAD && TAG == 2);
-  // forward / input-gradient products run on 16x16x32 MFMAs, the rest on 32x32x16 (see below)
-  constexpr bool kM16 = (EPI == EPI_RELU || EPI == EPI_DGRAD || (EPI == EPI_WGRAD && ABS_WGRAD16 && (!kATR || ABS_ATR16)));
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem3];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -874,15 +867,14 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
     }                                                                             \
   }
 
-  if constexpr (kM16) {
-  // ---- forward and input-gradient products: MFMA 16x16x32.  A wavefront's 128 x 64 sub-tile is
-  // 8 x 4 blocks of 16 x 16 (128 accumulator registers as before); lane l holds row l & 15 and the
-  // 8 k values 8 (l >> 4) .. of an operand block, and accumulator register r of a block is row
-  // 4 (l >> 4) + r, column l & 15.  Per flop this form moves a quarter of the accumulator
-  // registers in and out of the matrix pipe that the 32x32x16 form does; on random operands the
-  // pipes alone sustain 2.18 instead of 1.86 PFLOP/s before the chip lowers its clock.  The
+  // ---- main loop on MFMA 16x16x32.  A wavefront's 128 x 64 sub-tile is 8 x 4 blocks of 16 x 16
+  // (128 accumulator registers); lane l holds row l & 15 and the 8 k values 8 (l >> 4) .. of an
+  // operand block, and accumulator register r of a block is row 4 (l >> 4) + r, column l & 15.
+  // Per flop this form moves a quarter of the accumulator registers in and out of the matrix pipe
+  // that the 32x32x16 form does: on random operands the pipes alone sustain 2.18 instead of
+  // 1.86 PFLOP/s before the chip lowers its clock, and the products got 3-7 % faster.  The
   // fragments of a 32-wide sub-step are read in halves (rows 0-63, rows 64-127 of A; B once per
-  // sub-step) one half ahead of the MFMAs that use them.
+  // sub-step) one half ahead of the MFMAs that use them, pinned there with sched_group_barrier.
   f32x4_t acc[8][4];
 #pragma unroll
   for (int a = 0; a < 8; ++a)
@@ -894,10 +886,11 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   const int fa_row = (wm * 128 + lr) * BK, fb_row = TM3 * BK + (wn * 64 + lr) * BK;
   const int sw = (lr >> 1) & 7;
   const int ch0 = (lk ^ sw) << 3, ch1 = ((4 | lk) ^ sw) << 3;
-  // kATR (A stored [k][m], see the 32x32x16 path below): a block's fragment is two transposing reads.
-  // Quarter-wavefront q takes k rows 8 q .. 8 q + 7 of the 32-row sub-step (rows + 0 and + 4 of its
-  // 4 x 16 pieces), all quarters the same 16 columns; the block position is XORed with the row's low
-  // bits as stored.
+  // kATR (A stored [k][m]): a block's fragment is two transposing reads.  Such a read works on groups
+  // of 16 lanes: lane s of a group points at 4 consecutive columns of row s / 4 of a 4 x 16 piece and
+  // receives column s of its 4 rows.  Quarter-wavefront q takes k rows 8 q .. 8 q + 7 of the 32-row
+  // sub-step (pieces at rows + 0 and + 4), all quarters the same 16 columns; the block position is
+  // XORed with the row's low bits (= s / 4) as stored.
   const int t16s = lane & 15, t16r = t16s >> 2;
   int fa_tr[8];
 #pragma unroll
@@ -969,6 +962,8 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
       __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
     }
   }
+#undef ABS_DMA
+#undef ABS_AIDX
   __syncthreads();      // all fragment reads done before the staging area is reused
 
   // ---- epilogue: bf16 outputs leave through this wavefront's private LDS staging, half of the
@@ -977,16 +972,26 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   // bytes per row.  The ReLU mask of the tile is one bit per element in accumulator order:
   // word a / 2 of a lane, bit (a & 1) 16 + 4 b + r for block (a, b), register r.
   const int lcol = lane & 15, lrow4 = (lane >> 4) * 4;
-  if constexpr (EPI == EPI_WGRAD) {
-    // this piece's fp32 partial of the tile, straight from the accumulators (64 contiguous bytes per
-    // row and quarter-wavefront)
-    float* const outf = g.outf + (size_t)zsplit * g.split_stride + (size_t)(m0 + wm * 128 + lrow4) * g.ldof + n0 + wn * 64 + lcol;
+  if constexpr (EPI == EPI_WGRAD || EPI == EPI_LOGITS) {
+    // fp32 results straight from the accumulators (64 contiguous bytes per row and quarter-wavefront):
+    // this piece's partial of the tile, or the logits with their bias
+    float* const outf = g.outf + (EPI == EPI_WGRAD ? (size_t)zsplit * g.split_stride : (size_t)0) +
+                        (size_t)(m0 + wm * 128 + lrow4) * g.ldof + n0 + wn * 64 + lcol;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (EPI == EPI_LOGITS) {
+      const float* bias = g.bias + (size_t)slot * g.bias_slot_stride;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int n = n0 + wn * 64 + b * 16 + lcol;
+        bv[b] = n < g.n_valid ? bias[n] : 0.f;
+      }
+    }
 #pragma unroll
     for (int a = 0; a < 8; ++a)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) outf[(size_t)(a * 16 + rr) * g.ldof + b * 16] = acc[a][b][rr];
+        for (int b = 0; b < 4; ++b) outf[(size_t)(a * 16 + rr) * g.ldof + b * 16] = acc[a][b][rr] + bv[b];
     if (!kRuns || sk_u >= sk_end) break;
     continue;
   }
@@ -1077,214 +1082,6 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   }
   if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
   break;
-  } else {
-  f32x16_t acc[4][2];
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-  const int lr = lane & 31, lk = lane >> 5;
-  const int fa_row = (wm * 128 + lr) * BK, fb_row = TM3 * BK + (wn * 64 + lr) * BK;
-  const int sw = (lr >> 1) & 7;
-  // kATR fragment addresses.  A transposing read works on groups of 16 lanes: lane s of a group
-  // points at 4 consecutive columns of row s / 4 of a 4 x 16 block and receives column s of its
-  // 4 rows.  Group g of the wavefront takes columns 16 (g & 1) .. + 16 of the 32-column MFMA block
-  // and rows 8 (g >> 1) .. of the 16-row sub-step; two reads (rows + 0 and + 4) give the 8 k values
-  // of a lane.  The block position is XORed with the row's low bits (= s / 4) as stored.
-  const int tg = lane >> 4, ts = lane & 15, tr = ts >> 2;
-  int fa_tr[4];
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi)
-    fa_tr[mi] = (tr + 8 * (tg >> 1)) * TM3 + (wm * 4 + (mi ^ tr)) * 32 + 16 * (tg & 1) + 4 * (ts & 3);
-  if (ks0 < ks1) {
-    if (kATR) ABS_AIDX(ks0);
-    ABS_DMA(ks0, 0);
-    if (kATR) ABS_AIDX(min(ks0 + 1, ks1 - 1));
-    for (int ks = ks0; ks < ks1; ++ks) {
-      const int stage = (ks - ks0) & 1;
-      __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's part of tile ks is in LDS
-      __syncthreads();                         // ... and everybody's; everybody is done with tile ks-1
-      if (ks + 1 < ks1) ABS_DMA(ks + 1, stage ^ 1);
-      if (kATR) ABS_AIDX(min(ks + 2, ks1 - 1));
-      const uint16_t* sS = smem + stage * kStage3;
-      bf16x8_t fa[2][4], fb[2][2];
-#define ABS_FRAGS(set, s_)                                                                        \
-  {                                                                                               \
-    const int ch_ = ((((s_) << 1) | lk) ^ sw) << 3;                                               \
-    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) {                                            \
-      if (kATR) {                                                                                 \
-        typedef short s16x4_ __attribute__((ext_vector_type(4)));                                 \
-        const uint16_t* q_ = sS + fa_tr[mi] + (s_) * 16 * TM3;                                    \
-        union { s16x4_ h[2]; bf16x8_t v; } u_;                                                    \
-        u_.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_*)(q_));            \
-        u_.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_*)(q_ + 4 * TM3));  \
-        fa[set][mi] = u_.v;                                                                       \
-      } else {                                                                                    \
-        fa[set][mi] = *(const bf16x8_t*)&sS[fa_row + mi * 32 * BK + ch_];                         \
-      }                                                                                           \
-    }                                                                                             \
-    _Pragma("unroll") for (int ni = 0; ni < 2; ++ni)                                              \
-      fb[set][ni] = *(const bf16x8_t*)&sS[fb_row + ni * 32 * BK + ch_];                           \
-  }
-      ABS_FRAGS(0, 0);
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        if (s < 3) ABS_FRAGS((s + 1) & 1, s + 1);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][mi], fb[s & 1][ni], acc[mi][ni], 0, 0, 0);
-      }
-#undef ABS_FRAGS
-      // issue order: the first fragment set, then one LDS read behind each MFMA (a transposed
-      // A operand takes two reads per fragment: 10 instead of 6 reads per sub-step)
-      if (kATR) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-#pragma unroll
-          for (int i = 0; i < 2; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-          }
-#pragma unroll
-          for (int i = 0; i < 6; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
-        }
-      } else {
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-#pragma unroll
-          for (int i = 0; i < 6; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
-          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        }
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-    }
-  }
-#undef ABS_DMA
-  __syncthreads();      // all fragment reads done before the staging area is reused
-
-  // ---- epilogue (accumulator layout as in the 128-row kernel).  bf16 outputs leave through
-  // this wavefront's private LDS staging, once per orientation, so that every global store
-  // is 16 bytes per lane and 128 contiguous bytes per row: half of the wavefront's tile
-  // (64 x 64) at a time, staged as [n][m] for the transposed copy and as [m][n] for the
-  // row-major one.  LDS operations of one wavefront execute in order, so no barrier is
-  // needed between a wavefront's own staging writes and reads.
-  const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
-  const float* bias = nullptr;
-  if (EPI == EPI_RELU || EPI == EPI_LOGITS) bias = g.bias + (size_t)slot * g.bias_slot_stride;
-  float* outf = g.outf;
-  if (EPI == EPI_WGRAD) outf += (size_t)zsplit * g.split_stride;
-  // the tile's ReLU mask bits of this lane (EPI_RELU collects them, EPI_DGRAD has them from the forward pass)
-  uint32_t mbits[4] = {0u, 0u, 0u, 0u};
-  uint32_t* const mbits_at =
-      g.maskbits ? g.maskbits + ((((size_t)(m0 / TM3) * g.nt + n0 / TN3) * 8 + wave) * 64 + lane) * 4 : nullptr;
-  if (EPI == EPI_DGRAD && mbits_at) {
-    const uint4 q = *(const uint4*)mbits_at;
-    mbits[0] = q.x; mbits[1] = q.y; mbits[2] = q.z; mbits[3] = q.w;
-  }
-  uint16_t* const sT = smem + wave * (2 * 64 * kEpiPitch3);     // [64 n][72]
-  uint16_t* const sN = sT + 64 * kEpiPitch3;                    // [64 m][72]
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    float cs[2] = {0.f, 0.f};             // EPI_DGRAD: column sums over this half's 64 rows
-    if (EPI == EPI_DGRAD && !mbits_at) {
-      // the ReLU mask of this half, H_l^T [64 n][64 m], fetched as whole 128-byte rows into sT;
-      // every lane later replaces the 4 entries it read by its 4 results
-      const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int q = lane + 64 * i, r = q >> 3, ch = (q & 7) * 8;
-        *(uint4*)&sT[r * kEpiPitch3 + ch] = *(const uint4*)(g.maskT + (size_t)(ncol + r) * g.ldmaskT + mrow + ch);
-      }
-    }
-#pragma unroll
-    for (int mh = 0; mh < 2; ++mh) {
-      const int mi = half * 2 + mh;
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int nl = ni * 32 + lcol;
-        const int n = n0 + wn * 64 + nl;
-        float bv = 0.f;
-        if (EPI == EPI_RELU || EPI == EPI_LOGITS) bv = n < g.n_valid ? bias[n] : 0.f;
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          const int ml = mh * 32 + rg * 8 + lrow4;                // row inside this half
-          const int mbase = m0 + wm * 128 + half * 64 + ml;
-          uint16_t h[4];
-          uint2 hm = make_uint2(0, 0);
-          if (EPI == EPI_DGRAD && !mbits_at) hm = *(const uint2*)&sT[nl * kEpiPitch3 + ml];
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const int m = mbase + rr;
-            float v = acc[mi][ni][rg * 4 + rr];
-            if (EPI == EPI_RELU) {
-              v = fmaxf(v + bv, 0.f);
-              // (the mask is taken from the narrowed value, as the transposed copy would give it)
-              if ((f32_to_bf16(v) & 0x7FFFu) != 0) mbits[mi] |= 1u << (((ni * 4 + rg) * 4) + rr);
-            } else if (EPI == EPI_LOGITS) {
-              v += bv;
-              outf[(size_t)m * g.ldof + n] = v;
-            } else if (EPI == EPI_DGRAD) {
-              const uint32_t pair = rr < 2 ? hm.x : hm.y;
-              const bool pass = mbits_at ? ((mbits[mi] >> (((ni * 4 + rg) * 4) + rr)) & 1u) != 0
-                                         : ((pair >> ((rr & 1) * 16)) & 0x7FFFu) != 0;
-              v = pass ? v : 0.f;
-            } else {
-              outf[(size_t)m * g.ldof + n] = v;
-            }
-            if (kStageT) {
-              h[rr] = f32_to_bf16(v);
-              if (EPI == EPI_DGRAD) cs[ni] += __uint_as_float((uint32_t)h[rr] << 16);
-              if (g.out) sN[(ml + rr) * kEpiPitch3 + nl] = h[rr];
-            }
-          }
-          if (kStageT) {
-            uint2 o;
-            o.x = h[0] | ((uint32_t)h[1] << 16);
-            o.y = h[2] | ((uint32_t)h[3] << 16);
-            *(uint2*)&sT[nl * kEpiPitch3 + ml] = o;
-          }
-        }
-      }
-    }
-    if (EPI == EPI_DGRAD) {
-      // the bias gradient's share of these 64 rows (the two half-wavefronts hold alternate rows)
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const float c = cs[ni] + __shfl_xor(cs[ni], 32, 64);
-        if (lane < 32)
-          g.colsum[(size_t)((m0 + wm * 128 + half * 64) >> 6) * g.ldcs + n0 + wn * 64 + ni * 32 + lcol] = c;
-      }
-    }
-    if (kStageT) {
-      const int mrow = m0 + wm * 128 + half * 64, ncol = n0 + wn * 64;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int q = lane + 64 * i, r = q >> 3, ch = (q & 7) * 8;
-        const uint4 vt = *(const uint4*)&sT[r * kEpiPitch3 + ch];
-        *(uint4*)(g.outT + (size_t)(ncol + r) * g.ldoT + mrow + ch) = vt;
-        if (g.out) {
-          const uint4 vn = *(const uint4*)&sN[r * kEpiPitch3 + ch];
-          *(uint4*)(g.out + (size_t)(mrow + r) * g.ldo + ncol + ch) = vn;
-        }
-      }
-    }
-  }
-  if (EPI == EPI_RELU && mbits_at) *(uint4*)mbits_at = make_uint4(mbits[0], mbits[1], mbits[2], mbits[3]);
-  if (!kRuns || sk_u >= sk_end) break;
-  }      // 32x32x16 path
   }
 }
 

@@ -52,6 +52,8 @@ def test_softmax():
     (dict(M=4096, dims=[200, 96, 10], N=8, B=40, n_slow=2, lr=1e-3), 30, 1500),           # several passes, ragged tail
     (dict(M=8192, dims=[256, 256, 512, 10], N=6, B=256, K0=2, n_slow=1, lr=5e-4), 12, 1000),  # 256-tile kernels, one partial pass
     (dict(M=8192, dims=[256, 128, 256, 100], n_classes=100, N=8, B=128, n_slow=0, lr=5e-4), 12, 2049),
+    # 256 classes and passes of 128 * 256 rows: the logits product itself runs on the 256 x 256 tile kernel
+    (dict(M=65536, dims=[128, 256, 256], n_classes=256, N=128, B=256, K0=4, n_slow=0, lr=2e-4), 3, 40_000),
 ])
 def test_mlp(over, T, rows):
     _check(workloads.scaled_preset(3, **over), T, rows, 2e-3)
