@@ -376,6 +376,9 @@ __device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_bl
 #ifndef ABS_RING64
 #define ABS_RING64 3
 #endif
+#ifndef ABS_RING64_KPS
+#define ABS_RING64_KPS 2
+#endif
 #ifndef ABS_RING128
 #define ABS_RING128 2
 #endif
@@ -395,14 +398,17 @@ struct GemmCfg {
 // tiles in flight and one barrier per k-step (as in the 256 x 256 kernel, swizzle on the global
 // side).  For products with few tiles per CU, where one tile in flight per workgroup leaves the
 // k-steps waiting for memory latency one after the other.  Needs whole 64-wide k-steps of A
-// (a_kvalid a multiple of BK covering the contraction).
-template <int TN, int EPI, bool GATHER, bool PER_UPLOAD, int TAG, int RING = 0>
-__global__ __launch_bounds__(256, (RING * GemmCfg<TN>::kMainElems * 2 > 80 * 1024) ? 1 : 2)
+// (a_kvalid a multiple of BK covering the contraction).  KPS > 1: a stage holds KPS consecutive
+// k-steps, requested, awaited and released together (one barrier per KPS k-steps).
+template <int TN, int EPI, bool GATHER, bool PER_UPLOAD, int TAG, int RING = 0, int KPS = 1>
+__global__ __launch_bounds__(256, (RING * KPS * GemmCfg<TN>::kMainElems * 2 > 80 * 1024) ? 1 : 2)
 void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
   using Cfg = GemmCfg<TN>;
   constexpr int WN = Cfg::WN, NI = Cfg::NI, BCH = Cfg::BCH;
   constexpr bool kStageT = (EPI == EPI_RELU || EPI == EPI_DGRAD);
-  constexpr int kMain = (RING ? RING : 1) * Cfg::kMainElems;
+  static_assert(KPS == 1 || RING > 0, "several k-steps per stage: ring only");
+  constexpr int kStageElems = KPS * Cfg::kMainElems;       // a ring stage holds KPS consecutive k-steps
+  constexpr int kMain = (RING ? RING : 1) * kStageElems;
   constexpr int kSmem = kStageT && Cfg::kEpiElems > kMain ? Cfg::kEpiElems : kMain;
   static_assert(kSmem * 2 <= 160 * 1024, "LDS budget");
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem];
@@ -525,21 +531,21 @@ void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
   const int sw = (lr >> 1) & 7;
   // one request per 8 rows: stage `st_` receives tile `ks_`
 #define ABS_RING_DMA(ks_, st_)                                                            \
-  {                                                                                       \
-    const int k0_ = (ks_) * BK;                                                           \
-    uint16_t* a_ = smem + (st_) * Cfg::kMainElems + wave * 32 * BK;                       \
-    uint16_t* b_ = smem + (st_) * Cfg::kMainElems + TM * BK + wave * (TN / 4) * BK;       \
+  _Pragma("unroll") for (int p_ = 0; p_ < KPS; ++p_) {                                    \
+    const int k0_ = ((ks_) + p_) * BK;                                                    \
+    uint16_t* a_ = smem + (st_) * kStageElems + p_ * Cfg::kMainElems + wave * 32 * BK;    \
+    uint16_t* b_ = smem + (st_) * kStageElems + p_ * Cfg::kMainElems + TM * BK + wave * (TN / 4) * BK; \
     lds_dma16(pa0 + k0_, a_);            lds_dma16(pa1 + k0_, a_ + 8 * BK);               \
     lds_dma16(pa2 + k0_, a_ + 16 * BK);  lds_dma16(pa3 + k0_, a_ + 24 * BK);              \
     _Pragma("unroll") for (int i = 0; i < TN / 32; ++i)                                   \
       lds_dma16(pb0 + i * b_step + ((i & 1) ? c_odd : c_even) + k0_, b_ + i * 8 * BK);    \
   }
-  constexpr int kDmaPerWave = 4 + TN / 32;
+  constexpr int kDmaPerWave = KPS * (4 + TN / 32);        // requests per wavefront and stage
   if (ks0 < ks1) {
     if (RING) {
 #pragma unroll
       for (int j = 0; j < RING - 1; ++j)
-        if (ks0 + j < ks1) ABS_RING_DMA(ks0 + j, j);
+        if (ks0 + j * KPS < ks1) ABS_RING_DMA(ks0 + j * KPS, j);
     } else {
       ABS_FETCH(ks0);
     }
@@ -547,14 +553,19 @@ void mlp_gemm_kernel(GemmArgs g, RoundDesc rd) {
     for (int ks = ks0; ks < ks1; ++ks) {
       const uint16_t* sA = smem;
       if (RING) {
-        // tile ks has landed when at most the RING - 2 tiles behind it are outstanding
-        constexpr int kOut = RING > 2 ? (RING - 2) * kDmaPerWave : 0;
-        if (ks + RING - 2 < ks1) __builtin_amdgcn_s_waitcnt(0x0F70 | (kOut & 15) | ((kOut >> 4) << 14));
-        else                     __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();      // ... for every wavefront; and everybody is done with tile ks - 1
-        if (ks + RING - 1 < ks1) ABS_RING_DMA(ks + RING - 1, stage == 0 ? RING - 1 : stage - 1);
-        sA = smem + stage * Cfg::kMainElems;
-        stage = stage + 1 == RING ? 0 : stage + 1;
+        // (KPS > 1: the launcher hands over whole stages, ks1 - ks0 a multiple of KPS; wait, barrier and
+        // requests happen once per stage, at its first k-step)
+        const int pnl = KPS > 1 ? (ks - ks0) % KPS : 0;
+        if (pnl == 0) {
+          // stage ks has landed when at most the RING - 2 stages behind it are outstanding
+          constexpr int kOut = RING > 2 ? (RING - 2) * kDmaPerWave : 0;
+          if (ks + (RING - 2) * KPS < ks1) __builtin_amdgcn_s_waitcnt(0x0F70 | (kOut & 15) | ((kOut >> 4) << 14));
+          else                             __builtin_amdgcn_s_waitcnt(0x0F70);
+          __syncthreads();      // ... for every wavefront; and everybody is done with stage ks - KPS
+          if (ks + (RING - 1) * KPS < ks1) ABS_RING_DMA(ks + (RING - 1) * KPS, stage == 0 ? RING - 1 : stage - 1);
+        }
+        sA = smem + stage * kStageElems + pnl * Cfg::kMainElems;
+        if (pnl == KPS - 1) stage = stage + 1 == RING ? 0 : stage + 1;
       } else {
         ABS_STAGE();
         __syncthreads();
@@ -1765,6 +1776,16 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   // DMA ring: whole k-steps only
   const bool ring_ok = EPI != EPI_LOGITS && (!GATHER || (g.a_kvalid % BK == 0 && g.a_kvalid >= g.ksteps_total * BK));
   if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU) {
+    // two k-steps per stage (one barrier, one wait, one batch of requests for 128 of the contraction):
+    // these tiles do 8 MFMAs per wavefront and k-step, and what a k-step costs is mostly its fixed part
+    // (cfg 3's first-layer forward 43-46 -> 35-38 us; three k-steps in a ring of two stages 32-35 us.
+    // The 128-wide tiles lose with it: two k-steps per stage leave room for one workgroup per CU
+    // instead of two, cfg 4's first-layer forward 65 -> 91 us)
+    if (ABS_RING64_KPS > 1 && g.ksteps_per_split % ABS_RING64_KPS == 0 && g.ksteps_total % ABS_RING64_KPS == 0) {
+      plan_note("fwd_ring2", TM, tn, nsplit);
+      ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64, ABS_RING64_KPS>), grid1, block, s, g, rd);
+      return false;
+    }
     plan_note(EPI == EPI_RELU ? "fwd_ring" : EPI == EPI_DGRAD ? "dgrad_ring" : "wgrad_ring", TM, tn, nsplit);
     ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64>), grid1, block, s, g, rd);
     return false;
