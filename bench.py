@@ -202,12 +202,57 @@ def calibrate_mfma(args):
     scratch = torch.zeros(wgs * 512, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     out = {"mode": "calibrate_mfma", "workgroups": wgs, "iters": iters, "peak_tflops": PEAK_MFMA_BF16_TFLOPS, "runs": []}
-    for data_mode, label in ((0, "constant operands"), (1, "random bf16 operands")):
+    for data_mode, label in ((0, "32x32x16, constant operands"), (1, "32x32x16, random bf16 operands"),
+                             (2, "16x16x32, constant operands"), (3, "16x16x32, random bf16 operands")):
         best = None
         for _ in range(3):
             ms, tf = lib.abs_calibrate_mfma(data_mode, iters, wgs, scratch.data_ptr(), stream)
             best = (ms, tf) if best is None or tf > best[1] else best
         out["runs"].append({"operands": label, "ms": best[0], "tflops": best[1], "frac_of_peak": best[1] / PEAK_MFMA_BF16_TFLOPS})
+    print(json.dumps(out))
+
+
+def library_gemm(args):
+    """Context only, not part of the library under test: the vendor BLAS (torch.matmul) on the shapes of the
+    workload's large products - plain GEMMs, no gather, bias, ReLU, mask, second output orientation or per-upload
+    weights - with operands distributed like the round's (ReLU'd unit normals times small normals).  One JSON line."""
+    import torch
+    import workloads
+    p = workloads.preset(args.config)
+    d = p["dims"]
+    torch.manual_seed(0)
+    dev = "cuda"
+    out = {"mode": "library_gemm", "workload": p["name"], "note": "torch.matmul, bf16 in / bf16 out, 200 launches each after 50 warm-up launches", "products": []}
+
+    def run(name, rows, m, n, k, transposed):
+        if transposed:      # contraction over the leading dimension of both operands (a weight gradient)
+            a = torch.relu(torch.randn(k, m, device=dev)).bfloat16()
+            b = (torch.randn(k, n, device=dev) * 0.03).bfloat16()
+            f = lambda: torch.matmul(a.t(), b)
+        else:
+            a = torch.relu(torch.randn(m, k, device=dev)).bfloat16()
+            b = (torch.randn(n, k, device=dev) * 0.03).bfloat16()
+            f = lambda: torch.matmul(a, b.t())
+        for _ in range(50):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 200 * 1e3
+        out["products"].append({"product": name, "stacked_rows": rows, "m": m, "n": n, "k": k, "us": round(us, 1),
+                                "tflops": round(2.0 * m * n * k / us / 1e6, 1)})
+
+    for K in (p["K0"], p["N"]):
+        rows = K * p["B"]
+        run("first-layer forward", rows, rows, d[1], d[0], False)
+        run("first-layer weight gradient", rows, d[0], d[1], rows, True)
+        if len(d) > 3:
+            run("hidden forward / input gradient", rows, rows, d[2], d[1], False)
+            run("hidden weight gradient", rows, d[1], d[2], rows, True)
     print(json.dumps(out))
 
 
@@ -286,6 +331,8 @@ def main():
                     help="configs 1-2: advance this many independent simulations (seeds) per launch")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="run the library's MFMA-only loop (constant and random operands), print its rate, exit")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="context only: time the vendor BLAS (torch.matmul) on the shapes of the workload's large products, exit")
     ap.add_argument("--calibrate-iters", type=int, default=4000, help="iterations of the MFMA-only loop")
     ap.add_argument("--full-k-rounds", type=int, default=8,
                     help="MLP workloads: extra rounds at K = N after the timed region for the roofline_full_k block (0: none)")
@@ -304,6 +351,8 @@ def main():
 
     if args.calibrate_mfma:
         return calibrate_mfma(args)
+    if args.library_gemm:
+        return library_gemm(args)
 
     import numpy as np
     import torch

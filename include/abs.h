@@ -310,15 +310,17 @@ const char* abs_batch_last_error(const abs_batch* b);
 void abs_batch_destroy(abs_batch* b);
 
 /*
- * Measurement aid, not part of the method: run nothing but the matrix-core instructions of the large
- * GEMM tile (MFMA 32x32x16 bf16, 32 per wavefront and iteration, 8 wavefronts per workgroup, operands
- * in registers, no memory traffic) and report the sustained rate, so that the GEMM kernels' figures
- * can be read against what the chip's matrix cores deliver at the clock they settle at.
- *  data_mode   0: all operand elements 1.0;  1: random bf16 values (sign, mantissa, exponent 2^-2..2^0)
+ * Measurement aid, not part of the method: run nothing but the matrix-core instructions of a GEMM
+ * tile (the flops of a 128 x 64 x 64 wavefront step per iteration, as 32 MFMA 32x32x16 bf16 or as 64 MFMA
+ * 16x16x32 bf16; 8 wavefronts per workgroup, operands in registers, no memory traffic) and report the
+ * sustained rate, so that the GEMM kernels' figures can be read against what the chip's matrix cores
+ * deliver at the clock they settle at.
+ *  data_mode   0: all operand elements 1.0;  1: random bf16 values (sign, mantissa, exponent 2^-2..2^0);
+ *              + 2: the 16x16x32 form (the large-tile kernel's) instead of 32x32x16
  *  iters       loop iterations per wavefront;  workgroups: grid size (e.g. 512 = two per CU)
  *  d_scratch   DEVICE, at least workgroups * 512 floats (not written in practice)
- *  h_ms, h_tflops  HOST: duration of one launch (HIP events on hip_stream) and 2 x 32 x 32 x 16 flops
- *              per instruction over it.  Synchronises the stream.
+ *  h_ms, h_tflops  HOST: duration of one launch (HIP events on hip_stream) and its flops (2 x 128 x 64 x 64
+ *              per wavefront and iteration) over it.  Synchronises the stream.
  */
 int abs_calibrate_mfma(int32_t data_mode, int32_t iters, int32_t workgroups, float* d_scratch,
                        void* hip_stream, double* h_ms, double* h_tflops);
