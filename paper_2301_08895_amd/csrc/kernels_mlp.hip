@@ -376,9 +376,6 @@ __device__ __forceinline__ void lds_dma16(const uint16_t* gsrc, uint16_t* lds_bl
 #ifndef ABS_RING64
 #define ABS_RING64 3
 #endif
-#ifndef ABS_RING64_KPS
-#define ABS_RING64_KPS 2
-#endif
 #ifndef ABS_RING128
 #define ABS_RING128 2
 #endif
@@ -1775,19 +1772,15 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   const dim3 grid1(8 * g.rows_per_xcd * g.nt + g.pig_blocks + g.bias_blocks, 1, 1);
   // DMA ring: whole k-steps only
   const bool ring_ok = EPI != EPI_LOGITS && (!GATHER || (g.a_kvalid % BK == 0 && g.a_kvalid >= g.ksteps_total * BK));
-  if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU) {
-    // two k-steps per stage (one barrier, one wait, one batch of requests for 128 of the contraction):
-    // these tiles do 8 MFMAs per wavefront and k-step, and what a k-step costs is mostly its fixed part
-    // (cfg 3's first-layer forward 43-46 -> 35-38 us; three k-steps in a ring of two stages 32-35 us.
-    // The 128-wide tiles lose with it: two k-steps per stage leave room for one workgroup per CU
-    // instead of two, cfg 4's first-layer forward 65 -> 91 us)
-    if (ABS_RING64_KPS > 1 && g.ksteps_per_split % ABS_RING64_KPS == 0 && g.ksteps_total % ABS_RING64_KPS == 0) {
-      plan_note("fwd_ring2", TM, tn, nsplit);
-      ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64, ABS_RING64_KPS>), grid1, block, s, g, rd);
-      return false;
-    }
-    plan_note(EPI == EPI_RELU ? "fwd_ring" : EPI == EPI_DGRAD ? "dgrad_ring" : "wgrad_ring", TM, tn, nsplit);
-    ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64>), grid1, block, s, g, rd);
+  // 64-wide forward tiles: two k-steps per ring stage (one barrier, one wait, one batch of requests for
+  // 128 of the contraction): these tiles do 8 MFMAs per wavefront and k-step, and what a k-step costs is
+  // mostly its fixed part (cfg 3's first-layer forward 43-46 -> 35-38 us; three k-steps in a ring of two
+  // stages 32-35 us.  The 128-wide tiles lose with it: two k-steps per stage leave room for one workgroup
+  // per CU instead of two, cfg 4's first-layer forward 65 -> 91 us).  Widths are padded to 128, so a
+  // forward product always has an even number of k-steps.
+  if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU && g.ksteps_per_split % 2 == 0 && g.ksteps_total % 2 == 0) {
+    plan_note("fwd_ring2", TM, tn, nsplit);
+    ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64, 2>), grid1, block, s, g, rd);
     return false;
   }
   if (ring_ok && tn == 128 && ABS_RING128) {
