@@ -24,6 +24,8 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <string>
 
 #include "kernels.h"
@@ -740,7 +742,11 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
   // a_rowidx and the contraction running over those rows, i.e. A arrives as [k][m] instead of
   // [m][k]; its fragments are read with the transposing LDS read, so no transposed copy of
   // the minibatch is ever written.
-  constexpr bool kATR = (EPI == EPI_WGRAD && TAG == 2);
+  // TAG 3 (forward / input gradient of a hidden layer): the A operand is the TRANSPOSED copy of the
+  // activations / output gradients, [k = features][m = stacked rows], read the same way - the layer
+  // that produced it then writes no row-major copy at all.
+  constexpr bool kATR = (EPI == EPI_WGRAD && TAG == 2) || ((EPI == EPI_RELU || EPI == EPI_DGRAD) && TAG == 3);
+  constexpr bool kARows = kATR && EPI == EPI_WGRAD;      // the k rows of A are gathered through a_rowidx
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmem3];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -851,9 +857,12 @@ __global__ __launch_bounds__(512, 1) void mlp_gemm256_kernel(GemmArgs g, RoundDe
 
   // (kATR) the four dataset rows this lane requests for k-step ks
 #define ABS_AIDX(ks)                                                              \
-  {                                                                               \
+  if (kARows) {                                                                   \
     const uint32_t* ri_ = g.a_rowidx + (size_t)(ks) * BK + atr_row;               \
     aidx0 = ri_[0]; aidx1 = ri_[2]; aidx2 = ri_[4]; aidx3 = ri_[6];               \
+  } else {                                                                        \
+    aidx0 = (uint32_t)((ks) * BK + atr_row);                                      \
+    aidx1 = aidx0 + 2; aidx2 = aidx0 + 4; aidx3 = aidx0 + 6;                      \
   }
 #define ABS_DMA(ks, stage)                                                        \
   {                                                                               \
@@ -1733,6 +1742,10 @@ template <int EPI, bool GATHER, bool PER_UPLOAD, int TAG = 0>
 bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit, hipStream_t s) {
   g.nsplit = nsplit;
   const bool big = g.sk_q > 0 || gemm_is_big(GATHER, PER_UPLOAD, g, Mdim, Ndim, nsplit);
+  if (TAG == 3 && !big) {      // the caller picks TAG 3 with this very test: only the large-tile kernel reads a transposed A
+    std::fprintf(stderr, "libabs: transposed-A product outside the large-tile kernel\n");
+    std::abort();
+  }
   if (big && g.sk_q > 0) {
     // runs of sk_q k-steps across the tiles: one workgroup per run
     g.mt = Mdim / TM3;
@@ -1752,8 +1765,8 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
     // the first layer's forward product, whose gathered rows come from memory anyway: 368 -> 374 us)
     g.stream_out = (EPI == EPI_RELU || EPI == EPI_DGRAD) && !GATHER && g.ksteps_total >= 16 &&
                    (size_t)Mdim * (size_t)Ndim * 2 >= ABS_STREAM_MIN_BYTES;
-    plan_note(EPI == EPI_RELU ? "fwd" : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? "dgrad" : TAG == 2 ? "wgrad_x" : "wgrad",
-              TM3, TN3, nsplit);
+    plan_note(EPI == EPI_RELU ? (TAG == 3 ? "fwd_t" : "fwd") : EPI == EPI_LOGITS ? "logits" : EPI == EPI_DGRAD ? (TAG == 3 ? "dgrad_t" : "dgrad")
+              : TAG == 2 ? "wgrad_x" : "wgrad", TM3, TN3, nsplit);
     ABS_LAUNCH_K((mlp_gemm256_kernel<EPI, GATHER, PER_UPLOAD, TAG>), dim3(8 * g.rows_per_xcd * g.nt + g.pig_blocks + g.bias_blocks), dim3(512), s, g, rd);
     return true;
   }
@@ -1811,6 +1824,13 @@ unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd
   const int L = p.L;
   uint32_t* rowidx = at<uint32_t>(a, p.off_rowidx);
   const bool train = draw0 >= 0;
+  // H_l is read row-major by the next layer's product and transposed by its weight gradient and mask.
+  // When both the product that writes H_l and the one that reads it run on the 256 x 256 tile kernel,
+  // the reader takes the transposed copy (transposing LDS reads, TAG 3) and the row-major copy is never
+  // written: half of the writer's output bytes (cfg 5's first-layer forward at 32768 rows: 134 MB, 368 -> 351 us;
+  // the reader pays 7 us for the two LDS reads per fragment; a round at K = 128 -1.4 %, at K = 40 -2 %).
+  // The last hidden layer keeps both: the output-layer kernels read it row-major.
+  bool a_transposed = false;           // this layer reads H_l^T
   for (int l = 0; l < (train ? L - 1 : L); ++l) {
     GemmArgs g{};
     if (l == 0) {
@@ -1819,6 +1839,8 @@ unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd
         g.gen_rows = 1; g.gen_B = p.B; g.gen_shard_rows = a.shard_rows; g.gen_batch_key = a.batch_key;
         g.gen_draw0 = (uint32_t)draw0; g.gen_y = a.y; g.gen_rowidx = rowidx; g.gen_label = at<int32_t>(a, p.off_label);
       }
+    } else if (a_transposed) {
+      g.A = at<uint16_t>(a, p.off_ht[l]); g.lda = p.ldm;
     } else {
       g.A = at<uint16_t>(a, p.off_h[l]); g.lda = (size_t)p.ld[l];
     }
@@ -1835,8 +1857,18 @@ unsigned mlp_forward(const MlpArgs& a, const uint16_t* Xsrc, const RoundDesc& rd
       const int kind = l == 0 ? KK_MLP_FWD_L1 : KK_MLP_FWD_HIDDEN;
       kbegin(hook, kind, fl, arows * (p.d[l] * 2.0 + p.d[l + 1] * 4.0));
       if (want_bits) g.maskbits = at<uint32_t>(a, p.off_maskbits[l + 1]);
-      const bool big = l == 0 ? launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s)
-                              : launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      // does the next layer's product read H_{l+1} transposed?  (both on the large-tile kernel)
+      bool next_transposed = false;
+      if (l + 1 <= L - 2) {
+        GemmArgs nx{};
+        nx.rows_per_upload = p.Bp;
+        next_transposed = gemm_is_big(l == 0, true, g, rows, p.dp[l + 1], 1) && gemm_is_big(false, true, nx, rows, p.dp[l + 2], 1);
+      }
+      if (next_transposed) g.out = nullptr;
+      const bool big = l == 0        ? launch_gemm<EPI_RELU, true, true>(g, rd, rows, p.dp[l + 1], 1, s)
+                       : a_transposed ? launch_gemm<EPI_RELU, false, true, 3>(g, rd, rows, p.dp[l + 1], 1, s)
+                                      : launch_gemm<EPI_RELU, false, true>(g, rd, rows, p.dp[l + 1], 1, s);
+      a_transposed = next_transposed;
       if (big && want_bits) have_bits |= 1u << (l + 1);
       kend(hook, kind);
     } else {
@@ -1939,9 +1971,13 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
     }
 
     // ---- input gradients back through W_{L-1} .. W_1 (none is needed for the first layer)
+    // (dZ_l likewise: read row-major only by the next product down; when writer and reader both run on
+    // the large-tile kernel the reader takes dZ_l^T and the row-major copy is not written)
+    bool dz_transposed = false;          // this product reads dZ_{l+1}^T
     for (int l = L - 1; l >= 1; --l) {
       GemmArgs g{};
-      g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.ld[l + 1];
+      if (dz_transposed) { g.A = at<uint16_t>(a, p.off_dzt[l + 1]); g.lda = p.ldm; }
+      else               { g.A = at<uint16_t>(a, p.off_dz[l + 1]); g.lda = (size_t)p.ld[l + 1]; }
       g.Bt = sbase + p.wn_off[l]; g.ldb = (size_t)p.ld[l + 1];
       g.bt_slot_stride = p.shadow_stride;
       g.by_upload = own;
@@ -1961,8 +1997,14 @@ hipError_t launch_mlp_round(const MlpArgs& a, const RoundDesc& rd, hipStream_t s
       // the product through the output layer contracts over the classes only: bandwidth-bound
       const int kind = l == L - 1 ? KK_MLP_DGRAD_OUT : KK_MLP_DGRAD;
       kbegin(hook, kind, 2.0 * arows * p.d[l] * p.d[l + 1], arows * (p.d[l + 1] * 2.0 + p.d[l] * 6.0));
-      if (l == L - 1) launch_gemm<EPI_DGRAD, false, true, 1>(g, rd, rows, p.dp[l], 1, s);
-      else            launch_gemm<EPI_DGRAD, false, true, 0>(g, rd, rows, p.dp[l], 1, s);
+      bool next_transposed = false;      // the product for layer l - 1 reads dZ_l^T
+      if (l >= 2)
+        next_transposed = gemm_is_big(false, true, g, rows, p.dp[l], 1) && gemm_is_big(false, true, g, rows, p.dp[l - 1], 1);
+      if (next_transposed) g.out = nullptr;
+      if (l == L - 1)         launch_gemm<EPI_DGRAD, false, true, 1>(g, rd, rows, p.dp[l], 1, s);
+      else if (dz_transposed) launch_gemm<EPI_DGRAD, false, true, 3>(g, rd, rows, p.dp[l], 1, s);
+      else                    launch_gemm<EPI_DGRAD, false, true, 0>(g, rd, rows, p.dp[l], 1, s);
+      dz_transposed = next_transposed;
       kend(hook, kind);
     }
 
