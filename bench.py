@@ -32,8 +32,8 @@ MFMA_KINDS = {"mlp_fwd_l1", "mlp_fwd_hidden", "mlp_dgrad", "mlp_wgrad_l1", "mlp_
 # rocprofv3 symbol (substring) of each kernel kind in the cfg 5 run, for the HBM-traffic import
 KIND_SYMBOL = {
     "mlp_fwd_l1": "mlp_gemm256_kernel<0, true, true, 0>",
-    "mlp_fwd_hidden": "mlp_gemm256_kernel<0, false, true, 0>",
-    "mlp_dgrad": "mlp_gemm256_kernel<2, false, true, 0>",
+    "mlp_fwd_hidden": "mlp_gemm256_kernel<0, false, true, 3>",     # (A operand read from the transposed copy)
+    "mlp_dgrad": "mlp_gemm256_kernel<2, false, true, 3>",
     "mlp_wgrad_l1": "mlp_gemm256_kernel<3, false, false, 2>",
 }
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_hbm_traffic.txt")
