@@ -1791,6 +1791,12 @@ bool launch_gemm(GemmArgs g, const RoundDesc& rd, int Mdim, int Ndim, int nsplit
   // stages 32-35 us.  The 128-wide tiles lose with it: two k-steps per stage leave room for one workgroup
   // per CU instead of two, cfg 4's first-layer forward 65 -> 91 us).  Widths are padded to 128, so a
   // forward product always has an even number of k-steps.
+  // Where the k-step count allows, three k-steps per stage in a ring of two (the same 144 KB).
+  if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU && g.ksteps_per_split % 3 == 0 && g.ksteps_total % 3 == 0) {
+    plan_note("fwd_ring3", TM, tn, nsplit);
+    ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, 2, 3>), grid1, block, s, g, rd);
+    return false;
+  }
   if (ring_ok && tn == 64 && ABS_RING64 && EPI == EPI_RELU && g.ksteps_per_split % 2 == 0 && g.ksteps_total % 2 == 0) {
     plan_note("fwd_ring2", TM, tn, nsplit);
     ABS_LAUNCH_K((mlp_gemm_kernel<64, EPI, GATHER, PER_UPLOAD, TAG, ABS_RING64, 2>), grid1, block, s, g, rd);
